@@ -1,0 +1,163 @@
+/*
+ * dinfer: the block-denoising hot path of diffusion-LLM inference on one MI355X (gfx950).
+ *
+ * One call of dinfer_step is one iteration of the inner loop of the paper's Algorithm 1 (blockwise dLLM
+ * inference): a model forward on the active block with a KV cache (bidirectional attention of the block
+ * over the cached prefix plus the block itself, Section 2), then the decoder (threshold decoding, Section 2,
+ * with a commit-at-least-one fallback so that the loop of Algorithm 1 terminates).  dinfer_generate_block
+ * is that inner loop; dinfer_refresh_block is the cache update of a fully decoded block (Section 2,
+ * "KV-cache management"); dinfer_prefill builds the prompt's cache.
+ *
+ * Conventions for every entry point
+ *  - All `d_` pointers are DEVICE pointers, `h_` pointers are HOST pointers.  The caller owns every buffer;
+ *    the library allocates no device memory and keeps only the pointers given to dinfer_create.
+ *  - `stream` is a hipStream_t passed as void*; work is enqueued on it and the call returns without waiting
+ *    (dinfer_generate_block in threshold mode waits between steps to read the mask).  Outputs are valid
+ *    after the caller synchronises the stream.
+ *  - Return value: 0 on success, a negative DINFER_E* code otherwise.  Nothing is launched when an argument
+ *    is rejected.  dinfer_last_error() returns a thread-local description of the last failure.
+ *  - Calls on one context must not overlap: the workspace is shared state.
+ *
+ * Model: pre-norm transformer, RMSNorm, rotary embedding (rotate-half pairing), multi-head attention,
+ * softmax top-k router over SwiGLU experts, untied embedding / LM head.  Limits: head_dim 64 or 128,
+ * hidden, n_heads*head_dim and moe_inter multiples of 64, n_experts <= 64, top_k <= 8, block_len <= 64.
+ */
+#ifndef DINFER_H
+#define DINFER_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { DINFER_F32 = 0, DINFER_BF16 = 1 };
+
+enum {
+  DINFER_OK = 0,
+  DINFER_EINVAL = -1,      /* null pointer, size or shape out of range */
+  DINFER_EUNSUPPORTED = -2,/* a shape the kernels are not built for */
+  DINFER_ENOSPACE = -3,    /* workspace, page table or KV pool too small */
+  DINFER_EHIP = -4         /* a HIP call failed; see dinfer_last_error */
+};
+
+/* Tensor ids for dinfer_set_tensor.  Every matrix is given row-major as [out_features][in_features] in the
+ * configuration's dtype; gains are float32. */
+enum {
+  DINFER_T_EMB = 0,        /* [vocab][hidden] */
+  DINFER_T_LM_HEAD = 1,    /* [vocab][hidden] */
+  DINFER_T_FINAL_GAIN = 2, /* [hidden] float32 */
+  DINFER_T_ATTN_GAIN = 3,  /* [hidden] float32, per layer */
+  DINFER_T_WQ = 4,         /* [n_heads*head_dim][hidden], per layer */
+  DINFER_T_WK = 5,
+  DINFER_T_WV = 6,
+  DINFER_T_WO = 7,         /* [hidden][n_heads*head_dim], per layer */
+  DINFER_T_FFN_GAIN = 8,   /* [hidden] float32, per layer */
+  DINFER_T_ROUTER = 9,     /* [n_experts][hidden], per layer */
+  DINFER_T_GATE = 10,      /* [n_experts][moe_inter][hidden], per layer */
+  DINFER_T_UP = 11,        /* [n_experts][moe_inter][hidden], per layer */
+  DINFER_T_DOWN = 12,      /* [n_experts][hidden][moe_inter], per layer */
+  DINFER_T_COUNT = 13
+};
+
+typedef struct dinfer_config {
+  int32_t n_layers, hidden, n_heads, head_dim, n_experts, top_k, moe_inter, vocab;
+  int32_t dtype;      /* DINFER_F32 or DINFER_BF16: storage of weights, activations fed to the matrix cores
+                         and the KV cache; accumulation is always float32 */
+  int32_t page_size;  /* tokens per KV page; must be 16 */
+  int32_t mask_id;    /* id that marks an undecided position (Algorithm 1) */
+  int32_t norm_topk;  /* 1: the k selected router probabilities are renormalised to sum to 1 */
+  int32_t max_pos;    /* positions 0..max_pos-1 may be used (size of the rotary table) */
+  float rms_eps, rope_theta, logit_scale;
+} dinfer_config;
+
+/* Decoder settings.  fixed_k == 0: commit every masked position whose confidence is at or above
+ * `threshold`, or the single most confident one if none is.  fixed_k > 0: commit the fixed_k most confident
+ * masked positions (all that remain if fewer).  Ties go to the lower position. */
+typedef struct dinfer_decode {
+  float threshold;
+  int32_t fixed_k;
+} dinfer_decode;
+
+typedef struct dinfer_ctx dinfer_ctx;
+
+/* Sizes of the three device buffers the caller must allocate (256-byte aligned).  0 on a bad config. */
+size_t dinfer_weights_bytes(const dinfer_config* cfg);
+size_t dinfer_kv_bytes(const dinfer_config* cfg, int32_t n_pages);
+/* max_seqs <= 64 sequences per call, max_tokens = most tokens one forward processes over all sequences
+ * (the block for a step, the prompt for a prefill). */
+size_t dinfer_workspace_bytes(const dinfer_config* cfg, int32_t max_seqs, int32_t max_tokens);
+
+/* Validates the configuration, records the buffers, builds the rotary table in the workspace (enqueued on
+ * `stream`).  The KV pool is laid out by the library; its contents are opaque (dinfer_kv_read/_write move
+ * rows in and out).  *out is freed by dinfer_destroy (host memory only). */
+int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_bytes, void* d_kv_pool,
+                  int32_t n_pages, void* d_workspace, size_t workspace_bytes, int32_t max_seqs,
+                  int32_t max_tokens, void* stream, dinfer_ctx** out);
+void dinfer_destroy(dinfer_ctx* ctx);
+const char* dinfer_last_error(void);
+
+/* Copies one tensor (layer ignored for the three global ones) from `d_src`, row-major as listed above, into
+ * the library's packed layout inside d_weights.  `bytes` must equal the tensor's size. */
+int dinfer_set_tensor(dinfer_ctx* ctx, int32_t tensor_id, int32_t layer, const void* d_src, size_t bytes,
+                      void* stream);
+
+/* Prompt prefill: a bidirectional forward over each sequence's prompt alone, writing K,V of positions
+ * 0..len-1 into the pages of its page-table row.  d_tokens: the prompts back to back (sum of lens);
+ * h_lens: [n_seq] on the host; d_page_table: [n_seq][pt_stride] page ids. */
+int dinfer_prefill(dinfer_ctx* ctx, int32_t n_seq, const int32_t* d_tokens, const int32_t* h_lens,
+                   const int32_t* d_page_table, int32_t pt_stride, void* stream);
+
+/* One denoising step (Algorithm 1, steps 3 and 4) for n_seq sequences, each with a block of block_len
+ * positions that follows its d_prefix_len[s] cached positions.
+ *   d_block_tokens [n_seq][block_len] in/out: mask_id at undecided positions; committed positions receive
+ *                  their id.
+ *   d_mask         [n_seq] in/out: bit i set = position i undecided.  Bits only ever get cleared.
+ *   d_prefix_len   [n_seq] in: cached positions before the block.  Their K,V pages are only read.
+ *   d_page_table   [n_seq][pt_stride]: page ids; must cover prefix_len + block_len positions.  K,V of the
+ *                  block's positions are (re)written every step.
+ *   d_conf, d_argmax [n_seq][block_len] out: confidence (largest softmax probability of the position's
+ *                  logits) and candidate id (lowest id on ties) of every position.
+ *   d_n_committed  [n_seq] out.
+ * A sequence whose mask is empty commits nothing. */
+int dinfer_step(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
+                void* stream);
+
+/* Cache update of a decoded block: the same forward without LM head and decoder over the block's final
+ * ids, leaving the block's K,V final, then d_prefix_len[s] += block_len. */
+int dinfer_refresh_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, const int32_t* d_block_tokens,
+                         int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, void* stream);
+
+/* The inner loop of Algorithm 1: steps until every mask is empty or max_steps were taken.  With
+ * fixed_k > 0 and h_masked_hint > 0 (the caller's count of undecided positions per sequence, the same for
+ * all) exactly ceil(h_masked_hint / fixed_k) steps are enqueued without waiting; otherwise the masks are
+ * read back after each step.  *h_steps_taken (host, may be NULL) receives the number of steps. */
+int dinfer_generate_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens,
+                          uint64_t* d_mask, const int32_t* d_prefix_len, const int32_t* d_page_table,
+                          int32_t pt_stride, const dinfer_decode* decode, float* d_conf, int32_t* d_argmax,
+                          int32_t* d_n_committed, int32_t max_steps, int32_t h_masked_hint,
+                          int32_t* h_steps_taken, void* stream);
+
+/* Moves K,V rows of one layer and one sequence between the pool and plain float32 arrays
+ * d_k, d_v: [n_pos][n_heads*head_dim] for positions first_pos .. first_pos+n_pos-1 (keys as stored, i.e.
+ * after the rotary embedding).  d_page_row: that sequence's page-table row. */
+int dinfer_kv_write(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, int32_t first_pos,
+                    int32_t n_pos, const float* d_k, const float* d_v, void* stream);
+int dinfer_kv_read(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, int32_t first_pos, int32_t n_pos,
+                   float* d_k, float* d_v, void* stream);
+
+/* Test hooks.  dinfer_debug_logits recomputes the logits of the last forward's n_rows first rows through
+ * the LM-head kernel's arithmetic and stores them: d_out [n_rows][vocab] float32.  dinfer_debug_get copies
+ * an intermediate of the last forward: what = 0 residual stream leaving the last layer [T][hidden] f32;
+ * 1 router expert ids of every layer [n_layers][T][top_k] i32; 2 their mixture weights, same shape, f32;
+ * and of the last layer: 3 expert row counts [n_experts] i32; 4 expert offsets [n_experts+1] i32;
+ * 5 permutation [T*top_k] i32. */
+int dinfer_debug_logits(dinfer_ctx* ctx, int32_t n_rows, float* d_out, void* stream);
+int dinfer_debug_get(dinfer_ctx* ctx, int32_t what, void* d_out, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

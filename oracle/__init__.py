@@ -43,7 +43,7 @@ class CWeights(ctypes.Structure):
 
 
 class CTrace(ctypes.Structure):
-    _fields_ = [(n, c_vp) for n in ("topk_idx", "topk_w", "resid", "attn_out")]
+    _fields_ = [(n, c_vp) for n in ("topk_idx", "topk_w", "resid", "attn_out", "router_p", "forced_idx")]
 
 
 _lib = None
@@ -101,13 +101,21 @@ def f64(a):
 class Trace:
     """Intermediates of one forward over n_tok tokens."""
 
-    def __init__(self, cfg, n_tok):
+    def __init__(self, cfg, n_tok, forced_idx=None):
+        """forced_idx: optional int32 [L][n_tok][k] expert ids the forward must use (see oracle.h)."""
         L, H, D, K = cfg.n_layers, cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.top_k
         self.topk_idx = np.zeros((L, n_tok, K), dtype=np.int32)
         self.topk_w = np.zeros((L, n_tok, K), dtype=np.float64)
         self.resid = np.zeros((L + 1, n_tok, H), dtype=np.float64)
         self.attn_out = np.zeros((L, n_tok, D), dtype=np.float64)
-        self.c = CTrace(_p(self.topk_idx), _p(self.topk_w), _p(self.resid), _p(self.attn_out))
+        self.router_p = np.zeros((L, n_tok, cfg.n_experts), dtype=np.float64)
+        self.forced_idx = None
+        if forced_idx is not None:
+            self.forced_idx = np.ascontiguousarray(forced_idx, dtype=np.int32)
+            assert self.forced_idx.shape == (L, n_tok, K)
+            assert self.forced_idx.min() >= 0 and self.forced_idx.max() < cfg.n_experts
+        self.c = CTrace(_p(self.topk_idx), _p(self.topk_w), _p(self.resid), _p(self.attn_out), _p(self.router_p),
+                        _p(self.forced_idx))
 
 
 class Oracle:

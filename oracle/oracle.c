@@ -110,11 +110,8 @@ void oracle_attention(const double* q, int n_q, const double* k, const double* v
   }
 }
 
-/* Router: softmax over all experts, the k largest probabilities (ties -> lower expert id), in
- * selection order; weights renormalised to sum 1 when norm_topk. */
-void oracle_router(int wdtype, const void* w_router, int n_experts, int hidden, const double* h, int top_k,
-                   int norm_topk, int32_t* idx, double* weight) {
-  double* p = (double*)malloc(sizeof(double) * (size_t)n_experts);
+/* Router probabilities: softmax over all experts of h . w_router[e]. */
+void oracle_router_probs(int wdtype, const void* w_router, int n_experts, int hidden, const double* h, double* p) {
   double m = -INFINITY;
   for (int e = 0; e < n_experts; ++e) {
     p[e] = dot_row(wdtype, w_router, (size_t)e, hidden, h);
@@ -126,6 +123,14 @@ void oracle_router(int wdtype, const void* w_router, int n_experts, int hidden, 
     z += p[e];
   }
   for (int e = 0; e < n_experts; ++e) p[e] /= z;
+}
+
+/* Router: the k largest probabilities (ties -> lower expert id), in selection order; weights
+ * renormalised to sum 1 when norm_topk. */
+void oracle_router(int wdtype, const void* w_router, int n_experts, int hidden, const double* h, int top_k,
+                   int norm_topk, int32_t* idx, double* weight) {
+  double* p = (double*)malloc(sizeof(double) * (size_t)n_experts);
+  oracle_router_probs(wdtype, w_router, n_experts, hidden, h, p);
   double sel = 0.0;
   for (int j = 0; j < top_k; ++j) {
     int best = -1;
@@ -186,6 +191,7 @@ int oracle_forward(const oracle_config* c, const oracle_weights* w, int n_tok, c
   if (prefix_len < 0 || n_tok <= 0 || prefix_len + n_tok > cache_cap) return -1;
   for (int t = 0; t < n_tok; ++t)
     if (tokens[t] < 0 || tokens[t] >= c->vocab) return -2;
+  if (c->n_experts > 64 || c->top_k > 64) return -3;
 
   double* x = hidden_out; /* residual stream [n_tok][H] */
   double* hn = (double*)malloc(sizeof(double) * (size_t)n_tok * H);
@@ -228,6 +234,23 @@ int oracle_forward(const oracle_config* c, const oracle_weights* w, int n_tok, c
       oracle_router(c->wdtype, L->w_router, c->n_experts, H, hn + (size_t)t * H, K, c->norm_topk, idx, wt);
       if (trace && trace->topk_idx) memcpy(trace->topk_idx + ((size_t)l * n_tok + t) * K, idx, sizeof(int32_t) * K);
       if (trace && trace->topk_w) memcpy(trace->topk_w + ((size_t)l * n_tok + t) * K, wt, sizeof(double) * K);
+      if (trace && (trace->router_p || trace->forced_idx)) {
+        double p[64];
+        oracle_router_probs(c->wdtype, L->w_router, c->n_experts, H, hn + (size_t)t * H, p);
+        if (trace->router_p) memcpy(trace->router_p + ((size_t)l * n_tok + t) * c->n_experts, p, sizeof(double) * c->n_experts);
+        if (trace->forced_idx) {
+          /* the caller dictates the expert set (to follow another implementation through a near-tie);
+           * the mixture weights are still this oracle's own probabilities of those experts */
+          double sel = 0.0;
+          for (int j = 0; j < K; ++j) {
+            idx[j] = trace->forced_idx[((size_t)l * n_tok + t) * K + j];
+            wt[j] = p[idx[j]];
+            sel += wt[j];
+          }
+          if (c->norm_topk)
+            for (int j = 0; j < K; ++j) wt[j] /= sel;
+        }
+      }
       oracle_moe_ffn(c, L, hn + (size_t)t * H, idx, wt, proj + (size_t)t * H);
     }
     for (size_t i = 0; i < (size_t)n_tok * H; ++i) x[i] += proj[i];

@@ -62,6 +62,11 @@ typedef struct {
   double* topk_w;    /* [L][T][k] their mixture weights */
   double* resid;     /* [L+1][T][H] residual stream entering layer l; [L] = leaving the last layer */
   double* attn_out;  /* [L][T][nh*hd] attention output before the output projection */
+  double* router_p;  /* [L][T][E] router probabilities */
+  /* INPUT, normally NULL: [L][T][k] expert ids to use instead of the oracle's own top-k.  Tests use it to
+   * follow the HIP path through a near-tie of the k-th and (k+1)-th probability, where either choice is
+   * valid; topk_idx still reports the oracle's own choice so that the two can be compared. */
+  const int32_t* forced_idx;
 } oracle_trace;
 
 /* ---- building blocks (exported so that each can be pinned on its own) ---- */
@@ -70,6 +75,7 @@ void oracle_rope(double* vec, int head_dim, int pos, double theta);
 void oracle_linear(int wdtype, const void* W, int n_out, int n_in, const double* x, int n_tok, double* out);
 void oracle_attention(const double* q, int n_q, const double* k, const double* v, int n_keys, int n_heads,
                       int head_dim, double* out);
+void oracle_router_probs(int wdtype, const void* w_router, int n_experts, int hidden, const double* h, double* p);
 void oracle_router(int wdtype, const void* w_router, int n_experts, int hidden, const double* h, int top_k,
                    int norm_topk, int32_t* idx, double* weight);
 void oracle_moe_ffn(const oracle_config* c, const oracle_layer* l, const double* h, const int32_t* idx,

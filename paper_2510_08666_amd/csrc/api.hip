@@ -1,0 +1,507 @@
+// C-ABI of the dinfer library: argument checks, buffer carving, and the launch sequence of one forward.
+#include "../../include/dinfer.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace dinfer;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(DINFER_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct LayerW {
+  size_t attn_gain, wqkv, wo, ffn_gain, router, gate_up, down;   // byte offsets into d_weights
+};
+struct WeightMap {
+  size_t emb, lm_head, final_gain;
+  std::vector<LayerW> layers;
+  size_t total;
+};
+
+struct Carve {   // bump allocator over a byte range
+  size_t at = 0;
+  size_t take(size_t bytes) {
+    const size_t o = at;
+    at = align_up(at + bytes);
+    return o;
+  }
+};
+
+int check_config(const dinfer_config* c) {
+  if (!c) return fail(DINFER_EINVAL, "config is null");
+  if (c->dtype != DINFER_F32 && c->dtype != DINFER_BF16) return fail(DINFER_EINVAL, "dtype %d", c->dtype);
+  if (c->n_layers < 1 || c->hidden < 64 || c->n_heads < 1 || c->n_experts < 1 || c->top_k < 1 || c->moe_inter < 64 ||
+      c->vocab < 2 || c->max_pos < 1)
+    return fail(DINFER_EINVAL, "non-positive or too small dimension");
+  if (c->page_size != PAGE) return fail(DINFER_EUNSUPPORTED, "page_size must be %d", PAGE);
+  if (c->head_dim != 64 && c->head_dim != 128) return fail(DINFER_EUNSUPPORTED, "head_dim must be 64 or 128");
+  if (c->hidden % 64 || c->moe_inter % 64 || (c->n_heads * c->head_dim) % 64)
+    return fail(DINFER_EUNSUPPORTED, "hidden, moe_inter and n_heads*head_dim must be multiples of 64");
+  if (c->hidden > 4096) return fail(DINFER_EUNSUPPORTED, "hidden > 4096");
+  if (c->n_experts > MAX_EXPERTS) return fail(DINFER_EUNSUPPORTED, "n_experts > %d", MAX_EXPERTS);
+  if (c->top_k > MAX_TOPK || c->top_k > c->n_experts) return fail(DINFER_EINVAL, "top_k %d out of range", c->top_k);
+  if (c->mask_id < 0 || c->mask_id >= c->vocab) return fail(DINFER_EINVAL, "mask_id out of range");
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(DINFER_EINVAL, "rms_eps / rope_theta");
+  return DINFER_OK;
+}
+
+WeightMap map_weights(const dinfer_config& c) {
+  const bool bf = c.dtype == DINFER_BF16;
+  const size_t es = bf ? 2 : 4;
+  const int H = c.hidden, D = c.n_heads * c.head_dim, I = c.moe_inter, E = c.n_experts, V = c.vocab;
+  WeightMap m;
+  Carve cv;
+  m.emb = cv.take((size_t)V * H * es);
+  m.lm_head = cv.take((size_t)packed_bytes(bf, (V + 63) / 64, H));
+  m.final_gain = cv.take((size_t)H * 4);
+  m.layers.resize(c.n_layers);
+  for (auto& l : m.layers) {
+    l.attn_gain = cv.take((size_t)H * 4);
+    l.wqkv = cv.take((size_t)packed_bytes(bf, 3 * D / 64, H));
+    l.wo = cv.take((size_t)packed_bytes(bf, H / 64, D));
+    l.ffn_gain = cv.take((size_t)H * 4);
+    l.router = cv.take((size_t)E * H * es);
+    l.gate_up = cv.take((size_t)E * packed_bytes(bf, I / 32, H));
+    l.down = cv.take((size_t)E * packed_bytes(bf, H / 64, I));
+  }
+  m.total = cv.at;
+  return m;
+}
+
+int attn_splits(int n_qtiles, int n_heads) {
+  int s = 1024 / (n_qtiles * n_heads * 4);   // aim at ~1024 waves
+  if (s < 1) s = 1;
+  if (s > 32) s = 32;
+  return s;
+}
+
+struct Workspace {
+  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, h, q, a, attn_part, topk_idx, topk_w, cnt, off,
+      perm, pos_of_pair, y, o, lm_part, conf, argmax, total;
+};
+
+Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
+  const size_t es = c.dtype == DINFER_BF16 ? 2 : 4;
+  const int H = c.hidden, D = c.n_heads * c.head_dim, I = c.moe_inter, K = c.top_k;
+  const size_t T = (size_t)max_tokens;
+  const int max_qtiles = max_tokens / TILE + max_seqs;
+  Workspace w;
+  Carve cv;
+  w.cos_tab = cv.take((size_t)c.max_pos * (c.head_dim / 2) * 4);
+  w.sin_tab = cv.take((size_t)c.max_pos * (c.head_dim / 2) * 4);
+  w.tok_seq = cv.take(T * 4);
+  w.tok_pos = cv.take(T * 4);
+  w.seq_nkeys = cv.take((size_t)max_seqs * 4);
+  w.qtile = cv.take((size_t)max_qtiles * 3 * 4);
+  w.x = cv.take(T * H * 4);
+  w.h = cv.take(T * H * es);
+  w.q = cv.take(T * D * es);
+  w.a = cv.take(T * D * es);
+  size_t part = 0;   // the split policy depends on the number of query tiles only
+  for (int nq = 1; nq <= max_qtiles; ++nq) {
+    const size_t p = attn_part_floats(nq, c.n_heads, attn_splits(nq, c.n_heads), c.head_dim);
+    if (p > part) part = p;
+  }
+  w.attn_part = cv.take(part * 4);
+  w.topk_idx = cv.take((size_t)c.n_layers * T * K * 4);   // kept per layer (tests read the routing back)
+  w.topk_w = cv.take((size_t)c.n_layers * T * K * 4);
+  w.cnt = cv.take((size_t)MAX_EXPERTS * 4);
+  w.off = cv.take((size_t)(MAX_EXPERTS + 1) * 4);
+  w.perm = cv.take(T * K * 4);
+  w.pos_of_pair = cv.take(T * K * 4);
+  w.y = cv.take(T * K * I * es);
+  w.o = cv.take(T * K * H * 4);
+  w.lm_part = cv.take((size_t)lm_head_waves(c.vocab) * T * 4 * 4);
+  w.conf = cv.take(T * 4);
+  w.argmax = cv.take(T * 4);
+  w.total = cv.at;
+  return w;
+}
+
+}  // namespace
+
+struct dinfer_ctx {
+  dinfer_config cfg;
+  bool bf16;
+  char* weights;
+  char* kv;
+  char* ws;
+  int n_pages, max_seqs, max_tokens;
+  WeightMap wm;
+  Workspace wsm;
+  KvGeom geom;
+  size_t kv_layer_bytes;
+  int last_T;   // tokens of the last forward (debug hooks)
+  uint64_t* h_mask_pinned;
+};
+
+namespace {
+
+template <typename T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
+
+// One forward over the packed tokens of `span`.  with_head: final norm into h (ready for the LM head).
+int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const int32_t* d_base,
+            const int32_t* d_page_table, int pt_stride, bool with_head, hipStream_t st) {
+  const dinfer_config& f = c->cfg;
+  const bool bf = c->bf16;
+  const int T = span.off[span.n_seq];
+  const int H = f.hidden, D = f.n_heads * f.head_dim;
+  char* ws = c->ws;
+  const Workspace& w = c->wsm;
+  int n_qtiles = 0;
+  for (int s = 0; s < span.n_seq; ++s) n_qtiles += (span.off[s + 1] - span.off[s] + TILE - 1) / TILE;
+  FwdMeta meta{at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
+               at<int32_t>(ws, w.qtile)};
+  const int limit = f.max_pos < pt_stride * PAGE ? f.max_pos : pt_stride * PAGE;
+  launch_meta(span, d_base, limit, at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
+              at<int32_t>(ws, w.qtile), st);
+  float* x = at<float>(ws, w.x);
+  void* h = ws + w.h;
+  for (int l = 0; l < f.n_layers; ++l) {
+    const LayerW& lw = c->wm.layers[l];
+    char* kv_layer = c->kv + (size_t)l * c->kv_layer_bytes;
+    int32_t* topk_idx = at<int32_t>(ws, w.topk_idx) + (size_t)l * T * f.top_k;
+    float* topk_w = at<float>(ws, w.topk_w) + (size_t)l * T * f.top_k;
+    if (l == 0)
+      launch_embed_norm(bf, d_tokens, c->weights + c->wm.emb, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H,
+                        f.vocab, x, h, st);
+    else
+      launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k,
+                          f.top_k, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H, h, st);
+    QkvArgs qa{c->weights + lw.wqkv, h, ws + w.q, kv_layer, c->geom, meta, d_page_table, pt_stride,
+               at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H};
+    launch_qkv(bf, qa, st);
+    AttnArgs aa{ws + w.q, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
+                attn_splits(n_qtiles, f.n_heads), at<float>(ws, w.attn_part), ws + w.a};
+    launch_attention(bf, aa, st);
+    launch_oproj(bf, c->weights + lw.wo, ws + w.a, x, T, D, H, st);
+    launch_router(bf, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, c->weights + lw.router, T, H, f.n_experts,
+                  f.top_k, f.norm_topk, h, topk_idx, topk_w, st);
+    launch_permute(topk_idx, T * f.top_k, f.n_experts, at<int32_t>(ws, w.cnt),
+                   at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), st);
+    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, h, ws + w.y, at<float>(ws, w.o),
+                  at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), T, H, f.moe_inter,
+                  f.n_experts, f.top_k};
+    launch_experts(bf, ea, st);
+  }
+  // the last layer's expert outputs are folded into the residual here; the norm written to h is the final one
+  launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
+                      at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k,
+                      at<float>(c->weights, c->wm.final_gain), f.rms_eps, T, H, h, st);
+  (void)with_head;
+  c->last_T = T;
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int check_block_args(dinfer_ctx* c, int n_seq, int block_len, const void* tokens, const void* prefix_len,
+                     const void* page_table, int pt_stride) {
+  if (!c) return fail(DINFER_EINVAL, "context is null");
+  if (!tokens || !prefix_len || !page_table) return fail(DINFER_EINVAL, "null device pointer");
+  if (n_seq < 1 || n_seq > c->max_seqs) return fail(DINFER_EINVAL, "n_seq %d outside [1, %d]", n_seq, c->max_seqs);
+  if (block_len < 1 || block_len > 64) return fail(DINFER_EINVAL, "block_len %d outside [1, 64]", block_len);
+  if ((int64_t)n_seq * block_len > c->max_tokens)
+    return fail(DINFER_ENOSPACE, "n_seq*block_len %d exceeds max_tokens %d", n_seq * block_len, c->max_tokens);
+  if (pt_stride < (block_len + PAGE - 1) / PAGE) return fail(DINFER_ENOSPACE, "page table row too short");
+  if (block_len > c->cfg.max_pos) return fail(DINFER_ENOSPACE, "block_len exceeds max_pos");
+  return DINFER_OK;
+}
+
+SeqSpan uniform_span(int n_seq, int len) {
+  SeqSpan s;
+  s.n_seq = n_seq;
+  for (int i = 0; i <= n_seq; ++i) s.off[i] = i * len;
+  return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dinfer_last_error(void) { return g_err; }
+
+size_t dinfer_weights_bytes(const dinfer_config* cfg) {
+  if (check_config(cfg) != DINFER_OK) return 0;
+  return map_weights(*cfg).total;
+}
+
+size_t dinfer_kv_bytes(const dinfer_config* cfg, int32_t n_pages) {
+  if (check_config(cfg) != DINFER_OK || n_pages < 1) return 0;
+  const size_t es = cfg->dtype == DINFER_BF16 ? 2 : 4;
+  return (size_t)cfg->n_layers * n_pages * 2 * cfg->n_heads * PAGE * cfg->head_dim * es;
+}
+
+size_t dinfer_workspace_bytes(const dinfer_config* cfg, int32_t max_seqs, int32_t max_tokens) {
+  if (check_config(cfg) != DINFER_OK || max_seqs < 1 || max_seqs > MAX_SEQS || max_tokens < 1) return 0;
+  return map_workspace(*cfg, max_seqs, max_tokens).total;
+}
+
+int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_bytes, void* d_kv_pool, int32_t n_pages,
+                  void* d_workspace, size_t workspace_bytes, int32_t max_seqs, int32_t max_tokens, void* stream,
+                  dinfer_ctx** out) {
+  if (!out) return fail(DINFER_EINVAL, "out is null");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != DINFER_OK) return rc;
+  if (!d_weights || !d_kv_pool || !d_workspace) return fail(DINFER_EINVAL, "null device buffer");
+  if (((uintptr_t)d_weights | (uintptr_t)d_kv_pool | (uintptr_t)d_workspace) & 255)
+    return fail(DINFER_EINVAL, "device buffers must be 256-byte aligned");
+  if (n_pages < 1) return fail(DINFER_EINVAL, "n_pages < 1");
+  if (max_seqs < 1 || max_seqs > MAX_SEQS) return fail(DINFER_EINVAL, "max_seqs outside [1, %d]", MAX_SEQS);
+  if (max_tokens < 1) return fail(DINFER_EINVAL, "max_tokens < 1");
+  dinfer_ctx* c = new (std::nothrow) dinfer_ctx();
+  if (!c) return fail(DINFER_EINVAL, "out of host memory");
+  c->cfg = *cfg;
+  c->bf16 = cfg->dtype == DINFER_BF16;
+  c->wm = map_weights(*cfg);
+  c->wsm = map_workspace(*cfg, max_seqs, max_tokens);
+  if (weights_bytes < c->wm.total || workspace_bytes < c->wsm.total) {
+    rc = fail(DINFER_ENOSPACE, "weights buffer %zu < %zu or workspace %zu < %zu", weights_bytes, c->wm.total,
+              workspace_bytes, c->wsm.total);
+    delete c;
+    return rc;
+  }
+  c->weights = (char*)d_weights;
+  c->kv = (char*)d_kv_pool;
+  c->ws = (char*)d_workspace;
+  c->n_pages = n_pages;
+  c->max_seqs = max_seqs;
+  c->max_tokens = max_tokens;
+  const size_t es = c->bf16 ? 2 : 4;
+  c->geom.n_heads = cfg->n_heads;
+  c->geom.head_dim = cfg->head_dim;
+  c->geom.n_pages = n_pages;
+  c->geom.page_stride = (int64_t)2 * cfg->n_heads * PAGE * cfg->head_dim;
+  c->geom.layer_stride = c->geom.page_stride * n_pages;
+  c->kv_layer_bytes = (size_t)c->geom.layer_stride * es;
+  c->last_T = 0;
+  c->h_mask_pinned = nullptr;
+  if (hipHostMalloc((void**)&c->h_mask_pinned, MAX_SEQS * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+    delete c;
+    return fail(DINFER_EHIP, "hipHostMalloc failed");
+  }
+  configure_kernels();
+  launch_rope_table(at<float>(c->ws, c->wsm.cos_tab), at<float>(c->ws, c->wsm.sin_tab), cfg->max_pos, cfg->head_dim,
+                    cfg->rope_theta, (hipStream_t)stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    rc = fail(DINFER_EHIP, "rotary table launch: %s", hipGetErrorString(e));
+    (void)hipHostFree(c->h_mask_pinned);
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return DINFER_OK;
+}
+
+void dinfer_destroy(dinfer_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->h_mask_pinned) (void)hipHostFree(ctx->h_mask_pinned);
+  delete ctx;
+}
+
+int dinfer_set_tensor(dinfer_ctx* c, int32_t tensor_id, int32_t layer, const void* d_src, size_t bytes, void* stream) {
+  if (!c || !d_src) return fail(DINFER_EINVAL, "null argument");
+  if (tensor_id < 0 || tensor_id >= DINFER_T_COUNT) return fail(DINFER_EINVAL, "tensor id %d", tensor_id);
+  const dinfer_config& f = c->cfg;
+  const bool per_layer = tensor_id >= DINFER_T_ATTN_GAIN;
+  if (per_layer && (layer < 0 || layer >= f.n_layers)) return fail(DINFER_EINVAL, "layer %d", layer);
+  const bool bf = c->bf16;
+  const size_t es = bf ? 2 : 4;
+  const int H = f.hidden, D = f.n_heads * f.head_dim, I = f.moe_inter, E = f.n_experts, V = f.vocab;
+  hipStream_t st = (hipStream_t)stream;
+  const LayerW* lw = per_layer ? &c->wm.layers[layer] : nullptr;
+  size_t want = 0;
+  switch (tensor_id) {
+    case DINFER_T_EMB: want = (size_t)V * H * es; break;
+    case DINFER_T_LM_HEAD: want = (size_t)V * H * es; break;
+    case DINFER_T_FINAL_GAIN: case DINFER_T_ATTN_GAIN: case DINFER_T_FFN_GAIN: want = (size_t)H * 4; break;
+    case DINFER_T_WQ: case DINFER_T_WK: case DINFER_T_WV: case DINFER_T_WO: want = (size_t)D * H * es; break;
+    case DINFER_T_ROUTER: want = (size_t)E * H * es; break;
+    default: want = (size_t)E * I * H * es; break;
+  }
+  if (bytes != want) return fail(DINFER_EINVAL, "tensor %d: %zu bytes given, %zu expected", tensor_id, bytes, want);
+  char* W = c->weights;
+  const size_t qk_bytes = (size_t)packed_bytes(bf, D / 64, H);
+  switch (tensor_id) {
+    case DINFER_T_EMB: HIP_TRY(hipMemcpyAsync(W + c->wm.emb, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_LM_HEAD: launch_pack(bf, d_src, W + c->wm.lm_head, 1, V, H, (V + 63) / 64, PACK_ADJACENT, 0, st); break;
+    case DINFER_T_FINAL_GAIN: HIP_TRY(hipMemcpyAsync(W + c->wm.final_gain, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_ATTN_GAIN: HIP_TRY(hipMemcpyAsync(W + lw->attn_gain, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_FFN_GAIN: HIP_TRY(hipMemcpyAsync(W + lw->ffn_gain, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_WQ: launch_pack(bf, d_src, W + lw->wqkv, 1, D, H, D / 64, PACK_ROPE_PAIR, f.head_dim, st); break;
+    case DINFER_T_WK: launch_pack(bf, d_src, W + lw->wqkv + qk_bytes, 1, D, H, D / 64, PACK_ROPE_PAIR, f.head_dim, st); break;
+    case DINFER_T_WV: launch_pack(bf, d_src, W + lw->wqkv + 2 * qk_bytes, 1, D, H, D / 64, PACK_ADJACENT, 0, st); break;
+    case DINFER_T_WO: launch_pack(bf, d_src, W + lw->wo, 1, H, D, H / 64, PACK_ADJACENT, 0, st); break;
+    case DINFER_T_ROUTER: HIP_TRY(hipMemcpyAsync(W + lw->router, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_GATE: launch_pack(bf, d_src, W + lw->gate_up, E, I, H, I / 32, PACK_HALF0, 0, st); break;
+    case DINFER_T_UP: launch_pack(bf, d_src, W + lw->gate_up, E, I, H, I / 32, PACK_HALF1, 0, st); break;
+    case DINFER_T_DOWN: launch_pack(bf, d_src, W + lw->down, E, H, I, H / 64, PACK_ADJACENT, 0, st); break;
+  }
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_prefill(dinfer_ctx* c, int32_t n_seq, const int32_t* d_tokens, const int32_t* h_lens,
+                   const int32_t* d_page_table, int32_t pt_stride, void* stream) {
+  if (!c) return fail(DINFER_EINVAL, "context is null");
+  if (!d_tokens || !h_lens || !d_page_table) return fail(DINFER_EINVAL, "null pointer");
+  if (n_seq < 1 || n_seq > c->max_seqs) return fail(DINFER_EINVAL, "n_seq %d outside [1, %d]", n_seq, c->max_seqs);
+  SeqSpan span;
+  span.n_seq = n_seq;
+  span.off[0] = 0;
+  int qtiles = 0;
+  for (int s = 0; s < n_seq; ++s) {
+    if (h_lens[s] < 1 || h_lens[s] > c->cfg.max_pos) return fail(DINFER_EINVAL, "prompt length %d", h_lens[s]);
+    if (pt_stride * PAGE < h_lens[s]) return fail(DINFER_ENOSPACE, "page table row too short for prompt %d", s);
+    span.off[s + 1] = span.off[s] + h_lens[s];
+    qtiles += (h_lens[s] + TILE - 1) / TILE;
+  }
+  if (span.off[n_seq] > c->max_tokens || qtiles > c->max_tokens / TILE + c->max_seqs)
+    return fail(DINFER_ENOSPACE, "prefill of %d tokens exceeds max_tokens %d", span.off[n_seq], c->max_tokens);
+  return forward(c, span, d_tokens, nullptr, d_page_table, pt_stride, false, (hipStream_t)stream);
+}
+
+int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, const dinfer_decode* decode,
+                float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
+  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  hipStream_t st = (hipStream_t)stream;
+  rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, true, st);
+  if (rc != DINFER_OK) return rc;
+  const dinfer_config& f = c->cfg;
+  const int T = n_seq * block_len;
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, T, f.hidden, f.vocab, f.logit_scale,
+            at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), nullptr};
+  launch_lm_head(c->bf16, la, st);
+  launch_lm_merge(la.part, la.n_lm_waves, T, d_conf, d_argmax, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, d_block_tokens, d_mask, decode->threshold, decode->fixed_k,
+                d_n_committed, st);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_refresh_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, const int32_t* d_block_tokens,
+                         int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, false, st);
+  if (rc != DINFER_OK) return rc;
+  launch_add_i32(d_prefix_len, n_seq, block_len, st);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_generate_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                          const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                          const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
+                          int32_t max_steps, int32_t h_masked_hint, int32_t* h_steps_taken, void* stream) {
+  if (max_steps < 1) return fail(DINFER_EINVAL, "max_steps < 1");
+  if (!decode) return fail(DINFER_EINVAL, "decode is null");
+  hipStream_t st = (hipStream_t)stream;
+  int steps = 0;
+  if (decode->fixed_k > 0 && h_masked_hint > 0) {
+    int n = (h_masked_hint + decode->fixed_k - 1) / decode->fixed_k;
+    if (n > max_steps) n = max_steps;
+    for (; steps < n; ++steps) {
+      int rc = dinfer_step(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
+                           d_conf, d_argmax, d_n_committed, stream);
+      if (rc != DINFER_OK) return rc;
+    }
+  } else {
+    while (steps < max_steps) {
+      if (!c || !d_mask || n_seq < 1 || n_seq > MAX_SEQS) return fail(DINFER_EINVAL, "bad argument");
+      HIP_TRY(hipMemcpyAsync(c->h_mask_pinned, d_mask, (size_t)n_seq * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      uint64_t any = 0;
+      for (int s = 0; s < n_seq; ++s) any |= c->h_mask_pinned[s];
+      if (!any) break;
+      int rc = dinfer_step(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
+                           d_conf, d_argmax, d_n_committed, stream);
+      if (rc != DINFER_OK) return rc;
+      ++steps;
+    }
+  }
+  if (h_steps_taken) *h_steps_taken = steps;
+  return DINFER_OK;
+}
+
+static int kv_copy(dinfer_ctx* c, bool to_pool, int32_t layer, const int32_t* d_page_row, int32_t first_pos,
+                   int32_t n_pos, float* d_k, float* d_v, void* stream) {
+  if (!c || !d_page_row || !d_k || !d_v) return fail(DINFER_EINVAL, "null argument");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(DINFER_EINVAL, "layer %d", layer);
+  if (first_pos < 0 || n_pos < 1 || first_pos + n_pos > c->cfg.max_pos) return fail(DINFER_EINVAL, "position range");
+  launch_kv_copy(c->bf16, to_pool, c->kv + (size_t)layer * c->kv_layer_bytes, c->geom, d_page_row, first_pos, n_pos, d_k,
+                 d_v, (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_kv_write(dinfer_ctx* c, int32_t layer, const int32_t* d_page_row, int32_t first_pos, int32_t n_pos,
+                    const float* d_k, const float* d_v, void* stream) {
+  return kv_copy(c, true, layer, d_page_row, first_pos, n_pos, const_cast<float*>(d_k), const_cast<float*>(d_v), stream);
+}
+
+int dinfer_kv_read(dinfer_ctx* c, int32_t layer, const int32_t* d_page_row, int32_t first_pos, int32_t n_pos,
+                   float* d_k, float* d_v, void* stream) {
+  return kv_copy(c, false, layer, d_page_row, first_pos, n_pos, d_k, d_v, stream);
+}
+
+int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* stream) {
+  if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
+  if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
+  const dinfer_config& f = c->cfg;
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, n_rows, f.hidden, f.vocab, f.logit_scale,
+            at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), d_out};
+  launch_lm_head(c->bf16, la, (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_debug_get(dinfer_ctx* c, int32_t what, void* d_out, size_t bytes, void* stream) {
+  if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
+  const dinfer_config& f = c->cfg;
+  const size_t T = (size_t)c->last_T;
+  size_t off = 0, want = 0;
+  switch (what) {
+    case 0: off = c->wsm.x; want = T * f.hidden * 4; break;
+    case 1: off = c->wsm.topk_idx; want = (size_t)f.n_layers * T * f.top_k * 4; break;
+    case 2: off = c->wsm.topk_w; want = (size_t)f.n_layers * T * f.top_k * 4; break;
+    case 3: off = c->wsm.cnt; want = (size_t)f.n_experts * 4; break;
+    case 4: off = c->wsm.off; want = (size_t)(f.n_experts + 1) * 4; break;
+    case 5: off = c->wsm.perm; want = T * f.top_k * 4; break;
+    default: return fail(DINFER_EINVAL, "what %d", what);
+  }
+  if (bytes != want || want == 0) return fail(DINFER_EINVAL, "%zu bytes given, %zu expected", bytes, want);
+  HIP_TRY(hipMemcpyAsync(d_out, c->ws + off, want, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return DINFER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,213 @@
+// Bidirectional (non-causal) attention of a tile of 32 query tokens over every key of its sequence: the
+// cached prefix pages plus the tokens of this forward, read through the page table.
+//
+// Work split: grid (split, head, query tile), 4 waves per workgroup; the key tiles (32 keys) are dealt
+// round-robin to the n_splits*4 waves of a (head, query tile).  Each wave keeps its own online-softmax state and writes one partial
+// (unnormalised output, running max, running sum); attn_merge_kernel folds the partials of a
+// (query tile, head) in fixed order and writes the normalised output.
+//
+// MFMA mapping (32x32 tiles):  S^T[key][query] = K_tile . Q^T   (A = K rows, B = Q columns), so a lane owns
+// one query column and softmax statistics are per lane;  O^T[d][query] += V^T_tile . P^T  (A = V^T rows read
+// from the transposed V page, B = P^T taken from the S^T accumulator registers without any shuffle).
+#include "gemm.hpp"
+#include "kernels.hpp"
+
+namespace dinfer {
+
+size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim) {
+  return (size_t)n_qtiles * n_heads * n_splits * 4 * TILE * (head_dim + 2);
+}
+
+// B operand of the PV product for k-step s2: the G probabilities this lane holds for that step's keys, and
+// the matching A operand (V^T of those keys for feature row d).  Keys of accumulator register v sit at
+// tile-local index acc_row(v, half).
+template <typename E> struct PvStep;
+template <> struct PvStep<bf16_t> {
+  // step s2 in {0,1}: registers 8*s2 .. 8*s2+7 -> keys 16*s2 + {4h..4h+3, 8+4h..8+4h+3}
+  static constexpr int STEPS = 2;
+  __device__ static bf16x8 p_vec(const float (&p)[16], int s2) {
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)p[8 * s2 + i];
+    return r;
+  }
+  // vrow: V^T row of feature d inside the page of this step (16 slots contiguous)
+  __device__ static bf16x8 v_vec(const bf16_t* vrow, int half, int /*s2*/) {
+    const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow + 4 * half);
+    const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + 8 + 4 * half);
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      r[i] = lo[i];
+      r[4 + i] = hi[i];
+    }
+    return r;
+  }
+  __device__ static int page_of_step(int s2) { return s2; }
+  __device__ static int key_of(int s2, int half, int i) { return 16 * s2 + (i < 4 ? 4 * half + i : 8 + 4 * half + i - 4); }
+};
+template <> struct PvStep<float> {
+  // step s2 in {0..3}: registers 4*s2 .. 4*s2+3 -> keys 8*s2 + 4h + {0..3}
+  static constexpr int STEPS = 4;
+  __device__ static f32x4 p_vec(const float (&p)[16], int s2) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = p[4 * s2 + i];
+    return r;
+  }
+  __device__ static f32x4 v_vec(const float* vrow, int half, int s2) {
+    return *reinterpret_cast<const f32x4*>(vrow + 8 * (s2 & 1) + 4 * half);
+  }
+  __device__ static int page_of_step(int s2) { return s2 >> 1; }
+  __device__ static int key_of(int s2, int half, int i) { return 8 * s2 + 4 * half + i; }
+};
+
+template <typename E, int HD>
+__global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q, const E* __restrict__ kv_layer,
+                                                         KvGeom geom, FwdMeta meta,
+                                                         const int32_t* __restrict__ page_table, int pt_stride,
+                                                         int n_splits, float* __restrict__ part) {
+  typedef typename ET<E>::vec vec;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE;
+  const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int seq = meta.qtile[qt * 3 + 0], tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
+  const int n_keys = meta.seq_nkeys[seq];
+  const int D = geom.n_heads * HD;
+  const float scale = rsqrtf((float)HD);
+  const int32_t* pt = page_table + (int64_t)seq * pt_stride;
+
+  // Q^T operand: this lane's query column, all of head_dim
+  vec qv[DSTEPS];
+  {
+    const E* qrow = Q + (int64_t)(tok0 + min(col, nvalid - 1)) * D + head * HD + half * G;
+#pragma unroll
+    for (int s = 0; s < DSTEPS; ++s) qv[s] = load16<E>(qrow + s * KS);
+  }
+  f32x16 o[DT];
+  zero_acc<DT>(o);
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int n_ktiles = (n_keys + TILE - 1) / TILE;
+  for (int kt = split * 4 + wave; kt < n_ktiles; kt += n_splits * 4) {   // key tiles dealt round-robin to all waves
+    // ---- S^T = K . Q^T
+    const int key = min(kt * TILE + col, n_keys - 1);
+    const E* krow = kv_layer + kv_k_index(geom, safe_page(geom, pt[key / PAGE]), head, key % PAGE, 0) + half * G;
+    f32x16 sacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < DSTEPS; ++s) mfma32(sacc, load16<E>(krow + s * KS), qv[s]);
+    float p[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const bool ok = kt * TILE + acc_row(v, half) < n_keys;
+      p[v] = ok ? sacc[v] * scale : -INFINITY;
+      mx = fmaxf(mx, p[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));      // the other half-wave holds the column's other 16 keys
+    const float m_new = fmaxf(m_run, mx);           // finite: a key tile always holds at least one valid key
+    const float alpha = __expf(m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      p[v] = __expf(p[v] - m_new);
+      psum += p[v];
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[t][v] *= alpha;
+    // ---- O^T += V^T . P^T
+    const bool last = (kt + 1) * TILE > n_keys;
+#pragma unroll
+    for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
+      const int pkey = min(kt * TILE + PvStep<E>::page_of_step(s2) * PAGE, n_keys - 1);
+      const int page = safe_page(geom, pt[pkey / PAGE]);
+      const vec pv = PvStep<E>::p_vec(p, s2);
+#pragma unroll
+      for (int t = 0; t < DT; ++t) {
+        const E* vrow = kv_layer + kv_v_index(geom, page, head, 0, t * TILE + col);
+        vec vv = PvStep<E>::v_vec(vrow, half, s2);
+        if (last) {   // slots past the last key may hold anything (NaN * 0 would poison the sum)
+#pragma unroll
+          for (int i = 0; i < G; ++i)
+            if (kt * TILE + PvStep<E>::key_of(s2, half, i) >= n_keys) vv[i] = (E)0.f;
+        }
+        mfma32(o[t], vv, pv);
+      }
+    }
+  }
+  // ---- partial of this wave: O [32 q][HD], m [32], l [32]
+  const int pidx = ((qt * geom.n_heads + head) * n_splits + split) * 4 + wave;
+  float* pbase = part + (int64_t)pidx * TILE * (HD + 2);
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      f32x4 r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] = o[t][4 * g + i];
+      *reinterpret_cast<f32x4*>(pbase + col * HD + t * TILE + acc_row(4 * g, half)) = r;
+    }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
+  if (half == 0) {
+    pbase[TILE * HD + col] = m_run;
+    pbase[TILE * HD + TILE + col] = l_tot;
+  }
+}
+
+template <typename E, int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, FwdMeta meta, int n_heads,
+                                                          int n_parts, E* __restrict__ out) {
+  const int head = blockIdx.x, qt = blockIdx.y;
+  const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
+  const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
+  const int D = n_heads * HD;
+  // thread -> (query, 4 consecutive features); 32 * HD / 4 items over 256 threads
+  for (int item = threadIdx.x; item < TILE * HD / 4; item += 256) {
+    const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
+    if (q >= nvalid) continue;
+    float M = -INFINITY;
+    for (int p = 0; p < n_parts; ++p) M = fmaxf(M, pb[(int64_t)p * TILE * (HD + 2) + TILE * HD + q]);
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < n_parts; ++p) {
+      const float* pp = pb + (int64_t)p * TILE * (HD + 2);
+      const float mp = pp[TILE * HD + q];
+      if (mp == -INFINITY) continue;             // a wave that saw no key tile
+      const float w = __expf(mp - M);
+      L += w * pp[TILE * HD + TILE + q];
+      const f32x4 ov = *reinterpret_cast<const f32x4*>(pp + q * HD + d);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] += w * ov[i];
+    }
+    const float inv = 1.f / L;
+    E* dst = out + (int64_t)(tok0 + q) * D + head * HD + d;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = from_f32<E>(acc[i] * inv);
+  }
+}
+
+template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
+  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(
+      (const E*)a.q, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part);
+  attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
+                                                                                a.n_splits * 4, (E*)a.out);
+}
+
+void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st) {
+  const int hd = a.geom.head_dim;
+  if (bf16) {
+    if (hd == 128) launch_attention_t<bf16_t, 128>(a, st);
+    else launch_attention_t<bf16_t, 64>(a, st);
+  } else {
+    if (hd == 128) launch_attention_t<float, 128>(a, st);
+    else launch_attention_t<float, 64>(a, st);
+  }
+}
+
+}  // namespace dinfer

@@ -1,0 +1,96 @@
+// Shared device helpers of the dinfer HIP library (gfx950 only): element types, MFMA wrappers,
+// wave-level reductions, and the structs passed from the host side to the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dinfer {
+
+typedef __bf16 bf16_t;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int WAVE = 64;
+constexpr int TILE = 32;        // features per weight tile = tokens per token tile (32x32 MFMA)
+constexpr int PAGE = 16;        // tokens per KV page
+constexpr int MAX_SEQS = 64;
+constexpr int MAX_TOPK = 8;
+constexpr int MAX_EXPERTS = 64;
+
+// Per element type: G = elements in one 16-byte lane chunk; one MFMA k-step covers KS = 2*G input features.
+template <typename E> struct ET;
+template <> struct ET<float> {
+  static constexpr int G = 4, KS = 8;
+  typedef f32x4 vec;
+};
+template <> struct ET<bf16_t> {
+  static constexpr int G = 8, KS = 16;
+  typedef bf16x8 vec;
+};
+
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return (float)v; }
+template <typename E> __device__ inline E from_f32(float v);
+template <> __device__ inline float from_f32<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }   // round to nearest even
+
+// acc[32 x 32] += A[32 x KS] * B[KS x 32].  Lane l supplies row (A) / column (B) l%32 and the G consecutive
+// k values that start at (l/32)*G; result: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4.
+__device__ inline void mfma32(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+}
+__device__ inline void mfma32(f32x16& acc, const f32x4& a, const f32x4& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
+}
+
+// Row of accumulator register v within the 32-row tile, for a lane in half `half` (= lane / 32).
+__device__ inline int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+template <typename E> __device__ inline typename ET<E>::vec load16(const E* p) {
+  return *reinterpret_cast<const typename ET<E>::vec*>(p);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+// Which sequence a forward's packed tokens belong to: sequence s owns tokens [off[s], off[s+1]).
+struct SeqSpan {
+  int32_t n_seq;
+  int32_t off[MAX_SEQS + 1];
+};
+
+// Where the KV pool keeps things.  Pool: [layer][page][K|V][head][PAGE*head_dim] elements.
+// K part of a (page, head): [slot][head_dim]; V part: [head_dim][slot] (transposed, so that the PV product
+// finds the keys of one page contiguous per feature).
+struct KvGeom {
+  int64_t layer_stride;   // elements
+  int64_t page_stride;    // elements = 2 * n_heads * PAGE * head_dim
+  int32_t n_heads, head_dim;
+  int32_t n_pages;
+};
+// Page ids come from the caller's page table: keep every access inside the pool whatever they hold.
+__device__ inline int safe_page(const KvGeom& g, int id) { return min(max(id, 0), g.n_pages - 1); }
+__device__ inline int64_t kv_k_index(const KvGeom& g, int page, int head, int slot, int d) {
+  return (int64_t)page * g.page_stride + ((int64_t)head * PAGE + slot) * g.head_dim + d;
+}
+__device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int slot, int d) {
+  return (int64_t)page * g.page_stride + (int64_t)g.n_heads * PAGE * g.head_dim +
+         ((int64_t)head * g.head_dim + d) * PAGE + slot;
+}
+
+}  // namespace dinfer

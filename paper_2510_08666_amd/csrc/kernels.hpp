@@ -1,0 +1,103 @@
+// Host-callable launchers of the dinfer kernels.  Every launcher only enqueues work on `st`; none waits.
+// `bf16` selects the element type (false: float32) of weights, activations fed to the MFMAs and the KV pool.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.hpp"
+
+namespace dinfer {
+
+// ---- weight packing (pack.hip) ----
+enum PackMode { PACK_ADJACENT = 0, PACK_ROPE_PAIR = 1, PACK_HALF0 = 2, PACK_HALF1 = 3 };
+// src: [batch][N][K] row-major; dst: [batch][n_tasks][K/KS][2][64][16 B]
+void launch_pack(bool bf16, const void* src, void* dst, int batch, int N, int K, int n_tasks, int mode,
+                 int head_dim, hipStream_t st);
+int64_t packed_bytes(bool bf16, int n_tasks, int K);
+
+// ---- forward pieces ----
+struct FwdMeta {            // device arrays describing the tokens of one forward
+  const int32_t* tok_seq;   // [T]
+  const int32_t* tok_pos;   // [T] absolute position
+  const int32_t* seq_nkeys; // [n_seq] keys visible to the sequence = base + its tokens in this forward
+  const int32_t* qtile;     // [n_qtiles][3]: sequence, first packed token, valid rows
+};
+
+void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st);
+void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
+                 int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
+void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
+                       int H, int V, float* x, void* h, hipStream_t st);
+void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
+                         int top_k, const float* gain, float eps, int T, int H, void* h, hipStream_t st);
+
+struct QkvArgs {
+  const void* w;            // packed fused QKV
+  const void* h;            // [T][H]
+  void* q;                  // [T][D]
+  void* kv_layer;           // pool base of this layer
+  KvGeom geom;
+  FwdMeta meta;
+  const int32_t* page_table;
+  int pt_stride;
+  const float* cos_tab;
+  const float* sin_tab;
+  int T, H;
+};
+void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st);
+
+struct AttnArgs {
+  const void* q;            // [T][D]
+  const void* kv_layer;
+  KvGeom geom;
+  FwdMeta meta;
+  const int32_t* page_table;
+  int pt_stride;
+  int n_qtiles, n_splits;
+  float* part;              // partial results, see attention.hip
+  void* out;                // [T][D]
+};
+size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim);
+void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
+
+void launch_oproj(bool bf16, const void* w, const void* a, float* x, int T, int D, int H, hipStream_t st);
+void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
+                   int E, int top_k, int norm_topk, void* h, int32_t* topk_idx, float* topk_w, hipStream_t st);
+void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
+                    int32_t* pos_of_pair, hipStream_t st);
+
+struct ExpertArgs {
+  const void* w_gate_up;    // packed [E][I/32 tasks]
+  const void* w_down;       // packed [E][H/64 tasks]
+  const void* h;            // [T][H]
+  void* y;                  // [T*k][I]
+  float* o;                 // [T*k][H]
+  const int32_t* cnt;
+  const int32_t* off;
+  const int32_t* perm;
+  int T, H, I, E, top_k;
+};
+void launch_experts(bool bf16, const ExpertArgs& a, hipStream_t st);
+
+struct LmArgs {
+  const void* w;            // packed LM head
+  const void* h;            // [T][H]
+  int T, H, V;
+  float scale;
+  float* part;              // [n_lm_waves][T][4]: max, sum-exp, argmax bits, unused
+  int n_lm_waves;
+  float* logits_out;        // debug: [T][V] or null
+};
+int lm_head_waves(int V);
+void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);
+void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st);
+void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
+                   uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, hipStream_t st);
+void launch_add_i32(int32_t* a, int n, int v, hipStream_t st);
+
+void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,
+                    int n_pos, float* k, float* v, hipStream_t st);
+
+void configure_kernels();   // one-time function attributes (dynamic LDS limits)
+
+}  // namespace dinfer

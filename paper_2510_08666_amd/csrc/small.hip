@@ -1,0 +1,387 @@
+// The non-GEMM kernels of the step: token bookkeeping, embedding + RMSNorm, expert-output combine + RMSNorm,
+// router (softmax + top-k), ballot-based token->expert permutation, LM-head partial merge, threshold commit,
+// and the KV import / export used by tests.
+#include "kernels.hpp"
+
+namespace dinfer {
+
+// ---------------------------------------------------------------- rotary table
+// cos / sin of pos * theta^(-2j/hd), computed in double on the device and stored as float.
+__global__ void rope_table_kernel(float* __restrict__ cos_tab, float* __restrict__ sin_tab, int max_pos, int head_dim,
+                                  float theta) {
+  const int half = head_dim / 2;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)max_pos * half) return;
+  const int pos = (int)(i / half), j = (int)(i % half);
+  const double ang = (double)pos * pow((double)theta, -2.0 * j / head_dim);
+  cos_tab[i] = (float)cos(ang);
+  sin_tab[i] = (float)sin(ang);
+}
+void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st) {
+  const int64_t n = (int64_t)max_pos * (head_dim / 2);
+  rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(cos_tab, sin_tab, max_pos, head_dim, theta);
+}
+
+// ---------------------------------------------------------------- token bookkeeping
+// `limit` = positions a sequence may use (rotary table and page-table row); a prefix length that would
+// leave it is pulled back so that no later kernel indexes outside its buffers.
+__global__ void meta_kernel(SeqSpan span, const int32_t* __restrict__ d_base, int limit, int32_t* __restrict__ tok_seq,
+                            int32_t* __restrict__ tok_pos, int32_t* __restrict__ seq_nkeys,
+                            int32_t* __restrict__ qtile) {
+  for (int s = 0; s < span.n_seq; ++s) {
+    const int o = span.off[s], len = span.off[s + 1] - o;
+    const int base = d_base ? max(0, min(d_base[s], limit - len)) : 0;
+    for (int i = threadIdx.x; i < len; i += blockDim.x) {
+      tok_seq[o + i] = s;
+      tok_pos[o + i] = base + i;
+    }
+    if (threadIdx.x == 0) seq_nkeys[s] = base + len;
+  }
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int s = 0; s < span.n_seq; ++s) {
+      const int o = span.off[s], len = span.off[s + 1] - o;
+      for (int i = 0; i < len; i += TILE) {
+        qtile[n * 3 + 0] = s;
+        qtile[n * 3 + 1] = o + i;
+        qtile[n * 3 + 2] = min(TILE, len - i);
+        ++n;
+      }
+    }
+  }
+}
+void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
+                 int32_t* seq_nkeys, int32_t* qtile, hipStream_t st) {
+  meta_kernel<<<1, 256, 0, st>>>(span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile);
+}
+
+// ---------------------------------------------------------------- RMSNorm helpers
+constexpr int NORM_THREADS = 256;
+constexpr int NORM_MAX_PER_THREAD = 16;   // hidden <= 4096
+
+__device__ inline float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) sh[wave] = v;
+  __syncthreads();
+  const float r = sh[0] + sh[1] + sh[2] + sh[3];
+  __syncthreads();
+  return r;
+}
+
+// x[t] = emb[token[t]];  h[t] = RMSNorm(x[t]) * gain
+template <typename E>
+__global__ __launch_bounds__(NORM_THREADS) void embed_norm_kernel(const int32_t* __restrict__ tokens,
+                                                                  const E* __restrict__ emb,
+                                                                  const float* __restrict__ gain, float eps, int H,
+                                                                  int V, float* __restrict__ x, E* __restrict__ h) {
+  __shared__ float sh[4];
+  const int t = blockIdx.x;
+  const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
+  float v[NORM_MAX_PER_THREAD];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    v[i] = c < H ? to_f32(row[c]) : 0.f;
+    ss += v[i] * v[i];
+  }
+  ss = block_sum_256(ss, sh);
+  const float r = rsqrtf(ss / H + eps);
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    if (c < H) {
+      x[(int64_t)t * H + c] = v[i];
+      h[(int64_t)t * H + c] = from_f32<E>(v[i] * r * gain[c]);
+    }
+  }
+}
+void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
+                       int H, int V, float* x, void* h, hipStream_t st) {
+  if (bf16) embed_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, gain, eps, H, V, x, (bf16_t*)h);
+  else embed_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, gain, eps, H, V, x, (float*)h);
+}
+
+// x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  h[t] = RMSNorm(x[t]) * gain
+template <typename E>
+__global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __restrict__ x, const float* __restrict__ O,
+                                                                    const int32_t* __restrict__ pos_of_pair,
+                                                                    const float* __restrict__ topk_w, int top_k,
+                                                                    const float* __restrict__ gain, float eps, int H,
+                                                                    E* __restrict__ h) {
+  __shared__ float sh[4];
+  const int t = blockIdx.x;
+  float v[NORM_MAX_PER_THREAD];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    float acc = 0.f;
+    if (c < H) {
+      for (int j = 0; j < top_k; ++j)
+        acc += topk_w[t * top_k + j] * O[(int64_t)pos_of_pair[t * top_k + j] * H + c];
+      acc += x[(int64_t)t * H + c];
+    }
+    v[i] = acc;
+    ss += acc * acc;
+  }
+  ss = block_sum_256(ss, sh);
+  const float r = rsqrtf(ss / H + eps);
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    if (c < H) {
+      x[(int64_t)t * H + c] = v[i];
+      h[(int64_t)t * H + c] = from_f32<E>(v[i] * r * gain[c]);
+    }
+  }
+}
+void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
+                         int top_k, const float* gain, float eps, int T, int H, void* h, hipStream_t st) {
+  if (bf16) combine_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (bf16_t*)h);
+  else combine_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (float*)h);
+}
+
+// ---------------------------------------------------------------- router
+// h[t] = RMSNorm(x[t]) * gain (stored for the expert GEMMs); router logits from the unrounded float h;
+// softmax over the experts; the top_k largest probabilities, ties to the lower expert id.
+template <typename E>
+__global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                              float eps, const E* __restrict__ Wr, int H, int n_exp,
+                                                              int top_k, int norm_topk, E* __restrict__ h,
+                                                              int32_t* __restrict__ topk_idx,
+                                                              float* __restrict__ topk_w) {
+  __shared__ float sh[4];
+  __shared__ float hn[NORM_THREADS * NORM_MAX_PER_THREAD];
+  __shared__ float logit[MAX_EXPERTS];
+  const int t = blockIdx.x;
+  float v[NORM_MAX_PER_THREAD];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    v[i] = c < H ? x[(int64_t)t * H + c] : 0.f;
+    ss += v[i] * v[i];
+  }
+  ss = block_sum_256(ss, sh);
+  const float r = rsqrtf(ss / H + eps);
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
+    const int c = threadIdx.x + i * NORM_THREADS;
+    if (c < H) {
+      const float y = v[i] * r * gain[c];
+      hn[c] = y;
+      h[(int64_t)t * H + c] = from_f32<E>(y);
+    }
+  }
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int e = wave; e < n_exp; e += 4) {
+    const E* w = Wr + (int64_t)e * H;
+    float acc = 0.f;
+    for (int c = lane; c < H; c += WAVE) acc += hn[c] * to_f32(w[c]);
+    acc = wave_sum(acc);
+    if (lane == 0) logit[e] = acc;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  const float z = lane < n_exp ? logit[lane] : -INFINITY;
+  const float m = wave_max(z);
+  const float ex = lane < n_exp ? expf(z - m) : 0.f;
+  const float p = ex / wave_sum(ex);
+  float val = lane < n_exp ? p : -1.f;
+  float wsel = 0.f, sel_sum = 0.f;    // lane j keeps the j-th selection
+  int isel = 0;
+  for (int j = 0; j < top_k; ++j) {
+    const float best = wave_max(val);
+    const uint64_t hit = __ballot(val == best);
+    const int winner = __ffsll((unsigned long long)hit) - 1;
+    if (lane == j) {
+      wsel = best;
+      isel = winner;
+    }
+    if (lane == winner) val = -1.f;
+    sel_sum += best;
+  }
+  if (lane < top_k) {
+    topk_idx[t * top_k + lane] = isel;
+    topk_w[t * top_k + lane] = norm_topk ? wsel / sel_sum : wsel;
+  }
+}
+void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
+                   int E, int top_k, int norm_topk, void* h, int32_t* topk_idx, float* topk_w, hipStream_t st) {
+  if (bf16) router_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const bf16_t*)w_router, H, E, top_k, norm_topk, (bf16_t*)h, topk_idx, topk_w);
+  else router_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const float*)w_router, H, E, top_k, norm_topk, (float*)h, topk_idx, topk_w);
+}
+
+// ---------------------------------------------------------------- token -> expert permutation
+// Stable counting sort of the n_pairs (token, slot) pairs by expert with wavefront ballots: for expert e,
+// the pairs are scanned 64 at a time; the ballot of "routed to e" gives the count (popcount) and, through
+// the bits below a lane, the stable rank of that lane's pair.
+__global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ expert_of_pair, int n_pairs,
+                                                        int n_exp, int32_t* __restrict__ cnt, int32_t* __restrict__ off,
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair) {
+  __shared__ int32_t s_cnt[MAX_EXPERTS], s_off[MAX_EXPERTS + 1];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  for (int e = wave; e < n_exp; e += n_waves) {
+    int c = 0;
+    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
+      const int p = p0 + lane;
+      c += __popcll(__ballot(p < n_pairs && expert_of_pair[p] == e));
+    }
+    if (lane == 0) s_cnt[e] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < n_exp; ++e) {
+      s_off[e] = run;
+      run += s_cnt[e];
+    }
+    s_off[n_exp] = run;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < n_exp; e += blockDim.x) cnt[e] = s_cnt[e];
+  for (int e = threadIdx.x; e <= n_exp; e += blockDim.x) off[e] = s_off[e];
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int e = wave; e < n_exp; e += n_waves) {
+    int run = s_off[e];
+    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
+      const int p = p0 + lane;
+      const bool mine = p < n_pairs && expert_of_pair[p] == e;
+      const uint64_t b = __ballot(mine);
+      if (mine) {
+        const int r = run + __popcll(b & below);
+        perm[r] = p;
+        pos_of_pair[p] = r;
+      }
+      run += __popcll(b);
+    }
+  }
+}
+void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
+                    int32_t* pos_of_pair, hipStream_t st) {
+  permute_kernel<<<1, 1024, 0, st>>>(topk_idx, n_pairs, E, cnt, off, perm, pos_of_pair);
+}
+
+// ---------------------------------------------------------------- LM-head partial merge
+// (max, sum-exp, id) partials combine associatively: the larger max wins (lower id on equal max) and the
+// sums are rescaled to it.  One workgroup per token row, fixed tree -> deterministic.
+struct LmStat {
+  float m, s;
+  int id;
+};
+__device__ inline LmStat lm_combine(LmStat a, LmStat b) {
+  if (b.m > a.m || (b.m == a.m && b.id < a.id)) {
+    const LmStat t = a;
+    a = b;
+    b = t;
+  }
+  if (b.m > -INFINITY) a.s += b.s * __expf(b.m - a.m);
+  return a;
+}
+__global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__ part, int n_waves, int T,
+                                                        float* __restrict__ conf, int32_t* __restrict__ argmax) {
+  __shared__ LmStat sh[4];
+  const int t = blockIdx.x;
+  LmStat a{-INFINITY, 0.f, 0x7fffffff};
+  for (int w = threadIdx.x; w < n_waves; w += 256) {
+    const float* p = part + ((int64_t)w * T + t) * 4;
+    a = lm_combine(a, LmStat{p[0], p[1], __float_as_int(p[2])});
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    LmStat b{__shfl_xor(a.m, o, WAVE), __shfl_xor(a.s, o, WAVE), __shfl_xor(a.id, o, WAVE)};
+    a = lm_combine(a, b);
+  }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = lm_combine(lm_combine(sh[0], sh[1]), lm_combine(sh[2], sh[3]));
+    conf[t] = 1.f / a.s;
+    argmax[t] = a.id;
+  }
+}
+void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st) {
+  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax);
+}
+
+// ---------------------------------------------------------------- decoder: threshold commit
+// One wavefront per sequence, lane = block position.  The set of lanes to commit is a 64-bit ballot.
+__global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ conf, const int32_t* __restrict__ argmax,
+                                                     int block_len, int32_t* __restrict__ tokens,
+                                                     uint64_t* __restrict__ mask, float threshold, int fixed_k,
+                                                     int32_t* __restrict__ n_committed) {
+  const int s = blockIdx.x, lane = threadIdx.x;
+  const uint64_t old = mask[s];
+  const bool masked = lane < block_len && ((old >> lane) & 1ull);
+  const float c = lane < block_len ? conf[s * block_len + lane] : -1.f;
+  uint64_t sel = 0;
+  if (fixed_k > 0) {
+    float val = masked ? c : -1.f;
+    for (int r = 0; r < fixed_k; ++r) {
+      const float best = wave_max(val);
+      if (best < 0.f) break;                       // nothing left
+      const uint64_t hit = __ballot(val == best);
+      const int winner = __ffsll((unsigned long long)hit) - 1;
+      sel |= 1ull << winner;
+      if (lane == winner) val = -1.f;
+    }
+  } else {
+    sel = __ballot(masked && c >= threshold);
+    if (sel == 0 && old != 0) {
+      const float val = masked ? c : -1.f;
+      const float best = wave_max(val);
+      const uint64_t hit = __ballot(masked && val == best);
+      if (hit) sel = 1ull << (__ffsll((unsigned long long)hit) - 1);
+    }
+  }
+  if ((sel >> lane) & 1ull) tokens[s * block_len + lane] = argmax[s * block_len + lane];
+  if (lane == 0) {
+    mask[s] = old & ~sel;
+    n_committed[s] = __popcll(sel);
+  }
+}
+void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
+                   uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, hipStream_t st) {
+  commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, tokens, mask, threshold, fixed_k, n_committed);
+}
+
+__global__ void add_i32_kernel(int32_t* a, int n, int v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) a[i] += v;
+}
+void launch_add_i32(int32_t* a, int n, int v, hipStream_t st) {
+  add_i32_kernel<<<(n + 63) / 64, 64, 0, st>>>(a, n, v);
+}
+
+// ---------------------------------------------------------------- KV import / export (tests)
+template <typename E>
+__global__ void kv_copy_kernel(bool to_pool, E* __restrict__ kv_layer, KvGeom geom, const int32_t* __restrict__ page_row,
+                               int first_pos, int n_pos, float* __restrict__ k, float* __restrict__ v) {
+  const int D = geom.n_heads * geom.head_dim;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n_pos * D) return;
+  const int r = (int)(i / D), f = (int)(i % D);
+  const int pos = first_pos + r;
+  const int page = safe_page(geom, page_row[pos / PAGE]), slot = pos % PAGE;
+  const int64_t ki = kv_k_index(geom, page, f / geom.head_dim, slot, f % geom.head_dim);
+  const int64_t vi = kv_v_index(geom, page, f / geom.head_dim, slot, f % geom.head_dim);
+  if (to_pool) {
+    kv_layer[ki] = from_f32<E>(k[i]);
+    kv_layer[vi] = from_f32<E>(v[i]);
+  } else {
+    k[i] = to_f32(kv_layer[ki]);
+    v[i] = to_f32(kv_layer[vi]);
+  }
+}
+void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,
+                    int n_pos, float* k, float* v, hipStream_t st) {
+  const int64_t n = (int64_t)n_pos * geom.n_heads * geom.head_dim;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (bf16) kv_copy_kernel<bf16_t><<<blocks, 256, 0, st>>>(to_pool, (bf16_t*)kv_layer, geom, page_row, first_pos, n_pos, k, v);
+  else kv_copy_kernel<float><<<blocks, 256, 0, st>>>(to_pool, (float*)kv_layer, geom, page_row, first_pos, n_pos, k, v);
+}
+
+}  // namespace dinfer

@@ -1,0 +1,255 @@
+"""Shared plumbing of the GPU parity tests, the smoke check and the benchmark's baseline leg: run the same
+seeded workload through the CPU oracle and through the HIP library, and compare under the stated bars.
+
+Bars (block-denoising benchmark statement): committed ids and positions bit-exact except at positions
+flagged as within `tau_margin` of the threshold or at an arg-max / most-confident near-tie; logits within
+relative `logit_rel` of the row's largest |logit|; confidences within absolute `conf_abs`.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+import dinfer_inputs as di
+import oracle
+
+
+@dataclass
+class Bars:
+    logit_rel: float
+    conf_abs: float
+    conf_rel: float      # extra, tighter than the stated bar when confidences are tiny
+    tau_margin: float
+    kv_abs: float
+    router_rel: float    # two router probabilities closer than this (relative) count as a near-tie
+
+
+def bars_for(cfg):
+    if cfg.dtype == "f32":
+        # float32 kernels against the float64 oracle: rounding only
+        return Bars(logit_rel=2e-4, conf_abs=2e-5, conf_rel=2e-3, tau_margin=1e-4, kv_abs=1e-4, router_rel=1e-4)
+    # bf16 inputs, float32 accumulation
+    return Bars(logit_rel=2e-2, conf_abs=1e-3, conf_rel=8e-2, tau_margin=1e-3, kv_abs=3e-2, router_rel=5e-2)
+
+
+class OracleRun:
+    """Oracle state of a workload: one KV cache per sequence, prefilled from the prompt."""
+
+    def __init__(self, cfg, weights, inp, cap):
+        self.o = oracle.Oracle(cfg, weights)
+        self.cfg, self.inp = cfg, inp
+        self.caches = []
+        for s, toks in enumerate(inp.prefix_tokens):
+            kc, vc = self.o.new_cache(cap)
+            if len(toks):
+                self.o.forward(toks, 0, kc, vc)
+            self.caches.append((kc, vc))
+
+    def step(self, s, tokens, mask, prefix_len, threshold, fixed_k=0, want_logits=False, trace=None):
+        kc, vc = self.caches[s]
+        return self.o.step(tokens, mask, prefix_len, kc, vc, threshold, fixed_k, want_logits, trace)
+
+    def step_following(self, s, tokens, mask, prefix_len, threshold, fixed_k, gpu_routing, bars, want_logits=True):
+        """The oracle's step with the expert sets the HIP path chose (gpu_routing: [L][S][k]).  The top-k of
+        the router is a discrete decision on floating-point values: where the oracle's own probabilities put
+        the k-th and (k+1)-th within `router_rel`, either set is valid and the oracle follows the GPU so that
+        the rest of the forward stays comparable; anywhere else the sets must be equal.  Returns
+        (step result, number of (layer, token) routings that were near-ties)."""
+        tr = oracle.Trace(self.cfg, len(tokens), forced_idx=gpu_routing)
+        ref = self.step(s, tokens, mask, prefix_len, threshold, fixed_k, want_logits, tr)
+        return ref, check_routing(tr, gpu_routing, self.cfg.top_k, bars)
+
+    def forward_following(self, s, tokens, prefix_len, gpu_routing, bars):
+        """A forward without decoder (prefill, or the refresh of a decoded block) that follows the GPU's
+        expert sets through router near-ties, as step_following does.  Writes K,V into sequence s's cache."""
+        kc, vc = self.caches[s]
+        tr = oracle.Trace(self.cfg, len(tokens), forced_idx=gpu_routing)
+        self.o.forward(tokens, prefix_len, kc, vc, tr)
+        return check_routing(tr, gpu_routing, self.cfg.top_k, bars)
+
+
+class GpuRun:
+    """The HIP library on the same workload.  Imports torch / the binding lazily (GPU machine only)."""
+
+    def __init__(self, cfg, weights, inp, max_tokens, max_pos):
+        import torch
+        from paper_2510_08666_amd import binding
+        self.torch, self.binding = torch, binding
+        self.cfg, self.inp = cfg, inp
+        self.dev = torch.device("cuda:0")
+        self.ctx = binding.Context(cfg, inp.n_pages, max(1, len(inp.prefix_tokens)), max_tokens, max_pos)
+        self.ctx.load_weights(weights)
+        self.page_table = torch.from_numpy(inp.page_table).to(self.dev)
+        self.prefix_len = torch.from_numpy(inp.prefix_len.astype(np.int32)).to(self.dev)
+        self.tokens = torch.from_numpy(inp.block_tokens.copy()).to(self.dev)
+        self.mask = torch.from_numpy(inp.mask_bits.view(np.int64).copy()).to(self.dev)
+        ns, S = inp.block_tokens.shape
+        self.conf = torch.zeros((ns, S), dtype=torch.float32, device=self.dev)
+        self.argmax = torch.zeros((ns, S), dtype=torch.int32, device=self.dev)
+        self.n_committed = torch.zeros(ns, dtype=torch.int32, device=self.dev)
+
+    def prefill(self):
+        torch = self.torch
+        toks = torch.from_numpy(np.concatenate(self.inp.prefix_tokens).astype(np.int32)).to(self.dev)
+        self.ctx.prefill(toks, [len(t) for t in self.inp.prefix_tokens], self.page_table)
+
+    def inject_prefix(self, caches):
+        """Write the oracle's prefix K,V into the pool, so that a step is judged apart from prefill error."""
+        torch = self.torch
+        for s, (kc, vc) in enumerate(caches):
+            P = int(self.inp.prefix_len[s])
+            if P == 0:
+                continue
+            for l in range(self.cfg.n_layers):
+                k = torch.from_numpy(kc[l, :P].astype(np.float32)).to(self.dev)
+                v = torch.from_numpy(vc[l, :P].astype(np.float32)).to(self.dev)
+                self.ctx.kv_write(l, self.page_table[s], 0, k, v)
+        torch.cuda.synchronize()
+
+    def read_kv(self, s, layer, first, n):
+        k, v = self.ctx.kv_read(layer, self.page_table[s], first, n)
+        return k.cpu().numpy(), v.cpu().numpy()
+
+    def set_state(self, tokens, masks, prefix_len=None):
+        torch = self.torch
+        self.tokens.copy_(torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)))
+        self.mask.copy_(torch.from_numpy(np.asarray(masks, dtype=np.uint64).view(np.int64)))
+        if prefix_len is not None:
+            self.prefix_len.copy_(torch.from_numpy(np.asarray(prefix_len, dtype=np.int32)))
+
+    def step(self, threshold, fixed_k=0):
+        self.ctx.step(self.tokens, self.mask, self.prefix_len, self.page_table, threshold, fixed_k, self.conf,
+                      self.argmax, self.n_committed)
+        self.torch.cuda.synchronize()
+        return self.state()
+
+    def state(self):
+        return dict(tokens=self.tokens.cpu().numpy(), mask=self.mask.cpu().numpy().view(np.uint64),
+                    conf=self.conf.cpu().numpy(), argmax=self.argmax.cpu().numpy(),
+                    n_committed=self.n_committed.cpu().numpy())
+
+    def routing(self, T=None):
+        """Expert ids of every layer of the last forward: [L][T][k]."""
+        T = self.tokens.numel() if T is None else T
+        shape = (self.cfg.n_layers, T, self.cfg.top_k)
+        out = self.ctx.debug_get(1, shape, self.torch.int32)
+        self.torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def logits(self, n_rows):
+        out = self.ctx.debug_logits(n_rows)
+        self.torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def refresh(self):
+        self.ctx.refresh_block(self.tokens, self.prefix_len, self.page_table)
+        self.torch.cuda.synchronize()
+
+    def generate_block(self, threshold, fixed_k, max_steps, masked_hint=0):
+        steps = self.ctx.generate_block(self.tokens, self.mask, self.prefix_len, self.page_table, threshold, fixed_k,
+                                        self.conf, self.argmax, self.n_committed, max_steps, masked_hint)
+        self.torch.cuda.synchronize()
+        return steps
+
+    def close(self):
+        self.ctx.close()
+
+
+def check_routing(trace, gpu_routing, top_k, bars):
+    """Every expert the GPU chose that the oracle did not (and vice versa) must sit within router_rel of the
+    oracle's k-th largest probability.  Returns how many (layer, token) routings differed."""
+    flagged = 0
+    L, T, _ = gpu_routing.shape
+    for l in range(L):
+        for t in range(T):
+            mine, theirs = set(trace.topk_idx[l, t].tolist()), set(gpu_routing[l, t].tolist())
+            assert len(theirs) == top_k, "GPU routing repeats an expert at layer %d token %d" % (l, t)
+            if mine == theirs:
+                continue
+            p = trace.router_p[l, t]
+            kth = np.sort(p)[::-1][top_k - 1]
+            for e in mine ^ theirs:
+                assert abs(p[e] - kth) <= bars.router_rel * kth, \
+                    "routing differs beyond a near-tie at layer %d token %d expert %d" % (l, t, e)
+            flagged += 1
+    return flagged
+
+
+def max_abs_err(got, ref):
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max()) if np.size(ref) else 0.0
+
+
+def compare_logits(ref, got, bars):
+    """Per row: max |got - ref| <= logit_rel * max(max |ref|, 1e-3).  Returns the worst ratio error/allowed."""
+    worst = 0.0
+    for i in range(ref.shape[0]):
+        allowed = bars.logit_rel * max(np.abs(ref[i]).max(), 1e-3)
+        err = np.abs(got[i].astype(np.float64) - ref[i]).max()
+        worst = max(worst, err / allowed)
+    assert worst <= 1.0, "logits off by %.3g x the allowed error" % worst
+    return worst
+
+
+def compare_step(ref, got_tokens, got_mask, got_conf, got_argmax, got_n, old_tokens, old_mask, threshold, fixed_k,
+                 bars, ref_logits=None):
+    """One sequence, one step.  ref: the oracle's step result.  Returns dict(flagged=..., conf_err=...).
+
+    Positions are flagged (and excused from bit-exactness) when the oracle's own numbers leave the decision
+    within the error bars: confidence within tau_margin of the threshold; the position GPU chose as most
+    confident within 2*conf tolerance of the oracle's best; an arg max whose oracle logit is within the logit
+    bar of the oracle's top logit."""
+    S = len(ref["conf"])
+    old_mask, got_mask = int(old_mask), int(got_mask)
+    masked = [i for i in range(S) if (old_mask >> i) & 1]
+    conf_o, conf_g = ref["conf"], got_conf.astype(np.float64)
+    ctol = np.minimum(bars.conf_abs, bars.conf_rel * np.maximum(conf_o, 1e-30))
+    cerr = np.abs(conf_g - conf_o)
+    assert np.all(cerr <= ctol), "confidence error %.3g (allowed %.3g) at %d" % (
+        cerr.max(), ctol[int(np.argmax(cerr / ctol))], int(np.argmax(cerr / ctol)))
+    flagged = set()
+    # candidate ids
+    for i in range(S):
+        if got_argmax[i] != ref["argmax"][i]:
+            assert ref_logits is not None, "arg max differs at %d and no logits to judge a tie" % i
+            gap = ref_logits[i, ref["argmax"][i]] - ref_logits[i, got_argmax[i]]
+            allowed = 2 * bars.logit_rel * max(np.abs(ref_logits[i]).max(), 1e-3)
+            assert gap <= allowed, "arg max differs at %d beyond a near-tie (gap %.3g)" % (i, gap)
+            flagged.add(i)
+    # structural invariants that hold whatever the numbers are
+    assert got_mask & ~old_mask == 0, "a decided position returned to the mask"
+    sel_g = old_mask & ~got_mask
+    sel_o = old_mask & ~ref["mask"]
+    assert bin(sel_g).count("1") == int(got_n)
+    assert (int(got_n) >= 1) == (old_mask != 0), "a step with masked positions must commit at least one"
+    for i in range(S):
+        if (sel_g >> i) & 1:
+            assert got_tokens[i] == got_argmax[i]
+        else:
+            assert got_tokens[i] == old_tokens[i], "an uncommitted position changed"
+    # which positions
+    if sel_g != sel_o:
+        if fixed_k > 0:
+            # the k-th and (k+1)-th confidences may be a near-tie
+            kth = sorted((conf_o[i] for i in masked), reverse=True)[min(fixed_k, len(masked)) - 1]
+            near = {i for i in masked if abs(conf_o[i] - kth) <= 2 * ctol[i]}
+        else:
+            margin = min(bars.tau_margin, bars.conf_rel * threshold)
+            near = {i for i in masked if abs(conf_o[i] - threshold) <= margin + ctol[i]}
+            if not any(conf_o[i] >= threshold + margin for i in masked):
+                best = max(conf_o[i] for i in masked)
+                near |= {i for i in masked if best - conf_o[i] <= 2 * ctol[i]}
+        diff = {i for i in range(S) if ((sel_g ^ sel_o) >> i) & 1}
+        assert diff <= near, "commit sets differ outside flagged positions: %s (flagged %s)" % (sorted(diff), sorted(near))
+        flagged |= diff
+    for i in range(S):
+        if (sel_g >> i) & 1 and (sel_o >> i) & 1 and i not in flagged:
+            assert got_tokens[i] == ref["tokens"][i]
+    return dict(flagged=sorted(flagged), conf_err=float(cerr.max()), conf_rel_err=float((cerr / conf_o).max()))
+
+
+def make_case(wl, seed=None, room=None, cfg=None):
+    """Weights + inputs of a workload (optionally with a modified model config of the same shapes)."""
+    cfg = cfg or wl.model
+    seed = di.BASE_SEED + wl.seed_index if seed is None else seed
+    weights = di.make_weights(cfg, seed)
+    inp = di.make_workload_inputs(wl, seed, room)
+    return cfg, weights, inp

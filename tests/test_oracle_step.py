@@ -232,3 +232,22 @@ def test_a_sequence_does_not_depend_on_cache_capacity_or_other_rows(tiny):
     a = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, big_k, big_v, 0.15)
     b = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, kc.copy(), vc.copy(), 0.15)
     assert np.array_equal(a["conf"], b["conf"]) and a["mask"] == b["mask"]
+
+
+def test_forced_routing_equal_to_own_choice_changes_nothing_and_other_choice_is_used(tiny):
+    wl, cfg, w, inp, o, kc, vc = tiny
+    free = oracle.Trace(cfg, 32)
+    a = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, kc.copy(), vc.copy(), 0.9, want_logits=True, trace=free)
+    same = oracle.Trace(cfg, 32, forced_idx=free.topk_idx)
+    b = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, kc.copy(), vc.copy(), 0.9, want_logits=True, trace=same)
+    assert np.array_equal(a["logits"], b["logits"])
+    assert np.allclose(free.router_p.sum(-1), 1.0, atol=1e-12)
+    other = free.topk_idx.copy()
+    other[1, 5] = [(other[1, 5, 0] + 3) % cfg.n_experts, (other[1, 5, 0] + 4) % cfg.n_experts]
+    tr = oracle.Trace(cfg, 32, forced_idx=other)
+    c = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, kc.copy(), vc.copy(), 0.9, want_logits=True, trace=tr)
+    assert not np.allclose(c["logits"][5], a["logits"][5]) and np.array_equal(tr.topk_idx[0], free.topk_idx[0])
+    # forcing the oracle's own sets in another order leaves the mixture (a sum) unchanged up to rounding
+    swapped = oracle.Trace(cfg, 32, forced_idx=free.topk_idx[:, :, ::-1])
+    d = o.step(inp.block_tokens[0], int(inp.mask_bits[0]), 64, kc.copy(), vc.copy(), 0.9, want_logits=True, trace=swapped)
+    assert np.allclose(d["logits"], a["logits"], atol=1e-11)
