@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-denoising step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4]
+
+A "step" is one dinfer_step: the whole hot path (embedding, 16 transformer layers with paged non-causal
+attention and the routed-expert grouped GEMMs, LM head fused with the confidence reduction, threshold
+commit) over one batch of synthetic input.  Default workload: the LLaDA-MoE-shaped batch-1 step (512-token
+cached prefix, 32-position fully masked block, threshold 0.9, bf16 random-init weights).  Every timed step
+starts from the same token / mask state, restored by two small device copies inside the timed region.
+Inputs are resident in HBM before timing starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def step_bytes(cfg, n_tok, prefix_lens, block_len, experts_touched_per_layer):
+    """Algorithmic HBM bytes of one step: every weight byte the step needs once, the KV it reads and writes.
+    Returns (total, per-stage dict per layer-summed)."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    H, D, I, E, V, L = cfg.hidden, cfg.qkv_dim, cfg.moe_inter, cfg.n_experts, cfg.vocab, cfg.n_layers
+    qkv = L * 3 * D * H * es
+    oproj = L * H * D * es
+    router = L * E * H * es
+    gate_up = sum(experts_touched_per_layer) * 2 * I * H * es
+    down = sum(experts_touched_per_layer) * H * I * es
+    lm = V * H * es
+    kv_read = L * sum(p + block_len for p in prefix_lens) * 2 * D * es
+    kv_write = L * n_tok * 2 * D * es
+    stages = dict(qkv=qkv, oproj=oproj, router=router, expert_gate_up=gate_up, expert_down=down, lm_head=lm,
+                  kv_read=kv_read, kv_write=kv_write)
+    return sum(stages.values()), stages
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported. "
+              "The reported value is one GPU's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import dinfer_inputs as di
+    from paper_2510_08666_amd import binding
+
+    wl = di.workload_preset(args.workload)
+    cfg = wl.model
+    seed = di.BASE_SEED + wl.seed_index
+    t0 = time.time()
+    weights = di.make_weights(cfg, di.BASE_SEED + 2)       # one weight set for every LLaDA-MoE-shaped workload
+    inp = di.make_workload_inputs(wl, seed)
+    ns, S = inp.block_tokens.shape
+    T = ns * S
+    max_pos = int(inp.prefix_len.max()) + S + 16
+    ctx = binding.Context(cfg, inp.n_pages, ns, max(T, 64), max_pos)
+    ctx.load_weights(weights)
+    dev = ctx.device
+    page_table = torch.from_numpy(inp.page_table).to(dev)
+    # cached prefix: seeded synthetic K,V (the workloads state a cached prefix; its values do not change the work)
+    for s in range(ns):
+        P = int(inp.prefix_len[s])
+        k, v = di.synthetic_prefix_kv(cfg, seed, s, P)
+        for l in range(cfg.n_layers):
+            ctx.kv_write(l, page_table[s], 0, torch.from_numpy(k[l]).to(dev), torch.from_numpy(v[l]).to(dev))
+        del k, v
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    prefix_len = torch.from_numpy(inp.prefix_len.astype(np.int32)).to(dev)
+    tokens0 = torch.from_numpy(inp.block_tokens.copy()).to(dev)
+    mask0 = torch.from_numpy(inp.mask_bits.view(np.int64).copy()).to(dev)
+    tokens, mask = tokens0.clone(), mask0.clone()
+    conf = torch.zeros((ns, S), dtype=torch.float32, device=dev)
+    argmax = torch.zeros((ns, S), dtype=torch.int32, device=dev)
+    n_committed = torch.zeros(ns, dtype=torch.int32, device=dev)
+
+    def one_step():
+        tokens.copy_(tokens0)
+        mask.copy_(mask0)
+        ctx.step(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    ctx.profile_start(args.profile_stage)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    launches, stage_ms = ctx.profile_stop()
+
+    committed = float(n_committed.sum().item())
+    routing = ctx.debug_get(1, (cfg.n_layers, T, cfg.top_k), torch.int32).cpu().numpy()
+    touched = [len(np.unique(routing[l])) for l in range(cfg.n_layers)]
+    total_bytes, stages = step_bytes(cfg, T, [int(p) for p in inp.prefix_len], S, touched)
+    ms_per_step = dt / args.steps * 1e3
+    steps_per_s = args.steps / dt
+
+    stage_names = {0: "qkv", 2: "oproj", 3: "expert_gate_up", 4: "expert_down", 5: "lm_head"}
+    roofline = None
+    if launches > 0 and args.profile_stage in stage_names:
+        name = stage_names[args.profile_stage]
+        per_launch_calls = cfg.n_layers if name != "lm_head" else 1
+        bytes_per_launch = stages[name] / per_launch_calls
+        avg_ms = stage_ms / launches
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2),
+                    "launches_timed": launches}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.Oracle(cfg, weights)
+        P = int(inp.prefix_len[0])
+        kc, vc = o.new_cache(P + S)
+        k, v = di.synthetic_prefix_kv(cfg, seed, 0, P)
+        kc[:, :P], vc[:, :P] = k, v
+        tc = time.perf_counter()
+        o.step(inp.block_tokens[0], int(inp.mask_bits[0]), P, kc, vc, wl.threshold, wl.fixed_k)
+        cdt = time.perf_counter() - tc
+        cpu = {"value": round(1.0 / (cdt * ns), 5), "unit": "steps/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": "one full oracle step of sequence 0 of this workload (all layers, LM head, "
+               "commit; same weights, same synthetic prefix K,V), %.1f s; scaled by 1/n_seq" % cdt}
+
+    out = {
+        "metric": "block denoising steps/s (committed tokens/s alongside), batch %d" % ns,
+        "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "n_seq": ns, "block_len": S, "prefix_len": [int(p) for p in inp.prefix_len][:4],
+                   "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),
+                   "prefix_kv": "seeded synthetic N(0,0.9)"},
+        "committed_tokens_per_s": round(steps_per_s * committed, 2),
+        "committed_per_step": committed,
+        "step_algorithmic_GB": round(total_bytes / 1e9, 3),
+        "step_hbm_frac": round(total_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "experts_touched_per_layer": round(float(np.mean(touched)), 2),
+        "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

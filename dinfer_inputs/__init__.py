@@ -22,6 +22,7 @@ from .configs import (  # noqa: F401
     tensor_shape,
     make_weights,
     make_workload_inputs,
+    synthetic_prefix_kv,
     bf16_to_f32,
     f32_to_bf16,
 )

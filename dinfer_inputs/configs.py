@@ -192,6 +192,18 @@ def make_workload_inputs(wl, seed=None, room=None):
     return WorkloadInputs(prefix, block, bits, plen.astype(np.int32), table, n_pages, seed)
 
 
+KV_STD = 0.9   # std of a key / value element of the random-init LLaDA-MoE-shaped model (0.02 * sqrt(2048))
+
+
+def synthetic_prefix_kv(cfg, seed, s, length, std=KV_STD):
+    """Seeded stand-in for the cached prefix of sequence s: K,V rows ~ N(0, std^2), every value representable
+    in bfloat16 (so that a bf16 and a float64 consumer see the same numbers).  Returns float32 [L][length][D]."""
+    D = cfg.qkv_dim
+    k = g.normal(g.stream_key(seed, 200, s), (cfg.n_layers, length, D), std, "bf16")
+    v = g.normal(g.stream_key(seed, 201, s), (cfg.n_layers, length, D), std, "bf16")
+    return bf16_to_f32(k), bf16_to_f32(v)
+
+
 def scaled(cfg, **kw):
     """Copy of a model config with fields replaced (test variants)."""
     return replace(cfg, **kw)

@@ -157,6 +157,22 @@ int dinfer_kv_read(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, in
 int dinfer_debug_logits(dinfer_ctx* ctx, int32_t n_rows, float* d_out, void* stream);
 int dinfer_debug_get(dinfer_ctx* ctx, int32_t what, void* d_out, size_t bytes, void* stream);
 
+/* Per-launch timing of one stage of the forward, for benchmarks: between dinfer_profile_start and
+ * dinfer_profile_stop every launch of that stage is bracketed by a HIP event pair on the caller's stream
+ * (at most 8192 launches are recorded).  _stop waits for the recorded events and returns their count and
+ * the summed elapsed milliseconds.  The attention stage covers its two kernels (partials + merge). */
+enum {
+  DINFER_STAGE_QKV = 0,
+  DINFER_STAGE_ATTENTION = 1,
+  DINFER_STAGE_OPROJ = 2,
+  DINFER_STAGE_EXPERT_GATE_UP = 3,
+  DINFER_STAGE_EXPERT_DOWN = 4,
+  DINFER_STAGE_LM_HEAD = 5,
+  DINFER_STAGE_COUNT = 6
+};
+int dinfer_profile_start(dinfer_ctx* ctx, int32_t stage);
+int dinfer_profile_stop(dinfer_ctx* ctx, int32_t* n_launches, float* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,9 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
 
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_refresh_block",
-           "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get"]
+           "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
+           "dinfer_profile_start", "dinfer_profile_stop"]
+(STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD) = range(6)
 
 
 class Config(ctypes.Structure):
@@ -79,6 +81,10 @@ def _load():
     L.dinfer_debug_logits.argtypes = [c_vp, c_i32, c_vp, c_vp]
     L.dinfer_debug_get.restype = c_i32
     L.dinfer_debug_get.argtypes = [c_vp, c_i32, c_vp, c_sz, c_vp]
+    L.dinfer_profile_start.restype = c_i32
+    L.dinfer_profile_start.argtypes = [c_vp, c_i32]
+    L.dinfer_profile_stop.restype = c_i32
+    L.dinfer_profile_stop.argtypes = [c_vp, P(c_i32), P(c_f32)]
     return L
 
 
@@ -112,7 +118,9 @@ def _ptr(t):
 class Context:
     """A dinfer context plus the three device buffers it lives in (allocated through torch)."""
 
-    def __init__(self, cfg, n_pages, max_seqs, max_tokens, max_pos, device="cuda:0"):
+    def __init__(self, cfg, n_pages, max_seqs, max_tokens, max_pos, device="cuda:0", weights_buffer=None):
+        """weights_buffer: the `weights` tensor of another Context of the same configuration whose tensors are
+        already loaded (the packed weights are position independent, so contexts may share them)."""
         self.cfg = cfg
         self.device = torch.device(device)
         self.ccfg = make_config(cfg, max_pos)
@@ -122,11 +130,16 @@ class Context:
         if wb == 0 or kb == 0 or sb == 0:
             raise DinferError(-1, last_error())
         self.n_pages, self.max_seqs, self.max_tokens = n_pages, max_seqs, max_tokens
-        self.weights = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        if weights_buffer is not None:
+            if weights_buffer.numel() < wb or weights_buffer.device != self.device:
+                raise ValueError("weights_buffer does not fit this configuration")
+            self.weights = weights_buffer
+        else:
+            self.weights = torch.empty(wb, dtype=torch.uint8, device=self.device)
         self.kv = torch.empty(kb, dtype=torch.uint8, device=self.device)
         self.ws = torch.empty(sb, dtype=torch.uint8, device=self.device)
         h = c_vp()
-        _check(lib.dinfer_create(self.ccfg, _ptr(self.weights), wb, _ptr(self.kv), n_pages, _ptr(self.ws), sb, max_seqs,
+        _check(lib.dinfer_create(self.ccfg, _ptr(self.weights), self.weights.numel(), _ptr(self.kv), n_pages, _ptr(self.ws), sb, max_seqs,
                                  max_tokens, _stream(), ctypes.byref(h)))
         self.h = h
 
@@ -203,6 +216,15 @@ class Context:
         out = torch.empty((n_rows, self.cfg.vocab), dtype=torch.float32, device=self.device)
         _check(lib.dinfer_debug_logits(self.h, n_rows, _ptr(out), _stream()))
         return out
+
+    def profile_start(self, stage):
+        _check(lib.dinfer_profile_start(self.h, stage))
+
+    def profile_stop(self):
+        """(launches recorded, summed milliseconds) of the profiled stage."""
+        n, ms = c_i32(0), c_f32(0.0)
+        _check(lib.dinfer_profile_stop(self.h, ctypes.byref(n), ctypes.byref(ms)))
+        return n.value, ms.value
 
     def debug_get(self, what, shape, dtype):
         out = torch.empty(shape, dtype=dtype, device=self.device)

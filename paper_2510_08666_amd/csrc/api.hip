@@ -117,9 +117,10 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.seq_nkeys = cv.take((size_t)max_seqs * 4);
   w.qtile = cv.take((size_t)max_qtiles * 3 * 4);
   w.x = cv.take(T * H * 4);
-  w.h = cv.take(T * H * es);
-  w.q = cv.take(T * D * es);
-  w.a = cv.take(T * D * es);
+  const size_t planes = c.dtype == DINFER_BF16 ? 2 : 1;   // bf16 activations are kept as hi + lo planes
+  w.h = cv.take(planes * T * H * es);
+  w.q = cv.take(planes * T * D * es);
+  w.a = cv.take(planes * T * D * es);
   size_t part = 0;   // the split policy depends on the number of query tiles only
   for (int nq = 1; nq <= max_qtiles; ++nq) {
     const size_t p = attn_part_floats(nq, c.n_heads, attn_splits(nq, c.n_heads), c.head_dim);
@@ -132,7 +133,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.off = cv.take((size_t)(MAX_EXPERTS + 1) * 4);
   w.perm = cv.take(T * K * 4);
   w.pos_of_pair = cv.take(T * K * 4);
-  w.y = cv.take(T * K * I * es);
+  w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
   w.lm_part = cv.take((size_t)lm_head_waves(c.vocab) * T * 4 * 4);
   w.conf = cv.take(T * 4);
@@ -156,11 +157,36 @@ struct dinfer_ctx {
   size_t kv_layer_bytes;
   int last_T;   // tokens of the last forward (debug hooks)
   uint64_t* h_mask_pinned;
+  // optional per-launch timing of one stage (dinfer_profile_start / _stop)
+  int prof_stage;
+  size_t prof_n;
+  std::vector<hipEvent_t> prof_ev;   // start/stop pairs
 };
 
 namespace {
 
 template <typename T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
+
+constexpr size_t PROF_MAX_LAUNCHES = 8192;
+
+// Brackets the launches of one stage with an event pair when that stage is being profiled.
+struct StageTimer {
+  dinfer_ctx* c;
+  hipStream_t st;
+  bool on;
+  StageTimer(dinfer_ctx* c_, int stage, hipStream_t st_) : c(c_), st(st_), on(false) {
+    if (c->prof_stage == stage && c->prof_n < PROF_MAX_LAUNCHES) {
+      on = true;
+      (void)hipEventRecord(c->prof_ev[2 * c->prof_n], st);
+    }
+  }
+  ~StageTimer() {
+    if (on) {
+      (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st);
+      ++c->prof_n;
+    }
+  }
+};
 
 // One forward over the packed tokens of `span`.  with_head: final norm into h (ready for the LM head).
 int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const int32_t* d_base,
@@ -180,6 +206,8 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
               at<int32_t>(ws, w.qtile), st);
   float* x = at<float>(ws, w.x);
   void* h = ws + w.h;
+  const int64_t h_plane = (int64_t)c->max_tokens * H, a_plane = (int64_t)c->max_tokens * D,
+                y_plane = (int64_t)c->max_tokens * f.top_k * f.moe_inter;
   for (int l = 0; l < f.n_layers; ++l) {
     const LayerW& lw = c->wm.layers[l];
     char* kv_layer = c->kv + (size_t)l * c->kv_layer_bytes;
@@ -187,30 +215,46 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     float* topk_w = at<float>(ws, w.topk_w) + (size_t)l * T * f.top_k;
     if (l == 0)
       launch_embed_norm(bf, d_tokens, c->weights + c->wm.emb, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H,
-                        f.vocab, x, h, st);
+                        f.vocab, x, h, h_plane, st);
     else
       launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k,
-                          f.top_k, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H, h, st);
-    QkvArgs qa{c->weights + lw.wqkv, h, ws + w.q, kv_layer, c->geom, meta, d_page_table, pt_stride,
+                          f.top_k, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H, h, h_plane, st);
+    QkvArgs qa{c->weights + lw.wqkv, h, h_plane, ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride,
                at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H};
-    launch_qkv(bf, qa, st);
-    AttnArgs aa{ws + w.q, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
-                attn_splits(n_qtiles, f.n_heads), at<float>(ws, w.attn_part), ws + w.a};
-    launch_attention(bf, aa, st);
-    launch_oproj(bf, c->weights + lw.wo, ws + w.a, x, T, D, H, st);
+    {
+      StageTimer tm(c, DINFER_STAGE_QKV, st);
+      launch_qkv(bf, qa, st);
+    }
+    AttnArgs aa{ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
+                attn_splits(n_qtiles, f.n_heads), at<float>(ws, w.attn_part), ws + w.a, a_plane};
+    {
+      StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
+      launch_attention(bf, aa, st);
+    }
+    {
+      StageTimer tm(c, DINFER_STAGE_OPROJ, st);
+      launch_oproj(bf, c->weights + lw.wo, ws + w.a, a_plane, x, T, D, H, st);
+    }
     launch_router(bf, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, c->weights + lw.router, T, H, f.n_experts,
-                  f.top_k, f.norm_topk, h, topk_idx, topk_w, st);
+                  f.top_k, f.norm_topk, h, h_plane, topk_idx, topk_w, st);
     launch_permute(topk_idx, T * f.top_k, f.n_experts, at<int32_t>(ws, w.cnt),
                    at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), st);
-    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, h, ws + w.y, at<float>(ws, w.o),
+    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, h, h_plane, ws + w.y, y_plane, at<float>(ws, w.o),
                   at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), T, H, f.moe_inter,
                   f.n_experts, f.top_k};
-    launch_experts(bf, ea, st);
+    {
+      StageTimer tm(c, DINFER_STAGE_EXPERT_GATE_UP, st);
+      launch_expert_gate_up(bf, ea, st);
+    }
+    {
+      StageTimer tm(c, DINFER_STAGE_EXPERT_DOWN, st);
+      launch_expert_down(bf, ea, st);
+    }
   }
   // the last layer's expert outputs are folded into the residual here; the norm written to h is the final one
   launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
                       at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k,
-                      at<float>(c->weights, c->wm.final_gain), f.rms_eps, T, H, h, st);
+                      at<float>(c->weights, c->wm.final_gain), f.rms_eps, T, H, h, h_plane, st);
   (void)with_head;
   c->last_T = T;
   HIP_TRY(hipGetLastError());
@@ -298,6 +342,8 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   c->geom.layer_stride = c->geom.page_stride * n_pages;
   c->kv_layer_bytes = (size_t)c->geom.layer_stride * es;
   c->last_T = 0;
+  c->prof_stage = -1;
+  c->prof_n = 0;
   c->h_mask_pinned = nullptr;
   if (hipHostMalloc((void**)&c->h_mask_pinned, MAX_SEQS * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
     delete c;
@@ -319,6 +365,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
 
 void dinfer_destroy(dinfer_ctx* ctx) {
   if (!ctx) return;
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   if (ctx->h_mask_pinned) (void)hipHostFree(ctx->h_mask_pinned);
   delete ctx;
 }
@@ -397,9 +444,12 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   if (rc != DINFER_OK) return rc;
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, T, f.hidden, f.vocab, f.logit_scale,
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, (int64_t)c->max_tokens * f.hidden, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), nullptr};
-  launch_lm_head(c->bf16, la, st);
+  {
+    StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
+    launch_lm_head(c->bf16, la, st);
+  }
   launch_lm_merge(la.part, la.n_lm_waves, T, d_conf, d_argmax, st);
   launch_commit(d_conf, d_argmax, n_seq, block_len, d_block_tokens, d_mask, decode->threshold, decode->fixed_k,
                 d_n_committed, st);
@@ -474,11 +524,41 @@ int dinfer_kv_read(dinfer_ctx* c, int32_t layer, const int32_t* d_page_row, int3
   return kv_copy(c, false, layer, d_page_row, first_pos, n_pos, d_k, d_v, stream);
 }
 
+int dinfer_profile_start(dinfer_ctx* c, int32_t stage) {
+  if (!c) return fail(DINFER_EINVAL, "context is null");
+  if (stage < 0 || stage >= DINFER_STAGE_COUNT) return fail(DINFER_EINVAL, "stage %d", stage);
+  while (c->prof_ev.size() < 2 * PROF_MAX_LAUNCHES) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreate(&e));
+    c->prof_ev.push_back(e);
+  }
+  c->prof_stage = stage;
+  c->prof_n = 0;
+  return DINFER_OK;
+}
+
+int dinfer_profile_stop(dinfer_ctx* c, int32_t* n_launches, float* total_ms) {
+  if (!c || !n_launches || !total_ms) return fail(DINFER_EINVAL, "null argument");
+  if (c->prof_stage < 0) return fail(DINFER_EINVAL, "no profile running");
+  float sum = 0.f;
+  for (size_t i = 0; i < c->prof_n; ++i) {
+    HIP_TRY(hipEventSynchronize(c->prof_ev[2 * i + 1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    sum += ms;
+  }
+  *n_launches = (int32_t)c->prof_n;
+  *total_ms = sum;
+  c->prof_stage = -1;
+  c->prof_n = 0;
+  return DINFER_OK;
+}
+
 int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* stream) {
   if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
   if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, n_rows, f.hidden, f.vocab, f.logit_scale,
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, (int64_t)c->max_tokens * f.hidden, n_rows, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());

@@ -25,10 +25,14 @@ template <typename E> struct PvStep;
 template <> struct PvStep<bf16_t> {
   // step s2 in {0,1}: registers 8*s2 .. 8*s2+7 -> keys 16*s2 + {4h..4h+3, 8+4h..8+4h+3}
   static constexpr int STEPS = 2;
-  __device__ static bf16x8 p_vec(const float (&p)[16], int s2) {
+  // plane 0: bf16(p); plane 1: bf16(p - plane 0)
+  __device__ static bf16x8 p_vec(const float (&p)[16], int s2, int plane) {
     bf16x8 r;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)p[8 * s2 + i];
+    for (int i = 0; i < 8; ++i) {
+      const bf16_t hi = (bf16_t)p[8 * s2 + i];
+      r[i] = plane == 0 ? hi : (bf16_t)(p[8 * s2 + i] - (float)hi);
+    }
     return r;
   }
   // vrow: V^T row of feature d inside the page of this step (16 slots contiguous)
@@ -49,7 +53,7 @@ template <> struct PvStep<bf16_t> {
 template <> struct PvStep<float> {
   // step s2 in {0..3}: registers 4*s2 .. 4*s2+3 -> keys 8*s2 + 4h + {0..3}
   static constexpr int STEPS = 4;
-  __device__ static f32x4 p_vec(const float (&p)[16], int s2) {
+  __device__ static f32x4 p_vec(const float (&p)[16], int s2, int /*plane*/) {
     f32x4 r;
 #pragma unroll
     for (int i = 0; i < 4; ++i) r[i] = p[4 * s2 + i];
@@ -63,12 +67,12 @@ template <> struct PvStep<float> {
 };
 
 template <typename E, int HD>
-__global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q, const E* __restrict__ kv_layer,
-                                                         KvGeom geom, FwdMeta meta,
+__global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q, int64_t q_plane,
+                                                         const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
                                                          int n_splits, float* __restrict__ part) {
   typedef typename ET<E>::vec vec;
-  constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE, NP = Planes<E>::N;
   const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int seq = meta.qtile[qt * 3 + 0], tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
@@ -78,11 +82,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
   const int32_t* pt = page_table + (int64_t)seq * pt_stride;
 
   // Q^T operand: this lane's query column, all of head_dim
-  vec qv[DSTEPS];
+  // (queries and probabilities enter the MFMAs as hi + lo planes when E is bf16, like every activation)
+  vec qv[DSTEPS][NP];
   {
     const E* qrow = Q + (int64_t)(tok0 + min(col, nvalid - 1)) * D + head * HD + half * G;
 #pragma unroll
-    for (int s = 0; s < DSTEPS; ++s) qv[s] = load16<E>(qrow + s * KS);
+    for (int s = 0; s < DSTEPS; ++s)
+#pragma unroll
+      for (int pl = 0; pl < NP; ++pl) qv[s][pl] = load16<E>(qrow + pl * q_plane + s * KS);
   }
   f32x16 o[DT];
   zero_acc<DT>(o);
@@ -97,7 +104,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
 #pragma unroll
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-    for (int s = 0; s < DSTEPS; ++s) mfma32(sacc, load16<E>(krow + s * KS), qv[s]);
+    for (int s = 0; s < DSTEPS; ++s) {
+      const vec kv = load16<E>(krow + s * KS);
+#pragma unroll
+      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, kv, qv[s][pl]);
+    }
     float p[16];
     float mx = -INFINITY;
 #pragma unroll
@@ -127,7 +138,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
       const int pkey = min(kt * TILE + PvStep<E>::page_of_step(s2) * PAGE, n_keys - 1);
       const int page = safe_page(geom, pt[pkey / PAGE]);
-      const vec pv = PvStep<E>::p_vec(p, s2);
+      vec pv[NP];
+#pragma unroll
+      for (int pl = 0; pl < NP; ++pl) pv[pl] = PvStep<E>::p_vec(p, s2, pl);
 #pragma unroll
       for (int t = 0; t < DT; ++t) {
         const E* vrow = kv_layer + kv_v_index(geom, page, head, 0, t * TILE + col);
@@ -137,7 +150,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
           for (int i = 0; i < G; ++i)
             if (kt * TILE + PvStep<E>::key_of(s2, half, i) >= n_keys) vv[i] = (E)0.f;
         }
-        mfma32(o[t], vv, pv);
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) mfma32(o[t], vv, pv[pl]);
       }
     }
   }
@@ -162,7 +176,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
 
 template <typename E, int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, FwdMeta meta, int n_heads,
-                                                          int n_parts, E* __restrict__ out) {
+                                                          int n_parts, E* __restrict__ out, int64_t out_plane) {
   const int head = blockIdx.x, qt = blockIdx.y;
   const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
   const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
@@ -186,17 +200,17 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
       for (int i = 0; i < 4; ++i) acc[i] += w * ov[i];
     }
     const float inv = 1.f / L;
-    E* dst = out + (int64_t)(tok0 + q) * D + head * HD + d;
+    const int64_t dst = (int64_t)(tok0 + q) * D + head * HD + d;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = from_f32<E>(acc[i] * inv);
+    for (int i = 0; i < 4; ++i) store_act<E>(out, dst + i, out_plane, acc[i] * inv);
   }
 }
 
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
   attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(
-      (const E*)a.q, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part);
+      (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part);
   attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
-                                                                                a.n_splits * 4, (E*)a.out);
+                                                                                a.n_splits * 4, (E*)a.out, a.out_plane);
 }
 
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st) {

@@ -38,6 +38,21 @@ template <typename E> __device__ inline E from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }   // round to nearest even
 
+// Activations that feed the matrix cores as bf16 are kept as TWO bf16 planes, hi = bf16(v) and
+// lo = bf16(v - hi), so that hi + lo carries ~16 mantissa bits: at small token counts the MFMA units idle
+// behind the weight stream, and a second MFMA per weight tile buys back the precision that a single bf16
+// rounding of every GEMM input would cost.  float32 activations need one plane.
+template <typename E> struct Planes { static constexpr int N = 1; };
+template <> struct Planes<bf16_t> { static constexpr int N = 2; };
+
+template <typename E> __device__ inline void store_act(E* base, int64_t idx, int64_t plane, float v);
+template <> __device__ inline void store_act<float>(float* base, int64_t idx, int64_t, float v) { base[idx] = v; }
+template <> __device__ inline void store_act<bf16_t>(bf16_t* base, int64_t idx, int64_t plane, float v) {
+  const bf16_t hi = (bf16_t)v;
+  base[idx] = hi;
+  base[idx + plane] = (bf16_t)(v - (float)hi);
+}
+
 // acc[32 x 32] += A[32 x KS] * B[KS x 32].  Lane l supplies row (A) / column (B) l%32 and the G consecutive
 // k values that start at (l/32)*G; result: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4.
 __device__ inline void mfma32(f32x16& acc, const bf16x8& a, const bf16x8& b) {

@@ -13,6 +13,7 @@ namespace dinfer {
 // ------------------------------------------------------------------------------------------------
 template <typename E> struct QkvEpi {
   E* q;
+  int64_t q_plane;
   E* kv_layer;
   KvGeom geom;
   const int32_t* tok_seq;
@@ -48,12 +49,20 @@ template <typename E> struct QkvEpi {
           lo[i] = a * c - b * s;
           hi[i] = b * c + a * s;
         }
-        E* dst = is_k ? kv_layer + kv_k_index(geom, page, head, slot, j0)
-                      : q + (int64_t)tok * D + head * hd + j0;
+        if (is_k) {
+          E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          dst[i] = from_f32<E>(lo[i]);
-          dst[hd / 2 + i] = from_f32<E>(hi[i]);
+          for (int i = 0; i < 4; ++i) {
+            dst[i] = from_f32<E>(lo[i]);
+            dst[hd / 2 + i] = from_f32<E>(hi[i]);
+          }
+        } else {
+          const int64_t dst = (int64_t)tok * D + head * hd + j0;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            store_act<E>(q, dst + i, q_plane, lo[i]);
+            store_act<E>(q, dst + hd / 2 + i, q_plane, hi[i]);
+          }
         }
       }
     } else {
@@ -92,8 +101,8 @@ struct ResidualEpi {
 
 template <typename E, int TT, int KSPLIT, class Epi>
 __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
-                                                                     const E* __restrict__ X, int T, int K,
-                                                                     Epi epi) {
+                                                                     const E* __restrict__ X, int64_t plane,
+                                                                     int T, int K, Epi epi) {
   extern __shared__ float red[];   // [KSPLIT-1][2*TT*16][64]
   constexpr int G = ET<E>::G;
   const int task = blockIdx.y, group = blockIdx.x;
@@ -110,7 +119,8 @@ __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __r
   zero_acc<TT>(acc1);
   const int per = (ksteps + KSPLIT - 1) / KSPLIT;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  if (ks0 < ks1) stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, bp, acc0, acc1);
+  if (ks0 < ks1)
+    stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, bp, plane, acc0, acc1);
   if (KSPLIT > 1) {
     if (wave > 0) {
       float* r = red + (int64_t)(wave - 1) * (2 * TT * 16) * WAVE + lane;
@@ -148,15 +158,15 @@ __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __r
 template <int TT, int KSPLIT> constexpr size_t ksplit_lds() { return (size_t)(KSPLIT - 1) * 2 * TT * 16 * WAVE * 4; }
 
 template <typename E, class Epi>
-static void launch_ksplit(const E* W, int ksteps, const E* X, int T, int K, int n_tasks, const Epi& epi,
-                          hipStream_t st) {
+static void launch_ksplit(const E* W, int ksteps, const E* X, int64_t plane, int T, int K, int n_tasks,
+                          const Epi& epi, hipStream_t st) {
   if (T <= 32) {
-    gemm_ksplit_kernel<E, 1, 8, Epi><<<dim3(1, n_tasks), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(W, ksteps, X, T, K, epi);
+    gemm_ksplit_kernel<E, 1, 8, Epi><<<dim3(1, n_tasks), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(W, ksteps, X, plane, T, K, epi);
   } else if (T <= 64) {
-    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(1, n_tasks), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, X, T, K, epi);
+    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(1, n_tasks), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, X, plane, T, K, epi);
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(groups, n_tasks), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, X, T, K, epi);
+    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(groups, n_tasks), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, X, plane, T, K, epi);
   }
 }
 
@@ -171,19 +181,20 @@ template <typename E, class Epi> static void configure_ksplit() {
 
 template <typename E> static void launch_qkv_t(const QkvArgs& a, hipStream_t st) {
   const int D = a.geom.n_heads * a.geom.head_dim;
-  QkvEpi<E> epi{(E*)a.q, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table, a.pt_stride,
+  QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table, a.pt_stride,
                 a.cos_tab, a.sin_tab, D};
-  launch_ksplit<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.h, a.T, a.H, 3 * D / 64, epi, st);
+  launch_ksplit<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.h, a.act_plane, a.T, a.H, 3 * D / 64, epi, st);
 }
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
   if (bf16) launch_qkv_t<bf16_t>(a, st);
   else launch_qkv_t<float>(a, st);
 }
 
-void launch_oproj(bool bf16, const void* w, const void* a, float* x, int T, int D, int H, hipStream_t st) {
+void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
+                  hipStream_t st) {
   ResidualEpi epi{x, H};
-  if (bf16) launch_ksplit<bf16_t>((const bf16_t*)w, D / 16, (const bf16_t*)a, T, D, H / 64, epi, st);
-  else launch_ksplit<float>((const float*)w, D / 8, (const float*)a, T, D, H / 64, epi, st);
+  if (bf16) launch_ksplit<bf16_t>((const bf16_t*)w, D / 16, (const bf16_t*)a, act_plane, T, D, H / 64, epi, st);
+  else launch_ksplit<float>((const float*)w, D / 8, (const float*)a, act_plane, T, D, H / 64, epi, st);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -199,7 +210,7 @@ __global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__
                                                             E* __restrict__ Y, const int32_t* __restrict__ cnt,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ perm, int H, int I,
-                                                            int top_k) {
+                                                            int top_k, int64_t h_plane, int64_t y_plane) {
   constexpr int G = ET<E>::G;
   const int e = blockIdx.y, group = blockIdx.z;
   const int n_rows = cnt[e];
@@ -222,13 +233,14 @@ __global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = H / ET<E>::KS;
-  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, acc0, acc1);
+  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, h_plane, acc0,
+                        acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     if (row[t] < n_rows) {
       E* yrow = Y + (int64_t)(base + row[t]) * I + task * TILE;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) yrow[acc_row(v, half)] = from_f32<E>(silu_f(acc0[t][v]) * acc1[t][v]);
+      for (int v = 0; v < 16; ++v) store_act<E>(yrow, acc_row(v, half), y_plane, silu_f(acc0[t][v]) * acc1[t][v]);
     }
   }
 }
@@ -236,7 +248,8 @@ __global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__
 template <typename E, int TT>
 __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                             float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                            const int32_t* __restrict__ off, int H, int I) {
+                                                            const int32_t* __restrict__ off, int H, int I,
+                                                            int64_t y_plane) {
   constexpr int G = ET<E>::G;
   const int e = blockIdx.y, group = blockIdx.z;
   const int n_rows = cnt[e];
@@ -258,7 +271,8 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = I / ET<E>::KS;
-  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, acc0, acc1);
+  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, y_plane, acc0,
+                        acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     if (row[t] < n_rows) {
@@ -278,25 +292,30 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
   }
 }
 
-template <typename E, int TT> static void launch_experts_t(const ExpertArgs& a, int groups, hipStream_t st) {
-  const int t1 = a.I / TILE, t2 = a.H / (2 * TILE);
+template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
+  const int t1 = a.I / TILE;
   expert_gemm1_kernel<E, TT><<<dim3((t1 + 3) / 4, a.E, groups), 256, 0, st>>>(
-      (const E*)a.w_gate_up, (const E*)a.h, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k);
+      (const E*)a.w_gate_up, (const E*)a.h, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.h_plane, a.y_plane);
+}
+template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
+  const int t2 = a.H / (2 * TILE);
   expert_gemm2_kernel<E, TT><<<dim3((t2 + 3) / 4, a.E, groups), 256, 0, st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.H, a.I);
+      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.H, a.I, a.y_plane);
 }
 
-void launch_experts(bool bf16, const ExpertArgs& a, hipStream_t st) {
-  // an expert can receive at most T rows (a token selects an expert at most once)
-  if (a.T <= 32) {
-    if (bf16) launch_experts_t<bf16_t, 1>(a, 1, st); else launch_experts_t<float, 1>(a, 1, st);
-  } else if (a.T <= 64) {
-    if (bf16) launch_experts_t<bf16_t, 2>(a, 1, st); else launch_experts_t<float, 2>(a, 1, st);
-  } else {
-    const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    if (bf16) launch_experts_t<bf16_t, 4>(a, groups, st); else launch_experts_t<float, 4>(a, groups, st);
+// An expert can receive at most T rows (a token selects an expert at most once): T fixes the row tiling.
+#define DINFER_EXPERT_DISPATCH(FN)                                                              \
+  if (a.T <= 32) {                                                                              \
+    if (bf16) FN<bf16_t, 1>(a, 1, st); else FN<float, 1>(a, 1, st);                             \
+  } else if (a.T <= 64) {                                                                       \
+    if (bf16) FN<bf16_t, 2>(a, 1, st); else FN<float, 2>(a, 1, st);                             \
+  } else {                                                                                      \
+    const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);                                       \
+    if (bf16) FN<bf16_t, 4>(a, groups, st); else FN<float, 4>(a, groups, st);                   \
   }
-}
+
+void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER_EXPERT_DISPATCH(launch_gate_up_t) }
+void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER_EXPERT_DISPATCH(launch_down_t) }
 
 // ------------------------------------------------------------------------------------------------
 // LM head fused with the confidence reduction.  Each wave walks tasks (64 vocabulary ids each) and keeps,
@@ -306,7 +325,7 @@ void launch_experts(bool bf16, const ExpertArgs& a, hipStream_t st) {
 template <typename E, int TT>
 __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, const E* __restrict__ Hn, int T,
                                                        int H, int V, float scale, float* __restrict__ part,
-                                                       int n_waves, float* __restrict__ logits_out) {
+                                                       int n_waves, float* __restrict__ logits_out, int64_t plane) {
   constexpr int G = ET<E>::G;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int group = blockIdx.y;
@@ -328,7 +347,7 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
     f32x16 acc0[TT], acc1[TT];
     zero_acc<TT>(acc0);
     zero_acc<TT>(acc1);
-    stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, bp, acc0, acc1);
+    stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, bp, plane, acc0, acc1);
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
       const int tok = tok0 + t * TILE + (lane & 31);
@@ -403,15 +422,15 @@ template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = a.n_lm_waves / 4;
   if (a.T <= 32) {
     lm_head_kernel<E, 1><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out);
+                                                        a.n_lm_waves, a.logits_out, a.act_plane);
   } else if (a.T <= 64) {
     lm_head_kernel<E, 2><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out);
+                                                        a.n_lm_waves, a.logits_out, a.act_plane);
   } else {
     // token groups of 128 rows: the partials of group g live in rows [g*128, ...) of the same table
     const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
     lm_head_kernel<E, 4><<<dim3(wgs, groups), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale,
-                                                             a.part, a.n_lm_waves, a.logits_out);
+                                                             a.part, a.n_lm_waves, a.logits_out, a.act_plane);
   }
 }
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {

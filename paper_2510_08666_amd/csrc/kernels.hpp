@@ -26,15 +26,20 @@ struct FwdMeta {            // device arrays describing the tokens of one forwar
 void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st);
 void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
                  int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
+// Activation outputs (`h`, attention `out`, expert `y`) are written as Planes<E>::N planes (see common.hpp);
+// `*_plane` is the distance in elements from the hi plane to the lo plane (ignored for float32).
 void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
-                       int H, int V, float* x, void* h, hipStream_t st);
+                       int H, int V, float* x, void* h, int64_t h_plane, hipStream_t st);
 void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
-                         int top_k, const float* gain, float eps, int T, int H, void* h, hipStream_t st);
+                         int top_k, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
+                         hipStream_t st);
 
 struct QkvArgs {
   const void* w;            // packed fused QKV
   const void* h;            // [T][H]
+  int64_t act_plane;
   void* q;                  // [T][D]
+  int64_t q_plane;
   void* kv_layer;           // pool base of this layer
   KvGeom geom;
   FwdMeta meta;
@@ -48,6 +53,7 @@ void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st);
 
 struct AttnArgs {
   const void* q;            // [T][D]
+  int64_t q_plane;
   const void* kv_layer;
   KvGeom geom;
   FwdMeta meta;
@@ -56,13 +62,16 @@ struct AttnArgs {
   int n_qtiles, n_splits;
   float* part;              // partial results, see attention.hip
   void* out;                // [T][D]
+  int64_t out_plane;
 };
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim);
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
 
-void launch_oproj(bool bf16, const void* w, const void* a, float* x, int T, int D, int H, hipStream_t st);
+void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
+                  hipStream_t st);
 void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
-                   int E, int top_k, int norm_topk, void* h, int32_t* topk_idx, float* topk_w, hipStream_t st);
+                   int E, int top_k, int norm_topk, void* h, int64_t h_plane, int32_t* topk_idx, float* topk_w,
+                   hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st);
 
@@ -70,18 +79,22 @@ struct ExpertArgs {
   const void* w_gate_up;    // packed [E][I/32 tasks]
   const void* w_down;       // packed [E][H/64 tasks]
   const void* h;            // [T][H]
+  int64_t h_plane;
   void* y;                  // [T*k][I]
+  int64_t y_plane;
   float* o;                 // [T*k][H]
   const int32_t* cnt;
   const int32_t* off;
   const int32_t* perm;
   int T, H, I, E, top_k;
 };
-void launch_experts(bool bf16, const ExpertArgs& a, hipStream_t st);
+void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st);
+void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
 
 struct LmArgs {
   const void* w;            // packed LM head
   const void* h;            // [T][H]
+  int64_t act_plane;
   int T, H, V;
   float scale;
   float* part;              // [n_lm_waves][T][4]: max, sum-exp, argmax bits, unused

@@ -74,7 +74,8 @@ template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_norm_kernel(const int32_t* __restrict__ tokens,
                                                                   const E* __restrict__ emb,
                                                                   const float* __restrict__ gain, float eps, int H,
-                                                                  int V, float* __restrict__ x, E* __restrict__ h) {
+                                                                  int V, float* __restrict__ x, E* __restrict__ h,
+                                                                  int64_t h_plane) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
@@ -93,14 +94,14 @@ __global__ __launch_bounds__(NORM_THREADS) void embed_norm_kernel(const int32_t*
     const int c = threadIdx.x + i * NORM_THREADS;
     if (c < H) {
       x[(int64_t)t * H + c] = v[i];
-      h[(int64_t)t * H + c] = from_f32<E>(v[i] * r * gain[c]);
+      store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
     }
   }
 }
 void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
-                       int H, int V, float* x, void* h, hipStream_t st) {
-  if (bf16) embed_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, gain, eps, H, V, x, (bf16_t*)h);
-  else embed_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, gain, eps, H, V, x, (float*)h);
+                       int H, int V, float* x, void* h, int64_t h_plane, hipStream_t st) {
+  if (bf16) embed_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, gain, eps, H, V, x, (bf16_t*)h, h_plane);
+  else embed_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, gain, eps, H, V, x, (float*)h, h_plane);
 }
 
 // x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  h[t] = RMSNorm(x[t]) * gain
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __res
                                                                     const int32_t* __restrict__ pos_of_pair,
                                                                     const float* __restrict__ topk_w, int top_k,
                                                                     const float* __restrict__ gain, float eps, int H,
-                                                                    E* __restrict__ h) {
+                                                                    E* __restrict__ h, int64_t h_plane) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
   float v[NORM_MAX_PER_THREAD];
@@ -133,14 +134,15 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __res
     const int c = threadIdx.x + i * NORM_THREADS;
     if (c < H) {
       x[(int64_t)t * H + c] = v[i];
-      h[(int64_t)t * H + c] = from_f32<E>(v[i] * r * gain[c]);
+      store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
     }
   }
 }
 void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
-                         int top_k, const float* gain, float eps, int T, int H, void* h, hipStream_t st) {
-  if (bf16) combine_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (bf16_t*)h);
-  else combine_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (float*)h);
+                         int top_k, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
+                         hipStream_t st) {
+  if (bf16) combine_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (bf16_t*)h, h_plane);
+  else combine_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (float*)h, h_plane);
 }
 
 // ---------------------------------------------------------------- router
@@ -150,7 +152,7 @@ template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                               float eps, const E* __restrict__ Wr, int H, int n_exp,
                                                               int top_k, int norm_topk, E* __restrict__ h,
-                                                              int32_t* __restrict__ topk_idx,
+                                                              int64_t h_plane, int32_t* __restrict__ topk_idx,
                                                               float* __restrict__ topk_w) {
   __shared__ float sh[4];
   __shared__ float hn[NORM_THREADS * NORM_MAX_PER_THREAD];
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __res
     if (c < H) {
       const float y = v[i] * r * gain[c];
       hn[c] = y;
-      h[(int64_t)t * H + c] = from_f32<E>(y);
+      store_act<E>(h, (int64_t)t * H + c, h_plane, y);
     }
   }
   __syncthreads();
@@ -210,9 +212,10 @@ __global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __res
   }
 }
 void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
-                   int E, int top_k, int norm_topk, void* h, int32_t* topk_idx, float* topk_w, hipStream_t st) {
-  if (bf16) router_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const bf16_t*)w_router, H, E, top_k, norm_topk, (bf16_t*)h, topk_idx, topk_w);
-  else router_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const float*)w_router, H, E, top_k, norm_topk, (float*)h, topk_idx, topk_w);
+                   int E, int top_k, int norm_topk, void* h, int64_t h_plane, int32_t* topk_idx, float* topk_w,
+                   hipStream_t st) {
+  if (bf16) router_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const bf16_t*)w_router, H, E, top_k, norm_topk, (bf16_t*)h, h_plane, topk_idx, topk_w);
+  else router_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const float*)w_router, H, E, top_k, norm_topk, (float*)h, h_plane, topk_idx, topk_w);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation

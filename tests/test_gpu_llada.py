@@ -1,0 +1,219 @@
+"""GPU parity at the benchmark's full LLaDA-MoE shapes (16 layers, hidden 2048, 64 experts top-8, vocab
+157184, bf16), in the launch configuration bench.py times.
+
+The cached prefix is a seeded synthetic K,V (same values on both sides): an oracle prefill of thousands of
+tokens would take tens of minutes, and a step only ever reads the cache.  A real prefill at these shapes is
+checked on a short prompt.  One weight set (14.7 GB) serves every case.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import dinfer_inputs as di
+import oracle
+from harness import GpuRun, bars_for, compare_logits, compare_step, check_routing, max_abs_err
+
+pytestmark = pytest.mark.gpu
+
+WEIGHT_SEED = di.BASE_SEED + 2
+
+
+def log(msg):
+    print("[llada %s] %s" % (time.strftime("%H:%M:%S"), msg), flush=True)
+
+
+@pytest.fixture(scope="module")
+def model():
+    cfg = di.model_preset("llada_moe")
+    t = time.time()
+    w = di.make_weights(cfg, WEIGHT_SEED)
+    log("weights generated in %.0f s" % (time.time() - t))
+    return cfg, w, oracle.Oracle(cfg, w)
+
+
+_shared = {}     # the packed device weights, uploaded by the first case and reused by the others
+
+
+def gpu_run(model, inp, max_tokens, max_pos):
+    cfg, w, _ = model
+    t = time.time()
+    g = GpuRun(cfg, w, inp, max_tokens, max_pos, weights_buffer=_shared.get("w"))
+    if "w" not in _shared:
+        _shared["w"] = g.ctx.weights
+        log("weights uploaded and packed in %.0f s" % (time.time() - t))
+    return g
+
+
+class BigCase:
+    """One workload on both sides, prefix K,V synthetic.  Oracle caches hold [L][cap][D] per sequence."""
+
+    def __init__(self, model, wl, max_tokens=None):
+        self.cfg, self.w, self.o = model
+        self.wl = wl
+        self.inp = di.make_workload_inputs(wl)
+        self.ns, self.S = self.inp.block_tokens.shape
+        self.bars = bars_for(self.cfg)
+        max_pos = int(self.inp.prefix_len.max()) + max(self.S, wl.gen_len) + 16
+        self.gpu = gpu_run(model, self.inp, max_tokens or max(self.ns * self.S, 64), max_pos)
+        self.caches = []
+        torch = self.gpu.torch
+        for s in range(self.ns):
+            P = int(self.inp.prefix_len[s])
+            kc, vc = self.o.new_cache(P + max(self.S, wl.gen_len))
+            if P:
+                k, v = di.synthetic_prefix_kv(self.cfg, self.inp.seed, s, P)
+                kc[:, :P], vc[:, :P] = k, v
+                for l in range(self.cfg.n_layers):
+                    self.gpu.ctx.kv_write(l, self.gpu.page_table[s], 0, torch.from_numpy(k[l]).to(self.gpu.dev),
+                                          torch.from_numpy(v[l]).to(self.gpu.dev))
+            self.caches.append((kc, vc))
+        torch.cuda.synchronize()
+
+    def oracle_step_following(self, s, tokens, mask, prefix_len, threshold, fixed_k, routing):
+        kc, vc = self.caches[s]
+        tr = oracle.Trace(self.cfg, len(tokens), forced_idx=routing)
+        ref = self.o.step(tokens, mask, prefix_len, kc, vc, threshold, fixed_k, want_logits=True, trace=tr)
+        return ref, check_routing(tr, routing, self.cfg.top_k, self.bars)
+
+    def check_step(self, got, logits, routing, tokens, masks, prefix_len, threshold, fixed_k, seqs=None):
+        """Compare the sequences in `seqs` (default all) of a GPU step against the oracle."""
+        flagged, near_total = 0, 0
+        for s in (range(self.ns) if seqs is None else seqs):
+            t = time.time()
+            ref, near = self.oracle_step_following(s, tokens[s], int(masks[s]), int(prefix_len[s]), threshold, fixed_k,
+                                                   routing[:, s])
+            worst = compare_logits(ref["logits"], logits[s], self.bars)
+            rep = compare_step(ref, got["tokens"][s], got["mask"][s], got["conf"][s], got["argmax"][s],
+                               got["n_committed"][s], tokens[s], masks[s], threshold, fixed_k, self.bars,
+                               ref["logits"])
+            P = int(prefix_len[s])
+            kc, vc = self.caches[s]
+            for l in (0, self.cfg.n_layers - 1):
+                k, v = self.gpu.read_kv(s, l, P, self.S)
+                assert max_abs_err(k, kc[l, P:P + self.S]) <= self.bars.kv_abs
+                assert max_abs_err(v, vc[l, P:P + self.S]) <= self.bars.kv_abs
+            flagged += len(rep["flagged"])
+            near_total += near
+            log("%s seq %d: oracle step %.0f s, logits err %.2f of bar, conf rel err %.1e, flagged %s, "
+                "router near-ties %d, committed %d" % (self.wl.name, s, time.time() - t, worst, rep["conf_rel_err"],
+                                                       rep["flagged"], near, got["n_committed"][s]))
+        return flagged, near_total
+
+    def gpu_step(self, tokens, masks, prefix_len, threshold, fixed_k=0):
+        g = self.gpu
+        g.set_state(tokens, masks, prefix_len)
+        got = g.step(threshold, fixed_k)
+        logits = g.logits(self.ns * self.S).reshape(self.ns, self.S, -1)
+        routing = g.routing().reshape(self.cfg.n_layers, self.ns, self.S, self.cfg.top_k)
+        return got, logits, routing
+
+
+def test_c2_batch1_step(model):
+    """Configuration 2: batch 1, 512 cached positions, 32 masked positions, threshold 0.9."""
+    c = BigCase(model, di.workload_preset(2))
+    inp = c.inp
+    got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold)
+    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0)
+    assert got["n_committed"][0] == 1      # random-init confidences are far below 0.9: the fallback commits one
+    # a threshold inside the confidence distribution: several positions commit
+    tau = float(np.median(got["conf"][0]))
+    got2, logits2, routing2 = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, tau)
+    assert np.array_equal(logits2, logits), "same state, same bits"
+    c.check_step(got2, logits2, routing2, inp.block_tokens, inp.mask_bits, inp.prefix_len, tau, 0)
+    assert got2["n_committed"][0] > 1
+    c.gpu.close()
+
+
+def test_c3_long_prefix_half_committed(model):
+    """Configuration 3: 4096 cached positions, block of 64 with half the positions already decided,
+    threshold 0.8."""
+    c = BigCase(model, di.workload_preset(3))
+    inp = c.inp
+    got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold)
+    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0)
+    c.gpu.close()
+
+
+def test_c4_batch16_paged(model):
+    """Configuration 4: 16 sequences, prefixes 256..2048 on scattered pages.  Every sequence's decisions and
+    invariants are checked on the GPU side; three sequences (shortest, longest prefix, and one more) are
+    compared element by element against the oracle."""
+    c = BigCase(model, di.workload_preset(4))
+    inp = c.inp
+    got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold)
+    order = np.argsort(inp.prefix_len)
+    seqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])})
+    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0, seqs)
+    for s in range(c.ns):
+        assert got["n_committed"][s] == 1 and bin(int(got["mask"][s])).count("1") == c.S - 1
+        i = int(np.argmax(got["conf"][s]))
+        assert got["tokens"][s][i] == got["argmax"][s][i]
+    # a sequence computed alone equals the same sequence inside the batch (logits bit-identical is not
+    # required: the row tiling differs; the bars are)
+    cnt = c.gpu.ctx.debug_get(3, (c.cfg.n_experts,), c.gpu.torch.int32).cpu().numpy()
+    log("C4 last-layer expert rows: min %d max %d mean %.1f" % (cnt.min(), cnt.max(), cnt.mean()))
+    assert cnt.sum() == c.ns * c.S * c.cfg.top_k
+    c.gpu.close()
+
+
+def test_c5_first_block_fixed_k_and_refresh(model):
+    """Configuration 5's loop on its first block: 256 cached positions, block of 64, exactly 8 steps of 8
+    commits, then the refresh of the block.  Steps are compared teacher-forced (the oracle continues from the
+    GPU's state after each step)."""
+    wl = di.workload_preset(5)
+    c = BigCase(model, wl)
+    inp, g = c.inp, c.gpu
+    tokens, masks = inp.block_tokens.copy(), inp.mask_bits.copy()
+    n_steps = 0
+    while masks.any():
+        got, logits, routing = c.gpu_step(tokens, masks, inp.prefix_len, wl.threshold, wl.fixed_k)
+        if n_steps in (0, 7):      # the oracle takes ~15 s a step: first and last step are compared in full
+            c.check_step(got, logits, routing, tokens, masks, inp.prefix_len, wl.threshold, wl.fixed_k)
+        assert got["n_committed"][0] == 8
+        assert int(got["mask"][0]) & ~int(masks[0]) == 0
+        tokens, masks = got["tokens"].copy(), got["mask"].copy()
+        n_steps += 1
+    assert n_steps == 8
+    # the library's loop does the same from the same start, without waiting between steps
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    assert g.generate_block(wl.threshold, wl.fixed_k, max_steps=64, masked_hint=64) == 8
+    st = g.state()
+    assert np.array_equal(st["tokens"], tokens) and not st["mask"].any()
+    # refresh of the decoded block
+    g.refresh()
+    routing = g.routing().reshape(c.cfg.n_layers, 1, c.S, c.cfg.top_k)
+    P = int(inp.prefix_len[0])
+    assert g.prefix_len.cpu().numpy()[0] == P + c.S
+    kc, vc = c.caches[0]
+    tr = oracle.Trace(c.cfg, c.S, forced_idx=routing[:, 0])
+    c.o.forward(tokens[0], P, kc, vc, tr)
+    check_routing(tr, routing[:, 0], c.cfg.top_k, c.bars)
+    for l in range(c.cfg.n_layers):
+        k, v = g.read_kv(0, l, P, c.S)
+        assert max_abs_err(k, kc[l, P:P + c.S]) <= c.bars.kv_abs
+        assert max_abs_err(v, vc[l, P:P + c.S]) <= c.bars.kv_abs
+    c.gpu.close()
+
+
+def test_prefill_at_full_shapes(model):
+    """A real prefill (bidirectional forward over the prompt) of 100 tokens at the full model shapes."""
+    cfg, w, o = model
+    wl = di.Workload("prefill100", cfg, 1, 32, 100, 100, seed_index=11)
+    inp = di.make_workload_inputs(wl)
+    bars = bars_for(cfg)
+    g = gpu_run(model, inp, 128, 160)
+    g.prefill()
+    g.torch.cuda.synchronize()
+    routing = g.routing(100)
+    kc, vc = o.new_cache(160)
+    tr = oracle.Trace(cfg, 100, forced_idx=routing)
+    t = time.time()
+    o.forward(inp.prefix_tokens[0], 0, kc, vc, tr)
+    near = check_routing(tr, routing, cfg.top_k, bars)
+    log("prefill 100 tokens: oracle %.0f s, router near-ties %d" % (time.time() - t, near))
+    for l in range(cfg.n_layers):
+        k, v = g.read_kv(0, l, 0, 100)
+        assert max_abs_err(k, kc[l, :100]) <= bars.kv_abs, l
+        assert max_abs_err(v, vc[l, :100]) <= bars.kv_abs, l
+    g.close()
