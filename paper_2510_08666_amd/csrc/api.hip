@@ -83,7 +83,7 @@ WeightMap map_weights(const dinfer_config& c) {
     l.wqkv = cv.take((size_t)packed_bytes(bf, 3 * D / 64, H));
     l.wo = cv.take((size_t)packed_bytes(bf, H / 64, D));
     l.ffn_gain = cv.take((size_t)H * 4);
-    l.router = cv.take((size_t)E * H * es);
+    l.router = cv.take((size_t)packed_bytes(bf, 1, H));   // one task: experts 0-31 and 32-63
     l.gate_up = cv.take((size_t)E * packed_bytes(bf, I / 32, H));
     l.down = cv.take((size_t)E * packed_bytes(bf, H / 64, I));
   }
@@ -91,10 +91,14 @@ WeightMap map_weights(const dinfer_config& c) {
   return m;
 }
 
-int attn_splits(int n_qtiles, int n_heads) {
-  int s = 1024 / (n_qtiles * n_heads * 4);   // aim at ~1024 waves
-  if (s < 1) s = 1;
+// Key splits per (query tile, head): enough workgroups to cover the chip (~512), but no more splits than
+// give each wave a key tile of its own (key_bound = most keys a sequence can have in this call).
+int attn_splits(int n_qtiles, int n_heads, int key_bound) {
+  int s = (512 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
+  const int by_keys = ((key_bound + TILE - 1) / TILE + 3) / 4;
+  if (s > by_keys) s = by_keys;
   if (s > 32) s = 32;
+  if (s < 1) s = 1;
   return s;
 }
 
@@ -123,7 +127,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.a = cv.take(planes * T * D * es);
   size_t part = 0;   // the split policy depends on the number of query tiles only
   for (int nq = 1; nq <= max_qtiles; ++nq) {
-    const size_t p = attn_part_floats(nq, c.n_heads, attn_splits(nq, c.n_heads), c.head_dim);
+    const size_t p = attn_part_floats(nq, c.n_heads, attn_splits(nq, c.n_heads, c.max_pos), c.head_dim);
     if (p > part) part = p;
   }
   w.attn_part = cv.take(part * 4);
@@ -226,7 +230,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       launch_qkv(bf, qa, st);
     }
     AttnArgs aa{ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
-                attn_splits(n_qtiles, f.n_heads), at<float>(ws, w.attn_part), ws + w.a, a_plane};
+                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), ws + w.a, a_plane};
     {
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
       launch_attention(bf, aa, st);
@@ -235,8 +239,8 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       StageTimer tm(c, DINFER_STAGE_OPROJ, st);
       launch_oproj(bf, c->weights + lw.wo, ws + w.a, a_plane, x, T, D, H, st);
     }
-    launch_router(bf, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, c->weights + lw.router, T, H, f.n_experts,
-                  f.top_k, f.norm_topk, h, h_plane, topk_idx, topk_w, st);
+    launch_norm(bf, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, T, H, h, h_plane, st);
+    launch_router(bf, c->weights + lw.router, h, h_plane, T, H, f.n_experts, f.top_k, f.norm_topk, topk_idx, topk_w, st);
     launch_permute(topk_idx, T * f.top_k, f.n_experts, at<int32_t>(ws, w.cnt),
                    at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), st);
     ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, h, h_plane, ws + w.y, y_plane, at<float>(ws, w.o),
@@ -350,6 +354,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     return fail(DINFER_EHIP, "hipHostMalloc failed");
   }
   configure_kernels();
+  configure_attention();
   launch_rope_table(at<float>(c->ws, c->wsm.cos_tab), at<float>(c->ws, c->wsm.sin_tab), cfg->max_pos, cfg->head_dim,
                     cfg->rope_theta, (hipStream_t)stream);
   hipError_t e = hipGetLastError();
@@ -403,7 +408,7 @@ int dinfer_set_tensor(dinfer_ctx* c, int32_t tensor_id, int32_t layer, const voi
     case DINFER_T_WK: launch_pack(bf, d_src, W + lw->wqkv + qk_bytes, 1, D, H, D / 64, PACK_ROPE_PAIR, f.head_dim, st); break;
     case DINFER_T_WV: launch_pack(bf, d_src, W + lw->wqkv + 2 * qk_bytes, 1, D, H, D / 64, PACK_ADJACENT, 0, st); break;
     case DINFER_T_WO: launch_pack(bf, d_src, W + lw->wo, 1, H, D, H / 64, PACK_ADJACENT, 0, st); break;
-    case DINFER_T_ROUTER: HIP_TRY(hipMemcpyAsync(W + lw->router, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_ROUTER: launch_pack(bf, d_src, W + lw->router, 1, E, H, 1, PACK_ADJACENT, 0, st); break;
     case DINFER_T_GATE: launch_pack(bf, d_src, W + lw->gate_up, E, I, H, I / 32, PACK_HALF0, 0, st); break;
     case DINFER_T_UP: launch_pack(bf, d_src, W + lw->gate_up, E, I, H, I / 32, PACK_HALF1, 0, st); break;
     case DINFER_T_DOWN: launch_pack(bf, d_src, W + lw->down, E, H, I, H / 64, PACK_ADJACENT, 0, st); break;

@@ -2,9 +2,10 @@
 // cached prefix pages plus the tokens of this forward, read through the page table.
 //
 // Work split: grid (split, head, query tile), 4 waves per workgroup; the key tiles (32 keys) are dealt
-// round-robin to the n_splits*4 waves of a (head, query tile).  Each wave keeps its own online-softmax state and writes one partial
-// (unnormalised output, running max, running sum); attn_merge_kernel folds the partials of a
-// (query tile, head) in fixed order and writes the normalised output.
+// round-robin to the n_splits*4 waves of a (head, query tile).  Each wave keeps its own online-softmax state;
+// the four waves of a workgroup are folded through LDS in wave order.  With one split the workgroup writes
+// the normalised output itself; otherwise it writes one partial (unnormalised output, max, sum) and
+// attn_merge_kernel folds the partials of a (query tile, head) in split order.
 //
 // MFMA mapping (32x32 tiles):  S^T[key][query] = K_tile . Q^T   (A = K rows, B = Q columns), so a lane owns
 // one query column and softmax statistics are per lane;  O^T[d][query] += V^T_tile . P^T  (A = V^T rows read
@@ -15,7 +16,7 @@
 namespace dinfer {
 
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim) {
-  return (size_t)n_qtiles * n_heads * n_splits * 4 * TILE * (head_dim + 2);
+  return (size_t)n_qtiles * n_heads * n_splits * TILE * (head_dim + 2);
 }
 
 // B operand of the PV product for k-step s2: the G probabilities this lane holds for that step's keys, and
@@ -70,7 +71,8 @@ template <typename E, int HD>
 __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q, int64_t q_plane,
                                                          const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
-                                                         int n_splits, float* __restrict__ part) {
+                                                         int n_splits, float* __restrict__ part, E* __restrict__ out,
+                                                         int64_t out_plane) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE, NP = Planes<E>::N;
   const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
@@ -155,8 +157,57 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
       }
     }
   }
-  // ---- partial of this wave: O [32 q][HD], m [32], l [32]
-  const int pidx = ((qt * geom.n_heads + head) * n_splits + split) * 4 + wave;
+  // ---- fold the four waves through LDS (lane-major, conflict free); wave 0 finishes
+  extern __shared__ float lds[];                       // [3 waves][DT*16 + 2][64 lanes]
+  constexpr int PW = (DT * 16 + 2) * WAVE;
+  const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
+  if (wave > 0) {
+    float* pb = lds + (wave - 1) * PW + lane;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pb[(t * 16 + v) * WAVE] = o[t][v];
+    pb[(DT * 16) * WAVE] = m_run;
+    pb[(DT * 16 + 1) * WAVE] = l_tot;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  float M = m_run;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) M = fmaxf(M, lds[w * PW + (DT * 16) * WAVE + lane]);
+  const float s0 = m_run > -INFINITY ? __expf(m_run - M) : 0.f;
+  float L = l_tot * s0;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[t][v] *= s0;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) {
+    const float* pb = lds + w * PW + lane;
+    const float mw = pb[(DT * 16) * WAVE];
+    if (mw > -INFINITY) {                               // a wave that saw no key tile contributes nothing
+      const float sw = __expf(mw - M);
+      L += sw * pb[(DT * 16 + 1) * WAVE];
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] += sw * pb[(t * 16 + v) * WAVE];
+    }
+  }
+  if (n_splits == 1) {
+    // the whole key range was here: normalise and write the attention output
+    if (col < nvalid) {
+      const float inv = 1.f / L;
+      const int64_t dst = (int64_t)(tok0 + col) * D + head * HD;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) store_act<E>(out, dst + t * TILE + acc_row(v, half), out_plane, o[t][v] * inv);
+    }
+    return;
+  }
+  // partial of this split: O [32 q][HD] (unnormalised), m [32], l [32]
+  const int pidx = (qt * geom.n_heads + head) * n_splits + split;
   float* pbase = part + (int64_t)pidx * TILE * (HD + 2);
 #pragma unroll
   for (int t = 0; t < DT; ++t)
@@ -167,10 +218,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
       for (int i = 0; i < 4; ++i) r[i] = o[t][4 * g + i];
       *reinterpret_cast<f32x4*>(pbase + col * HD + t * TILE + acc_row(4 * g, half)) = r;
     }
-  const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
   if (half == 0) {
-    pbase[TILE * HD + col] = m_run;
-    pbase[TILE * HD + TILE + col] = l_tot;
+    pbase[TILE * HD + col] = M;
+    pbase[TILE * HD + TILE + col] = L;
   }
 }
 
@@ -206,11 +256,22 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   }
 }
 
+template <int HD> constexpr size_t attn_lds() { return (size_t)3 * ((HD / TILE) * 16 + 2) * WAVE * 4; }
+
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
-  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(
-      (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part);
-  attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
-                                                                                a.n_splits * 4, (E*)a.out, a.out_plane);
+  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, attn_lds<HD>(), st>>>(
+      (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
+      (E*)a.out, a.out_plane);
+  if (a.n_splits > 1)
+    attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
+                                                                                  a.n_splits, (E*)a.out, a.out_plane);
+}
+
+void configure_attention() {
+  (void)hipFuncSetAttribute((const void*)attention_kernel<bf16_t, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<128>());
+  (void)hipFuncSetAttribute((const void*)attention_kernel<float, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<128>());
+  (void)hipFuncSetAttribute((const void*)attention_kernel<bf16_t, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<64>());
+  (void)hipFuncSetAttribute((const void*)attention_kernel<float, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<64>());
 }
 
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st) {

@@ -99,6 +99,75 @@ struct ResidualEpi {
   }
 };
 
+// Router: the single task holds experts 0-31 (tile 0) and 32-63 (tile 1).  A token's 64 probabilities sit in
+// the two lanes l and l^32; softmax and the k selection rounds combine the pair with one shuffle each.
+struct RouterEpi {
+  int n_exp, top_k, norm_topk;
+  int32_t* topk_idx;
+  float* topk_w;
+  __device__ void operator()(int /*task*/, int tok, bool valid, int half, const f32x16& a0, const f32x16& a1) const {
+    float p[32];
+    int id[32];
+    float m = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {      // ids ascend with the index within each lane
+      id[v] = acc_row(v, half);
+      id[16 + v] = TILE + acc_row(v, half);
+      p[v] = id[v] < n_exp ? a0[v] : -INFINITY;
+      p[16 + v] = id[16 + v] < n_exp ? a1[v] : -INFINITY;
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) m = fmaxf(m, p[i]);
+    m = fmaxf(m, __shfl_xor(m, 32, WAVE));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      p[i] = id[i] < n_exp ? expf(p[i] - m) : 0.f;
+      sum += p[i];
+    }
+    sum += __shfl_xor(sum, 32, WAVE);
+    const float inv = 1.f / sum;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) p[i] = id[i] < n_exp ? p[i] * inv : -1.f;
+    float wsel[MAX_TOPK];
+    int isel[MAX_TOPK];
+    float sel_sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_TOPK; ++j) {
+      if (j < top_k) {
+        float bv = -1.f;
+        int bi = 0x7fffffff, slot = 0;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+          if (p[i] > bv) {
+            bv = p[i];
+            bi = id[i];
+            slot = i;
+          }
+        const float ov = __shfl_xor(bv, 32, WAVE);
+        const int oi = __shfl_xor(bi, 32, WAVE);
+        const bool mine = bv > ov || (bv == ov && bi < oi);
+        wsel[j] = mine ? bv : ov;
+        isel[j] = mine ? bi : oi;
+        sel_sum += wsel[j];
+        if (mine) {
+#pragma unroll
+          for (int i = 0; i < 32; ++i)
+            if (i == slot) p[i] = -1.f;
+        }
+      }
+    }
+    if (valid && half == 0) {
+#pragma unroll
+      for (int j = 0; j < MAX_TOPK; ++j)
+        if (j < top_k) {
+          topk_idx[tok * top_k + j] = isel[j];
+          topk_w[tok * top_k + j] = norm_topk ? wsel[j] / sel_sum : wsel[j];
+        }
+    }
+  }
+};
+
 template <typename E, int TT, int KSPLIT, class Epi>
 __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
                                                                      const E* __restrict__ X, int64_t plane,
@@ -120,7 +189,8 @@ __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __r
   const int per = (ksteps + KSPLIT - 1) / KSPLIT;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   if (ks0 < ks1)
-    stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, bp, plane, acc0, acc1);
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, bp, plane, acc0,
+                                          acc1);
   if (KSPLIT > 1) {
     if (wave > 0) {
       float* r = red + (int64_t)(wave - 1) * (2 * TT * 16) * WAVE + lane;
@@ -197,6 +267,13 @@ void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, fl
   else launch_ksplit<float>((const float*)w, D / 8, (const float*)a, act_plane, T, D, H / 64, epi, st);
 }
 
+void launch_router(bool bf16, const void* w_router_packed, const void* h, int64_t h_plane, int T, int H, int E,
+                   int top_k, int norm_topk, int32_t* topk_idx, float* topk_w, hipStream_t st) {
+  RouterEpi epi{E, top_k, norm_topk, topk_idx, topk_w};
+  if (bf16) launch_ksplit<bf16_t>((const bf16_t*)w_router_packed, H / 16, (const bf16_t*)h, h_plane, T, H, 1, epi, st);
+  else launch_ksplit<float>((const float*)w_router_packed, H / 8, (const float*)h, h_plane, T, H, 1, epi, st);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Routed experts.  Rows of expert e are the pairs perm[off[e] .. off[e]+cnt[e]) (pair = token*top_k + slot).
 // One wave per (expert, task, row group); experts without rows exit at once.
@@ -233,7 +310,7 @@ __global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = H / ET<E>::KS;
-  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, h_plane, acc0,
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, h_plane, acc0,
                         acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -271,7 +348,7 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = I / ET<E>::KS;
-  stream_task<E, TT, 4>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, y_plane, acc0,
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, y_plane, acc0,
                         acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -347,7 +424,7 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
     f32x16 acc0[TT], acc1[TT];
     zero_acc<TT>(acc0);
     zero_acc<TT>(acc1);
-    stream_task<E, TT, 4>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, bp, plane, acc0, acc1);
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, bp, plane, acc0, acc1);
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
       const int tok = tok0 + t * TILE + (lane & 31);
@@ -412,8 +489,8 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
 
 int lm_head_waves(int V) {
   const int n_tasks = (V + 63) / 64;
-  int wgs = (n_tasks + 7) / 8;          // about two tasks per wave
-  if (wgs > 512) wgs = 512;
+  int wgs = (n_tasks + 3) / 4;          // one task per wave while that keeps the partial table small
+  if (wgs > 768) wgs = 768;
   if (wgs < 1) wgs = 1;
   return wgs * 4;
 }
@@ -443,6 +520,8 @@ void configure_kernels() {
   configure_ksplit<float, QkvEpi<float>>();
   configure_ksplit<bf16_t, ResidualEpi>();
   configure_ksplit<float, ResidualEpi>();
+  configure_ksplit<bf16_t, RouterEpi>();
+  configure_ksplit<float, RouterEpi>();
 }
 
 }  // namespace dinfer

@@ -16,52 +16,70 @@ template <typename E> __host__ __device__ constexpr int64_t task_stride_elems(in
   return (int64_t)ksteps * 2 * WAVE * ET<E>::G;
 }
 
-// Accumulate k-steps [ks0, ks1) of one task for TT token tiles.
-//   wtask : packed weights of the task (k-step 0), bp[tt]: this lane's activation row + (lane/32)*G in the
-//   hi plane; the lo plane (bf16 only) sits `plane` elements further.
+// Software-pipelined core: PF k-steps of loads are always in flight.  The loop body is straight-line (no
+// predicated loads), so the compiler can count outstanding loads exactly and every MFMA waits only for its own
+// operands; n must be a positive multiple of PF.
 template <typename E, int TT, int PF>
-__device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, const E* const (&bp)[TT],
-                                   int64_t plane, f32x16 (&acc0)[TT], f32x16 (&acc1)[TT]) {
+__device__ inline void stream_steps(const E* __restrict__ wp, const E* const (&bp)[TT], int64_t plane, int ks0, int n,
+                                    f32x16 (&acc0)[TT], f32x16 (&acc1)[TT]) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
-  const int lane = threadIdx.x & (WAVE - 1);
-  const E* wp = wtask + (int64_t)ks0 * (2 * WAVE * G) + lane * G;
-  const int n = ks1 - ks0;
+  constexpr int64_t STEP = 2 * WAVE * G;   // elements of packed weights per k-step
   vec a0[PF], a1[PF], b[PF][TT][NP];
 #pragma unroll
   for (int i = 0; i < PF; ++i) {
-    if (i < n) {
-      a0[i] = load16<E>(wp + (int64_t)i * (2 * WAVE * G));
-      a1[i] = load16<E>(wp + (int64_t)i * (2 * WAVE * G) + WAVE * G);
+    a0[i] = load16<E>(wp + i * STEP);
+    a1[i] = load16<E>(wp + i * STEP + WAVE * G);
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + i) * KS);
+  }
+  for (int s = 0; s + PF < n; s += PF) {
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
 #pragma unroll
       for (int t = 0; t < TT; ++t)
 #pragma unroll
-        for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + i) * KS);
-    }
-  }
-  for (int s = 0; s < n; s += PF) {
-#pragma unroll
-    for (int i = 0; i < PF; ++i) {
-      if (s + i < n) {
-#pragma unroll
-        for (int t = 0; t < TT; ++t)
-#pragma unroll
-          for (int q = 0; q < NP; ++q) {
-            mfma32(acc0[t], a0[i], b[i][t][q]);
-            mfma32(acc1[t], a1[i], b[i][t][q]);
-          }
-        const int nx = s + i + PF;
-        if (nx < n) {
-          a0[i] = load16<E>(wp + (int64_t)nx * (2 * WAVE * G));
-          a1[i] = load16<E>(wp + (int64_t)nx * (2 * WAVE * G) + WAVE * G);
-#pragma unroll
-          for (int t = 0; t < TT; ++t)
-#pragma unroll
-            for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + nx) * KS);
+        for (int q = 0; q < NP; ++q) {
+          mfma32(acc0[t], a0[i], b[i][t][q]);
+          mfma32(acc1[t], a1[i], b[i][t][q]);
         }
-      }
+      const int nx = s + i + PF;
+      a0[i] = load16<E>(wp + nx * STEP);
+      a1[i] = load16<E>(wp + nx * STEP + WAVE * G);
+#pragma unroll
+      for (int t = 0; t < TT; ++t)
+#pragma unroll
+        for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + nx) * KS);
     }
   }
+#pragma unroll
+  for (int i = 0; i < PF; ++i)
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        mfma32(acc0[t], a0[i], b[i][t][q]);
+        mfma32(acc1[t], a1[i], b[i][t][q]);
+      }
+}
+
+// Accumulate k-steps [ks0, ks1) of one task for TT token tiles.
+//   wtask : packed weights of the task (k-step 0), bp[tt]: this lane's activation row + (lane/32)*G in the
+//   hi plane; the lo plane (bf16 only) sits `plane` elements further.
+// The prefetch depth follows the step count (a wave-uniform choice): PFMAX when it divides, else 4, else 1.
+template <typename E, int TT, int PFMAX>
+__device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, const E* const (&bp)[TT],
+                                   int64_t plane, f32x16 (&acc0)[TT], f32x16 (&acc1)[TT]) {
+  constexpr int G = ET<E>::G;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const E* wp = wtask + (int64_t)ks0 * (2 * WAVE * G) + lane * G;
+  const int n = ks1 - ks0;
+  if (n <= 0) return;
+  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, bp, plane, ks0, n, acc0, acc1);
+  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, bp, plane, ks0, n, acc0, acc1);
+  else stream_steps<E, TT, 1>(wp, bp, plane, ks0, n, acc0, acc1);
 }
 
 template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {

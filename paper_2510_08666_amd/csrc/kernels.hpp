@@ -69,9 +69,12 @@ void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
 
 void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
                   hipStream_t st);
-void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
-                   int E, int top_k, int norm_topk, void* h, int64_t h_plane, int32_t* topk_idx, float* topk_w,
-                   hipStream_t st);
+void launch_norm(bool bf16, const float* x, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
+                 hipStream_t st);
+// Router logits h . w_router on the matrix cores (hi + lo planes: float32-grade inputs), softmax over the
+// experts, the top_k largest probabilities (ties to the lower expert id), renormalised when norm_topk.
+void launch_router(bool bf16, const void* w_router_packed, const void* h, int64_t h_plane, int T, int H, int E,
+                   int top_k, int norm_topk, int32_t* topk_idx, float* topk_w, hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st);
 
@@ -111,6 +114,7 @@ void launch_add_i32(int32_t* a, int n, int v, hipStream_t st);
 void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,
                     int n_pos, float* k, float* v, hipStream_t st);
 
-void configure_kernels();   // one-time function attributes (dynamic LDS limits)
+void configure_kernels();
+void configure_attention();   // one-time function attributes (dynamic LDS limits)
 
 }  // namespace dinfer

@@ -1,5 +1,5 @@
 // The non-GEMM kernels of the step: token bookkeeping, embedding + RMSNorm, expert-output combine + RMSNorm,
-// router (softmax + top-k), ballot-based token->expert permutation, LM-head partial merge, threshold commit,
+// RMSNorm, ballot-based token->expert permutation, LM-head partial merge, threshold commit,
 // and the KV import / export used by tests.
 #include "kernels.hpp"
 
@@ -105,6 +105,7 @@ void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const 
 }
 
 // x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  h[t] = RMSNorm(x[t]) * gain
+// Thread i owns columns 4*i + 1024*c .. +3 (hidden is a multiple of 64, so chunks are whole or absent).
 template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __restrict__ x, const float* __restrict__ O,
                                                                     const int32_t* __restrict__ pos_of_pair,
@@ -112,29 +113,47 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __res
                                                                     const float* __restrict__ gain, float eps, int H,
                                                                     E* __restrict__ h, int64_t h_plane) {
   __shared__ float sh[4];
+  constexpr int CH = NORM_MAX_PER_THREAD / 4;
   const int t = blockIdx.x;
-  float v[NORM_MAX_PER_THREAD];
+  int64_t orow[MAX_TOPK];
+  float w[MAX_TOPK];
+#pragma unroll
+  for (int j = 0; j < MAX_TOPK; ++j) {
+    orow[j] = j < top_k ? (int64_t)pos_of_pair[t * top_k + j] * H : 0;
+    w[j] = j < top_k ? topk_w[t * top_k + j] : 0.f;
+  }
+  f32x4 v[CH];
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    float acc = 0.f;
-    if (c < H) {
-      for (int j = 0; j < top_k; ++j)
-        acc += topk_w[t * top_k + j] * O[(int64_t)pos_of_pair[t * top_k + j] * H + c];
-      acc += x[(int64_t)t * H + c];
+  for (int c = 0; c < CH; ++c) {
+    const int col = 4 * threadIdx.x + c * 4 * NORM_THREADS;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (col < H) {
+#pragma unroll
+      for (int j = 0; j < MAX_TOPK; ++j)
+        if (j < top_k) {
+          const f32x4 o = *reinterpret_cast<const f32x4*>(O + orow[j] + col);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[i] += w[j] * o[i];
+        }
+      const f32x4 xr = *reinterpret_cast<const f32x4*>(x + (int64_t)t * H + col);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] += xr[i];
     }
-    v[i] = acc;
-    ss += acc * acc;
+    v[c] = acc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss += acc[i] * acc[i];
   }
   ss = block_sum_256(ss, sh);
   const float r = rsqrtf(ss / H + eps);
 #pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    if (c < H) {
-      x[(int64_t)t * H + c] = v[i];
-      store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
+  for (int c = 0; c < CH; ++c) {
+    const int col = 4 * threadIdx.x + c * 4 * NORM_THREADS;
+    if (col < H) {
+      *reinterpret_cast<f32x4*>(x + (int64_t)t * H + col) = v[c];
+      const f32x4 g = *reinterpret_cast<const f32x4*>(gain + col);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) store_act<E>(h, (int64_t)t * H + col + i, h_plane, v[c][i] * r * g[i]);
     }
   }
 }
@@ -145,18 +164,11 @@ void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos
   else combine_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (float*)h, h_plane);
 }
 
-// ---------------------------------------------------------------- router
-// h[t] = RMSNorm(x[t]) * gain (stored for the expert GEMMs); router logits from the unrounded float h;
-// softmax over the experts; the top_k largest probabilities, ties to the lower expert id.
+// ---------------------------------------------------------------- RMSNorm alone (before the router / experts)
 template <typename E>
-__global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                              float eps, const E* __restrict__ Wr, int H, int n_exp,
-                                                              int top_k, int norm_topk, E* __restrict__ h,
-                                                              int64_t h_plane, int32_t* __restrict__ topk_idx,
-                                                              float* __restrict__ topk_w) {
+__global__ __launch_bounds__(NORM_THREADS) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                            float eps, int H, E* __restrict__ h, int64_t h_plane) {
   __shared__ float sh[4];
-  __shared__ float hn[NORM_THREADS * NORM_MAX_PER_THREAD];
-  __shared__ float logit[MAX_EXPERTS];
   const int t = blockIdx.x;
   float v[NORM_MAX_PER_THREAD];
   float ss = 0.f;
@@ -171,51 +183,13 @@ __global__ __launch_bounds__(NORM_THREADS) void router_kernel(const float* __res
 #pragma unroll
   for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
     const int c = threadIdx.x + i * NORM_THREADS;
-    if (c < H) {
-      const float y = v[i] * r * gain[c];
-      hn[c] = y;
-      store_act<E>(h, (int64_t)t * H + c, h_plane, y);
-    }
-  }
-  __syncthreads();
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int e = wave; e < n_exp; e += 4) {
-    const E* w = Wr + (int64_t)e * H;
-    float acc = 0.f;
-    for (int c = lane; c < H; c += WAVE) acc += hn[c] * to_f32(w[c]);
-    acc = wave_sum(acc);
-    if (lane == 0) logit[e] = acc;
-  }
-  __syncthreads();
-  if (wave != 0) return;
-  const float z = lane < n_exp ? logit[lane] : -INFINITY;
-  const float m = wave_max(z);
-  const float ex = lane < n_exp ? expf(z - m) : 0.f;
-  const float p = ex / wave_sum(ex);
-  float val = lane < n_exp ? p : -1.f;
-  float wsel = 0.f, sel_sum = 0.f;    // lane j keeps the j-th selection
-  int isel = 0;
-  for (int j = 0; j < top_k; ++j) {
-    const float best = wave_max(val);
-    const uint64_t hit = __ballot(val == best);
-    const int winner = __ffsll((unsigned long long)hit) - 1;
-    if (lane == j) {
-      wsel = best;
-      isel = winner;
-    }
-    if (lane == winner) val = -1.f;
-    sel_sum += best;
-  }
-  if (lane < top_k) {
-    topk_idx[t * top_k + lane] = isel;
-    topk_w[t * top_k + lane] = norm_topk ? wsel / sel_sum : wsel;
+    if (c < H) store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
   }
 }
-void launch_router(bool bf16, const float* x, const float* gain, float eps, const void* w_router, int T, int H,
-                   int E, int top_k, int norm_topk, void* h, int64_t h_plane, int32_t* topk_idx, float* topk_w,
-                   hipStream_t st) {
-  if (bf16) router_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const bf16_t*)w_router, H, E, top_k, norm_topk, (bf16_t*)h, h_plane, topk_idx, topk_w);
-  else router_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, (const float*)w_router, H, E, top_k, norm_topk, (float*)h, h_plane, topk_idx, topk_w);
+void launch_norm(bool bf16, const float* x, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
+                 hipStream_t st) {
+  if (bf16) norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, H, (bf16_t*)h, h_plane);
+  else norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, H, (float*)h, h_plane);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
