@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run one plain 1 GiB device-to-device copy kernel (known traffic: "
+                         "1 GiB read + 1 GiB written) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported. "
@@ -106,6 +109,14 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
     launches, stage_ms = ctx.profile_stop()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     committed = float(n_committed.sum().item())
     routing = ctx.debug_get(1, (cfg.n_layers, T, cfg.top_k), torch.int32).cpu().numpy()

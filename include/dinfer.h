@@ -168,7 +168,8 @@ enum {
   DINFER_STAGE_EXPERT_GATE_UP = 3,
   DINFER_STAGE_EXPERT_DOWN = 4,
   DINFER_STAGE_LM_HEAD = 5,
-  DINFER_STAGE_COUNT = 6
+  DINFER_STAGE_ROUTER = 6,   /* RMSNorm statistics + router + top-k + permutation */
+  DINFER_STAGE_COUNT = 7
 };
 int dinfer_profile_start(dinfer_ctx* ctx, int32_t stage);
 int dinfer_profile_stop(dinfer_ctx* ctx, int32_t* n_launches, float* total_ms);

@@ -103,7 +103,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 }
 
 struct Workspace {
-  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, h, q, a, attn_part, topk_idx, topk_w, cnt, off,
+  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
       perm, pos_of_pair, y, o, lm_part, conf, argmax, total;
 };
 
@@ -121,8 +121,9 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.seq_nkeys = cv.take((size_t)max_seqs * 4);
   w.qtile = cv.take((size_t)max_qtiles * 3 * 4);
   w.x = cv.take(T * H * 4);
-  const size_t planes = c.dtype == DINFER_BF16 ? 2 : 1;   // bf16 activations are kept as hi + lo planes
-  w.h = cv.take(planes * T * H * es);
+  w.rinv_a = cv.take(T * 4);   // 1/rms of the residual rows entering the attention half / the LM head
+  w.rinv_f = cv.take(T * 4);   // ... entering the expert half
+  const size_t planes = c.dtype == DINFER_BF16 ? 2 : 1;   // stored bf16 activations are hi + lo planes
   w.q = cv.take(planes * T * D * es);
   w.a = cv.take(planes * T * D * es);
   size_t part = 0;   // the split policy depends on the number of query tiles only
@@ -209,22 +210,21 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   launch_meta(span, d_base, limit, at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
               at<int32_t>(ws, w.qtile), st);
   float* x = at<float>(ws, w.x);
-  void* h = ws + w.h;
-  const int64_t h_plane = (int64_t)c->max_tokens * H, a_plane = (int64_t)c->max_tokens * D,
-                y_plane = (int64_t)c->max_tokens * f.top_k * f.moe_inter;
+  float* rinv_a = at<float>(ws, w.rinv_a);
+  float* rinv_f = at<float>(ws, w.rinv_f);
+  const int64_t a_plane = (int64_t)c->max_tokens * D, y_plane = (int64_t)c->max_tokens * f.top_k * f.moe_inter;
   for (int l = 0; l < f.n_layers; ++l) {
     const LayerW& lw = c->wm.layers[l];
     char* kv_layer = c->kv + (size_t)l * c->kv_layer_bytes;
     int32_t* topk_idx = at<int32_t>(ws, w.topk_idx) + (size_t)l * T * f.top_k;
     float* topk_w = at<float>(ws, w.topk_w) + (size_t)l * T * f.top_k;
     if (l == 0)
-      launch_embed_norm(bf, d_tokens, c->weights + c->wm.emb, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H,
-                        f.vocab, x, h, h_plane, st);
+      launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a, st);
     else
-      launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k,
-                          f.top_k, at<float>(c->weights, lw.attn_gain), f.rms_eps, T, H, h, h_plane, st);
-    QkvArgs qa{c->weights + lw.wqkv, h, h_plane, ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride,
-               at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H};
+      launch_combine(x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k, f.top_k,
+                     f.rms_eps, T, H, rinv_a, st);
+    QkvArgs qa{c->weights + lw.wqkv, x, at<float>(c->weights, lw.attn_gain), rinv_a, ws + w.q, a_plane, kv_layer,
+               c->geom, meta, d_page_table, pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H};
     {
       StageTimer tm(c, DINFER_STAGE_QKV, st);
       launch_qkv(bf, qa, st);
@@ -239,13 +239,16 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       StageTimer tm(c, DINFER_STAGE_OPROJ, st);
       launch_oproj(bf, c->weights + lw.wo, ws + w.a, a_plane, x, T, D, H, st);
     }
-    launch_norm(bf, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, T, H, h, h_plane, st);
-    launch_router(bf, c->weights + lw.router, h, h_plane, T, H, f.n_experts, f.top_k, f.norm_topk, topk_idx, topk_w, st);
-    launch_permute(topk_idx, T * f.top_k, f.n_experts, at<int32_t>(ws, w.cnt),
-                   at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), st);
-    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, h, h_plane, ws + w.y, y_plane, at<float>(ws, w.o),
-                  at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off), at<int32_t>(ws, w.perm), T, H, f.moe_inter,
-                  f.n_experts, f.top_k};
+    RouterArgs ra{c->weights + lw.router, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, T, H, f.n_experts, f.top_k,
+                  f.norm_topk, rinv_f, topk_idx, topk_w, at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
+                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair)};
+    {
+      StageTimer tm(c, DINFER_STAGE_ROUTER, st);
+      launch_router(bf, ra, st);
+    }
+    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, x, at<float>(c->weights, lw.ffn_gain), rinv_f,
+                  ws + w.y, y_plane, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
+                  at<int32_t>(ws, w.perm), T, H, f.moe_inter, f.n_experts, f.top_k};
     {
       StageTimer tm(c, DINFER_STAGE_EXPERT_GATE_UP, st);
       launch_expert_gate_up(bf, ea, st);
@@ -255,10 +258,9 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       launch_expert_down(bf, ea, st);
     }
   }
-  // the last layer's expert outputs are folded into the residual here; the norm written to h is the final one
-  launch_combine_norm(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
-                      at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k,
-                      at<float>(c->weights, c->wm.final_gain), f.rms_eps, T, H, h, h_plane, st);
+  // the last layer's expert outputs are folded into the residual here; rinv_a then belongs to the final norm
+  launch_combine(x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
+                 at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a, st);
   (void)with_head;
   c->last_T = T;
   HIP_TRY(hipGetLastError());
@@ -353,8 +355,11 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     delete c;
     return fail(DINFER_EHIP, "hipHostMalloc failed");
   }
-  configure_kernels();
-  configure_attention();
+  if (!configure_kernels() || !configure_attention()) {
+    (void)hipHostFree(c->h_mask_pinned);
+    delete c;
+    return fail(DINFER_EHIP, "the runtime refused the kernels' LDS sizes");
+  }
   launch_rope_table(at<float>(c->ws, c->wsm.cos_tab), at<float>(c->ws, c->wsm.sin_tab), cfg->max_pos, cfg->head_dim,
                     cfg->rope_theta, (hipStream_t)stream);
   hipError_t e = hipGetLastError();
@@ -449,7 +454,8 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   if (rc != DINFER_OK) return rc;
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, (int64_t)c->max_tokens * f.hidden, T, f.hidden, f.vocab, f.logit_scale,
+  LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
+            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), nullptr};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
@@ -563,7 +569,8 @@ int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* strea
   if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
   if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.h, (int64_t)c->max_tokens * f.hidden, n_rows, f.hidden, f.vocab, f.logit_scale,
+  LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
+            at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());

@@ -267,11 +267,14 @@ template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, 
                                                                                   a.n_splits, (E*)a.out, a.out_plane);
 }
 
-void configure_attention() {
-  (void)hipFuncSetAttribute((const void*)attention_kernel<bf16_t, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<128>());
-  (void)hipFuncSetAttribute((const void*)attention_kernel<float, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<128>());
-  (void)hipFuncSetAttribute((const void*)attention_kernel<bf16_t, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<64>());
-  (void)hipFuncSetAttribute((const void*)attention_kernel<float, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<64>());
+bool configure_attention() {
+  const void* fns[4] = {(const void*)attention_kernel<bf16_t, 128>, (const void*)attention_kernel<float, 128>,
+                        (const void*)attention_kernel<bf16_t, 64>, (const void*)attention_kernel<float, 64>};
+  bool ok = true;
+  for (const void* fn : fns)
+    ok = ok && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds<128>()) == hipSuccess;
+  (void)hipGetLastError();
+  return ok;
 }
 
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st) {

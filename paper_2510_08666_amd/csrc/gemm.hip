@@ -1,6 +1,9 @@
 // The dense contractions of the step as weight-streaming MFMA kernels (core in gemm.hpp):
 //   QKV projection + rotary embedding + KV-page write, output projection + residual,
-//   routed-expert grouped GEMMs (gate/up + SwiGLU, down), LM head + streaming max / arg max / sum-exp.
+//   RMSNorm + router + top-k (+ token->expert permutation), routed-expert grouped GEMMs (gate/up + SwiGLU,
+//   down), LM head + streaming max / arg max / sum-exp.
+// RMSNorm is never materialised: kernels that consume a normalised residual stream read the float32 stream
+// itself (times the gain, see XLoader) and scale their accumulators by the row's 1/rms in the epilogue.
 #include "gemm.hpp"
 #include "kernels.hpp"
 
@@ -11,6 +14,9 @@ namespace dinfer {
 // waves each stream a K slice of the task's weights, partial tiles are summed through LDS in wave order
 // (deterministic), wave 0 runs the epilogue.
 // ------------------------------------------------------------------------------------------------
+// Epilogues receive, for one token (lane) and one accumulator tile pair, PER consecutive accumulator registers
+// v0 .. v0+PER-1 of tile 0 (a0) and tile 1 (a1): rows acc_row(v0, half) .. +PER-1 of each tile, which are PER
+// consecutive features (v0 is a multiple of PER, PER divides 4).
 template <typename E> struct QkvEpi {
   E* q;
   int64_t q_plane;
@@ -22,9 +28,12 @@ template <typename E> struct QkvEpi {
   int pt_stride;
   const float* cos_tab;
   const float* sin_tab;
-  int D;   // n_heads * head_dim
+  const float* rinv;   // [T] 1/rms of the token's residual row
+  int D;               // n_heads * head_dim
 
-  __device__ void operator()(int task, int tok, bool valid, int half, const f32x16& a0, const f32x16& a1) const {
+  template <int PER>
+  __device__ void apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+                        const float (&a1)[PER]) const {
     if (!valid) return;
     const int hd = geom.head_dim;
     const int per_head = hd / 64;
@@ -32,47 +41,46 @@ template <typename E> struct QkvEpi {
     const int pos = tok_pos[tok];
     const int page = safe_page(geom, page_table[(int64_t)tok_seq[tok] * pt_stride + pos / PAGE]);
     const int slot = pos % PAGE;
+    const float r = rinv[tok];
+    const int row0 = acc_row(v0, half);
     if (task < 2 * qk_tasks) {
       // rotary pair: a0 holds feature j of the head, a1 feature j + hd/2
       const bool is_k = task >= qk_tasks;
-      const int r = is_k ? task - qk_tasks : task;
-      const int head = r / per_head, jt = r % per_head;
+      const int rr = is_k ? task - qk_tasks : task;
+      const int head = rr / per_head, jt = rr % per_head;
+      const int j0 = jt * TILE + row0;
+      float lo[PER], hi[PER];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int j0 = jt * TILE + acc_row(4 * g, half);   // 4 consecutive features j0..j0+3
-        float lo[4], hi[4];
+      for (int i = 0; i < PER; ++i) {
+        const float c = cos_tab[(int64_t)pos * (hd / 2) + j0 + i];
+        const float s = sin_tab[(int64_t)pos * (hd / 2) + j0 + i];
+        const float a = a0[i] * r, b = a1[i] * r;
+        lo[i] = a * c - b * s;
+        hi[i] = b * c + a * s;
+      }
+      if (is_k) {
+        E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float c = cos_tab[(int64_t)pos * (hd / 2) + j0 + i];
-          const float s = sin_tab[(int64_t)pos * (hd / 2) + j0 + i];
-          const float a = a0[4 * g + i], b = a1[4 * g + i];
-          lo[i] = a * c - b * s;
-          hi[i] = b * c + a * s;
+        for (int i = 0; i < PER; ++i) {
+          dst[i] = from_f32<E>(lo[i]);
+          dst[hd / 2 + i] = from_f32<E>(hi[i]);
         }
-        if (is_k) {
-          E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
+      } else {
+        const int64_t dst = (int64_t)tok * D + head * hd + j0;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            dst[i] = from_f32<E>(lo[i]);
-            dst[hd / 2 + i] = from_f32<E>(hi[i]);
-          }
-        } else {
-          const int64_t dst = (int64_t)tok * D + head * hd + j0;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            store_act<E>(q, dst + i, q_plane, lo[i]);
-            store_act<E>(q, dst + hd / 2 + i, q_plane, hi[i]);
-          }
+        for (int i = 0; i < PER; ++i) {
+          store_act<E>(q, dst + i, q_plane, lo[i]);
+          store_act<E>(q, dst + hd / 2 + i, q_plane, hi[i]);
         }
       }
     } else {
       const int t = task - 2 * qk_tasks;   // adjacent tiles 2t, 2t+1 of V
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int f0 = (2 * t) * TILE + acc_row(v, half);
+      for (int i = 0; i < PER; ++i) {
+        const int f0 = (2 * t) * TILE + row0 + i;
         const int f1 = f0 + TILE;
-        kv_layer[kv_v_index(geom, page, f0 / hd, slot, f0 % hd)] = from_f32<E>(a0[v]);
-        kv_layer[kv_v_index(geom, page, f1 / hd, slot, f1 % hd)] = from_f32<E>(a1[v]);
+        kv_layer[kv_v_index(geom, page, f0 / hd, slot, f0 % hd)] = from_f32<E>(a0[i] * r);
+        kv_layer[kv_v_index(geom, page, f1 / hd, slot, f1 % hd)] = from_f32<E>(a1[i] * r);
       }
     }
   }
@@ -81,179 +89,127 @@ template <typename E> struct QkvEpi {
 struct ResidualEpi {
   float* x;
   int H;
-  __device__ void operator()(int task, int tok, bool valid, int half, const f32x16& a0, const f32x16& a1) const {
+  template <int PER>
+  __device__ void apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+                        const float (&a1)[PER]) const {
     if (!valid) return;
+    float* p0 = x + (int64_t)tok * H + (2 * task) * TILE + acc_row(v0, half);
+    float* p1 = p0 + TILE;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float* p0 = x + (int64_t)tok * H + (2 * task) * TILE + acc_row(4 * g, half);
-      float* p1 = p0 + TILE;
-      f32x4 r0 = *reinterpret_cast<f32x4*>(p0), r1 = *reinterpret_cast<f32x4*>(p1);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        r0[i] += a0[4 * g + i];
-        r1[i] += a1[4 * g + i];
-      }
-      *reinterpret_cast<f32x4*>(p0) = r0;
-      *reinterpret_cast<f32x4*>(p1) = r1;
+    for (int i = 0; i < PER; ++i) {
+      p0[i] += a0[i];
+      p1[i] += a1[i];
     }
   }
 };
 
-// Router: the single task holds experts 0-31 (tile 0) and 32-63 (tile 1).  A token's 64 probabilities sit in
-// the two lanes l and l^32; softmax and the k selection rounds combine the pair with one shuffle each.
-struct RouterEpi {
-  int n_exp, top_k, norm_topk;
-  int32_t* topk_idx;
-  float* topk_w;
-  __device__ void operator()(int /*task*/, int tok, bool valid, int half, const f32x16& a0, const f32x16& a1) const {
-    float p[32];
-    int id[32];
-    float m = -INFINITY;
+// Every wave leaves its partial accumulators in LDS: red[wave][t*32 + tile*16 + v][lane].
+template <int TT, int ROWS>
+__device__ inline void spill_partials(float* red, int wave, int lane, const f32x16 (&acc0)[TT], const f32x16 (&acc1)[TT]) {
+  float* r = red + (int64_t)wave * ROWS * WAVE + lane;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {      // ids ascend with the index within each lane
-      id[v] = acc_row(v, half);
-      id[16 + v] = TILE + acc_row(v, half);
-      p[v] = id[v] < n_exp ? a0[v] : -INFINITY;
-      p[16 + v] = id[16 + v] < n_exp ? a1[v] : -INFINITY;
+  for (int t = 0; t < TT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      r[(t * 32 + v) * WAVE] = acc0[t][v];
+      r[(t * 32 + 16 + v) * WAVE] = acc1[t][v];
     }
-#pragma unroll
-    for (int i = 0; i < 32; ++i) m = fmaxf(m, p[i]);
-    m = fmaxf(m, __shfl_xor(m, 32, WAVE));
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      p[i] = id[i] < n_exp ? expf(p[i] - m) : 0.f;
-      sum += p[i];
-    }
-    sum += __shfl_xor(sum, 32, WAVE);
-    const float inv = 1.f / sum;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) p[i] = id[i] < n_exp ? p[i] * inv : -1.f;
-    float wsel[MAX_TOPK];
-    int isel[MAX_TOPK];
-    float sel_sum = 0.f;
-#pragma unroll
-    for (int j = 0; j < MAX_TOPK; ++j) {
-      if (j < top_k) {
-        float bv = -1.f;
-        int bi = 0x7fffffff, slot = 0;
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-          if (p[i] > bv) {
-            bv = p[i];
-            bi = id[i];
-            slot = i;
-          }
-        const float ov = __shfl_xor(bv, 32, WAVE);
-        const int oi = __shfl_xor(bi, 32, WAVE);
-        const bool mine = bv > ov || (bv == ov && bi < oi);
-        wsel[j] = mine ? bv : ov;
-        isel[j] = mine ? bi : oi;
-        sel_sum += wsel[j];
-        if (mine) {
-#pragma unroll
-          for (int i = 0; i < 32; ++i)
-            if (i == slot) p[i] = -1.f;
-        }
-      }
-    }
-    if (valid && half == 0) {
-#pragma unroll
-      for (int j = 0; j < MAX_TOPK; ++j)
-        if (j < top_k) {
-          topk_idx[tok * top_k + j] = isel[j];
-          topk_w[tok * top_k + j] = norm_topk ? wsel[j] / sel_sum : wsel[j];
-        }
-    }
-  }
-};
+}
 
-template <typename E, int TT, int KSPLIT, class Epi>
+// XIN: the B operand is the float32 residual stream times `gain` (XLoader); else E planes (PlaneLoader).
+// After the K slices are streamed, the sum over the KSPLIT partials (wave order: deterministic) and the
+// epilogue are shared out: wave w finishes accumulator registers w*PER .. w*PER+PER-1 of both tiles.
+template <typename E, int TT, int KSPLIT, bool XIN, class Epi>
 __global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
-                                                                     const E* __restrict__ X, int64_t plane,
-                                                                     int T, int K, Epi epi) {
-  extern __shared__ float red[];   // [KSPLIT-1][2*TT*16][64]
-  constexpr int G = ET<E>::G;
+                                                                     const void* __restrict__ B, int64_t plane,
+                                                                     const float* __restrict__ gain, int T, int K,
+                                                                     Epi epi) {
+  extern __shared__ float red[];   // [KSPLIT][2*TT*16][64]
+  __shared__ float s_gain[XIN ? MAX_HIDDEN : 4];
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / KSPLIT;
   const int task = blockIdx.y, group = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int tok0 = group * TT * TILE;
-  const E* bp[TT];
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    const int tok = min(tok0 + t * TILE + (lane & 31), T - 1);
-    bp[t] = X + (int64_t)tok * K + half * G;
-  }
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int per = (ksteps + KSPLIT - 1) / KSPLIT;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  if (ks0 < ks1)
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, bp, plane, acc0,
-                                          acc1);
-  if (KSPLIT > 1) {
-    if (wave > 0) {
-      float* r = red + (int64_t)(wave - 1) * (2 * TT * 16) * WAVE + lane;
+  const E* wtask = W + (int64_t)task * task_stride_elems<E>(ksteps);
+  if (XIN) {
+    stage_gain(s_gain, gain, K);
+    XLoader<E, TT, false> ld;
 #pragma unroll
-      for (int t = 0; t < TT; ++t)
+    for (int t = 0; t < TT; ++t)
+      ld.xp[t] = (const float*)B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
+    ld.gs = s_gain + half * G;
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(wtask, ks0, ks1, ld, acc0, acc1);
+  } else {
+    PlaneLoader<E, TT> ld;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          r[(t * 32 + v) * WAVE] = acc0[t][v];
-          r[(t * 32 + 16 + v) * WAVE] = acc1[t][v];
-        }
+    for (int t = 0; t < TT; ++t)
+      ld.bp[t] = (const E*)B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
+    ld.plane = plane;
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(wtask, ks0, ks1, ld, acc0, acc1);
+  }
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  const int v0 = wave * PER;
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    float a0[PER], a1[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      a0[i] = 0.f;
+      a1[i] = 0.f;
     }
-    __syncthreads();
-    if (wave == 0) {
-      for (int w = 1; w < KSPLIT; ++w) {
-        const float* r = red + (int64_t)(w - 1) * (2 * TT * 16) * WAVE + lane;
+    for (int w = 0; w < KSPLIT; ++w) {
+      const float* r = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
 #pragma unroll
-        for (int t = 0; t < TT; ++t)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            acc0[t][v] += r[(t * 32 + v) * WAVE];
-            acc1[t][v] += r[(t * 32 + 16 + v) * WAVE];
-          }
+      for (int i = 0; i < PER; ++i) {
+        a0[i] += r[i * WAVE];
+        a1[i] += r[(16 + i) * WAVE];
       }
     }
-  }
-  if (wave == 0) {
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-      const int tok = tok0 + t * TILE + (lane & 31);
-      epi(task, tok, tok < T, half, acc0[t], acc1[t]);
-    }
+    const int tok = tok0 + t * TILE + (lane & 31);
+    epi.template apply<PER>(task, tok, tok < T, half, v0, a0, a1);
   }
 }
 
-template <int TT, int KSPLIT> constexpr size_t ksplit_lds() { return (size_t)(KSPLIT - 1) * 2 * TT * 16 * WAVE * 4; }
+template <int TT, int KSPLIT> constexpr size_t ksplit_lds() { return (size_t)KSPLIT * 2 * TT * 16 * WAVE * 4; }
 
-template <typename E, class Epi>
-static void launch_ksplit(const E* W, int ksteps, const E* X, int64_t plane, int T, int K, int n_tasks,
-                          const Epi& epi, hipStream_t st) {
+template <typename E, bool XIN, class Epi>
+static void launch_ksplit(const E* W, int ksteps, const void* B, int64_t plane, const float* gain, int T, int K,
+                          int n_tasks, const Epi& epi, hipStream_t st) {
   if (T <= 32) {
-    gemm_ksplit_kernel<E, 1, 8, Epi><<<dim3(1, n_tasks), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(W, ksteps, X, plane, T, K, epi);
+    gemm_ksplit_kernel<E, 1, 8, XIN, Epi><<<dim3(1, n_tasks), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
   } else if (T <= 64) {
-    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(1, n_tasks), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, X, plane, T, K, epi);
+    gemm_ksplit_kernel<E, 2, 4, XIN, Epi><<<dim3(1, n_tasks), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(groups, n_tasks), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, X, plane, T, K, epi);
+    gemm_ksplit_kernel<E, 4, 4, XIN, Epi><<<dim3(groups, n_tasks), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
   }
 }
 
-template <typename E, class Epi> static void configure_ksplit() {
-  (void)hipFuncSetAttribute((const void*)gemm_ksplit_kernel<E, 1, 8, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)ksplit_lds<1, 8>());
-  (void)hipFuncSetAttribute((const void*)gemm_ksplit_kernel<E, 2, 4, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)ksplit_lds<2, 4>());
-  (void)hipFuncSetAttribute((const void*)gemm_ksplit_kernel<E, 4, 4, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)ksplit_lds<4, 4>());
+// Static + dynamic LDS of these kernels can pass the 64 KiB default: opt in to the 160 KiB LDS of gfx950
+// (dynamic limit = what the kernel's static LDS leaves).  Returns false if the runtime refuses.
+static bool opt_in_lds(const void* fn) {
+  hipFuncAttributes fa;
+  if (hipFuncGetAttributes(&fa, fn) != hipSuccess) return false;
+  const int room = 160 * 1024 - (int)fa.sharedSizeBytes;
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, room) == hipSuccess;
+}
+template <typename E, bool XIN, class Epi> static bool configure_ksplit() {
+  return opt_in_lds((const void*)gemm_ksplit_kernel<E, 1, 8, XIN, Epi>) &&
+         opt_in_lds((const void*)gemm_ksplit_kernel<E, 2, 4, XIN, Epi>) &&
+         opt_in_lds((const void*)gemm_ksplit_kernel<E, 4, 4, XIN, Epi>);
 }
 
 template <typename E> static void launch_qkv_t(const QkvArgs& a, hipStream_t st) {
   const int D = a.geom.n_heads * a.geom.head_dim;
-  QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table, a.pt_stride,
-                a.cos_tab, a.sin_tab, D};
-  launch_ksplit<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.h, a.act_plane, a.T, a.H, 3 * D / 64, epi, st);
+  QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
+                a.pt_stride, a.cos_tab, a.sin_tab, a.rinv, D};
+  launch_ksplit<E, true>((const E*)a.w, a.H / ET<E>::KS, a.x, 0, a.gain, a.T, a.H, 3 * D / 64, epi, st);
 }
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
   if (bf16) launch_qkv_t<bf16_t>(a, st);
@@ -263,61 +219,294 @@ void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
 void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
                   hipStream_t st) {
   ResidualEpi epi{x, H};
-  if (bf16) launch_ksplit<bf16_t>((const bf16_t*)w, D / 16, (const bf16_t*)a, act_plane, T, D, H / 64, epi, st);
-  else launch_ksplit<float>((const float*)w, D / 8, (const float*)a, act_plane, T, D, H / 64, epi, st);
+  if (bf16) launch_ksplit<bf16_t, false>((const bf16_t*)w, D / 16, a, act_plane, nullptr, T, D, H / 64, epi, st);
+  else launch_ksplit<float, false>((const float*)w, D / 8, a, act_plane, nullptr, T, D, H / 64, epi, st);
 }
 
-void launch_router(bool bf16, const void* w_router_packed, const void* h, int64_t h_plane, int T, int H, int E,
-                   int top_k, int norm_topk, int32_t* topk_idx, float* topk_w, hipStream_t st) {
-  RouterEpi epi{E, top_k, norm_topk, topk_idx, topk_w};
-  if (bf16) launch_ksplit<bf16_t>((const bf16_t*)w_router_packed, H / 16, (const bf16_t*)h, h_plane, T, H, 1, epi, st);
-  else launch_ksplit<float>((const float*)w_router_packed, H / 8, (const float*)h, h_plane, T, H, 1, epi, st);
+// ------------------------------------------------------------------------------------------------
+// Router.  One workgroup per token group: its KSPLIT waves split K; each reads the float32 residual rows
+// (XLoader, which also sums their squares); the single weight task holds experts 0-31 (tile 0) and 32-63
+// (tile 1).  Every wave leaves its partial in LDS; then all threads fold the partials into logits[token][expert]
+// (times the row's 1/rms), and groups of 16 lanes (4 experts per lane) take one token each through softmax and
+// the k selection rounds (ties to the lower expert id).  With a single token group the same workgroup goes on
+// to build the token->expert permutation.
+// ------------------------------------------------------------------------------------------------
+// All-reduce over the 16 lanes of a group.
+__device__ inline float group16_max(float v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+__device__ inline float group16_sum(float v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
+// Token->expert permutation of at most 8*64 pairs whose expert ids sit in LDS (s_idx): a stable counting sort
+// by wavefront ballots.  A wave takes 64 consecutive pairs; for every expert e the ballot of "my pair goes to e"
+// gives that chunk's count (kept by lane e) and, through the bits below a lane, the pair's rank inside the
+// chunk.  Lane e of wave 0 then turns the per-chunk counts into offsets.  s_cc: [8][MAX_EXPERTS] ints.
+__device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, int n_exp, int32_t* __restrict__ cnt,
+                                            int32_t* __restrict__ off, int32_t* __restrict__ perm,
+                                            int32_t* __restrict__ pos_of_pair, int32_t* s_cc) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int my_e[2], my_rank[2];   // a wave owns chunks wave and wave + n_waves (n_waves >= 4, n_chunks <= 8)
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = wave + i * n_waves;
+    my_e[i] = -1;
+    my_rank[i] = 0;
+    if (c < n_chunks) {
+      const int p = c * WAVE + lane;
+      my_e[i] = p < n_pairs ? s_idx[p] : -1;
+      int mine_cnt = 0;
+      for (int e = 0; e < n_exp; ++e) {
+        const uint64_t b = __ballot(my_e[i] == e);
+        if (lane == e) mine_cnt = __popcll(b);
+        if (my_e[i] == e) my_rank[i] = __popcll(b & below);
+      }
+      s_cc[c * MAX_EXPERTS + lane] = mine_cnt;     // lane = expert id (n_exp <= 64)
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int tot = 0;
+    for (int c = 0; c < n_chunks; ++c) tot += s_cc[c * MAX_EXPERTS + lane];
+    if (lane >= n_exp) tot = 0;
+    int incl = tot;   // inclusive scan over the lanes (experts)
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += up;
+    }
+    const int start = incl - tot;
+    if (lane < n_exp) {
+      cnt[lane] = tot;
+      off[lane] = start;
+      if (lane == n_exp - 1) off[n_exp] = incl;
+    }
+    int run = start;
+    for (int c = 0; c < n_chunks; ++c) {
+      const int here = s_cc[c * MAX_EXPERTS + lane];
+      s_cc[c * MAX_EXPERTS + lane] = run;          // becomes: first sorted position of (chunk c, expert lane)
+      run += here;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = wave + i * n_waves;
+    if (c < n_chunks && my_e[i] >= 0) {
+      const int p = c * WAVE + lane;
+      const int r = s_cc[c * MAX_EXPERTS + my_e[i]] + my_rank[i];
+      perm[r] = p;
+      pos_of_pair[p] = r;
+    }
+  }
+}
+
+template <typename E, int TT, int KSPLIT>
+__global__ __launch_bounds__(KSPLIT * WAVE) void router_kernel(const E* __restrict__ W, const float* __restrict__ x,
+                                                                const float* __restrict__ gain, float eps, int T, int H,
+                                                                int n_exp, int top_k, int norm_topk,
+                                                                float* __restrict__ rinv, int32_t* __restrict__ topk_idx,
+                                                                float* __restrict__ topk_w, int fuse_permute,
+                                                                int32_t* __restrict__ cnt, int32_t* __restrict__ off,
+                                                                int32_t* __restrict__ perm,
+                                                                int32_t* __restrict__ pos_of_pair) {
+  extern __shared__ float red[];   // [KSPLIT][2*TT*16 + TT][64] partials, then logits [TT*32][64]
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16 + TT, NTOK = TT * TILE, NTHREADS = KSPLIT * WAVE;
+  __shared__ float s_gain[MAX_HIDDEN];
+  constexpr int LOGIT_STRIDE = MAX_EXPERTS + 1;
+  __shared__ float s_logit[NTOK * LOGIT_STRIDE];
+  __shared__ int32_t s_idx[NTOK * MAX_TOPK];
+  __shared__ int32_t s_cc[8 * MAX_EXPERTS];
+  const int group = blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int tok0 = group * NTOK;
+  const int ksteps = H / ET<E>::KS;
+  f32x16 acc0[TT], acc1[TT];
+  zero_acc<TT>(acc0);
+  zero_acc<TT>(acc1);
+  XLoader<E, TT, true> ld;
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    ld.xp[t] = x + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * H + half * G;
+    ld.ss[t] = 0.f;
+  }
+  stage_gain(s_gain, gain, H);
+  ld.gs = s_gain + half * G;
+  const int per = (ksteps + KSPLIT - 1) / KSPLIT;
+  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
+  {
+    float* r = red + (int64_t)wave * ROWS * WAVE + lane;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+      r[(2 * TT * 16 + t) * WAVE] = ld.ss[t] + __shfl_xor(ld.ss[t], 32, WAVE);   // both halves of the row slice
+  }
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  // logits[token][expert] = (sum over the waves' partials) / rms(token).  A thread takes one accumulator
+  // register of one source lane, so that LDS reads run along the lanes (conflict free); the logit rows are
+  // padded by one float so that the transposed writes spread over the banks as well.
+  for (int item = threadIdx.x; item < 2 * TT * 16 * WAVE; item += NTHREADS) {
+    const int rr = item / WAVE, src_lane = item % WAVE;              // rr = t*32 + tile*16 + v
+    const int t = rr / 32, tile = (rr / 16) & 1, v = rr % 16;
+    const int tl = t * TILE + (src_lane & 31);
+    const int e = tile * TILE + acc_row(v, src_lane >> 5);
+    float sum = 0.f, ss = 0.f;
+    for (int w = 0; w < KSPLIT; ++w) {
+      sum += red[((int64_t)w * ROWS + rr) * WAVE + src_lane];
+      ss += red[((int64_t)w * ROWS + 2 * TT * 16 + t) * WAVE + (src_lane & 31)];
+    }
+    const float r = rsqrtf(ss / H + eps);
+    s_logit[tl * LOGIT_STRIDE + e] = sum * r;
+    if (e == 0 && tok0 + tl < T) rinv[tok0 + tl] = r;
+  }
+  __syncthreads();
+  // 16 lanes per token, 4 consecutive experts per lane
+  const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
+  for (int tl = grp; tl < NTOK; tl += NTHREADS / 16) {
+    float p[4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = 4 * sub + i < n_exp ? s_logit[tl * LOGIT_STRIDE + 4 * sub + i] : -INFINITY;
+      m = fmaxf(m, p[i]);
+    }
+    m = group16_max(m);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = 4 * sub + i < n_exp ? expf(p[i] - m) : 0.f;
+      sum += p[i];
+    }
+    const float inv = 1.f / group16_sum(sum);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = 4 * sub + i < n_exp ? p[i] * inv : -1.f;
+    float wsel = 0.f, sel_sum = 0.f;   // lane j of the group keeps the j-th selection
+    int isel = 0;
+    for (int j = 0; j < top_k; ++j) {
+      float bv = -1.f;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (p[i] > bv) {               // ids ascend with i: strict '>' keeps the lowest id
+          bv = p[i];
+          bi = 4 * sub + i;
+        }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, WAVE);
+        const int oi = __shfl_xor(bi, o, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) {
+          bv = ov;
+          bi = oi;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (4 * sub + i == bi) p[i] = -1.f;
+      if (sub == j) {
+        wsel = bv;
+        isel = bi;
+      }
+      sel_sum += bv;
+    }
+    if (sub < top_k) {
+      const int tok = tok0 + tl;
+      if (tok < T) {
+        topk_idx[tok * top_k + sub] = isel;
+        topk_w[tok * top_k + sub] = norm_topk ? wsel / sel_sum : wsel;
+      }
+      s_idx[tl * top_k + sub] = tok < T ? isel : -1;
+    }
+  }
+  if (!fuse_permute) return;
+  __syncthreads();
+  ballot_permute_small(s_idx, T * top_k, n_exp, cnt, off, perm, pos_of_pair, s_cc);
+}
+
+template <int TT, int KSPLIT> constexpr size_t router_lds() { return (size_t)KSPLIT * (2 * TT * 16 + TT) * WAVE * 4; }
+
+template <typename E> static void launch_router_t(const RouterArgs& a, hipStream_t st) {
+  const E* W = (const E*)a.w;
+  if (a.T <= 32) {
+    router_kernel<E, 1, 8><<<1, 8 * WAVE, router_lds<1, 8>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk,
+                                                                   a.rinv, a.topk_idx, a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair);
+  } else if (a.T <= 64) {
+    router_kernel<E, 2, 4><<<1, 4 * WAVE, router_lds<2, 4>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk,
+                                                                   a.rinv, a.topk_idx, a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair);
+  } else {
+    const int groups = (a.T + 2 * TILE - 1) / (2 * TILE);
+    router_kernel<E, 2, 4><<<groups, 4 * WAVE, router_lds<2, 4>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k,
+                                                                        a.norm_topk, a.rinv, a.topk_idx, a.topk_w, 0, a.cnt, a.off,
+                                                                        a.perm, a.pos_of_pair);
+    launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, st);
+  }
+}
+void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
+  if (bf16) launch_router_t<bf16_t>(a, st);
+  else launch_router_t<float>(a, st);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Routed experts.  Rows of expert e are the pairs perm[off[e] .. off[e]+cnt[e]) (pair = token*top_k + slot).
 // One wave per (expert, task, row group); experts without rows exit at once.
-//   GEMM 1: task = 32 gate features + the same 32 up features;  y = silu(gate) * up   -> Y[sorted row][I]
+//   GEMM 1: task = 32 gate features + the same 32 up features; input = residual rows (XLoader), scaled by the
+//           row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
 //   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[sorted row][H]
 // ------------------------------------------------------------------------------------------------
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
 template <typename E, int TT>
-__global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__ W, const E* __restrict__ Hn,
-                                                            E* __restrict__ Y, const int32_t* __restrict__ cnt,
+__global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__ W, const float* __restrict__ x,
+                                                            const float* __restrict__ gain,
+                                                            const float* __restrict__ rinv, E* __restrict__ Y,
+                                                            const int32_t* __restrict__ cnt,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ perm, int H, int I,
-                                                            int top_k, int64_t h_plane, int64_t y_plane) {
+                                                            int top_k, int64_t y_plane) {
   constexpr int G = ET<E>::G;
+  __shared__ float s_gain[MAX_HIDDEN];
   const int e = blockIdx.y, group = blockIdx.z;
   const int n_rows = cnt[e];
   const int row0 = group * TT * TILE;
-  if (row0 >= n_rows) return;
+  if (row0 >= n_rows) return;            // uniform over the block
+  stage_gain(s_gain, gain, H);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int task = blockIdx.x * 4 + wave;
   const int n_tasks = I / TILE;
   if (task >= n_tasks) return;
   const int base = off[e];
-  const E* bp[TT];
+  XLoader<E, TT, false> ld;
   int row[TT];
+  float r[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
-    const int pair = perm[base + min(row[t], n_rows - 1)];
-    bp[t] = Hn + (int64_t)(pair / top_k) * H + half * G;
+    const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
+    ld.xp[t] = x + (int64_t)tok * H + half * G;
+    r[t] = rinv[tok];
   }
+  ld.gs = s_gain + half * G;
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = H / ET<E>::KS;
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, h_plane, acc0,
-                        acc1);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, ld,
+                                        acc0, acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     if (row[t] < n_rows) {
       E* yrow = Y + (int64_t)(base + row[t]) * I + task * TILE;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) store_act<E>(yrow, acc_row(v, half), y_plane, silu_f(acc0[t][v]) * acc1[t][v]);
+      for (int v = 0; v < 16; ++v)
+        store_act<E>(yrow, acc_row(v, half), y_plane, silu_f(acc0[t][v] * r[t]) * (acc1[t][v] * r[t]));
     }
   }
 }
@@ -337,19 +526,20 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
   const int n_tasks = H / (2 * TILE);
   if (task >= n_tasks) return;
   const int base = off[e];
-  const E* bp[TT];
+  PlaneLoader<E, TT> ld;
   int row[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
-    bp[t] = Y + (int64_t)(base + min(row[t], n_rows - 1)) * I + half * G;
+    ld.bp[t] = Y + (int64_t)(base + min(row[t], n_rows - 1)) * I + half * G;
   }
+  ld.plane = y_plane;
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = I / ET<E>::KS;
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, bp, y_plane, acc0,
-                        acc1);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, ld,
+                                        acc0, acc1);
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     if (row[t] < n_rows) {
@@ -372,7 +562,7 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
 template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
   const int t1 = a.I / TILE;
   expert_gemm1_kernel<E, TT><<<dim3((t1 + 3) / 4, a.E, groups), 256, 0, st>>>(
-      (const E*)a.w_gate_up, (const E*)a.h, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.h_plane, a.y_plane);
+      (const E*)a.w_gate_up, a.x, a.gain, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.y_plane);
 }
 template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
   const int t2 = a.H / (2 * TILE);
@@ -398,33 +588,39 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER
 // LM head fused with the confidence reduction.  Each wave walks tasks (64 vocabulary ids each) and keeps,
 // per token column, the running maximum logit, its lowest id, and sum exp(z - max); logits are never stored
 // (unless the debug pointer is set).  One partial (max, sum, id) per (wave, token) is written at the end.
+// Input: the residual rows (XLoader with the final gain); logit = acc * (1/rms of the row) * logit_scale.
 // ------------------------------------------------------------------------------------------------
 template <typename E, int TT>
-__global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, const E* __restrict__ Hn, int T,
-                                                       int H, int V, float scale, float* __restrict__ part,
-                                                       int n_waves, float* __restrict__ logits_out, int64_t plane) {
+__global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, const float* __restrict__ x,
+                                                       const float* __restrict__ gain, const float* __restrict__ rinv,
+                                                       int T, int H, int V, float scale, float* __restrict__ part,
+                                                       int n_waves, float* __restrict__ logits_out) {
   constexpr int G = ET<E>::G;
+  __shared__ float s_gain[MAX_HIDDEN];
+  stage_gain(s_gain, gain, H);
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
   const int group = blockIdx.y;
   const int tok0 = group * TT * TILE;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
   const int ksteps = H / ET<E>::KS;
-  const E* bp[TT];
-  float m[TT], s[TT];
+  XLoader<E, TT, false> ld;
+  float m[TT], s[TT], zs[TT];
   int best[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int tok = min(tok0 + t * TILE + (lane & 31), T - 1);
-    bp[t] = Hn + (int64_t)tok * H + half * G;
+    ld.xp[t] = x + (int64_t)tok * H + half * G;
+    zs[t] = rinv[tok] * scale;
     m[t] = -INFINITY;
     s[t] = 0.f;
     best[t] = 0x7fffffff;
   }
+  ld.gs = s_gain + half * G;
   for (int task = wave; task < n_tasks; task += n_waves) {
     f32x16 acc0[TT], acc1[TT];
     zero_acc<TT>(acc0);
     zero_acc<TT>(acc1);
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, bp, plane, acc0, acc1);
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, ld, acc0, acc1);
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
       const int tok = tok0 + t * TILE + (lane & 31);
@@ -437,8 +633,8 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
       for (int v = 0; v < 16; ++v) {
         id[v] = (2 * task) * TILE + acc_row(v, half);
         id[16 + v] = id[v] + TILE;
-        z[v] = id[v] < V ? acc0[t][v] * scale : -INFINITY;
-        z[16 + v] = id[16 + v] < V ? acc1[t][v] * scale : -INFINITY;
+        z[v] = id[v] < V ? acc0[t][v] * zs[t] : -INFINITY;
+        z[16 + v] = id[16 + v] < V ? acc1[t][v] * zs[t] : -INFINITY;
       }
 #pragma unroll
       for (int v = 0; v < 32; ++v)
@@ -498,16 +694,16 @@ int lm_head_waves(int V) {
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = a.n_lm_waves / 4;
   if (a.T <= 32) {
-    lm_head_kernel<E, 1><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out, a.act_plane);
+    lm_head_kernel<E, 1><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale, a.part,
+                                                        a.n_lm_waves, a.logits_out);
   } else if (a.T <= 64) {
-    lm_head_kernel<E, 2><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out, a.act_plane);
+    lm_head_kernel<E, 2><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale, a.part,
+                                                        a.n_lm_waves, a.logits_out);
   } else {
     // token groups of 128 rows: the partials of group g live in rows [g*128, ...) of the same table
     const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    lm_head_kernel<E, 4><<<dim3(wgs, groups), 256, 0, st>>>((const E*)a.w, (const E*)a.h, a.T, a.H, a.V, a.scale,
-                                                             a.part, a.n_lm_waves, a.logits_out, a.act_plane);
+    lm_head_kernel<E, 4><<<dim3(wgs, groups), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale,
+                                                             a.part, a.n_lm_waves, a.logits_out);
   }
 }
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
@@ -515,13 +711,13 @@ void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
   else launch_lm_t<float>(a, st);
 }
 
-void configure_kernels() {
-  configure_ksplit<bf16_t, QkvEpi<bf16_t>>();
-  configure_ksplit<float, QkvEpi<float>>();
-  configure_ksplit<bf16_t, ResidualEpi>();
-  configure_ksplit<float, ResidualEpi>();
-  configure_ksplit<bf16_t, RouterEpi>();
-  configure_ksplit<float, RouterEpi>();
+bool configure_kernels() {
+  bool ok = configure_ksplit<bf16_t, true, QkvEpi<bf16_t>>() && configure_ksplit<float, true, QkvEpi<float>>() &&
+            configure_ksplit<bf16_t, false, ResidualEpi>() && configure_ksplit<float, false, ResidualEpi>();
+  ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
+       opt_in_lds((const void*)router_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)router_kernel<float, 2, 4>);
+  (void)hipGetLastError();
+  return ok;
 }
 
 }  // namespace dinfer

@@ -7,6 +7,11 @@
 //   a task is a pair of 32-feature tiles that one wave accumulates together (the pairing is chosen per
 //   matrix so that the epilogue finds its partner values in the same lane: rotary pairs, gate/up, ...);
 //   lane l of a tile holds feature l%32 and the G input features  kstep*KS + (l/32)*G ... +G.
+//
+// The B operand comes from a Loader:
+//   Raw  issue(t, ks)                 start the loads of token tile t, k-step ks; the data is not touched
+//   void finish(raw, t, ks, out[NP])  turn them into the NP MFMA operands (hi / lo planes for bf16)
+// Keeping the two apart lets the pipeline below issue loads PF k-steps ahead of their use.
 #pragma once
 #include "common.hpp"
 
@@ -16,70 +21,135 @@ template <typename E> __host__ __device__ constexpr int64_t task_stride_elems(in
   return (int64_t)ksteps * 2 * WAVE * ET<E>::G;
 }
 
+// Activations already stored as Planes<E>::N planes of E (attention output, expert intermediate).
+template <typename E, int TT> struct PlaneLoader {
+  typedef typename ET<E>::vec vec;
+  static constexpr int NP = Planes<E>::N, KS = ET<E>::KS;
+  struct Raw {
+    vec p[NP];
+  };
+  const E* bp[TT];   // this lane's row + (lane/32)*G, hi plane
+  int64_t plane;     // elements from the hi plane to the lo plane
+  __device__ Raw issue(int t, int ks) const {
+    Raw r;
+#pragma unroll
+    for (int q = 0; q < NP; ++q) r.p[q] = load16<E>(bp[t] + q * plane + (int64_t)ks * KS);
+    return r;
+  }
+  __device__ void finish(const Raw& r, int, int, vec (&out)[NP]) {
+#pragma unroll
+    for (int q = 0; q < NP; ++q) out[q] = r.p[q];
+  }
+};
+
+// Rows of the float32 residual stream, multiplied by the RMSNorm gain and split into hi / lo on the fly.  The
+// row's 1/rms factor is NOT applied here: the contraction is linear in it, so the consumer's epilogue scales its
+// accumulators by it.  With SUMSQ the lane also accumulates the squares of the x values it saw.
+template <typename E, int TT, bool SUMSQ> struct XLoader {
+  typedef typename ET<E>::vec vec;
+  static constexpr int NP = Planes<E>::N, KS = ET<E>::KS, G = ET<E>::G;
+  struct Raw {
+    f32x4 x[G / 4];
+  };
+  const float* xp[TT];   // this lane's row + (lane/32)*G
+  const float* gs;       // the gain vector staged in LDS (stage_gain) + (lane/32)*G
+  float ss[TT];
+  __device__ Raw issue(int t, int ks) const {
+    Raw r;
+#pragma unroll
+    for (int j = 0; j < G / 4; ++j) r.x[j] = *reinterpret_cast<const f32x4*>(xp[t] + (int64_t)ks * KS + 4 * j);
+    return r;
+  }
+  __device__ void finish(const Raw& r, int t, int ks, vec (&out)[NP]) {
+#pragma unroll
+    for (int j = 0; j < G / 4; ++j) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(gs + ks * KS + 4 * j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x = r.x[j][i];
+        if (SUMSQ) ss[t] += x * x;
+        const float v = x * g[i];
+        const E hi = from_f32<E>(v);
+        out[0][4 * j + i] = hi;
+        if (NP == 2) out[NP - 1][4 * j + i] = from_f32<E>(v - to_f32(hi));
+      }
+    }
+  }
+};
+
+constexpr int MAX_HIDDEN = 4096;
+// Copies the gain vector into LDS for the XLoaders of a workgroup (ends with a barrier).
+__device__ inline void stage_gain(float* s_gain, const float* __restrict__ gain, int H) {
+  for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4)
+    *reinterpret_cast<f32x4*>(s_gain + c) = *reinterpret_cast<const f32x4*>(gain + c);
+  __syncthreads();
+}
+
 // Software-pipelined core: PF k-steps of loads are always in flight.  The loop body is straight-line (no
 // predicated loads), so the compiler can count outstanding loads exactly and every MFMA waits only for its own
 // operands; n must be a positive multiple of PF.
-template <typename E, int TT, int PF>
-__device__ inline void stream_steps(const E* __restrict__ wp, const E* const (&bp)[TT], int64_t plane, int ks0, int n,
-                                    f32x16 (&acc0)[TT], f32x16 (&acc1)[TT]) {
+template <typename E, int TT, int PF, class Loader>
+__device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks0, int n, f32x16 (&acc0)[TT],
+                                    f32x16 (&acc1)[TT]) {
   typedef typename ET<E>::vec vec;
-  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  constexpr int G = ET<E>::G, NP = Planes<E>::N;
   constexpr int64_t STEP = 2 * WAVE * G;   // elements of packed weights per k-step
-  vec a0[PF], a1[PF], b[PF][TT][NP];
+  vec a0[PF], a1[PF];
+  typename Loader::Raw raw[PF][TT];
 #pragma unroll
   for (int i = 0; i < PF; ++i) {
     a0[i] = load16<E>(wp + i * STEP);
     a1[i] = load16<E>(wp + i * STEP + WAVE * G);
 #pragma unroll
-    for (int t = 0; t < TT; ++t)
-#pragma unroll
-      for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + i) * KS);
+    for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + i);
   }
   for (int s = 0; s + PF < n; s += PF) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
 #pragma unroll
-      for (int t = 0; t < TT; ++t)
+      for (int t = 0; t < TT; ++t) {
+        vec b[NP];
+        ld.finish(raw[i][t], t, ks0 + s + i, b);
 #pragma unroll
         for (int q = 0; q < NP; ++q) {
-          mfma32(acc0[t], a0[i], b[i][t][q]);
-          mfma32(acc1[t], a1[i], b[i][t][q]);
+          mfma32(acc0[t], a0[i], b[q]);
+          mfma32(acc1[t], a1[i], b[q]);
         }
+      }
       const int nx = s + i + PF;
       a0[i] = load16<E>(wp + nx * STEP);
       a1[i] = load16<E>(wp + nx * STEP + WAVE * G);
 #pragma unroll
-      for (int t = 0; t < TT; ++t)
-#pragma unroll
-        for (int q = 0; q < NP; ++q) b[i][t][q] = load16<E>(bp[t] + q * plane + (int64_t)(ks0 + nx) * KS);
+      for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + nx);
     }
   }
 #pragma unroll
   for (int i = 0; i < PF; ++i)
 #pragma unroll
-    for (int t = 0; t < TT; ++t)
+    for (int t = 0; t < TT; ++t) {
+      vec b[NP];
+      ld.finish(raw[i][t], t, ks0 + n - PF + i, b);
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        mfma32(acc0[t], a0[i], b[i][t][q]);
-        mfma32(acc1[t], a1[i], b[i][t][q]);
+        mfma32(acc0[t], a0[i], b[q]);
+        mfma32(acc1[t], a1[i], b[q]);
       }
+    }
 }
 
-// Accumulate k-steps [ks0, ks1) of one task for TT token tiles.
-//   wtask : packed weights of the task (k-step 0), bp[tt]: this lane's activation row + (lane/32)*G in the
-//   hi plane; the lo plane (bf16 only) sits `plane` elements further.
+// Accumulate k-steps [ks0, ks1) of one task for TT token tiles; wtask = packed weights of the task (k-step 0).
 // The prefetch depth follows the step count (a wave-uniform choice): PFMAX when it divides, else 4, else 1.
-template <typename E, int TT, int PFMAX>
-__device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, const E* const (&bp)[TT],
-                                   int64_t plane, f32x16 (&acc0)[TT], f32x16 (&acc1)[TT]) {
+template <typename E, int TT, int PFMAX, class Loader>
+__device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, Loader& ld, f32x16 (&acc0)[TT],
+                                   f32x16 (&acc1)[TT]) {
   constexpr int G = ET<E>::G;
   const int lane = threadIdx.x & (WAVE - 1);
   const E* wp = wtask + (int64_t)ks0 * (2 * WAVE * G) + lane * G;
   const int n = ks1 - ks0;
   if (n <= 0) return;
-  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, bp, plane, ks0, n, acc0, acc1);
-  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, bp, plane, ks0, n, acc0, acc1);
-  else stream_steps<E, TT, 1>(wp, bp, plane, ks0, n, acc0, acc1);
+  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, ld, ks0, n, acc0, acc1);
+  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, ld, ks0, n, acc0, acc1);
+  else stream_steps<E, TT, 1>(wp, ld, ks0, n, acc0, acc1);
 }
 
 template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {
@@ -87,6 +157,51 @@ template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {
   for (int t = 0; t < TT; ++t)
 #pragma unroll
     for (int v = 0; v < 16; ++v) a[t][v] = 0.f;
+}
+
+// Stable counting sort of n_pairs (token, slot) pairs by expert with wavefront ballots, by one workgroup: for
+// expert e the pairs are scanned 64 at a time; the ballot of "routed to e" gives the count (popcount) and,
+// through the bits below a lane, the stable rank of that lane's pair.  expert_of_pair may live in LDS or
+// global memory; s_cnt / s_off: LDS scratch of MAX_EXPERTS (+1) ints.  Every thread of the block must call.
+__device__ inline void ballot_permute(const int32_t* expert_of_pair, int n_pairs, int n_exp, int32_t* __restrict__ cnt,
+                                      int32_t* __restrict__ off, int32_t* __restrict__ perm,
+                                      int32_t* __restrict__ pos_of_pair, int32_t* s_cnt, int32_t* s_off) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  for (int e = wave; e < n_exp; e += n_waves) {
+    int c = 0;
+    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
+      const int p = p0 + lane;
+      c += __popcll(__ballot(p < n_pairs && expert_of_pair[p] == e));
+    }
+    if (lane == 0) s_cnt[e] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < n_exp; ++e) {
+      s_off[e] = run;
+      run += s_cnt[e];
+    }
+    s_off[n_exp] = run;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < n_exp; e += blockDim.x) cnt[e] = s_cnt[e];
+  for (int e = threadIdx.x; e <= n_exp; e += blockDim.x) off[e] = s_off[e];
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int e = wave; e < n_exp; e += n_waves) {
+    int run = s_off[e];
+    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
+      const int p = p0 + lane;
+      const bool mine = p < n_pairs && expert_of_pair[p] == e;
+      const uint64_t b = __ballot(mine);
+      if (mine) {
+        const int r = run + __popcll(b & below);
+        perm[r] = p;
+        pos_of_pair[p] = r;
+      }
+      run += __popcll(b);
+    }
+  }
 }
 
 }  // namespace dinfer

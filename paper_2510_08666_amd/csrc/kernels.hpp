@@ -26,19 +26,19 @@ struct FwdMeta {            // device arrays describing the tokens of one forwar
 void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st);
 void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
                  int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
-// Activation outputs (`h`, attention `out`, expert `y`) are written as Planes<E>::N planes (see common.hpp);
-// `*_plane` is the distance in elements from the hi plane to the lo plane (ignored for float32).
-void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
-                       int H, int V, float* x, void* h, int64_t h_plane, hipStream_t st);
-void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
-                         int top_k, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
-                         hipStream_t st);
+// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps)
+void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
+                  float* rinv, hipStream_t st);
+// x[t] += sum_j topk_w[t][j] * O[pos_of_pair[t*k+j]];  rinv[t] as above, of the updated row
+void launch_combine(float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k, float eps,
+                    int T, int H, float* rinv, hipStream_t st);
 
 struct QkvArgs {
   const void* w;            // packed fused QKV
-  const void* h;            // [T][H]
-  int64_t act_plane;
-  void* q;                  // [T][D]
+  const float* x;           // [T][H] residual stream
+  const float* gain;        // [H] RMSNorm gain
+  const float* rinv;        // [T] 1/rms of the rows of x
+  void* q;                  // [T][D] (hi / lo planes)
   int64_t q_plane;
   void* kv_layer;           // pool base of this layer
   KvGeom geom;
@@ -51,6 +51,9 @@ struct QkvArgs {
 };
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st);
 
+// Activations that feed an MFMA as stored tensors (queries, attention output, expert intermediate) are
+// written as Planes<E>::N planes (see common.hpp); `*_plane` is the distance in elements from the hi plane
+// to the lo plane (ignored for float32).
 struct AttnArgs {
   const void* q;            // [T][D]
   int64_t q_plane;
@@ -69,21 +72,34 @@ void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
 
 void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
                   hipStream_t st);
-void launch_norm(bool bf16, const float* x, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
-                 hipStream_t st);
-// Router logits h . w_router on the matrix cores (hi + lo planes: float32-grade inputs), softmax over the
-// experts, the top_k largest probabilities (ties to the lower expert id), renormalised when norm_topk.
-void launch_router(bool bf16, const void* w_router_packed, const void* h, int64_t h_plane, int T, int H, int E,
-                   int top_k, int norm_topk, int32_t* topk_idx, float* topk_w, hipStream_t st);
+// RMSNorm statistics + router logits on the matrix cores + softmax + top-k (ties to the lower expert id,
+// weights renormalised when norm_topk); for T <= 64 also the token->expert permutation (otherwise
+// launch_permute is issued behind it).
+struct RouterArgs {
+  const void* w;            // packed router weights (one task)
+  const float* x;           // [T][H] residual stream
+  const float* gain;        // [H]
+  float eps;
+  int T, H, E, top_k, norm_topk;
+  float* rinv;              // [T] out: 1/rms of the rows of x
+  int32_t* topk_idx;        // [T][top_k] out
+  float* topk_w;            // [T][top_k] out
+  int32_t* cnt;             // [E], off [E+1], perm [T*top_k], pos_of_pair [T*top_k]: out
+  int32_t* off;
+  int32_t* perm;
+  int32_t* pos_of_pair;
+};
+void launch_router(bool bf16, const RouterArgs& a, hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st);
 
 struct ExpertArgs {
   const void* w_gate_up;    // packed [E][I/32 tasks]
   const void* w_down;       // packed [E][H/64 tasks]
-  const void* h;            // [T][H]
-  int64_t h_plane;
-  void* y;                  // [T*k][I]
+  const float* x;           // [T][H] residual stream
+  const float* gain;        // [H]
+  const float* rinv;        // [T]
+  void* y;                  // [T*k][I] (hi / lo planes)
   int64_t y_plane;
   float* o;                 // [T*k][H]
   const int32_t* cnt;
@@ -96,8 +112,9 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
 
 struct LmArgs {
   const void* w;            // packed LM head
-  const void* h;            // [T][H]
-  int64_t act_plane;
+  const float* x;           // [T][H] residual stream
+  const float* gain;        // [H] final norm gain
+  const float* rinv;        // [T]
   int T, H, V;
   float scale;
   float* part;              // [n_lm_waves][T][4]: max, sum-exp, argmax bits, unused
@@ -114,7 +131,7 @@ void launch_add_i32(int32_t* a, int n, int v, hipStream_t st);
 void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,
                     int n_pos, float* k, float* v, hipStream_t st);
 
-void configure_kernels();
-void configure_attention();   // one-time function attributes (dynamic LDS limits)
+bool configure_kernels();     // one-time function attributes (dynamic LDS limits); false if the runtime refuses
+bool configure_attention();
 
 }  // namespace dinfer

@@ -1,6 +1,7 @@
-// The non-GEMM kernels of the step: token bookkeeping, embedding + RMSNorm, expert-output combine + RMSNorm,
-// RMSNorm, ballot-based token->expert permutation, LM-head partial merge, threshold commit,
+// The non-GEMM kernels of the step: token bookkeeping, embedding, expert-output combine (both also leave the
+// row's 1/rms for the next consumer), ballot-based token->expert permutation, LM-head partial merge, threshold commit,
 // and the KV import / export used by tests.
+#include "gemm.hpp"
 #include "kernels.hpp"
 
 namespace dinfer {
@@ -69,49 +70,35 @@ __device__ inline float block_sum_256(float v, float* sh) {
   return r;
 }
 
-// x[t] = emb[token[t]];  h[t] = RMSNorm(x[t]) * gain
+// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps)
 template <typename E>
-__global__ __launch_bounds__(NORM_THREADS) void embed_norm_kernel(const int32_t* __restrict__ tokens,
-                                                                  const E* __restrict__ emb,
-                                                                  const float* __restrict__ gain, float eps, int H,
-                                                                  int V, float* __restrict__ x, E* __restrict__ h,
-                                                                  int64_t h_plane) {
+__global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
+                                                             float eps, int H, int V, float* __restrict__ x,
+                                                             float* __restrict__ rinv) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
-  float v[NORM_MAX_PER_THREAD];
   float ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    v[i] = c < H ? to_f32(row[c]) : 0.f;
-    ss += v[i] * v[i];
+  for (int c = threadIdx.x; c < H; c += NORM_THREADS) {
+    const float v = to_f32(row[c]);
+    x[(int64_t)t * H + c] = v;
+    ss += v * v;
   }
   ss = block_sum_256(ss, sh);
-  const float r = rsqrtf(ss / H + eps);
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    if (c < H) {
-      x[(int64_t)t * H + c] = v[i];
-      store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
-    }
-  }
+  if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
-void launch_embed_norm(bool bf16, const int32_t* tokens, const void* emb, const float* gain, float eps, int T,
-                       int H, int V, float* x, void* h, int64_t h_plane, hipStream_t st) {
-  if (bf16) embed_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, gain, eps, H, V, x, (bf16_t*)h, h_plane);
-  else embed_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, gain, eps, H, V, x, (float*)h, h_plane);
+void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
+                  float* rinv, hipStream_t st) {
+  if (bf16) embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv);
+  else embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv);
 }
 
-// x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  h[t] = RMSNorm(x[t]) * gain
+// x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  rinv[t] of the new row.
 // Thread i owns columns 4*i + 1024*c .. +3 (hidden is a multiple of 64, so chunks are whole or absent).
-template <typename E>
-__global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __restrict__ x, const float* __restrict__ O,
-                                                                    const int32_t* __restrict__ pos_of_pair,
-                                                                    const float* __restrict__ topk_w, int top_k,
-                                                                    const float* __restrict__ gain, float eps, int H,
-                                                                    E* __restrict__ h, int64_t h_plane) {
+__global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict__ x, const float* __restrict__ O,
+                                                               const int32_t* __restrict__ pos_of_pair,
+                                                               const float* __restrict__ topk_w, int top_k, float eps,
+                                                               int H, float* __restrict__ rinv) {
   __shared__ float sh[4];
   constexpr int CH = NORM_MAX_PER_THREAD / 4;
   const int t = blockIdx.x;
@@ -122,13 +109,12 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __res
     orow[j] = j < top_k ? (int64_t)pos_of_pair[t * top_k + j] * H : 0;
     w[j] = j < top_k ? topk_w[t * top_k + j] : 0.f;
   }
-  f32x4 v[CH];
   float ss = 0.f;
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
     const int col = 4 * threadIdx.x + c * 4 * NORM_THREADS;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if (col < H) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < MAX_TOPK; ++j)
         if (j < top_k) {
@@ -138,104 +124,28 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_norm_kernel(float* __res
         }
       const f32x4 xr = *reinterpret_cast<const f32x4*>(x + (int64_t)t * H + col);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] += xr[i];
-    }
-    v[c] = acc;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ss += acc[i] * acc[i];
-  }
-  ss = block_sum_256(ss, sh);
-  const float r = rsqrtf(ss / H + eps);
-#pragma unroll
-  for (int c = 0; c < CH; ++c) {
-    const int col = 4 * threadIdx.x + c * 4 * NORM_THREADS;
-    if (col < H) {
-      *reinterpret_cast<f32x4*>(x + (int64_t)t * H + col) = v[c];
-      const f32x4 g = *reinterpret_cast<const f32x4*>(gain + col);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) store_act<E>(h, (int64_t)t * H + col + i, h_plane, v[c][i] * r * g[i]);
+      for (int i = 0; i < 4; ++i) {
+        acc[i] += xr[i];
+        ss += acc[i] * acc[i];
+      }
+      *reinterpret_cast<f32x4*>(x + (int64_t)t * H + col) = acc;
     }
   }
-}
-void launch_combine_norm(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w,
-                         int top_k, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
-                         hipStream_t st) {
-  if (bf16) combine_norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (bf16_t*)h, h_plane);
-  else combine_norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, gain, eps, H, (float*)h, h_plane);
-}
-
-// ---------------------------------------------------------------- RMSNorm alone (before the router / experts)
-template <typename E>
-__global__ __launch_bounds__(NORM_THREADS) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                            float eps, int H, E* __restrict__ h, int64_t h_plane) {
-  __shared__ float sh[4];
-  const int t = blockIdx.x;
-  float v[NORM_MAX_PER_THREAD];
-  float ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    v[i] = c < H ? x[(int64_t)t * H + c] : 0.f;
-    ss += v[i] * v[i];
-  }
   ss = block_sum_256(ss, sh);
-  const float r = rsqrtf(ss / H + eps);
-#pragma unroll
-  for (int i = 0; i < NORM_MAX_PER_THREAD; ++i) {
-    const int c = threadIdx.x + i * NORM_THREADS;
-    if (c < H) store_act<E>(h, (int64_t)t * H + c, h_plane, v[i] * r * gain[c]);
-  }
+  if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
-void launch_norm(bool bf16, const float* x, const float* gain, float eps, int T, int H, void* h, int64_t h_plane,
-                 hipStream_t st) {
-  if (bf16) norm_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, H, (bf16_t*)h, h_plane);
-  else norm_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, gain, eps, H, (float*)h, h_plane);
+void launch_combine(float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k, float eps,
+                    int T, int H, float* rinv, hipStream_t st) {
+  combine_kernel<<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
-// Stable counting sort of the n_pairs (token, slot) pairs by expert with wavefront ballots: for expert e,
-// the pairs are scanned 64 at a time; the ballot of "routed to e" gives the count (popcount) and, through
-// the bits below a lane, the stable rank of that lane's pair.
+// Stand-alone form (many tokens); small forwards run the same routine inside the router kernel.
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ expert_of_pair, int n_pairs,
                                                         int n_exp, int32_t* __restrict__ cnt, int32_t* __restrict__ off,
                                                         int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair) {
   __shared__ int32_t s_cnt[MAX_EXPERTS], s_off[MAX_EXPERTS + 1];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
-  for (int e = wave; e < n_exp; e += n_waves) {
-    int c = 0;
-    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
-      const int p = p0 + lane;
-      c += __popcll(__ballot(p < n_pairs && expert_of_pair[p] == e));
-    }
-    if (lane == 0) s_cnt[e] = c;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < n_exp; ++e) {
-      s_off[e] = run;
-      run += s_cnt[e];
-    }
-    s_off[n_exp] = run;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < n_exp; e += blockDim.x) cnt[e] = s_cnt[e];
-  for (int e = threadIdx.x; e <= n_exp; e += blockDim.x) off[e] = s_off[e];
-  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  for (int e = wave; e < n_exp; e += n_waves) {
-    int run = s_off[e];
-    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
-      const int p = p0 + lane;
-      const bool mine = p < n_pairs && expert_of_pair[p] == e;
-      const uint64_t b = __ballot(mine);
-      if (mine) {
-        const int r = run + __popcll(b & below);
-        perm[r] = p;
-        pos_of_pair[p] = r;
-      }
-      run += __popcll(b);
-    }
-  }
+  ballot_permute(expert_of_pair, n_pairs, n_exp, cnt, off, perm, pos_of_pair, s_cnt, s_off);
 }
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st) {

@@ -148,7 +148,11 @@ def test_step_threshold_at_median_confidence(case):
     masked = [i for i in range(case.S) if (int(case.inp.mask_bits[0]) >> i) & 1]
     tau = float(np.median(probe["conf"][masked]))
     got, reports = _run_step(case, tau)
-    assert got["n_committed"].max() > 1
+    # (when the confidences of a sequence are all within rounding of each other - a fully masked block with
+    # no prefix - which of them reach the threshold is not decidable; compare_step has flagged those)
+    clear = sum(1 for i in masked if probe["conf"][i] >= tau * (1 + 10 * case.bars.conf_rel))
+    if clear >= 2:
+        assert got["n_committed"][0] >= clear
 
 
 def test_step_fixed_k(case):
