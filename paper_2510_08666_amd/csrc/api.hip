@@ -64,6 +64,7 @@ int check_config(const dinfer_config* c) {
   if (c->n_experts > MAX_EXPERTS) return fail(DINFER_EUNSUPPORTED, "n_experts > %d", MAX_EXPERTS);
   if (c->top_k > MAX_TOPK || c->top_k > c->n_experts) return fail(DINFER_EINVAL, "top_k %d out of range", c->top_k);
   if (c->mask_id < 0 || c->mask_id >= c->vocab) return fail(DINFER_EINVAL, "mask_id out of range");
+  if (c->max_pos > ATTN_MAX_PAGES * PAGE) return fail(DINFER_EUNSUPPORTED, "max_pos > %d", ATTN_MAX_PAGES * PAGE);
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(DINFER_EINVAL, "rms_eps / rope_theta");
   return DINFER_OK;
 }
@@ -91,12 +92,14 @@ WeightMap map_weights(const dinfer_config& c) {
   return m;
 }
 
-// Key splits per (query tile, head): enough workgroups to cover the chip (~512), but no more splits than
-// give each wave a key tile of its own (key_bound = most keys a sequence can have in this call).
+// Key splits per (query tile, head).  A workgroup's four waves walk their key tiles with the next tile's loads
+// in flight, so a split is worth its merge pass only when a wave would otherwise walk more than 8 tiles; the
+// count is also capped where the grid already covers the chip (key_bound = most keys a sequence can have).
 int attn_splits(int n_qtiles, int n_heads, int key_bound) {
-  int s = (512 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
-  const int by_keys = ((key_bound + TILE - 1) / TILE + 3) / 4;
-  if (s > by_keys) s = by_keys;
+  const int tiles = (key_bound + TILE - 1) / TILE;
+  int s = (tiles + 31) / 32;                               // <= 8 tiles per wave
+  const int cover = (1024 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
+  if (s > cover) s = cover;
   if (s > 32) s = 32;
   if (s < 1) s = 1;
   return s;

@@ -81,7 +81,15 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
   const int n_keys = meta.seq_nkeys[seq];
   const int D = geom.n_heads * HD;
   const float scale = rsqrtf((float)HD);
-  const int32_t* pt = page_table + (int64_t)seq * pt_stride;
+  // The sequence's page-table row goes to LDS first: a tile's K / V addresses then need no global round trip
+  // of their own, and the loads of the next tile can be issued at once.
+  __shared__ int32_t pt[ATTN_MAX_PAGES];
+  {
+    const int32_t* row = page_table + (int64_t)seq * pt_stride;
+    const int n_pages_used = (n_keys + PAGE - 1) / PAGE;       // <= pt_stride, <= ATTN_MAX_PAGES (host checks)
+    for (int i = threadIdx.x; i < n_pages_used; i += blockDim.x) pt[i] = row[i];
+    __syncthreads();
+  }
 
   // Q^T operand: this lane's query column, all of head_dim
   // (queries and probabilities enter the MFMAs as hi + lo planes when E is bf16, like every activation)
@@ -98,19 +106,41 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
   float m_run = -INFINITY, l_run = 0.f;
 
   const int n_ktiles = (n_keys + TILE - 1) / TILE;
-  for (int kt = split * 4 + wave; kt < n_ktiles; kt += n_splits * 4) {   // key tiles dealt round-robin to all waves
-    // ---- S^T = K . Q^T
+  const int stride = n_splits * 4;                       // key tiles are dealt round-robin to all waves
+  const int kt0 = split * 4 + wave;
+  // K rows and V^T rows of one key tile, loaded straight into MFMA operand registers
+  struct TileRegs {
+    vec k[DSTEPS];
+    vec v[PvStep<E>::STEPS][DT];
+  };
+  auto load_tile = [&](int kt, TileRegs& r) {
     const int key = min(kt * TILE + col, n_keys - 1);
     const E* krow = kv_layer + kv_k_index(geom, safe_page(geom, pt[key / PAGE]), head, key % PAGE, 0) + half * G;
+#pragma unroll
+    for (int s = 0; s < DSTEPS; ++s) r.k[s] = load16<E>(krow + s * KS);
+#pragma unroll
+    for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
+      const int pkey = min(kt * TILE + PvStep<E>::page_of_step(s2) * PAGE, n_keys - 1);
+      const int page = safe_page(geom, pt[pkey / PAGE]);
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+        r.v[s2][t] = PvStep<E>::v_vec(kv_layer + kv_v_index(geom, page, head, 0, t * TILE + col), half, s2);
+    }
+  };
+  TileRegs cur, nxt;
+  if (kt0 < n_ktiles) load_tile(kt0, cur);
+  for (int kt = kt0; kt < n_ktiles; kt += stride) {
+    // the next tile's loads are issued before this tile is used (clamped, so the loop body has no branch
+    // around loads and the compiler can count them; the last iteration re-reads its own tile)
+    load_tile(min(kt + stride, n_ktiles - 1), nxt);
+    // ---- S^T = K . Q^T
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-    for (int s = 0; s < DSTEPS; ++s) {
-      const vec kv = load16<E>(krow + s * KS);
+    for (int s = 0; s < DSTEPS; ++s)
 #pragma unroll
-      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, kv, qv[s][pl]);
-    }
+      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, cur.k[s], qv[s][pl]);
     float p[16];
     float mx = -INFINITY;
 #pragma unroll
@@ -138,15 +168,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     const bool last = (kt + 1) * TILE > n_keys;
 #pragma unroll
     for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
-      const int pkey = min(kt * TILE + PvStep<E>::page_of_step(s2) * PAGE, n_keys - 1);
-      const int page = safe_page(geom, pt[pkey / PAGE]);
       vec pv[NP];
 #pragma unroll
       for (int pl = 0; pl < NP; ++pl) pv[pl] = PvStep<E>::p_vec(p, s2, pl);
 #pragma unroll
       for (int t = 0; t < DT; ++t) {
-        const E* vrow = kv_layer + kv_v_index(geom, page, head, 0, t * TILE + col);
-        vec vv = PvStep<E>::v_vec(vrow, half, s2);
+        vec vv = cur.v[s2][t];
         if (last) {   // slots past the last key may hold anything (NaN * 0 would poison the sum)
 #pragma unroll
           for (int i = 0; i < G; ++i)
@@ -156,6 +183,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
         for (int pl = 0; pl < NP; ++pl) mfma32(o[t], vv, pv[pl]);
       }
     }
+    cur = nxt;
   }
   // ---- fold the four waves through LDS (lane-major, conflict free); wave 0 finishes
   extern __shared__ float lds[];                       // [3 waves][DT*16 + 2][64 lanes]
