@@ -42,6 +42,19 @@ def step_bytes(cfg, n_tok, prefix_lens, block_len, experts_touched_per_layer):
     return sum(stages.values()), stages
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes, as summarised
+    (already scaled by the copy calibration) in profiles/<kernel>_<workload>_pmc.md; None if there is no summary."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.md" % (kernel, workload.split("-")[0]))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +112,25 @@ def main():
         mask.copy_(mask0)
         ctx.step(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed)
 
+    # practical HBM read ceiling: the streaming-read probe over the weight buffer, and over one launch's worth
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def probe(nbytes, reps):
+        binding.stream_read(ctx.weights, nbytes, sink)
+        torch.cuda.synchronize()
+        best = 1e30
+        for _ in range(reps):
+            ev0.record()
+            binding.stream_read(ctx.weights, nbytes, sink)
+            ev1.record()
+            torch.cuda.synchronize()
+            best = min(best, ev0.elapsed_time(ev1))
+        return nbytes / (best * 1e-3) / 1e9
+
+    ceiling_big = probe(min(ctx.weights.numel(), 8 << 30), 3)
+    ceiling_launch = probe(400 << 20, 5)
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -134,9 +166,12 @@ def main():
         avg_ms = stage_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": measured_traffic(name, wl.name),
                     "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2),
-                    "launches_timed": launches}
+                    "launches_timed": launches,
+                    "measured_read_ceiling_GBs": {"8GB_sweep": round(ceiling_big, 1), "400MB_launch": round(ceiling_launch, 1)},
+                    "frac_of_measured_ceiling": round(achieved / ceiling_launch, 4)}
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -174,6 +174,12 @@ enum {
 int dinfer_profile_start(dinfer_ctx* ctx, int32_t stage);
 int dinfer_profile_stop(dinfer_ctx* ctx, int32_t* n_launches, float* total_ms);
 
+/* Benchmark utility: one kernel that reads the first `bytes` (rounded down to 256 KiB) of d_buf once, with the
+ * access pattern of the library's weight streams, and stores nothing (d_sink: one float, never written for
+ * finite data).  Its duration gives the practical HBM read ceiling the weight-streaming kernels are judged
+ * against.  d_buf: device, 16-byte aligned. */
+int dinfer_stream_read(const void* d_buf, size_t bytes, float* d_sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

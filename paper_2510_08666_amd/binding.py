@@ -24,7 +24,7 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_refresh_block",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
-           "dinfer_profile_start", "dinfer_profile_stop"]
+           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
  STAGE_ROUTER) = range(7)
 
@@ -86,6 +86,8 @@ def _load():
     L.dinfer_profile_start.argtypes = [c_vp, c_i32]
     L.dinfer_profile_stop.restype = c_i32
     L.dinfer_profile_stop.argtypes = [c_vp, P(c_i32), P(c_f32)]
+    L.dinfer_stream_read.restype = c_i32
+    L.dinfer_stream_read.argtypes = [c_vp, c_sz, c_vp, c_vp]
     return L
 
 
@@ -114,6 +116,11 @@ def _stream():
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def stream_read(d_buf, nbytes, d_sink):
+    """One pass of the streaming-read probe over the first nbytes of a device tensor."""
+    _check(lib.dinfer_stream_read(_ptr(d_buf), int(nbytes), _ptr(d_sink), _stream()))
 
 
 class Context:

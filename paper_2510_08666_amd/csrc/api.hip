@@ -138,7 +138,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.topk_idx = cv.take((size_t)c.n_layers * T * K * 4);   // kept per layer (tests read the routing back)
   w.topk_w = cv.take((size_t)c.n_layers * T * K * 4);
   w.cnt = cv.take((size_t)MAX_EXPERTS * 4);
-  w.off = cv.take((size_t)(MAX_EXPERTS + 1) * 4);
+  w.off = cv.take((size_t)(2 * MAX_EXPERTS + 2) * 4);   // offsets, then the list of experts with rows
   w.perm = cv.take(T * K * 4);
   w.pos_of_pair = cv.take(T * K * 4);
   w.y = cv.take(planes * T * K * I * es);
@@ -459,12 +459,12 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   const int T = n_seq * block_len;
   LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
             at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
-            at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), nullptr};
+            at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
     launch_lm_head(c->bf16, la, st);
   }
-  launch_lm_merge(la.part, la.n_lm_waves, T, d_conf, d_argmax, st);
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, st);
   launch_commit(d_conf, d_argmax, n_seq, block_len, d_block_tokens, d_mask, decode->threshold, decode->fixed_k,
                 d_n_committed, st);
   HIP_TRY(hipGetLastError());
@@ -538,6 +538,14 @@ int dinfer_kv_read(dinfer_ctx* c, int32_t layer, const int32_t* d_page_row, int3
   return kv_copy(c, false, layer, d_page_row, first_pos, n_pos, d_k, d_v, stream);
 }
 
+int dinfer_stream_read(const void* d_buf, size_t bytes, float* d_sink, void* stream) {
+  if (!d_buf || !d_sink) return fail(DINFER_EINVAL, "null argument");
+  if (((uintptr_t)d_buf & 15) || bytes < (256u << 10)) return fail(DINFER_EINVAL, "buffer must be 16-byte aligned, >= 256 KiB");
+  launch_stream_read(d_buf, bytes, d_sink, (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
 int dinfer_profile_start(dinfer_ctx* c, int32_t stage) {
   if (!c) return fail(DINFER_EINVAL, "context is null");
   if (stage < 0 || stage >= DINFER_STAGE_COUNT) return fail(DINFER_EINVAL, "stage %d", stage);
@@ -574,7 +582,7 @@ int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* strea
   const dinfer_config& f = c->cfg;
   LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
             at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,
-            at<float>(c->ws, c->wsm.lm_part), lm_head_waves(f.vocab), d_out};
+            at<float>(c->ws, c->wsm.lm_part), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;

@@ -288,6 +288,9 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
       off[lane] = start;
       if (lane == n_exp - 1) off[n_exp] = incl;
     }
+    const uint64_t has_rows = __ballot(tot > 0);          // dense list of the experts with rows (ACTIVE_LIST)
+    if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
+    if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
     int run = start;
     for (int c = 0; c < n_chunks; ++c) {
       const int here = s_cc[c * MAX_EXPERTS + lane];
@@ -456,32 +459,39 @@ void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
 
 // ------------------------------------------------------------------------------------------------
 // Routed experts.  Rows of expert e are the pairs perm[off[e] .. off[e]+cnt[e]) (pair = token*top_k + slot).
-// One wave per (expert, task, row group); experts without rows exit at once.
+// One workgroup of EKS waves per (expert, task, row group): the waves split K (a single wave walking a whole
+// 256 KiB task with 16 KiB in flight is latency bound at a few GB/s, which sets a floor of ~50 us under the
+// kernel however few experts are touched), partials are folded through LDS in wave order, and each wave
+// finishes a share of the accumulator registers.  Experts without rows sit at the end of the grid and exit.
 //   GEMM 1: task = 32 gate features + the same 32 up features; input = residual rows (XLoader), scaled by the
 //           row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
 //   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[sorted row][H]
 // ------------------------------------------------------------------------------------------------
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
-template <typename E, int TT>
-__global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__ W, const float* __restrict__ x,
-                                                            const float* __restrict__ gain,
-                                                            const float* __restrict__ rinv, E* __restrict__ Y,
-                                                            const int32_t* __restrict__ cnt,
-                                                            const int32_t* __restrict__ off,
-                                                            const int32_t* __restrict__ perm, int H, int I,
-                                                            int top_k, int64_t y_plane) {
-  constexpr int G = ET<E>::G;
+template <int TT> struct ExpertSplit { static constexpr int EKS = TT <= 2 ? 4 : 2; };
+template <int TT, int EKS> constexpr size_t expert_lds() { return (size_t)EKS * 2 * TT * 16 * WAVE * 4; }
+
+template <typename E, int TT, int EKS>
+__global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __restrict__ W, const float* __restrict__ x,
+                                                                   const float* __restrict__ gain,
+                                                                   const float* __restrict__ rinv, E* __restrict__ Y,
+                                                                   const int32_t* __restrict__ cnt,
+                                                                   const int32_t* __restrict__ off,
+                                                                   const int32_t* __restrict__ perm, int H, int I,
+                                                                   int top_k, int64_t y_plane) {
+  extern __shared__ float red[];   // [EKS][2*TT*16][64]
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
   __shared__ float s_gain[MAX_HIDDEN];
-  const int e = blockIdx.y, group = blockIdx.z;
+  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
+  const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
   const int n_rows = cnt[e];
   const int row0 = group * TT * TILE;
-  if (row0 >= n_rows) return;            // uniform over the block
+  if (row0 >= n_rows) return;
   stage_gain(s_gain, gain, H);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int task = blockIdx.x * 4 + wave;
+  const int task = blockIdx.x;
   const int n_tasks = I / TILE;
-  if (task >= n_tasks) return;
   const int base = off[e];
   XLoader<E, TT, false> ld;
   int row[TT];
@@ -498,33 +508,53 @@ __global__ __launch_bounds__(256) void expert_gemm1_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = H / ET<E>::KS;
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, ld,
+  const int per = (ksteps + EKS - 1) / EKS;
+  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
                                         acc0, acc1);
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  const int v0 = wave * PER;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
+    float g[PER], u[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      g[i] = 0.f;
+      u[i] = 0.f;
+    }
+    for (int w = 0; w < EKS; ++w) {
+      const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        g[i] += rp[i * WAVE];
+        u[i] += rp[(16 + i) * WAVE];
+      }
+    }
     if (row[t] < n_rows) {
       E* yrow = Y + (int64_t)(base + row[t]) * I + task * TILE;
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        store_act<E>(yrow, acc_row(v, half), y_plane, silu_f(acc0[t][v] * r[t]) * (acc1[t][v] * r[t]));
+      for (int i = 0; i < PER; ++i)
+        store_act<E>(yrow, acc_row(v0 + i, half), y_plane, silu_f(g[i] * r[t]) * (u[i] * r[t]));
     }
   }
 }
 
-template <typename E, int TT>
-__global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
-                                                            float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                            const int32_t* __restrict__ off, int H, int I,
-                                                            int64_t y_plane) {
-  constexpr int G = ET<E>::G;
-  const int e = blockIdx.y, group = blockIdx.z;
+template <typename E, int TT, int EKS>
+__global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+                                                                   float* __restrict__ O, const int32_t* __restrict__ cnt,
+                                                                   const int32_t* __restrict__ off, int H, int I,
+                                                                   int64_t y_plane) {
+  extern __shared__ float red[];   // [EKS][2*TT*16][64]
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
+  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
+  const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
   const int n_rows = cnt[e];
   const int row0 = group * TT * TILE;
   if (row0 >= n_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int task = blockIdx.x * 4 + wave;
+  const int task = blockIdx.x;
   const int n_tasks = H / (2 * TILE);
-  if (task >= n_tasks) return;
   const int base = off[e];
   PlaneLoader<E, TT> ld;
   int row[TT];
@@ -538,36 +568,53 @@ __global__ __launch_bounds__(256) void expert_gemm2_kernel(const E* __restrict__
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
   const int ksteps = I / ET<E>::KS;
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), 0, ksteps, ld,
+  const int per = (ksteps + EKS - 1) / EKS;
+  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
                                         acc0, acc1);
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  const int v0 = wave * PER;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
+    float a0[PER], a1[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      a0[i] = 0.f;
+      a1[i] = 0.f;
+    }
+    for (int w = 0; w < EKS; ++w) {
+      const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        a0[i] += rp[i * WAVE];
+        a1[i] += rp[(16 + i) * WAVE];
+      }
+    }
     if (row[t] < n_rows) {
       float* orow = O + (int64_t)(base + row[t]) * H + (2 * task) * TILE;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 r0, r1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          r0[i] = acc0[t][4 * g + i];
-          r1[i] = acc1[t][4 * g + i];
-        }
-        *reinterpret_cast<f32x4*>(orow + acc_row(4 * g, half)) = r0;
-        *reinterpret_cast<f32x4*>(orow + TILE + acc_row(4 * g, half)) = r1;
+      for (int i = 0; i < PER; ++i) {
+        orow[acc_row(v0 + i, half)] = a0[i];
+        orow[TILE + acc_row(v0 + i, half)] = a1[i];
       }
     }
   }
 }
 
 template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
-  const int t1 = a.I / TILE;
-  expert_gemm1_kernel<E, TT><<<dim3((t1 + 3) / 4, a.E, groups), 256, 0, st>>>(
+  constexpr int EKS = ExpertSplit<TT>::EKS;
+  expert_gemm1_kernel<E, TT, EKS><<<dim3(a.I / TILE, a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
       (const E*)a.w_gate_up, a.x, a.gain, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.y_plane);
 }
 template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
-  const int t2 = a.H / (2 * TILE);
-  expert_gemm2_kernel<E, TT><<<dim3((t2 + 3) / 4, a.E, groups), 256, 0, st>>>(
+  constexpr int EKS = ExpertSplit<TT>::EKS;
+  expert_gemm2_kernel<E, TT, EKS><<<dim3(a.H / (2 * TILE), a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
       (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.H, a.I, a.y_plane);
+}
+template <typename E, int TT> static bool configure_experts() {
+  constexpr int EKS = ExpertSplit<TT>::EKS;
+  return opt_in_lds((const void*)expert_gemm1_kernel<E, TT, EKS>) && opt_in_lds((const void*)expert_gemm2_kernel<E, TT, EKS>);
 }
 
 // An expert can receive at most T rows (a token selects an expert at most once): T fixes the row tiling.
@@ -590,21 +637,27 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER
 // (unless the debug pointer is set).  One partial (max, sum, id) per (wave, token) is written at the end.
 // Input: the residual rows (XLoader with the final gain); logit = acc * (1/rms of the row) * logit_scale.
 // ------------------------------------------------------------------------------------------------
-template <typename E, int TT>
-__global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, const float* __restrict__ x,
-                                                       const float* __restrict__ gain, const float* __restrict__ rinv,
-                                                       int T, int H, int V, float scale, float* __restrict__ part,
-                                                       int n_waves, float* __restrict__ logits_out) {
-  constexpr int G = ET<E>::G;
+// Workgroups of EKS waves walk the tasks (64 vocabulary ids each): K is split over the waves as in the expert
+// GEMMs; after the fold each wave owns 16/EKS accumulator registers of both tiles, i.e. a fixed subset of every
+// task's ids for each token, over which it keeps the running maximum logit, its lowest id and sum exp(z - max).
+// One (max, sum-exp, id) partial per (workgroup, wave, token) is written at the end; logits are never stored.
+template <typename E, int TT, int EKS>
+__global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict__ W, const float* __restrict__ x,
+                                                              const float* __restrict__ gain,
+                                                              const float* __restrict__ rinv, int T, int H, int V,
+                                                              float scale, float* __restrict__ part,
+                                                              float* __restrict__ logits_out) {
+  extern __shared__ float red[];   // [EKS][2*TT*16][64]
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
   __shared__ float s_gain[MAX_HIDDEN];
   stage_gain(s_gain, gain, H);
-  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int group = blockIdx.y;
   const int tok0 = group * TT * TILE;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
   const int ksteps = H / ET<E>::KS;
   XLoader<E, TT, false> ld;
-  float m[TT], s[TT], zs[TT];
+  float m[TT], sum[TT], zs[TT];
   int best[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -612,58 +665,70 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
     ld.xp[t] = x + (int64_t)tok * H + half * G;
     zs[t] = rinv[tok] * scale;
     m[t] = -INFINITY;
-    s[t] = 0.f;
+    sum[t] = 0.f;
     best[t] = 0x7fffffff;
   }
   ld.gs = s_gain + half * G;
-  for (int task = wave; task < n_tasks; task += n_waves) {
+  const int per = (ksteps + EKS - 1) / EKS;
+  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
+  const int v0 = wave * PER;
+  for (int task = blockIdx.x; task < n_tasks; task += gridDim.x) {
     f32x16 acc0[TT], acc1[TT];
     zero_acc<TT>(acc0);
     zero_acc<TT>(acc1);
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), 0, ksteps, ld, acc0, acc1);
+    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, ld, acc0, acc1);
+    spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+    __syncthreads();
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
       const int tok = tok0 + t * TILE + (lane & 31);
-      // this lane's 32 logits of the task, ids ascending within each tile
-      float z[32];
-      int id[32];
+      // this lane's 2*PER logits of the task, ids ascending
+      float z[2 * PER];
+      int id[2 * PER];
+#pragma unroll
+      for (int i = 0; i < 2 * PER; ++i) z[i] = 0.f;
+      for (int w = 0; w < EKS; ++w) {
+        const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          z[i] += rp[i * WAVE];
+          z[PER + i] += rp[(16 + i) * WAVE];
+        }
+      }
       float tm = -INFINITY;
       int ti = 0x7fffffff;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        id[v] = (2 * task) * TILE + acc_row(v, half);
-        id[16 + v] = id[v] + TILE;
-        z[v] = id[v] < V ? acc0[t][v] * zs[t] : -INFINITY;
-        z[16 + v] = id[16 + v] < V ? acc1[t][v] * zs[t] : -INFINITY;
-      }
-#pragma unroll
-      for (int v = 0; v < 32; ++v)
-        if (z[v] > tm) {          // ids ascend with v, so strict '>' keeps the lowest id
-          tm = z[v];
-          ti = id[v];
+      for (int i = 0; i < 2 * PER; ++i) {
+        id[i] = (2 * task + (i >= PER)) * TILE + acc_row(v0 + (i % PER), half);
+        z[i] = id[i] < V ? z[i] * zs[t] : -INFINITY;
+        if (z[i] > tm) {          // ids ascend with i, so strict '>' keeps the lowest id
+          tm = z[i];
+          ti = id[i];
         }
+      }
       if (logits_out && tok < T) {
 #pragma unroll
-        for (int v = 0; v < 32; ++v)
-          if (id[v] < V) logits_out[(int64_t)tok * V + id[v]] = z[v];
+        for (int i = 0; i < 2 * PER; ++i)
+          if (id[i] < V) logits_out[(int64_t)tok * V + id[i]] = z[i];
       }
       if (tm > m[t] || (tm == m[t] && ti < best[t])) {
-        s[t] *= __expf(m[t] - tm);      // exp(-inf) = 0 on the first task
+        sum[t] *= __expf(m[t] - tm);      // exp(-inf) = 0 on the first task
         m[t] = tm;
         best[t] = ti;
       }
       if (m[t] > -INFINITY) {
 #pragma unroll
-        for (int v = 0; v < 32; ++v) s[t] += __expf(z[v] - m[t]);
+        for (int i = 0; i < 2 * PER; ++i) sum[t] += __expf(z[i] - m[t]);
       }
     }
+    __syncthreads();   // the partials are consumed: the next task may overwrite them
   }
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     // fold the two half-waves (same token, other rows)
-    const float om = __shfl_xor(m[t], 32, WAVE), os = __shfl_xor(s[t], 32, WAVE);
+    const float om = __shfl_xor(m[t], 32, WAVE), os = __shfl_xor(sum[t], 32, WAVE);
     const int ob = __shfl_xor(best[t], 32, WAVE);
-    float M = m[t], S = s[t];
+    float M = m[t], S = sum[t];
     int B = best[t];
     if (om > M || (om == M && ob < B)) {
       S = (M > -INFINITY ? S * __expf(M - om) : 0.f) + os;
@@ -674,7 +739,7 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
     }
     const int tok = tok0 + t * TILE + (lane & 31);
     if (half == 0 && tok < T) {
-      float* p = part + ((int64_t)wave * T + tok) * 4;
+      float* p = part + ((int64_t)(blockIdx.x * EKS + wave) * T + tok) * 4;
       p[0] = M;
       p[1] = S;
       p[2] = __int_as_float(B);
@@ -683,29 +748,30 @@ __global__ __launch_bounds__(256) void lm_head_kernel(const E* __restrict__ W, c
   }
 }
 
-int lm_head_waves(int V) {
+// Workgroups along the vocabulary: about three per compute unit, never more than tasks.
+static int lm_head_wgs(int V) {
   const int n_tasks = (V + 63) / 64;
-  int wgs = (n_tasks + 3) / 4;          // one task per wave while that keeps the partial table small
-  if (wgs > 768) wgs = 768;
-  if (wgs < 1) wgs = 1;
-  return wgs * 4;
+  return n_tasks < 768 ? n_tasks : 768;
 }
+// Partials per token row: upper bound (workspace sizing) and what a launch for T tokens writes.
+int lm_head_waves(int V) { return lm_head_wgs(V) * 4; }
+int lm_head_parts(int V, int T) { return lm_head_wgs(V) * (T <= 64 ? 4 : 2); }
 
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
-  const int wgs = a.n_lm_waves / 4;
+  const int wgs = lm_head_wgs(a.V);
   if (a.T <= 32) {
-    lm_head_kernel<E, 1><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out);
+    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V,
+                                                                              a.scale, a.part, a.logits_out);
   } else if (a.T <= 64) {
-    lm_head_kernel<E, 2><<<dim3(wgs, 1), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale, a.part,
-                                                        a.n_lm_waves, a.logits_out);
+    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V,
+                                                                              a.scale, a.part, a.logits_out);
   } else {
-    // token groups of 128 rows: the partials of group g live in rows [g*128, ...) of the same table
     const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    lm_head_kernel<E, 4><<<dim3(wgs, groups), 256, 0, st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V, a.scale,
-                                                             a.part, a.n_lm_waves, a.logits_out);
+    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H,
+                                                                                   a.V, a.scale, a.part, a.logits_out);
   }
 }
+
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
   if (bf16) launch_lm_t<bf16_t>(a, st);
   else launch_lm_t<float>(a, st);
@@ -716,6 +782,11 @@ bool configure_kernels() {
             configure_ksplit<bf16_t, false, ResidualEpi>() && configure_ksplit<float, false, ResidualEpi>();
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)router_kernel<float, 2, 4>);
+  ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&
+       opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>) &&
+       opt_in_lds((const void*)lm_head_kernel<bf16_t, 4, 2>) && opt_in_lds((const void*)lm_head_kernel<float, 4, 2>);
+  ok = ok && configure_experts<bf16_t, 1>() && configure_experts<bf16_t, 2>() && configure_experts<bf16_t, 4>() &&
+       configure_experts<float, 1>() && configure_experts<float, 2>() && configure_experts<float, 4>();
   (void)hipGetLastError();
   return ok;
 }

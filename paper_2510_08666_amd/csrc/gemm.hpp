@@ -159,6 +159,12 @@ template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {
     for (int v = 0; v < 16; ++v) a[t][v] = 0.f;
 }
 
+// The offset array is followed by the list of experts that received at least one row: off[ACTIVE_LIST + i] is
+// the i-th such expert (ascending), off[ACTIVE_LIST + MAX_EXPERTS] their number.  The grouped GEMMs index their
+// grid through it, so that workgroups of experts without rows sit at the end of the grid instead of leaving
+// holes in the dispatch order.
+constexpr int ACTIVE_LIST = MAX_EXPERTS + 1;
+
 // Stable counting sort of n_pairs (token, slot) pairs by expert with wavefront ballots, by one workgroup: for
 // expert e the pairs are scanned 64 at a time; the ballot of "routed to e" gives the count (popcount) and,
 // through the bits below a lane, the stable rank of that lane's pair.  expert_of_pair may live in LDS or
@@ -187,6 +193,13 @@ __device__ inline void ballot_permute(const int32_t* expert_of_pair, int n_pairs
   __syncthreads();
   for (int e = threadIdx.x; e < n_exp; e += blockDim.x) cnt[e] = s_cnt[e];
   for (int e = threadIdx.x; e <= n_exp; e += blockDim.x) off[e] = s_off[e];
+  if (threadIdx.x == 0) {   // dense list of the experts that received rows (see ACTIVE_LIST)
+    int32_t* act = off + ACTIVE_LIST;
+    int n = 0;
+    for (int e = 0; e < n_exp; ++e)
+      if (s_cnt[e] > 0) act[n++] = e;
+    act[MAX_EXPERTS] = n;
+  }
   const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   for (int e = wave; e < n_exp; e += n_waves) {
     int run = s_off[e];

@@ -117,11 +117,11 @@ struct LmArgs {
   const float* rinv;        // [T]
   int T, H, V;
   float scale;
-  float* part;              // [n_lm_waves][T][4]: max, sum-exp, argmax bits, unused
-  int n_lm_waves;
+  float* part;              // [lm_head_parts(V, T)][T][4]: max, sum-exp, argmax bits, unused
   float* logits_out;        // debug: [T][V] or null
 };
-int lm_head_waves(int V);
+int lm_head_waves(int V);          // upper bound of partials per token row (workspace sizing)
+int lm_head_parts(int V, int T);   // partials per token row launch_lm_head writes for T tokens
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st);
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
@@ -130,6 +130,8 @@ void launch_add_i32(int32_t* a, int n, int v, hipStream_t st);
 
 void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,
                     int n_pos, float* k, float* v, hipStream_t st);
+
+void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
 
 bool configure_kernels();     // one-time function attributes (dynamic LDS limits); false if the runtime refuses
 bool configure_attention();

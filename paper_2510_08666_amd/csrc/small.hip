@@ -243,6 +243,33 @@ void launch_add_i32(int32_t* a, int n, int v, hipStream_t st) {
   add_i32_kernel<<<(n + 63) / 64, 64, 0, st>>>(a, n, v);
 }
 
+// ---------------------------------------------------------------- streaming-read probe (benchmarks)
+// Reads `bytes` once with the access pattern of the weight streams (each wave walks contiguous 256 KiB chunks,
+// 16 KiB-loads in flight) and keeps nothing: its duration is the practical HBM read ceiling of the chip.
+__global__ __launch_bounds__(256) void stream_read_kernel(const f32x4* __restrict__ p, size_t n_chunks, float* sink) {
+  constexpr size_t CHUNK = (256 << 10) / 16;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (size_t c = wave; c < n_chunks; c += (size_t)gridDim.x * 4) {
+    const f32x4* q = p + c * CHUNK + lane;
+    for (size_t i = 0; i < CHUNK; i += 64 * 16) {
+      f32x4 v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = q[i + u * 64];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) acc += v[u];
+    }
+  }
+  if (acc[0] + acc[1] + acc[2] + acc[3] == 1.2345e38f) sink[0] = 1.f;   // never true for finite sums of this data
+}
+void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st) {
+  const size_t n_chunks = bytes / (256 << 10);
+  if (n_chunks == 0) return;
+  const unsigned wgs = (unsigned)(n_chunks < 4096 ? (n_chunks + 3) / 4 : 1024);
+  stream_read_kernel<<<wgs, 256, 0, st>>>((const f32x4*)buf, n_chunks, sink);
+}
+
 // ---------------------------------------------------------------- KV import / export (tests)
 template <typename E>
 __global__ void kv_copy_kernel(bool to_pool, E* __restrict__ kv_layer, KvGeom geom, const int32_t* __restrict__ page_row,
