@@ -181,12 +181,15 @@ def main():
         kc, vc = o.new_cache(P + S)
         k, v = di.synthetic_prefix_kv(cfg, seed, 0, P)
         kc[:, :P], vc[:, :P] = k, v
-        tc = time.perf_counter()
-        o.step(inp.block_tokens[0], int(inp.mask_bits[0]), P, kc, vc, wl.threshold, wl.fixed_k)
-        cdt = time.perf_counter() - tc
+        # a bounded sample: whole oracle steps of sequence 0, repeated until about 10 s of CPU work are done
+        n_done, tc = 0, time.perf_counter()
+        while n_done == 0 or (time.perf_counter() - tc < 10.0 and n_done < 200):
+            o.step(inp.block_tokens[0], int(inp.mask_bits[0]), P, kc, vc, wl.threshold, wl.fixed_k)
+            n_done += 1
+        cdt = (time.perf_counter() - tc) / n_done
         cpu = {"value": round(1.0 / (cdt * ns), 5), "unit": "steps/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": "one full oracle step of sequence 0 of this workload (all layers, LM head, "
-               "commit; same weights, same synthetic prefix K,V), %.1f s; scaled by 1/n_seq" % cdt}
+               "kind": "oracle", "sample": "%d full oracle steps of sequence 0 of this workload (all layers, LM head, "
+               "commit; same weights, same synthetic prefix K,V), %.2f s each; scaled by 1/n_seq" % (n_done, cdt)}
 
     out = {
         "metric": "block denoising steps/s (committed tokens/s alongside), batch %d" % ns,

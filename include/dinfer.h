@@ -180,6 +180,11 @@ int dinfer_profile_stop(dinfer_ctx* ctx, int32_t* n_launches, float* total_ms);
  * against.  d_buf: device, 16-byte aligned. */
 int dinfer_stream_read(const void* d_buf, size_t bytes, float* d_sink, void* stream);
 
+/* Profiling aid of libraries built with -DDINFER_TRACE=<kernel id>: copies the phase timestamps (100 MHz wall
+ * clock, [workgroup][8 slots] of uint64) that the chosen kernel's last launch left, to the HOST buffer h_out
+ * (synchronous).  unit: 0 = GEMM kernels, 1 = attention.  Ordinary builds return DINFER_EINVAL. */
+int dinfer_debug_trace(int32_t unit, void* h_out, size_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdinfer.so")
+LIB_PATH = os.environ.get("DINFER_LIB") or os.path.join(_HERE, "libdinfer.so")   # DINFER_LIB: another build of it
 
 c_i32, c_u64, c_f32, c_vp, c_sz = ctypes.c_int32, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
 
@@ -24,7 +24,7 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_refresh_block",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
-           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read"]
+           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
  STAGE_ROUTER) = range(7)
 
@@ -86,6 +86,8 @@ def _load():
     L.dinfer_profile_start.argtypes = [c_vp, c_i32]
     L.dinfer_profile_stop.restype = c_i32
     L.dinfer_profile_stop.argtypes = [c_vp, P(c_i32), P(c_f32)]
+    L.dinfer_debug_trace.restype = c_i32
+    L.dinfer_debug_trace.argtypes = [c_i32, c_vp, c_sz]
     L.dinfer_stream_read.restype = c_i32
     L.dinfer_stream_read.argtypes = [c_vp, c_sz, c_vp, c_vp]
     return L
@@ -116,6 +118,14 @@ def _stream():
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def debug_trace(unit, n_wgs):
+    """Phase timestamps [n_wgs][8] (uint64, 10 ns ticks) of a library built with DINFER_TRACE=<kernel id>."""
+    import numpy as np
+    out = np.zeros((n_wgs, 8), dtype=np.uint64)
+    _check(lib.dinfer_debug_trace(int(unit), out.ctypes.data, out.nbytes))
+    return out
 
 
 def stream_read(d_buf, nbytes, d_sink):

@@ -6,15 +6,17 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libdinfer.so")
+LIB = os.environ.get("DINFER_LIB_OUT") or os.path.join(HERE, "libdinfer.so")
 SOURCES = ["api.hip", "gemm.hip", "attention.hip", "small.hip", "pack.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+if os.environ.get("DINFER_TRACE"):      # in-kernel phase timestamps for one kernel id (see csrc/common.hpp)
+    FLAGS.append("-DDINFER_TRACE=" + os.environ["DINFER_TRACE"])
 
 
 def build(verbose=True):
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build" + os.environ.get("DINFER_TRACE", ""))
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):

@@ -106,7 +106,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 }
 
 struct Workspace {
-  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
+  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
       perm, pos_of_pair, y, o, lm_part, conf, argmax, total;
 };
 
@@ -127,6 +127,25 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.rinv_a = cv.take(T * 4);   // 1/rms of the residual rows entering the attention half / the LM head
   w.rinv_f = cv.take(T * 4);   // ... entering the expert half
   const size_t planes = c.dtype == DINFER_BF16 ? 2 : 1;   // stored bf16 activations are hi + lo planes
+  w.xn = cv.take(planes * T * H * es);   // normalised-input planes of the residual rows
+  w.ssq = cv.take((size_t)(H / 64) * T * 4);
+  {
+    // cross-workgroup split-K scratch: units (tasks) x slices x [2 * token tiles * 16][64] floats, for one and
+    // two token tiles, over the QKV projection (K = H), the output projection (K = D) and the router
+    const bool bf = c.dtype == DINFER_BF16;
+    size_t most = 0;
+    for (int tt = 1; tt <= 2; ++tt) {
+      const size_t tile = (size_t)2 * tt * 16 * WAVE * 4;
+      const size_t qkv = (size_t)(3 * D / 64) * gemm_slices(bf, H, tt * TILE) * tile;
+      const size_t opr = (size_t)(H / 64) * gemm_slices(bf, D, tt * TILE) * tile;
+      most = qkv > most ? qkv : most;
+      most = opr > most ? opr : most;
+    }
+    w.tk_part = cv.take(most);
+    const int units = 3 * D / 64 > H / 64 ? 3 * D / 64 : H / 64;
+    w.tickets_bytes = (size_t)units * 4;
+    w.tickets = cv.take(w.tickets_bytes);
+  }
   w.q = cv.take(planes * T * D * es);
   w.a = cv.take(planes * T * D * es);
   size_t part = 0;   // the split policy depends on the number of query tiles only
@@ -221,16 +240,24 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     char* kv_layer = c->kv + (size_t)l * c->kv_layer_bytes;
     int32_t* topk_idx = at<int32_t>(ws, w.topk_idx) + (size_t)l * T * f.top_k;
     float* topk_w = at<float>(ws, w.topk_w) + (size_t)l * T * f.top_k;
+    const int64_t xn_plane = (int64_t)c->max_tokens * H;
+    void* xn = ws + w.xn;
+    float* tk_part = at<float>(ws, w.tk_part);
+    int32_t* tickets = at<int32_t>(ws, w.tickets);
     if (l == 0)
-      launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a, st);
+      launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a,
+                   at<float>(c->weights, lw.attn_gain), xn, xn_plane, st);
     else
-      launch_combine(x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k, f.top_k,
-                     f.rms_eps, T, H, rinv_a, st);
-    QkvArgs qa{c->weights + lw.wqkv, x, at<float>(c->weights, lw.attn_gain), rinv_a, ws + w.q, a_plane, kv_layer,
-               c->geom, meta, d_page_table, pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H};
+      launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k, f.top_k,
+                     f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, xn_plane, st);
+    QkvArgs qa{c->weights + lw.wqkv, xn, xn_plane, rinv_a, ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table,
+               pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H, tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_QKV, st);
       launch_qkv(bf, qa, st);
+#ifdef DINFER_TRACE
+      if (DINFER_TRACE == 1 && getenv("DINFER_TRACE_REPEAT")) launch_qkv(bf, qa, st);   // second launch: warm caches
+#endif
     }
     AttnArgs aa{ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
                 attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), ws + w.a, a_plane};
@@ -238,18 +265,20 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
       launch_attention(bf, aa, st);
     }
+    OprojArgs oa{c->weights + lw.wo, ws + w.a, a_plane, x, at<float>(c->weights, lw.ffn_gain), xn, xn_plane,
+                 at<float>(ws, w.ssq), T, D, H, tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_OPROJ, st);
-      launch_oproj(bf, c->weights + lw.wo, ws + w.a, a_plane, x, T, D, H, st);
+      launch_oproj(bf, oa, st);
     }
-    RouterArgs ra{c->weights + lw.router, x, at<float>(c->weights, lw.ffn_gain), f.rms_eps, T, H, f.n_experts, f.top_k,
+    RouterArgs ra{c->weights + lw.router, xn, xn_plane, at<float>(ws, w.ssq), f.rms_eps, T, H, f.n_experts, f.top_k,
                   f.norm_topk, rinv_f, topk_idx, topk_w, at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
-                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair)};
+                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_ROUTER, st);
       launch_router(bf, ra, st);
     }
-    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, x, at<float>(c->weights, lw.ffn_gain), rinv_f,
+    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, xn, xn_plane, rinv_f,
                   ws + w.y, y_plane, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
                   at<int32_t>(ws, w.perm), T, H, f.moe_inter, f.n_experts, f.top_k};
     {
@@ -262,8 +291,9 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     }
   }
   // the last layer's expert outputs are folded into the residual here; rinv_a then belongs to the final norm
-  launch_combine(x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
-                 at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a, st);
+  launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
+                 at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a,
+                 at<float>(c->weights, c->wm.final_gain), ws + w.xn, (int64_t)c->max_tokens * H, st);
   (void)with_head;
   c->last_T = T;
   HIP_TRY(hipGetLastError());
@@ -363,6 +393,12 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     delete c;
     return fail(DINFER_EHIP, "the runtime refused the kernels' LDS sizes");
   }
+  // the arrival counters start at zero and every kernel that uses them leaves them at zero
+  if (hipMemsetAsync(c->ws + c->wsm.tickets, 0, c->wsm.tickets_bytes, (hipStream_t)stream) != hipSuccess) {
+    (void)hipHostFree(c->h_mask_pinned);
+    delete c;
+    return fail(DINFER_EHIP, "clearing the workspace failed");
+  }
   launch_rope_table(at<float>(c->ws, c->wsm.cos_tab), at<float>(c->ws, c->wsm.sin_tab), cfg->max_pos, cfg->head_dim,
                     cfg->rope_theta, (hipStream_t)stream);
   hipError_t e = hipGetLastError();
@@ -457,7 +493,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   if (rc != DINFER_OK) return rc;
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
-  LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn, (int64_t)c->max_tokens * f.hidden,
             at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
@@ -580,7 +616,7 @@ int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* strea
   if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
   if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
-  LmArgs la{c->weights + c->wm.lm_head, at<float>(c->ws, c->wsm.x), at<float>(c->weights, c->wm.final_gain),
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn, (int64_t)c->max_tokens * f.hidden,
             at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);
@@ -604,6 +640,14 @@ int dinfer_debug_get(dinfer_ctx* c, int32_t what, void* d_out, size_t bytes, voi
   }
   if (bytes != want || want == 0) return fail(DINFER_EINVAL, "%zu bytes given, %zu expected", bytes, want);
   HIP_TRY(hipMemcpyAsync(d_out, c->ws + off, want, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return DINFER_OK;
+}
+
+int dinfer_debug_trace(int32_t unit, void* h_out, size_t bytes) {
+  if (!h_out) return fail(DINFER_EINVAL, "null argument");
+  const int r = unit == 0 ? trace_read_gemm(h_out, bytes) : unit == 1 ? trace_read_attention(h_out, bytes) : -2;
+  if (r == -1) return fail(DINFER_EINVAL, "library built without DINFER_TRACE, or buffer too large");
+  if (r != 0) return fail(DINFER_EINVAL, "trace read failed (%d)", r);
   return DINFER_OK;
 }
 

@@ -81,6 +81,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
   const int n_keys = meta.seq_nkeys[seq];
   const int D = geom.n_heads * HD;
   const float scale = rsqrtf((float)HD);
+  TRACE_MARK(7, 0);
   // The sequence's page-table row goes to LDS first: a tile's K / V addresses then need no global round trip
   // of their own, and the loads of the next tile can be issued at once.
   __shared__ int32_t pt[ATTN_MAX_PAGES];
@@ -90,6 +91,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     for (int i = threadIdx.x; i < n_pages_used; i += blockDim.x) pt[i] = row[i];
     __syncthreads();
   }
+  TRACE_MARK(7, 1);
 
   // Q^T operand: this lane's query column, all of head_dim
   // (queries and probabilities enter the MFMAs as hi + lo planes when E is bf16, like every activation)
@@ -185,6 +187,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     }
     cur = nxt;
   }
+  TRACE_MARK(7, 2);
   // ---- fold the four waves through LDS (lane-major, conflict free); wave 0 finishes
   extern __shared__ float lds[];                       // [3 waves][DT*16 + 2][64 lanes]
   constexpr int PW = (DT * 16 + 2) * WAVE;
@@ -199,6 +202,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     pb[(DT * 16 + 1) * WAVE] = l_tot;
   }
   __syncthreads();
+  TRACE_MARK(7, 3);
   if (wave != 0) return;
   float M = m_run;
 #pragma unroll
@@ -232,6 +236,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
 #pragma unroll
         for (int v = 0; v < 16; ++v) store_act<E>(out, dst + t * TILE + acc_row(v, half), out_plane, o[t][v] * inv);
     }
+    TRACE_MARK(7, 4);
     return;
   }
   // partial of this split: O [32 q][HD] (unnormalised), m [32], l [32]
@@ -315,5 +320,7 @@ void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st) {
     else launch_attention_t<float, 64>(a, st);
   }
 }
+
+TRACE_READER(trace_read_attention)
 
 }  // namespace dinfer

@@ -54,6 +54,22 @@ template <> __device__ inline void store_act<bf16_t>(bf16_t* base, int64_t idx, 
   base[idx + plane] = (bf16_t)(v - (float)hi);
 }
 
+// Four consecutive activations at once (idx a multiple of 4).
+template <typename E> __device__ inline void store_act4(E* base, int64_t idx, int64_t plane, const f32x4& v);
+template <> __device__ inline void store_act4<float>(float* base, int64_t idx, int64_t, const f32x4& v) {
+  *reinterpret_cast<f32x4*>(base + idx) = v;
+}
+template <> __device__ inline void store_act4<bf16_t>(bf16_t* base, int64_t idx, int64_t plane, const f32x4& v) {
+  bf16x4 hi, lo;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = (bf16_t)v[i];
+    lo[i] = (bf16_t)(v[i] - (float)hi[i]);
+  }
+  *reinterpret_cast<bf16x4*>(base + idx) = hi;
+  *reinterpret_cast<bf16x4*>(base + idx + plane) = lo;
+}
+
 // acc[32 x 32] += A[32 x KS] * B[KS x 32].  Lane l supplies row (A) / column (B) l%32 and the G consecutive
 // k values that start at (l/32)*G; result: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4.
 __device__ inline void mfma32(f32x16& acc, const bf16x8& a, const bf16x8& b) {
@@ -84,6 +100,32 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
+// Data handed from one workgroup to another INSIDE a kernel goes through device-coherent accesses (they bypass
+// the per-XCD L2, which is not coherent across the chip): no cache-wide write-back or invalidate is needed then.
+__device__ inline void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float coherent_load(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Completion ticket over the n workgroups that share the counter *c (zero before the first arrives): true in every
+// thread of the workgroup that arrives last, which has then reset the counter for the next use.  What the other
+// n-1 workgroups wrote with coherent_store before their call can be read with coherent_load afterwards: every
+// thread waits for its own stores to complete, then one thread counts the arrival.  Nothing spins, so the order
+// in which workgroups are scheduled does not matter.  Every thread of the workgroup must call.
+__device__ inline bool last_arrival(int32_t* c, int n, int32_t* s_flag) {
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's global stores have been performed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int last = atomicAdd(c, 1) == n - 1;
+    if (last) atomicExch(c, 0);
+    *s_flag = last;
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
 // Which sequence a forward's packed tokens belong to: sequence s owns tokens [off[s], off[s+1]).
 struct SeqSpan {
   int32_t n_seq;
@@ -108,5 +150,28 @@ __device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int sl
   return (int64_t)page * g.page_stride + (int64_t)g.n_heads * PAGE * g.head_dim +
          ((int64_t)head * g.head_dim + d) * PAGE + slot;
 }
+
+// Optional in-kernel phase timestamps (builds with -DDINFER_TRACE=<kernel id> only): thread 0 of every workgroup
+// of the chosen kernel stores the 100 MHz wall clock at each mark.  Kernel ids: 1 QKV, 2 O-proj, 3 router,
+// 4 expert GEMM 1, 5 expert GEMM 2, 6 LM head, 7 attention, 8 combine.
+#ifdef DINFER_TRACE
+constexpr int TRACE_WGS = 8192, TRACE_SLOTS = 8;
+static __device__ unsigned long long g_trace[TRACE_WGS * TRACE_SLOTS];
+#define TRACE_MARK(kid, slot)                                                                          \
+  do {                                                                                                 \
+    if ((kid) == DINFER_TRACE && threadIdx.x == 0) {                                                   \
+      const unsigned wg_ = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;             \
+      if (wg_ < (unsigned)TRACE_WGS) g_trace[wg_ * TRACE_SLOTS + (slot)] = wall_clock64();             \
+    }                                                                                                  \
+  } while (0)
+#define TRACE_READER(name)                                                                             \
+  int name(void* h_out, size_t bytes) {                                                                \
+    if (bytes > sizeof(unsigned long long) * TRACE_WGS * TRACE_SLOTS) return -1;                       \
+    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_trace), bytes);                                \
+  }
+#else
+#define TRACE_MARK(kid, slot) do {} while (0)
+#define TRACE_READER(name) int name(void*, size_t) { return -1; }
+#endif
 
 }  // namespace dinfer

@@ -1,23 +1,30 @@
 // The dense contractions of the step as weight-streaming MFMA kernels (core in gemm.hpp):
 //   QKV projection + rotary embedding + KV-page write, output projection + residual,
-//   RMSNorm + router + top-k (+ token->expert permutation), routed-expert grouped GEMMs (gate/up + SwiGLU,
-//   down), LM head + streaming max / arg max / sum-exp.
-// RMSNorm is never materialised: kernels that consume a normalised residual stream read the float32 stream
-// itself (times the gain, see XLoader) and scale their accumulators by the row's 1/rms in the epilogue.
+//   router + top-k (+ token->expert permutation), routed-expert grouped GEMMs (gate/up + SwiGLU, down),
+//   LM head + streaming max / arg max / sum-exp.
+// RMSNorm is never materialised.  Whoever produces a residual row also stores it multiplied by the gain of the
+// norm that follows, as MFMA-ready planes ("normalised-input planes", without the 1/rms factor); the consumers
+// feed those planes to the matrix cores and scale their accumulators by the row's 1/rms in the epilogue.
 #include "gemm.hpp"
 #include "kernels.hpp"
 
 namespace dinfer {
 
 // ------------------------------------------------------------------------------------------------
-// Split-K kernel for the attention-side projections: one workgroup per (token group, task); its KSPLIT
-// waves each stream a K slice of the task's weights, partial tiles are summed through LDS in wave order
-// (deterministic), wave 0 runs the epilogue.
+// Split-K kernel for the attention-side projections.  A task (64 output features) of one token group is shared
+// by `slices` workgroups of KW waves; every wave streams its own K range.  The partial tiles of a workgroup are
+// summed through LDS in wave order; with more than one slice the workgroup sums go to global memory and the
+// workgroup that arrives last adds them in slice order (so the result does not depend on scheduling) and runs
+// the epilogue.  At small token counts the host picks the slices so that a wave's whole K range is in flight at
+// once: these kernels are bound by memory latency, not bandwidth, and every further dependent round trip
+// costs microseconds.
 // ------------------------------------------------------------------------------------------------
 // Epilogues receive, for one token (lane) and one accumulator tile pair, PER consecutive accumulator registers
 // v0 .. v0+PER-1 of tile 0 (a0) and tile 1 (a1): rows acc_row(v0, half) .. +PER-1 of each tile, which are PER
-// consecutive features (v0 is a multiple of PER, PER divides 4).
+// consecutive features (v0 is a multiple of PER, PER divides 4).  apply() returns the lane's contribution to the
+// row statistic of the epilogue (ROWSUM), which the kernel sums over the task and hands to row_sum().
 template <typename E> struct QkvEpi {
+  static constexpr bool ROWSUM = false;
   E* q;
   int64_t q_plane;
   E* kv_layer;
@@ -32,9 +39,9 @@ template <typename E> struct QkvEpi {
   int D;               // n_heads * head_dim
 
   template <int PER>
-  __device__ void apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
-                        const float (&a1)[PER]) const {
-    if (!valid) return;
+  __device__ float apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+                         const float (&a1)[PER]) const {
+    if (!valid) return 0.f;
     const int hd = geom.head_dim;
     const int per_head = hd / 64;
     const int qk_tasks = geom.n_heads * per_head;
@@ -83,24 +90,42 @@ template <typename E> struct QkvEpi {
         kv_layer[kv_v_index(geom, page, f1 / hd, slot, f1 % hd)] = from_f32<E>(a1[i] * r);
       }
     }
+    return 0.f;
   }
+  __device__ void row_sum(int, int, float) const {}
 };
 
-struct ResidualEpi {
+// x += result; the new row also goes out as normalised-input planes for the expert half (times its norm's gain),
+// and the task's share of the row's sum of squares to ssq[task][token].
+template <typename E> struct ResidualEpi {
+  static constexpr bool ROWSUM = true;
   float* x;
   int H;
+  const float* gain;   // [H] gain of the norm that follows
+  E* xn;               // [T][H] planes
+  int64_t xn_plane;
+  float* ssq;          // [H/64][T]
+  int T;
+
   template <int PER>
-  __device__ void apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
-                        const float (&a1)[PER]) const {
-    if (!valid) return;
-    float* p0 = x + (int64_t)tok * H + (2 * task) * TILE + acc_row(v0, half);
-    float* p1 = p0 + TILE;
+  __device__ float apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+                         const float (&a1)[PER]) const {
+    if (!valid) return 0.f;
+    const int col = (2 * task) * TILE + acc_row(v0, half);
+    float* p0 = x + (int64_t)tok * H + col;
+    float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      p0[i] += a0[i];
-      p1[i] += a1[i];
+      const float n0 = p0[i] + a0[i], n1 = p0[TILE + i] + a1[i];
+      p0[i] = n0;
+      p0[TILE + i] = n1;
+      store_act<E>(xn, (int64_t)tok * H + col + i, xn_plane, n0 * gain[col + i]);
+      store_act<E>(xn, (int64_t)tok * H + col + TILE + i, xn_plane, n1 * gain[col + TILE + i]);
+      ss += n0 * n0 + n1 * n1;
     }
+    return ss;
   }
+  __device__ void row_sum(int task, int tok, float s) const { ssq[(int64_t)task * T + tok] = s; }
 };
 
 // Every wave leaves its partial accumulators in LDS: red[wave][t*32 + tile*16 + v][lane].
@@ -116,78 +141,147 @@ __device__ inline void spill_partials(float* red, int wave, int lane, const f32x
     }
 }
 
-// XIN: the B operand is the float32 residual stream times `gain` (XLoader); else E planes (PlaneLoader).
-// After the K slices are streamed, the sum over the KSPLIT partials (wave order: deterministic) and the
-// epilogue are shared out: wave w finishes accumulator registers w*PER .. w*PER+PER-1 of both tiles.
-template <typename E, int TT, int KSPLIT, bool XIN, class Epi>
-__global__ __launch_bounds__(KSPLIT * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
-                                                                     const void* __restrict__ B, int64_t plane,
-                                                                     const float* __restrict__ gain, int T, int K,
-                                                                     Epi epi) {
-  extern __shared__ float red[];   // [KSPLIT][2*TT*16][64]
-  __shared__ float s_gain[XIN ? MAX_HIDDEN : 4];
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / KSPLIT;
-  const int task = blockIdx.y, group = blockIdx.x;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int tok0 = group * TT * TILE;
-  f32x16 acc0[TT], acc1[TT];
-  zero_acc<TT>(acc0);
-  zero_acc<TT>(acc1);
-  const int per = (ksteps + KSPLIT - 1) / KSPLIT;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  const E* wtask = W + (int64_t)task * task_stride_elems<E>(ksteps);
-  if (XIN) {
-    stage_gain(s_gain, gain, K);
-    XLoader<E, TT, false> ld;
-#pragma unroll
-    for (int t = 0; t < TT; ++t)
-      ld.xp[t] = (const float*)B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
-    ld.gs = s_gain + half * G;
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(wtask, ks0, ks1, ld, acc0, acc1);
-  } else {
-    PlaneLoader<E, TT> ld;
-#pragma unroll
-    for (int t = 0; t < TT; ++t)
-      ld.bp[t] = (const E*)B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
-    ld.plane = plane;
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(wtask, ks0, ks1, ld, acc0, acc1);
-  }
-  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-  __syncthreads();
-  const int v0 = wave * PER;
+// Sum over the KW waves' partials in LDS: wave w takes accumulator registers w*PER .. w*PER+PER-1 of both tiles.
+template <int TT, int KW, int PER>
+__device__ inline void fold_partials(const float* red, int lane, int v0, float (&a0)[TT][PER], float (&a1)[TT][PER]) {
+  constexpr int ROWS = 2 * TT * 16;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
-    float a0[PER], a1[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      a0[i] = 0.f;
-      a1[i] = 0.f;
+      a0[t][i] = 0.f;
+      a1[t][i] = 0.f;
     }
-    for (int w = 0; w < KSPLIT; ++w) {
+    for (int w = 0; w < KW; ++w) {
       const float* r = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        a0[i] += r[i * WAVE];
-        a1[i] += r[(16 + i) * WAVE];
+        a0[t][i] += r[i * WAVE];
+        a1[t][i] += r[(16 + i) * WAVE];
       }
     }
-    const int tok = tok0 + t * TILE + (lane & 31);
-    epi.template apply<PER>(task, tok, tok < T, half, v0, a0, a1);
   }
 }
 
-template <int TT, int KSPLIT> constexpr size_t ksplit_lds() { return (size_t)KSPLIT * 2 * TT * 16 * WAVE * 4; }
+// The workgroup's sums leave for / come back from the cross-workgroup buffer: part[unit][slice][row][lane].
+template <int TT, int PER>
+__device__ inline void put_slice(float* part, int64_t unit_slice, int lane, int v0, const float (&a0)[TT][PER],
+                                 const float (&a1)[TT][PER]) {
+  float* p = part + unit_slice * (2 * TT * 16) * WAVE + lane;
+#pragma unroll
+  for (int t = 0; t < TT; ++t)
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      coherent_store(p + (t * 32 + v0 + i) * WAVE, a0[t][i]);
+      coherent_store(p + (t * 32 + 16 + v0 + i) * WAVE, a1[t][i]);
+    }
+}
+template <int TT, int PER>
+__device__ inline void sum_slices(const float* part, int64_t unit, int n_slices, int lane, int v0, float (&a0)[TT][PER],
+                                  float (&a1)[TT][PER]) {
+#pragma unroll
+  for (int t = 0; t < TT; ++t)
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      a0[t][i] = 0.f;
+      a1[t][i] = 0.f;
+    }
+  for (int s = 0; s < n_slices; ++s) {
+    const float* p = part + (unit * n_slices + s) * (2 * TT * 16) * WAVE + lane;
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        a0[t][i] += coherent_load(p + (t * 32 + v0 + i) * WAVE);
+        a1[t][i] += coherent_load(p + (t * 32 + 16 + v0 + i) * WAVE);
+      }
+  }
+}
 
-template <typename E, bool XIN, class Epi>
-static void launch_ksplit(const E* W, int ksteps, const void* B, int64_t plane, const float* gain, int T, int K,
-                          int n_tasks, const Epi& epi, hipStream_t st) {
+template <typename E, int TT, int KW, class Epi>
+__global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
+                                                                 const E* __restrict__ B, int64_t plane, int T, int K,
+                                                                 float* __restrict__ part, int32_t* __restrict__ tickets,
+                                                                 Epi epi) {
+  extern __shared__ float red[];   // [KW][2*TT*16][64]
+  __shared__ int32_t s_flag;
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / KW;
+  [[maybe_unused]] constexpr int KID = Epi::ROWSUM ? 2 : 1;
+  const int slice = blockIdx.x, n_slices = gridDim.x, task = blockIdx.y, group = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int tok0 = group * TT * TILE;
+  TRACE_MARK(KID, 0);
+  f32x16 acc0[TT], acc1[TT];
+  zero_acc<TT>(acc0);
+  zero_acc<TT>(acc1);
+  const int per = (ksteps + n_slices * KW - 1) / (n_slices * KW);
+  const int ks0 = min(ksteps, (slice * KW + wave) * per), ks1 = min(ksteps, ks0 + per);
+  PlaneLoader<E, TT> ld;
+#pragma unroll
+  for (int t = 0; t < TT; ++t) ld.bp[t] = B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
+  ld.plane = plane;
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, ld, acc0, acc1);
+  TRACE_MARK(KID, 1);
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  TRACE_MARK(KID, 2);
+  const int v0 = wave * PER;
+  float a0[TT][PER], a1[TT][PER];
+  fold_partials<TT, KW, PER>(red, lane, v0, a0, a1);
+  if (n_slices > 1) {
+    const int64_t unit = (int64_t)task * gridDim.z + group;
+    put_slice<TT, PER>(part, unit * n_slices + slice, lane, v0, a0, a1);
+    if (!last_arrival(tickets + unit, n_slices, &s_flag)) return;
+    TRACE_MARK(KID, 3);
+    sum_slices<TT, PER>(part, unit, n_slices, lane, v0, a0, a1);
+  }
+  float ss[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int tok = tok0 + t * TILE + (lane & 31);
+    ss[t] = epi.template apply<PER>(task, tok, tok < T, half, v0, a0[t], a1[t]);
+  }
+  if (Epi::ROWSUM) {
+    // the task's row statistic: both half-waves of a column, then the KW waves in order
+    __syncthreads();   // the partials in `red` are consumed
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      const float s2 = ss[t] + __shfl_xor(ss[t], 32, WAVE);
+      if (half == 0) red[(wave * TT + t) * TILE + lane] = s2;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < TT * TILE; i += KW * WAVE) {
+      float s = 0.f;
+      for (int w = 0; w < KW; ++w) s += red[w * TT * TILE + i];
+      const int tok = tok0 + i;
+      if (tok < T) epi.row_sum(task, tok, s);
+    }
+  }
+  TRACE_MARK(KID, 4);
+}
+
+template <int TT, int KW> constexpr size_t ksplit_lds() { return (size_t)KW * 2 * TT * 16 * WAVE * 4; }
+
+// K slices (workgroups) per task: as many as leave every wave exactly one burst of k-steps (8 with one token
+// tile, 4 with two), when K divides that way; one otherwise and whenever there are several token groups.
+int gemm_slices(bool bf16, int K, int T) {
+  if (T > 2 * TILE) return 1;
+  const int ksteps = K / (bf16 ? 16 : 8);
+  const int burst = 4 * (T <= TILE ? 8 : 4);   // KW = 4 waves
+  return ksteps % burst == 0 ? ksteps / burst : 1;
+}
+
+template <typename E, class Epi>
+static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int64_t plane, int T, int K, int n_tasks,
+                          float* part, int32_t* tickets, const Epi& epi, hipStream_t st) {
+  const int slices = gemm_slices(bf16, K, T);
   if (T <= 32) {
-    gemm_ksplit_kernel<E, 1, 8, XIN, Epi><<<dim3(1, n_tasks), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
+    gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
   } else if (T <= 64) {
-    gemm_ksplit_kernel<E, 2, 4, XIN, Epi><<<dim3(1, n_tasks), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
+    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, XIN, Epi><<<dim3(groups, n_tasks), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, plane, gain, T, K, epi);
+    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
   }
 }
 
@@ -199,37 +293,41 @@ static bool opt_in_lds(const void* fn) {
   const int room = 160 * 1024 - (int)fa.sharedSizeBytes;
   return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, room) == hipSuccess;
 }
-template <typename E, bool XIN, class Epi> static bool configure_ksplit() {
-  return opt_in_lds((const void*)gemm_ksplit_kernel<E, 1, 8, XIN, Epi>) &&
-         opt_in_lds((const void*)gemm_ksplit_kernel<E, 2, 4, XIN, Epi>) &&
-         opt_in_lds((const void*)gemm_ksplit_kernel<E, 4, 4, XIN, Epi>);
+template <typename E, class Epi> static bool configure_ksplit() {
+  return opt_in_lds((const void*)gemm_ksplit_kernel<E, 1, 4, Epi>) &&
+         opt_in_lds((const void*)gemm_ksplit_kernel<E, 2, 4, Epi>) &&
+         opt_in_lds((const void*)gemm_ksplit_kernel<E, 4, 4, Epi>);
 }
 
-template <typename E> static void launch_qkv_t(const QkvArgs& a, hipStream_t st) {
+template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipStream_t st) {
   const int D = a.geom.n_heads * a.geom.head_dim;
   QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
                 a.pt_stride, a.cos_tab, a.sin_tab, a.rinv, D};
-  launch_ksplit<E, true>((const E*)a.w, a.H / ET<E>::KS, a.x, 0, a.gain, a.T, a.H, 3 * D / 64, epi, st);
+  launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.xn_plane, a.T, a.H, 3 * D / 64, a.part,
+                   a.tickets, epi, st);
 }
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
-  if (bf16) launch_qkv_t<bf16_t>(a, st);
-  else launch_qkv_t<float>(a, st);
+  if (bf16) launch_qkv_t<bf16_t>(true, a, st);
+  else launch_qkv_t<float>(false, a, st);
 }
 
-void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
-                  hipStream_t st) {
-  ResidualEpi epi{x, H};
-  if (bf16) launch_ksplit<bf16_t, false>((const bf16_t*)w, D / 16, a, act_plane, nullptr, T, D, H / 64, epi, st);
-  else launch_ksplit<float, false>((const float*)w, D / 8, a, act_plane, nullptr, T, D, H / 64, epi, st);
+template <typename E> static void launch_oproj_t(bool bf16, const OprojArgs& a, hipStream_t st) {
+  ResidualEpi<E> epi{a.x, a.H, a.gain, (E*)a.xn, a.xn_plane, a.ssq, a.T};
+  launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.a_plane, a.T, a.D, a.H / 64, a.part, a.tickets,
+                   epi, st);
+}
+void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
+  if (bf16) launch_oproj_t<bf16_t>(true, a, st);
+  else launch_oproj_t<float>(false, a, st);
 }
 
 // ------------------------------------------------------------------------------------------------
-// Router.  One workgroup per token group: its KSPLIT waves split K; each reads the float32 residual rows
-// (XLoader, which also sums their squares); the single weight task holds experts 0-31 (tile 0) and 32-63
-// (tile 1).  Every wave leaves its partial in LDS; then all threads fold the partials into logits[token][expert]
-// (times the row's 1/rms), and groups of 16 lanes (4 experts per lane) take one token each through softmax and
-// the k selection rounds (ties to the lower expert id).  With a single token group the same workgroup goes on
-// to build the token->expert permutation.
+// Router.  The single weight task holds experts 0-31 (tile 0) and 32-63 (tile 1); per token group its K range is
+// shared by `slices` workgroups of KW waves exactly as in the split-K kernel above.  The workgroup that holds the
+// complete sums turns them into logits[token][expert] (times the row's 1/rms, which it derives from the per-task
+// sums of squares the output projection left), then groups of 16 lanes (4 experts per lane) take one token each
+// through softmax and the k selection rounds (ties to the lower expert id).  With a single token group the same
+// workgroup goes on to build the token->expert permutation.
 // ------------------------------------------------------------------------------------------------
 // All-reduce over the 16 lanes of a group.
 __device__ inline float group16_max(float v) {
@@ -311,66 +409,75 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
   }
 }
 
-template <typename E, int TT, int KSPLIT>
-__global__ __launch_bounds__(KSPLIT * WAVE) void router_kernel(const E* __restrict__ W, const float* __restrict__ x,
-                                                                const float* __restrict__ gain, float eps, int T, int H,
-                                                                int n_exp, int top_k, int norm_topk,
-                                                                float* __restrict__ rinv, int32_t* __restrict__ topk_idx,
-                                                                float* __restrict__ topk_w, int fuse_permute,
-                                                                int32_t* __restrict__ cnt, int32_t* __restrict__ off,
-                                                                int32_t* __restrict__ perm,
-                                                                int32_t* __restrict__ pos_of_pair) {
-  extern __shared__ float red[];   // [KSPLIT][2*TT*16 + TT][64] partials, then logits [TT*32][64]
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16 + TT, NTOK = TT * TILE, NTHREADS = KSPLIT * WAVE;
-  __shared__ float s_gain[MAX_HIDDEN];
-  constexpr int LOGIT_STRIDE = MAX_EXPERTS + 1;
+template <typename E, int TT, int KW>
+__global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                            int64_t xn_plane, const float* __restrict__ ssq, int n_ssq,
+                                                            float eps, int T, int H, int n_exp, int top_k, int norm_topk,
+                                                            float* __restrict__ rinv, int32_t* __restrict__ topk_idx,
+                                                            float* __restrict__ topk_w, int fuse_permute,
+                                                            int32_t* __restrict__ cnt, int32_t* __restrict__ off,
+                                                            int32_t* __restrict__ perm,
+                                                            int32_t* __restrict__ pos_of_pair, float* __restrict__ part,
+                                                            int32_t* __restrict__ tickets) {
+  extern __shared__ float red[];   // [KW][2*TT*16][64] partials
+  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, NTOK = TT * TILE, NTHREADS = KW * WAVE, PER = 16 / KW;
+  constexpr int LOGIT_STRIDE = MAX_EXPERTS + 1;   // padded: the transposed writes spread over the banks
   __shared__ float s_logit[NTOK * LOGIT_STRIDE];
+  __shared__ float s_rinv[NTOK];
   __shared__ int32_t s_idx[NTOK * MAX_TOPK];
   __shared__ int32_t s_cc[8 * MAX_EXPERTS];
-  const int group = blockIdx.x;
+  __shared__ int32_t s_flag;
+  const int slice = blockIdx.x, n_slices = gridDim.x, group = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int tok0 = group * NTOK;
   const int ksteps = H / ET<E>::KS;
+  TRACE_MARK(3, 0);
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
-  XLoader<E, TT, true> ld;
+  PlaneLoader<E, TT> ld;
+#pragma unroll
+  for (int t = 0; t < TT; ++t) ld.bp[t] = xn + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * H + half * G;
+  ld.plane = xn_plane;
+  const int per = (ksteps + n_slices * KW - 1) / (n_slices * KW);
+  const int ks0 = min(ksteps, (slice * KW + wave) * per), ks1 = min(ksteps, ks0 + per);
+  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
+  TRACE_MARK(3, 1);
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  // the row's sum of squares = sum of the per-task shares, in task order
+  float row_ss = 0.f;
+  if (threadIdx.x < NTOK) {
+    const int tok = min(tok0 + (int)threadIdx.x, T - 1);
+    for (int j = 0; j < n_ssq; ++j) row_ss += ssq[(int64_t)j * T + tok];
+  }
+  __syncthreads();
+  TRACE_MARK(3, 2);
+  const int v0 = wave * PER;
+  float a0[TT][PER], a1[TT][PER];
+  fold_partials<TT, KW, PER>(red, lane, v0, a0, a1);
+  if (n_slices > 1) {
+    put_slice<TT, PER>(part, (int64_t)group * n_slices + slice, lane, v0, a0, a1);
+    if (!last_arrival(tickets + group, n_slices, &s_flag)) return;
+    sum_slices<TT, PER>(part, group, n_slices, lane, v0, a0, a1);
+  }
+  if (threadIdx.x < NTOK) {
+    const float r = rsqrtf(row_ss / H + eps);
+    s_rinv[threadIdx.x] = r;
+    if (tok0 + (int)threadIdx.x < T) rinv[tok0 + threadIdx.x] = r;
+  }
+  __syncthreads();
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
-    ld.xp[t] = x + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * H + half * G;
-    ld.ss[t] = 0.f;
-  }
-  stage_gain(s_gain, gain, H);
-  ld.gs = s_gain + half * G;
-  const int per = (ksteps + KSPLIT - 1) / KSPLIT;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
-  {
-    float* r = red + (int64_t)wave * ROWS * WAVE + lane;
+    const int tl = t * TILE + (lane & 31);
+    const float r = s_rinv[tl];
 #pragma unroll
-    for (int t = 0; t < TT; ++t)
-      r[(2 * TT * 16 + t) * WAVE] = ld.ss[t] + __shfl_xor(ld.ss[t], 32, WAVE);   // both halves of the row slice
-  }
-  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-  __syncthreads();
-  // logits[token][expert] = (sum over the waves' partials) / rms(token).  A thread takes one accumulator
-  // register of one source lane, so that LDS reads run along the lanes (conflict free); the logit rows are
-  // padded by one float so that the transposed writes spread over the banks as well.
-  for (int item = threadIdx.x; item < 2 * TT * 16 * WAVE; item += NTHREADS) {
-    const int rr = item / WAVE, src_lane = item % WAVE;              // rr = t*32 + tile*16 + v
-    const int t = rr / 32, tile = (rr / 16) & 1, v = rr % 16;
-    const int tl = t * TILE + (src_lane & 31);
-    const int e = tile * TILE + acc_row(v, src_lane >> 5);
-    float sum = 0.f, ss = 0.f;
-    for (int w = 0; w < KSPLIT; ++w) {
-      sum += red[((int64_t)w * ROWS + rr) * WAVE + src_lane];
-      ss += red[((int64_t)w * ROWS + 2 * TT * 16 + t) * WAVE + (src_lane & 31)];
+    for (int i = 0; i < PER; ++i) {
+      s_logit[tl * LOGIT_STRIDE + acc_row(v0 + i, half)] = a0[t][i] * r;
+      s_logit[tl * LOGIT_STRIDE + TILE + acc_row(v0 + i, half)] = a1[t][i] * r;
     }
-    const float r = rsqrtf(ss / H + eps);
-    s_logit[tl * LOGIT_STRIDE + e] = sum * r;
-    if (e == 0 && tok0 + tl < T) rinv[tok0 + tl] = r;
   }
   __syncthreads();
+  TRACE_MARK(3, 3);
   // 16 lanes per token, 4 consecutive experts per lane
   const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
   for (int tl = grp; tl < NTOK; tl += NTHREADS / 16) {
@@ -429,32 +536,35 @@ __global__ __launch_bounds__(KSPLIT * WAVE) void router_kernel(const E* __restri
       s_idx[tl * top_k + sub] = tok < T ? isel : -1;
     }
   }
+  TRACE_MARK(3, 4);
   if (!fuse_permute) return;
   __syncthreads();
   ballot_permute_small(s_idx, T * top_k, n_exp, cnt, off, perm, pos_of_pair, s_cc);
+  TRACE_MARK(3, 5);
 }
 
-template <int TT, int KSPLIT> constexpr size_t router_lds() { return (size_t)KSPLIT * (2 * TT * 16 + TT) * WAVE * 4; }
-
-template <typename E> static void launch_router_t(const RouterArgs& a, hipStream_t st) {
+template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a, hipStream_t st) {
   const E* W = (const E*)a.w;
+  const int slices = gemm_slices(bf16, a.H, a.T);
   if (a.T <= 32) {
-    router_kernel<E, 1, 8><<<1, 8 * WAVE, router_lds<1, 8>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk,
-                                                                   a.rinv, a.topk_idx, a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair);
+    router_kernel<E, 1, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(
+        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else if (a.T <= 64) {
-    router_kernel<E, 2, 4><<<1, 4 * WAVE, router_lds<2, 4>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk,
-                                                                   a.rinv, a.topk_idx, a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair);
+    router_kernel<E, 2, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
+        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else {
     const int groups = (a.T + 2 * TILE - 1) / (2 * TILE);
-    router_kernel<E, 2, 4><<<groups, 4 * WAVE, router_lds<2, 4>(), st>>>(W, a.x, a.gain, a.eps, a.T, a.H, a.E, a.top_k,
-                                                                        a.norm_topk, a.rinv, a.topk_idx, a.topk_w, 0, a.cnt, a.off,
-                                                                        a.perm, a.pos_of_pair);
+    router_kernel<E, 2, 4><<<dim3(1, groups), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
+        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
     launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, st);
   }
 }
 void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
-  if (bf16) launch_router_t<bf16_t>(a, st);
-  else launch_router_t<float>(a, st);
+  if (bf16) launch_router_t<bf16_t>(true, a, st);
+  else launch_router_t<float>(false, a, st);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -463,8 +573,8 @@ void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
 // 256 KiB task with 16 KiB in flight is latency bound at a few GB/s, which sets a floor of ~50 us under the
 // kernel however few experts are touched), partials are folded through LDS in wave order, and each wave
 // finishes a share of the accumulator registers.  Experts without rows sit at the end of the grid and exit.
-//   GEMM 1: task = 32 gate features + the same 32 up features; input = residual rows (XLoader), scaled by the
-//           row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
+//   GEMM 1: task = 32 gate features + the same 32 up features; input = normalised-input planes of the token rows,
+//           scaled by the row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
 //   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[sorted row][H]
 // ------------------------------------------------------------------------------------------------
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
@@ -473,37 +583,36 @@ template <int TT> struct ExpertSplit { static constexpr int EKS = TT <= 2 ? 4 : 
 template <int TT, int EKS> constexpr size_t expert_lds() { return (size_t)EKS * 2 * TT * 16 * WAVE * 4; }
 
 template <typename E, int TT, int EKS>
-__global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __restrict__ W, const float* __restrict__ x,
-                                                                   const float* __restrict__ gain,
-                                                                   const float* __restrict__ rinv, E* __restrict__ Y,
-                                                                   const int32_t* __restrict__ cnt,
+__global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                                   int64_t xn_plane, const float* __restrict__ rinv,
+                                                                   E* __restrict__ Y, const int32_t* __restrict__ cnt,
                                                                    const int32_t* __restrict__ off,
                                                                    const int32_t* __restrict__ perm, int H, int I,
                                                                    int top_k, int64_t y_plane) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
   constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
-  __shared__ float s_gain[MAX_HIDDEN];
+  TRACE_MARK(4, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
   const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
   const int n_rows = cnt[e];
   const int row0 = group * TT * TILE;
   if (row0 >= n_rows) return;
-  stage_gain(s_gain, gain, H);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int task = blockIdx.x;
   const int n_tasks = I / TILE;
   const int base = off[e];
-  XLoader<E, TT, false> ld;
+  PlaneLoader<E, TT> ld;
   int row[TT];
   float r[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
     const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
-    ld.xp[t] = x + (int64_t)tok * H + half * G;
+    ld.bp[t] = xn + (int64_t)tok * H + half * G;
     r[t] = rinv[tok];
   }
-  ld.gs = s_gain + half * G;
+  ld.plane = xn_plane;
+  TRACE_MARK(4, 1);
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
@@ -512,8 +621,10 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
                                         acc0, acc1);
+  TRACE_MARK(4, 2);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
   __syncthreads();
+  TRACE_MARK(4, 3);
   const int v0 = wave * PER;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -538,6 +649,7 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
         store_act<E>(yrow, acc_row(v0 + i, half), y_plane, silu_f(g[i] * r[t]) * (u[i] * r[t]));
     }
   }
+  TRACE_MARK(4, 4);
 }
 
 template <typename E, int TT, int EKS>
@@ -547,6 +659,7 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
                                                                    int64_t y_plane) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
   constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
+  TRACE_MARK(5, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
   const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
   const int n_rows = cnt[e];
@@ -572,8 +685,10 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
                                         acc0, acc1);
+  TRACE_MARK(5, 2);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
   __syncthreads();
+  TRACE_MARK(5, 3);
   const int v0 = wave * PER;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -605,7 +720,7 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
 template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
   constexpr int EKS = ExpertSplit<TT>::EKS;
   expert_gemm1_kernel<E, TT, EKS><<<dim3(a.I / TILE, a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_gate_up, a.x, a.gain, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.y_plane);
+      (const E*)a.w_gate_up, (const E*)a.xn, a.xn_plane, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.y_plane);
 }
 template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
   constexpr int EKS = ExpertSplit<TT>::EKS;
@@ -632,43 +747,39 @@ void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) { DIN
 void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER_EXPERT_DISPATCH(launch_down_t) }
 
 // ------------------------------------------------------------------------------------------------
-// LM head fused with the confidence reduction.  Each wave walks tasks (64 vocabulary ids each) and keeps,
-// per token column, the running maximum logit, its lowest id, and sum exp(z - max); logits are never stored
-// (unless the debug pointer is set).  One partial (max, sum, id) per (wave, token) is written at the end.
-// Input: the residual rows (XLoader with the final gain); logit = acc * (1/rms of the row) * logit_scale.
+// LM head fused with the confidence reduction.  Workgroups of EKS waves walk the tasks (64 vocabulary ids each):
+// K is split over the waves as in the expert GEMMs; after the fold each wave owns 16/EKS accumulator registers of
+// both tiles, i.e. a fixed subset of every task's ids for each token, over which it keeps the running maximum
+// logit, its lowest id and sum exp(z - max).  One (max, sum-exp, id) partial per (workgroup, wave, token) is
+// written at the end; logits are never stored (unless the debug pointer is set).
+// Input: normalised-input planes (final gain); logit = acc * (1/rms of the row) * logit_scale.
 // ------------------------------------------------------------------------------------------------
-// Workgroups of EKS waves walk the tasks (64 vocabulary ids each): K is split over the waves as in the expert
-// GEMMs; after the fold each wave owns 16/EKS accumulator registers of both tiles, i.e. a fixed subset of every
-// task's ids for each token, over which it keeps the running maximum logit, its lowest id and sum exp(z - max).
-// One (max, sum-exp, id) partial per (workgroup, wave, token) is written at the end; logits are never stored.
 template <typename E, int TT, int EKS>
-__global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict__ W, const float* __restrict__ x,
-                                                              const float* __restrict__ gain,
+__global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                              int64_t xn_plane,
                                                               const float* __restrict__ rinv, int T, int H, int V,
                                                               float scale, float* __restrict__ part,
                                                               float* __restrict__ logits_out) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
   constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
-  __shared__ float s_gain[MAX_HIDDEN];
-  stage_gain(s_gain, gain, H);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int group = blockIdx.y;
   const int tok0 = group * TT * TILE;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
   const int ksteps = H / ET<E>::KS;
-  XLoader<E, TT, false> ld;
+  PlaneLoader<E, TT> ld;
   float m[TT], sum[TT], zs[TT];
   int best[TT];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int tok = min(tok0 + t * TILE + (lane & 31), T - 1);
-    ld.xp[t] = x + (int64_t)tok * H + half * G;
+    ld.bp[t] = xn + (int64_t)tok * H + half * G;
     zs[t] = rinv[tok] * scale;
     m[t] = -INFINITY;
     sum[t] = 0.f;
     best[t] = 0x7fffffff;
   }
-  ld.gs = s_gain + half * G;
+  ld.plane = xn_plane;
   const int per = (ksteps + EKS - 1) / EKS;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   const int v0 = wave * PER;
@@ -760,14 +871,14 @@ int lm_head_parts(int V, int T) { return lm_head_wgs(V) * (T <= 64 ? 4 : 2); }
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = lm_head_wgs(a.V);
   if (a.T <= 32) {
-    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V,
+    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
   } else if (a.T <= 64) {
-    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H, a.V,
+    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
   } else {
     const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, a.x, a.gain, a.rinv, a.T, a.H,
+    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H,
                                                                                    a.V, a.scale, a.part, a.logits_out);
   }
 }
@@ -778,9 +889,9 @@ void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
 }
 
 bool configure_kernels() {
-  bool ok = configure_ksplit<bf16_t, true, QkvEpi<bf16_t>>() && configure_ksplit<float, true, QkvEpi<float>>() &&
-            configure_ksplit<bf16_t, false, ResidualEpi>() && configure_ksplit<float, false, ResidualEpi>();
-  ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
+  bool ok = configure_ksplit<bf16_t, QkvEpi<bf16_t>>() && configure_ksplit<float, QkvEpi<float>>() &&
+            configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>();
+  ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)router_kernel<float, 1, 4>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)router_kernel<float, 2, 4>);
   ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&
        opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>) &&
@@ -790,5 +901,7 @@ bool configure_kernels() {
   (void)hipGetLastError();
   return ok;
 }
+
+TRACE_READER(trace_read_gemm)
 
 }  // namespace dinfer

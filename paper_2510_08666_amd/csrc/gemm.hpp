@@ -21,7 +21,8 @@ template <typename E> __host__ __device__ constexpr int64_t task_stride_elems(in
   return (int64_t)ksteps * 2 * WAVE * ET<E>::G;
 }
 
-// Activations already stored as Planes<E>::N planes of E (attention output, expert intermediate).
+// Activations stored as Planes<E>::N planes of E (normalised-input planes of the residual stream, queries,
+// attention output, expert intermediate).
 template <typename E, int TT> struct PlaneLoader {
   typedef typename ET<E>::vec vec;
   static constexpr int NP = Planes<E>::N, KS = ET<E>::KS;
@@ -41,49 +42,6 @@ template <typename E, int TT> struct PlaneLoader {
     for (int q = 0; q < NP; ++q) out[q] = r.p[q];
   }
 };
-
-// Rows of the float32 residual stream, multiplied by the RMSNorm gain and split into hi / lo on the fly.  The
-// row's 1/rms factor is NOT applied here: the contraction is linear in it, so the consumer's epilogue scales its
-// accumulators by it.  With SUMSQ the lane also accumulates the squares of the x values it saw.
-template <typename E, int TT, bool SUMSQ> struct XLoader {
-  typedef typename ET<E>::vec vec;
-  static constexpr int NP = Planes<E>::N, KS = ET<E>::KS, G = ET<E>::G;
-  struct Raw {
-    f32x4 x[G / 4];
-  };
-  const float* xp[TT];   // this lane's row + (lane/32)*G
-  const float* gs;       // the gain vector staged in LDS (stage_gain) + (lane/32)*G
-  float ss[TT];
-  __device__ Raw issue(int t, int ks) const {
-    Raw r;
-#pragma unroll
-    for (int j = 0; j < G / 4; ++j) r.x[j] = *reinterpret_cast<const f32x4*>(xp[t] + (int64_t)ks * KS + 4 * j);
-    return r;
-  }
-  __device__ void finish(const Raw& r, int t, int ks, vec (&out)[NP]) {
-#pragma unroll
-    for (int j = 0; j < G / 4; ++j) {
-      const f32x4 g = *reinterpret_cast<const f32x4*>(gs + ks * KS + 4 * j);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float x = r.x[j][i];
-        if (SUMSQ) ss[t] += x * x;
-        const float v = x * g[i];
-        const E hi = from_f32<E>(v);
-        out[0][4 * j + i] = hi;
-        if (NP == 2) out[NP - 1][4 * j + i] = from_f32<E>(v - to_f32(hi));
-      }
-    }
-  }
-};
-
-constexpr int MAX_HIDDEN = 4096;
-// Copies the gain vector into LDS for the XLoaders of a workgroup (ends with a barrier).
-__device__ inline void stage_gain(float* s_gain, const float* __restrict__ gain, int H) {
-  for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4)
-    *reinterpret_cast<f32x4*>(s_gain + c) = *reinterpret_cast<const f32x4*>(gain + c);
-  __syncthreads();
-}
 
 // Software-pipelined core: PF k-steps of loads are always in flight.  The loop body is straight-line (no
 // predicated loads), so the compiler can count outstanding loads exactly and every MFMA waits only for its own

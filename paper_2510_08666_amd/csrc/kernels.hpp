@@ -26,18 +26,25 @@ struct FwdMeta {            // device arrays describing the tokens of one forwar
 void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st);
 void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
                  int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
-// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps)
+// Normalised-input planes: whoever produces a residual row x[t] also stores x[t] * gain (gain of the RMSNorm
+// that follows; the row's 1/rms factor is NOT applied) as Planes<E>::N planes of the element type, [T][H] each,
+// `xn_plane` elements apart.  The consumers feed them to the matrix cores and apply 1/rms in their epilogues.
+// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, hipStream_t st);
-// x[t] += sum_j topk_w[t][j] * O[pos_of_pair[t*k+j]];  rinv[t] as above, of the updated row
-void launch_combine(float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k, float eps,
-                    int T, int H, float* rinv, hipStream_t st);
+                  float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st);
+// x[t] += sum_j topk_w[t][j] * O[pos_of_pair[t*k+j]];  rinv[t] and xn[t] as above, of the updated row
+void launch_combine(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k,
+                    float eps, int T, int H, float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st);
+
+// Cross-workgroup split-K scratch shared by the projections and the router (see gemm.hip): `part` holds the
+// workgroup sums, `tickets` one arrival counter per (task, token group), all zero between launches.
+int gemm_slices(bool bf16, int K, int T);   // workgroups that share one task's K range for T tokens
 
 struct QkvArgs {
   const void* w;            // packed fused QKV
-  const float* x;           // [T][H] residual stream
-  const float* gain;        // [H] RMSNorm gain
-  const float* rinv;        // [T] 1/rms of the rows of x
+  const void* xn;           // [T][H] normalised-input planes (attention gain)
+  int64_t xn_plane;
+  const float* rinv;        // [T] 1/rms of the residual rows
   void* q;                  // [T][D] (hi / lo planes)
   int64_t q_plane;
   void* kv_layer;           // pool base of this layer
@@ -48,6 +55,8 @@ struct QkvArgs {
   const float* cos_tab;
   const float* sin_tab;
   int T, H;
+  float* part;
+  int32_t* tickets;
 };
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st);
 
@@ -70,24 +79,41 @@ struct AttnArgs {
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim);
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
 
-void launch_oproj(bool bf16, const void* w, const void* a, int64_t act_plane, float* x, int T, int D, int H,
-                  hipStream_t st);
-// RMSNorm statistics + router logits on the matrix cores + softmax + top-k (ties to the lower expert id,
-// weights renormalised when norm_topk); for T <= 64 also the token->expert permutation (otherwise
-// launch_permute is issued behind it).
+// x += a . Wo^T; the new rows also leave as normalised-input planes (FFN gain) and, per 64-feature task, their
+// share of the row's sum of squares: ssq[H/64][T].
+struct OprojArgs {
+  const void* w;            // packed output projection
+  const void* a;            // [T][D] attention output planes
+  int64_t a_plane;
+  float* x;                 // [T][H] residual stream, updated in place
+  const float* gain;        // [H] FFN norm gain
+  void* xn;
+  int64_t xn_plane;
+  float* ssq;
+  int T, D, H;
+  float* part;
+  int32_t* tickets;
+};
+void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st);
+// Router logits on the matrix cores + softmax + top-k (ties to the lower expert id, weights renormalised when
+// norm_topk); rinv[t] from the sums of squares above; for T <= 64 also the token->expert permutation
+// (otherwise launch_permute is issued behind it).
 struct RouterArgs {
   const void* w;            // packed router weights (one task)
-  const float* x;           // [T][H] residual stream
-  const float* gain;        // [H]
+  const void* xn;           // [T][H] normalised-input planes (FFN gain)
+  int64_t xn_plane;
+  const float* ssq;         // [H/64][T]
   float eps;
   int T, H, E, top_k, norm_topk;
-  float* rinv;              // [T] out: 1/rms of the rows of x
+  float* rinv;              // [T] out: 1/rms of the residual rows
   int32_t* topk_idx;        // [T][top_k] out
   float* topk_w;            // [T][top_k] out
   int32_t* cnt;             // [E], off [E+1], perm [T*top_k], pos_of_pair [T*top_k]: out
   int32_t* off;
   int32_t* perm;
   int32_t* pos_of_pair;
+  float* part;
+  int32_t* tickets;
 };
 void launch_router(bool bf16, const RouterArgs& a, hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
@@ -96,8 +122,8 @@ void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, i
 struct ExpertArgs {
   const void* w_gate_up;    // packed [E][I/32 tasks]
   const void* w_down;       // packed [E][H/64 tasks]
-  const float* x;           // [T][H] residual stream
-  const float* gain;        // [H]
+  const void* xn;           // [T][H] normalised-input planes (FFN gain)
+  int64_t xn_plane;
   const float* rinv;        // [T]
   void* y;                  // [T*k][I] (hi / lo planes)
   int64_t y_plane;
@@ -112,8 +138,8 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
 
 struct LmArgs {
   const void* w;            // packed LM head
-  const float* x;           // [T][H] residual stream
-  const float* gain;        // [H] final norm gain
+  const void* xn;           // [T][H] normalised-input planes (final gain)
+  int64_t xn_plane;
   const float* rinv;        // [T]
   int T, H, V;
   float scale;
@@ -135,5 +161,9 @@ void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t 
 
 bool configure_kernels();     // one-time function attributes (dynamic LDS limits); false if the runtime refuses
 bool configure_attention();
+
+// In-kernel phase timestamps of builds with -DDINFER_TRACE (see common.hpp); return -1 in ordinary builds.
+int trace_read_gemm(void* h_out, size_t bytes);
+int trace_read_attention(void* h_out, size_t bytes);
 
 }  // namespace dinfer

@@ -31,13 +31,18 @@ def _variant(name):
                   9, 32, 5, 300, threshold=0.9, seed_index=9),
         "wide_bf16": W("wide_bf16", sc(tiny, n_heads=2, head_dim=128, n_experts=64, top_k=8, moe_inter=128,
                                        vocab=1000, dtype="bf16", logit_scale=1.0), 9, 32, 5, 300, threshold=0.9, seed_index=9),
+        # hidden 1024: the K range of a projection task is shared by several workgroups (cross-workgroup sums,
+        # last arrival runs the epilogue), with one and with two token tiles
+        "deep": W("deep", sc(tiny, hidden=1024), 1, 32, 40, 40, threshold=0.9, seed_index=12),
+        "deep_bf16": W("deep_bf16", sc(tiny, hidden=1024, dtype="bf16", logit_scale=1.0), 1, 64, 40, 40, threshold=0.9,
+                       seed_index=13),
         # no prefix at all: the block attends to itself only
         "noprefix": W("noprefix", tiny, 2, 32, 0, 0, threshold=0.9, seed_index=10),
     }
     return table[name]
 
 
-CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "noprefix"]
+CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "noprefix"]
 
 
 class Case:
