@@ -234,23 +234,22 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   float* x = at<float>(ws, w.x);
   float* rinv_a = at<float>(ws, w.rinv_a);
   float* rinv_f = at<float>(ws, w.rinv_f);
-  const int64_t a_plane = (int64_t)c->max_tokens * D, y_plane = (int64_t)c->max_tokens * f.top_k * f.moe_inter;
+  const int64_t q_plane = (int64_t)c->max_tokens * D;
   for (int l = 0; l < f.n_layers; ++l) {
     const LayerW& lw = c->wm.layers[l];
     char* kv_layer = c->kv + (size_t)l * c->kv_layer_bytes;
     int32_t* topk_idx = at<int32_t>(ws, w.topk_idx) + (size_t)l * T * f.top_k;
     float* topk_w = at<float>(ws, w.topk_w) + (size_t)l * T * f.top_k;
-    const int64_t xn_plane = (int64_t)c->max_tokens * H;
     void* xn = ws + w.xn;
     float* tk_part = at<float>(ws, w.tk_part);
     int32_t* tickets = at<int32_t>(ws, w.tickets);
     if (l == 0)
       launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a,
-                   at<float>(c->weights, lw.attn_gain), xn, xn_plane, st);
+                   at<float>(c->weights, lw.attn_gain), xn, st);
     else
       launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k, f.top_k,
-                     f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, xn_plane, st);
-    QkvArgs qa{c->weights + lw.wqkv, xn, xn_plane, rinv_a, ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table,
+                     f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, st);
+    QkvArgs qa{c->weights + lw.wqkv, xn, rinv_a, ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table,
                pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H, tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_QKV, st);
@@ -259,27 +258,27 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       if (DINFER_TRACE == 1 && getenv("DINFER_TRACE_REPEAT")) launch_qkv(bf, qa, st);   // second launch: warm caches
 #endif
     }
-    AttnArgs aa{ws + w.q, a_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
-                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), ws + w.a, a_plane};
+    AttnArgs aa{ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
+                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), ws + w.a, T};
     {
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
       launch_attention(bf, aa, st);
     }
-    OprojArgs oa{c->weights + lw.wo, ws + w.a, a_plane, x, at<float>(c->weights, lw.ffn_gain), xn, xn_plane,
+    OprojArgs oa{c->weights + lw.wo, ws + w.a, x, at<float>(c->weights, lw.ffn_gain), xn,
                  at<float>(ws, w.ssq), T, D, H, tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_OPROJ, st);
       launch_oproj(bf, oa, st);
     }
-    RouterArgs ra{c->weights + lw.router, xn, xn_plane, at<float>(ws, w.ssq), f.rms_eps, T, H, f.n_experts, f.top_k,
+    RouterArgs ra{c->weights + lw.router, xn, at<float>(ws, w.ssq), f.rms_eps, T, H, f.n_experts, f.top_k,
                   f.norm_topk, rinv_f, topk_idx, topk_w, at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
                   at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_ROUTER, st);
       launch_router(bf, ra, st);
     }
-    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, xn, xn_plane, rinv_f,
-                  ws + w.y, y_plane, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
+    ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, xn, rinv_f,
+                  ws + w.y, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
                   at<int32_t>(ws, w.perm), T, H, f.moe_inter, f.n_experts, f.top_k};
     {
       StageTimer tm(c, DINFER_STAGE_EXPERT_GATE_UP, st);
@@ -293,7 +292,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   // the last layer's expert outputs are folded into the residual here; rinv_a then belongs to the final norm
   launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
                  at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a,
-                 at<float>(c->weights, c->wm.final_gain), ws + w.xn, (int64_t)c->max_tokens * H, st);
+                 at<float>(c->weights, c->wm.final_gain), ws + w.xn, st);
   (void)with_head;
   c->last_T = T;
   HIP_TRY(hipGetLastError());
@@ -493,7 +492,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   if (rc != DINFER_OK) return rc;
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn, (int64_t)c->max_tokens * f.hidden,
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
             at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
@@ -616,7 +615,7 @@ int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* strea
   if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
   if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
-  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn, (int64_t)c->max_tokens * f.hidden,
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
             at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);

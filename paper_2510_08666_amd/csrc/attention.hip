@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
                                                          const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
                                                          int n_splits, float* __restrict__ part, E* __restrict__ out,
-                                                         int64_t out_plane) {
+                                                         int T_out) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE, NP = Planes<E>::N;
   const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
@@ -230,11 +230,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     // the whole key range was here: normalise and write the attention output
     if (col < nvalid) {
       const float inv = 1.f / L;
-      const int64_t dst = (int64_t)(tok0 + col) * D + head * HD;
 #pragma unroll
       for (int t = 0; t < DT; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) store_act<E>(out, dst + t * TILE + acc_row(v, half), out_plane, o[t][v] * inv);
+        for (int v = 0; v < 16; ++v)
+          store_actk<E>(out, T_out, tok0 + col, head * HD + t * TILE + acc_row(v, half), o[t][v] * inv);
     }
     TRACE_MARK(7, 4);
     return;
@@ -259,11 +259,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
 
 template <typename E, int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, FwdMeta meta, int n_heads,
-                                                          int n_parts, E* __restrict__ out, int64_t out_plane) {
+                                                          int n_parts, E* __restrict__ out, int T_out) {
   const int head = blockIdx.x, qt = blockIdx.y;
   const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
   const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
-  const int D = n_heads * HD;
   // thread -> (query, 4 consecutive features); 32 * HD / 4 items over 256 threads
   for (int item = threadIdx.x; item < TILE * HD / 4; item += 256) {
     const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
@@ -283,9 +282,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
       for (int i = 0; i < 4; ++i) acc[i] += w * ov[i];
     }
     const float inv = 1.f / L;
-    const int64_t dst = (int64_t)(tok0 + q) * D + head * HD + d;
+    f32x4 r;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) store_act<E>(out, dst + i, out_plane, acc[i] * inv);
+    for (int i = 0; i < 4; ++i) r[i] = acc[i] * inv;
+    store_actk4<E>(out, T_out, tok0 + q, head * HD + d, r);
   }
 }
 
@@ -294,10 +294,10 @@ template <int HD> constexpr size_t attn_lds() { return (size_t)3 * ((HD / TILE) 
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
   attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, attn_lds<HD>(), st>>>(
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
-      (E*)a.out, a.out_plane);
+      (E*)a.out, a.T);
   if (a.n_splits > 1)
     attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
-                                                                                  a.n_splits, (E*)a.out, a.out_plane);
+                                                                                  a.n_splits, (E*)a.out, a.T);
 }
 
 bool configure_attention() {

@@ -70,6 +70,21 @@ template <> __device__ inline void store_act4<bf16_t>(bf16_t* base, int64_t idx,
   *reinterpret_cast<bf16x4*>(base + idx + plane) = lo;
 }
 
+// Stored activation matrices [n_rows][K] that feed the matrix cores as the B operand are kept "k-major":
+//   [K / KS][n_rows][Planes<E>::N][KS]
+// so that what a wave loads for one MFMA k-step (32 rows x 2 half-lanes x 16 bytes, both planes) is one
+// contiguous piece for consecutive rows, and a handful of cache lines for gathered rows.
+template <typename E> __device__ inline int64_t act_index(int64_t n_rows, int64_t row, int col) {
+  constexpr int KS = ET<E>::KS, NP = Planes<E>::N;
+  return ((int64_t)(col / KS) * n_rows + row) * (NP * KS) + col % KS;
+}
+template <typename E> __device__ inline void store_actk(E* base, int64_t n_rows, int64_t row, int col, float v) {
+  store_act<E>(base, act_index<E>(n_rows, row, col), ET<E>::KS, v);
+}
+template <typename E> __device__ inline void store_actk4(E* base, int64_t n_rows, int64_t row, int col, const f32x4& v) {
+  store_act4<E>(base, act_index<E>(n_rows, row, col), ET<E>::KS, v);   // col a multiple of 4
+}
+
 // acc[32 x 32] += A[32 x KS] * B[KS x 32].  Lane l supplies row (A) / column (B) l%32 and the G consecutive
 // k values that start at (l/32)*G; result: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4.
 __device__ inline void mfma32(f32x16& acc, const bf16x8& a, const bf16x8& b) {

@@ -102,8 +102,7 @@ template <typename E> struct ResidualEpi {
   float* x;
   int H;
   const float* gain;   // [H] gain of the norm that follows
-  E* xn;               // [T][H] planes
-  int64_t xn_plane;
+  E* xn;               // [T][H] k-major planes
   float* ssq;          // [H/64][T]
   int T;
 
@@ -119,8 +118,8 @@ template <typename E> struct ResidualEpi {
       const float n0 = p0[i] + a0[i], n1 = p0[TILE + i] + a1[i];
       p0[i] = n0;
       p0[TILE + i] = n1;
-      store_act<E>(xn, (int64_t)tok * H + col + i, xn_plane, n0 * gain[col + i]);
-      store_act<E>(xn, (int64_t)tok * H + col + TILE + i, xn_plane, n1 * gain[col + TILE + i]);
+      store_actk<E>(xn, T, tok, col + i, n0 * gain[col + i]);
+      store_actk<E>(xn, T, tok, col + TILE + i, n1 * gain[col + TILE + i]);
       ss += n0 * n0 + n1 * n1;
     }
     return ss;
@@ -200,12 +199,12 @@ __device__ inline void sum_slices(const float* part, int64_t unit, int n_slices,
 
 template <typename E, int TT, int KW, class Epi>
 __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
-                                                                 const E* __restrict__ B, int64_t plane, int T, int K,
+                                                                 const E* __restrict__ B, int T, int K,
                                                                  float* __restrict__ part, int32_t* __restrict__ tickets,
                                                                  Epi epi) {
   extern __shared__ float red[];   // [KW][2*TT*16][64]
   __shared__ int32_t s_flag;
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / KW;
+  constexpr int ROWS = 2 * TT * 16, PER = 16 / KW;
   [[maybe_unused]] constexpr int KID = Epi::ROWSUM ? 2 : 1;
   const int slice = blockIdx.x, n_slices = gridDim.x, task = blockIdx.y, group = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
@@ -218,8 +217,7 @@ __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restr
   const int ks0 = min(ksteps, (slice * KW + wave) * per), ks1 = min(ksteps, ks0 + per);
   PlaneLoader<E, TT> ld;
 #pragma unroll
-  for (int t = 0; t < TT; ++t) ld.bp[t] = B + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * K + half * G;
-  ld.plane = plane;
+  for (int t = 0; t < TT; ++t) ld.set(t, B, T, min(tok0 + t * TILE + (lane & 31), T - 1), half);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, ld, acc0, acc1);
   TRACE_MARK(KID, 1);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
@@ -272,16 +270,16 @@ int gemm_slices(bool bf16, int K, int T) {
 }
 
 template <typename E, class Epi>
-static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int64_t plane, int T, int K, int n_tasks,
+static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int T, int K, int n_tasks,
                           float* part, int32_t* tickets, const Epi& epi, hipStream_t st) {
   const int slices = gemm_slices(bf16, K, T);
   if (T <= 32) {
-    gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   } else if (T <= 64) {
-    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, plane, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   }
 }
 
@@ -303,7 +301,7 @@ template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipS
   const int D = a.geom.n_heads * a.geom.head_dim;
   QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
                 a.pt_stride, a.cos_tab, a.sin_tab, a.rinv, D};
-  launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.xn_plane, a.T, a.H, 3 * D / 64, a.part,
+  launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, a.H, 3 * D / 64, a.part,
                    a.tickets, epi, st);
 }
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
@@ -312,8 +310,8 @@ void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
 }
 
 template <typename E> static void launch_oproj_t(bool bf16, const OprojArgs& a, hipStream_t st) {
-  ResidualEpi<E> epi{a.x, a.H, a.gain, (E*)a.xn, a.xn_plane, a.ssq, a.T};
-  launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.a_plane, a.T, a.D, a.H / 64, a.part, a.tickets,
+  ResidualEpi<E> epi{a.x, a.H, a.gain, (E*)a.xn, a.ssq, a.T};
+  launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.T, a.D, a.H / 64, a.part, a.tickets,
                    epi, st);
 }
 void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
@@ -411,7 +409,7 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
 
 template <typename E, int TT, int KW>
 __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                            int64_t xn_plane, const float* __restrict__ ssq, int n_ssq,
+                                                            const float* __restrict__ ssq, int n_ssq,
                                                             float eps, int T, int H, int n_exp, int top_k, int norm_topk,
                                                             float* __restrict__ rinv, int32_t* __restrict__ topk_idx,
                                                             float* __restrict__ topk_w, int fuse_permute,
@@ -420,7 +418,7 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
                                                             int32_t* __restrict__ pos_of_pair, float* __restrict__ part,
                                                             int32_t* __restrict__ tickets) {
   extern __shared__ float red[];   // [KW][2*TT*16][64] partials
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, NTOK = TT * TILE, NTHREADS = KW * WAVE, PER = 16 / KW;
+  constexpr int ROWS = 2 * TT * 16, NTOK = TT * TILE, NTHREADS = KW * WAVE, PER = 16 / KW;
   constexpr int LOGIT_STRIDE = MAX_EXPERTS + 1;   // padded: the transposed writes spread over the banks
   __shared__ float s_logit[NTOK * LOGIT_STRIDE];
   __shared__ float s_rinv[NTOK];
@@ -437,8 +435,7 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
   zero_acc<TT>(acc1);
   PlaneLoader<E, TT> ld;
 #pragma unroll
-  for (int t = 0; t < TT; ++t) ld.bp[t] = xn + (int64_t)min(tok0 + t * TILE + (lane & 31), T - 1) * H + half * G;
-  ld.plane = xn_plane;
+  for (int t = 0; t < TT; ++t) ld.set(t, xn, T, min(tok0 + t * TILE + (lane & 31), T - 1), half);
   const int per = (ksteps + n_slices * KW - 1) / (n_slices * KW);
   const int ks0 = min(ksteps, (slice * KW + wave) * per), ks1 = min(ksteps, ks0 + per);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
@@ -548,16 +545,16 @@ template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a
   const int slices = gemm_slices(bf16, a.H, a.T);
   if (a.T <= 32) {
     router_kernel<E, 1, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(
-        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else if (a.T <= 64) {
     router_kernel<E, 2, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
-        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else {
     const int groups = (a.T + 2 * TILE - 1) / (2 * TILE);
     router_kernel<E, 2, 4><<<dim3(1, groups), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
-        W, (const E*)a.xn, a.xn_plane, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
+        W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
     launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, st);
   }
@@ -584,13 +581,13 @@ template <int TT, int EKS> constexpr size_t expert_lds() { return (size_t)EKS * 
 
 template <typename E, int TT, int EKS>
 __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                                   int64_t xn_plane, const float* __restrict__ rinv,
-                                                                   E* __restrict__ Y, const int32_t* __restrict__ cnt,
+                                                                   const float* __restrict__ rinv, E* __restrict__ Y,
+                                                                   const int32_t* __restrict__ cnt,
                                                                    const int32_t* __restrict__ off,
-                                                                   const int32_t* __restrict__ perm, int H, int I,
-                                                                   int top_k, int64_t y_plane) {
+                                                                   const int32_t* __restrict__ perm, int T, int H, int I,
+                                                                   int top_k) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
+  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
   TRACE_MARK(4, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
   const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
@@ -608,10 +605,9 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
     const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
-    ld.bp[t] = xn + (int64_t)tok * H + half * G;
+    ld.set(t, xn, T, tok, half);
     r[t] = rinv[tok];
   }
-  ld.plane = xn_plane;
   TRACE_MARK(4, 1);
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
@@ -643,10 +639,10 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
       }
     }
     if (row[t] < n_rows) {
-      E* yrow = Y + (int64_t)(base + row[t]) * I + task * TILE;
 #pragma unroll
       for (int i = 0; i < PER; ++i)
-        store_act<E>(yrow, acc_row(v0 + i, half), y_plane, silu_f(g[i] * r[t]) * (u[i] * r[t]));
+        store_actk<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0 + i, half),
+                      silu_f(g[i] * r[t]) * (u[i] * r[t]));
     }
   }
   TRACE_MARK(4, 4);
@@ -655,10 +651,10 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
 template <typename E, int TT, int EKS>
 __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                                    float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                                   const int32_t* __restrict__ off, int H, int I,
-                                                                   int64_t y_plane) {
+                                                                   const int32_t* __restrict__ off, int n_pairs, int H,
+                                                                   int I) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
+  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
   TRACE_MARK(5, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
   const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
@@ -674,9 +670,8 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
-    ld.bp[t] = Y + (int64_t)(base + min(row[t], n_rows - 1)) * I + half * G;
+    ld.set(t, Y, n_pairs, base + min(row[t], n_rows - 1), half);
   }
-  ld.plane = y_plane;
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
@@ -720,12 +715,12 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
 template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
   constexpr int EKS = ExpertSplit<TT>::EKS;
   expert_gemm1_kernel<E, TT, EKS><<<dim3(a.I / TILE, a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_gate_up, (const E*)a.xn, a.xn_plane, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.H, a.I, a.top_k, a.y_plane);
+      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.T, a.H, a.I, a.top_k);
 }
 template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
   constexpr int EKS = ExpertSplit<TT>::EKS;
   expert_gemm2_kernel<E, TT, EKS><<<dim3(a.H / (2 * TILE), a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.H, a.I, a.y_plane);
+      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.T * a.top_k, a.H, a.I);
 }
 template <typename E, int TT> static bool configure_experts() {
   constexpr int EKS = ExpertSplit<TT>::EKS;
@@ -756,12 +751,11 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER
 // ------------------------------------------------------------------------------------------------
 template <typename E, int TT, int EKS>
 __global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                              int64_t xn_plane,
                                                               const float* __restrict__ rinv, int T, int H, int V,
                                                               float scale, float* __restrict__ part,
                                                               float* __restrict__ logits_out) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int G = ET<E>::G, ROWS = 2 * TT * 16, PER = 16 / EKS;
+  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int group = blockIdx.y;
   const int tok0 = group * TT * TILE;
@@ -773,13 +767,12 @@ __global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int tok = min(tok0 + t * TILE + (lane & 31), T - 1);
-    ld.bp[t] = xn + (int64_t)tok * H + half * G;
+    ld.set(t, xn, T, tok, half);
     zs[t] = rinv[tok] * scale;
     m[t] = -INFINITY;
     sum[t] = 0.f;
     best[t] = 0x7fffffff;
   }
-  ld.plane = xn_plane;
   const int per = (ksteps + EKS - 1) / EKS;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   const int v0 = wave * PER;
@@ -871,14 +864,14 @@ int lm_head_parts(int V, int T) { return lm_head_wgs(V) * (T <= 64 ? 4 : 2); }
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = lm_head_wgs(a.V);
   if (a.T <= 32) {
-    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H, a.V,
+    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
   } else if (a.T <= 64) {
-    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H, a.V,
+    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
   } else {
     const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, (const E*)a.xn, a.xn_plane, a.rinv, a.T, a.H,
+    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H,
                                                                                    a.V, a.scale, a.part, a.logits_out);
   }
 }

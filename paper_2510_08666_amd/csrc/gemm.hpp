@@ -21,20 +21,24 @@ template <typename E> __host__ __device__ constexpr int64_t task_stride_elems(in
   return (int64_t)ksteps * 2 * WAVE * ET<E>::G;
 }
 
-// Activations stored as Planes<E>::N planes of E (normalised-input planes of the residual stream, queries,
-// attention output, expert intermediate).
+// Activations stored k-major (see act_index in common.hpp): normalised-input planes of the residual stream,
+// attention output, expert intermediate.
 template <typename E, int TT> struct PlaneLoader {
   typedef typename ET<E>::vec vec;
-  static constexpr int NP = Planes<E>::N, KS = ET<E>::KS;
+  static constexpr int NP = Planes<E>::N, KS = ET<E>::KS, G = ET<E>::G;
   struct Raw {
     vec p[NP];
   };
-  const E* bp[TT];   // this lane's row + (lane/32)*G, hi plane
-  int64_t plane;     // elements from the hi plane to the lo plane
+  const E* bp[TT];   // this lane's row in k-step 0, hi plane, + (lane/32)*G
+  int64_t kstride;   // elements from one k-step to the next = n_rows * NP * KS
+  __device__ void set(int t, const E* base, int64_t n_rows, int64_t row, int half) {
+    bp[t] = base + row * (NP * KS) + half * G;
+    kstride = n_rows * (NP * KS);
+  }
   __device__ Raw issue(int t, int ks) const {
     Raw r;
 #pragma unroll
-    for (int q = 0; q < NP; ++q) r.p[q] = load16<E>(bp[t] + q * plane + (int64_t)ks * KS);
+    for (int q = 0; q < NP; ++q) r.p[q] = load16<E>(bp[t] + ks * kstride + q * KS);
     return r;
   }
   __device__ void finish(const Raw& r, int, int, vec (&out)[NP]) {

@@ -27,14 +27,14 @@ void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim
 void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
                  int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
 // Normalised-input planes: whoever produces a residual row x[t] also stores x[t] * gain (gain of the RMSNorm
-// that follows; the row's 1/rms factor is NOT applied) as Planes<E>::N planes of the element type, [T][H] each,
-// `xn_plane` elements apart.  The consumers feed them to the matrix cores and apply 1/rms in their epilogues.
+// that follows; the row's 1/rms factor is NOT applied) as a k-major activation matrix [T][H] (act_index in
+// common.hpp).  The consumers feed it to the matrix cores and apply 1/rms in their epilogues.
 // x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st);
+                  float* rinv, const float* gain, void* xn, hipStream_t st);
 // x[t] += sum_j topk_w[t][j] * O[pos_of_pair[t*k+j]];  rinv[t] and xn[t] as above, of the updated row
 void launch_combine(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k,
-                    float eps, int T, int H, float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st);
+                    float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st);
 
 // Cross-workgroup split-K scratch shared by the projections and the router (see gemm.hip): `part` holds the
 // workgroup sums, `tickets` one arrival counter per (task, token group), all zero between launches.
@@ -43,7 +43,6 @@ int gemm_slices(bool bf16, int K, int T);   // workgroups that share one task's 
 struct QkvArgs {
   const void* w;            // packed fused QKV
   const void* xn;           // [T][H] normalised-input planes (attention gain)
-  int64_t xn_plane;
   const float* rinv;        // [T] 1/rms of the residual rows
   void* q;                  // [T][D] (hi / lo planes)
   int64_t q_plane;
@@ -60,9 +59,8 @@ struct QkvArgs {
 };
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st);
 
-// Activations that feed an MFMA as stored tensors (queries, attention output, expert intermediate) are
-// written as Planes<E>::N planes (see common.hpp); `*_plane` is the distance in elements from the hi plane
-// to the lo plane (ignored for float32).
+// Queries are stored row-major as Planes<E>::N planes (see common.hpp), q_plane elements apart; the attention
+// output is a k-major activation matrix [T][D].
 struct AttnArgs {
   const void* q;            // [T][D]
   int64_t q_plane;
@@ -73,8 +71,8 @@ struct AttnArgs {
   int pt_stride;
   int n_qtiles, n_splits;
   float* part;              // partial results, see attention.hip
-  void* out;                // [T][D]
-  int64_t out_plane;
+  void* out;                // [T][D] k-major
+  int T;
 };
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim);
 void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
@@ -83,12 +81,10 @@ void launch_attention(bool bf16, const AttnArgs& a, hipStream_t st);
 // share of the row's sum of squares: ssq[H/64][T].
 struct OprojArgs {
   const void* w;            // packed output projection
-  const void* a;            // [T][D] attention output planes
-  int64_t a_plane;
+  const void* a;            // [T][D] attention output, k-major
   float* x;                 // [T][H] residual stream, updated in place
   const float* gain;        // [H] FFN norm gain
   void* xn;
-  int64_t xn_plane;
   float* ssq;
   int T, D, H;
   float* part;
@@ -101,7 +97,6 @@ void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st);
 struct RouterArgs {
   const void* w;            // packed router weights (one task)
   const void* xn;           // [T][H] normalised-input planes (FFN gain)
-  int64_t xn_plane;
   const float* ssq;         // [H/64][T]
   float eps;
   int T, H, E, top_k, norm_topk;
@@ -123,10 +118,8 @@ struct ExpertArgs {
   const void* w_gate_up;    // packed [E][I/32 tasks]
   const void* w_down;       // packed [E][H/64 tasks]
   const void* xn;           // [T][H] normalised-input planes (FFN gain)
-  int64_t xn_plane;
   const float* rinv;        // [T]
-  void* y;                  // [T*k][I] (hi / lo planes)
-  int64_t y_plane;
+  void* y;                  // [T*k][I] k-major
   float* o;                 // [T*k][H]
   const int32_t* cnt;
   const int32_t* off;
@@ -139,7 +132,6 @@ void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
 struct LmArgs {
   const void* w;            // packed LM head
   const void* xn;           // [T][H] normalised-input planes (final gain)
-  int64_t xn_plane;
   const float* rinv;        // [T]
   int T, H, V;
   float scale;

@@ -75,7 +75,7 @@ template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
                                                              float eps, int H, int V, float* __restrict__ x,
                                                              float* __restrict__ rinv, const float* __restrict__ gain,
-                                                             E* __restrict__ xn, int64_t xn_plane) {
+                                                             E* __restrict__ xn, int T) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
@@ -83,20 +83,18 @@ __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __re
   for (int c = threadIdx.x; c < H; c += NORM_THREADS) {
     const float v = to_f32(row[c]);
     x[(int64_t)t * H + c] = v;
-    store_act<E>(xn, (int64_t)t * H + c, xn_plane, v * gain[c]);
+    store_actk<E>(xn, T, t, c, v * gain[c]);
     ss += v * v;
   }
   ss = block_sum_256(ss, sh);
   if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st) {
+                  float* rinv, const float* gain, void* xn, hipStream_t st) {
   if (bf16)
-    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv, gain, (bf16_t*)xn,
-                                                    xn_plane);
+    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv, gain, (bf16_t*)xn, T);
   else
-    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn,
-                                                   xn_plane);
+    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn, T);
 }
 
 // x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  rinv[t] and the
@@ -108,7 +106,7 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
                                                                const float* __restrict__ topk_w, int top_k, float eps,
                                                                int H, float* __restrict__ rinv,
                                                                const float* __restrict__ gain, E* __restrict__ xn,
-                                                               int64_t xn_plane) {
+                                                               int T) {
   __shared__ float sh[4];
   constexpr int CH = NORM_MAX_PER_THREAD / 4;
   const int t = blockIdx.x;
@@ -142,20 +140,18 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
         n[i] = acc[i] * g[i];
       }
       *reinterpret_cast<f32x4*>(x + (int64_t)t * H + col) = acc;
-      store_act4<E>(xn, (int64_t)t * H + col, xn_plane, n);
+      store_actk4<E>(xn, T, t, col, n);
     }
   }
   ss = block_sum_256(ss, sh);
   if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
 void launch_combine(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k,
-                    float eps, int T, int H, float* rinv, const float* gain, void* xn, int64_t xn_plane, hipStream_t st) {
+                    float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st) {
   if (bf16)
-    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (bf16_t*)xn,
-                                                      xn_plane);
+    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (bf16_t*)xn, T);
   else
-    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (float*)xn,
-                                                     xn_plane);
+    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (float*)xn, T);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
