@@ -92,12 +92,13 @@ WeightMap map_weights(const dinfer_config& c) {
   return m;
 }
 
-// Key splits per (query tile, head).  A workgroup's four waves walk their key tiles with the next tile's loads
-// in flight, so a split is worth its merge pass only when a wave would otherwise walk more than 8 tiles; the
-// count is also capped where the grid already covers the chip (key_bound = most keys a sequence can have).
+// Key splits per (query tile, head).  A workgroup's eight waves walk their key tiles with the next tile's loads
+// in flight, every tile a dependent memory round trip; a split is worth its merge pass when a wave would
+// otherwise walk more than 4 tiles.  The count is capped where the grid already covers the chip (key_bound =
+// most keys a sequence can have).
 int attn_splits(int n_qtiles, int n_heads, int key_bound) {
   const int tiles = (key_bound + TILE - 1) / TILE;
-  int s = (tiles + 31) / 32;                               // <= 8 tiles per wave
+  int s = (tiles + 31) / 32;                               // <= 4 tiles per wave, 8 waves
   const int cover = (1024 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
   if (s > cover) s = cover;
   if (s > 32) s = 32;

@@ -1,11 +1,12 @@
 // Bidirectional (non-causal) attention of a tile of 32 query tokens over every key of its sequence: the
 // cached prefix pages plus the tokens of this forward, read through the page table.
 //
-// Work split: grid (split, head, query tile), 4 waves per workgroup; the key tiles (32 keys) are dealt
-// round-robin to the n_splits*4 waves of a (head, query tile).  Each wave keeps its own online-softmax state;
-// the four waves of a workgroup are folded through LDS in wave order.  With one split the workgroup writes
-// the normalised output itself; otherwise it writes one partial (unnormalised output, max, sum) and
-// attn_merge_kernel folds the partials of a (query tile, head) in split order.
+// Work split: grid (split, head, query tile), ATTN_WAVES waves per workgroup; the key tiles (32 keys) are dealt
+// round-robin to the n_splits*ATTN_WAVES waves of a (head, query tile).  Each wave keeps its own online-softmax
+// state; the waves of a workgroup are folded through LDS in wave order, each wave finishing its share of the
+// output rows.  With one split the workgroup writes the normalised output itself; otherwise it writes one
+// partial (unnormalised output, max, sum) and attn_merge_kernel folds the partials of a (query tile, head) in
+// split order.
 //
 // MFMA mapping (32x32 tiles):  S^T[key][query] = K_tile . Q^T   (A = K rows, B = Q columns), so a lane owns
 // one query column and softmax statistics are per lane;  O^T[d][query] += V^T_tile . P^T  (A = V^T rows read
@@ -14,6 +15,8 @@
 #include "kernels.hpp"
 
 namespace dinfer {
+
+constexpr int ATTN_WAVES = 8;
 
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim) {
   return (size_t)n_qtiles * n_heads * n_splits * TILE * (head_dim + 2);
@@ -68,7 +71,7 @@ template <> struct PvStep<float> {
 };
 
 template <typename E, int HD>
-__global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q, int64_t q_plane,
+__global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* __restrict__ Q, int64_t q_plane,
                                                          const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
                                                          int n_splits, float* __restrict__ part, E* __restrict__ out,
@@ -89,27 +92,26 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     const int32_t* row = page_table + (int64_t)seq * pt_stride;
     const int n_pages_used = (n_keys + PAGE - 1) / PAGE;       // <= pt_stride, <= ATTN_MAX_PAGES (host checks)
     for (int i = threadIdx.x; i < n_pages_used; i += blockDim.x) pt[i] = row[i];
-    __syncthreads();
   }
-  TRACE_MARK(7, 1);
 
-  // Q^T operand: this lane's query column, all of head_dim
-  // (queries and probabilities enter the MFMAs as hi + lo planes when E is bf16, like every activation)
-  vec qv[DSTEPS][NP];
+  // Q^T operand (queries and probabilities enter the MFMAs as hi + lo planes when E is bf16, like every
+  // activation): all waves use the same query tile, so it is staged once in LDS in operand order
+  // [head_dim k-step][plane][lane] and read from there in the tile loop instead of living in registers.
+  __shared__ vec qs[DSTEPS * NP * WAVE];
   {
     const E* qrow = Q + (int64_t)(tok0 + min(col, nvalid - 1)) * D + head * HD + half * G;
-#pragma unroll
-    for (int s = 0; s < DSTEPS; ++s)
-#pragma unroll
-      for (int pl = 0; pl < NP; ++pl) qv[s][pl] = load16<E>(qrow + pl * q_plane + s * KS);
+    for (int i = wave; i < DSTEPS * NP; i += ATTN_WAVES)
+      qs[i * WAVE + lane] = load16<E>(qrow + (i % NP) * q_plane + (i / NP) * KS);
   }
+  __syncthreads();
+  TRACE_MARK(7, 1);
   f32x16 o[DT];
   zero_acc<DT>(o);
   float m_run = -INFINITY, l_run = 0.f;
 
   const int n_ktiles = (n_keys + TILE - 1) / TILE;
-  const int stride = n_splits * 4;                       // key tiles are dealt round-robin to all waves
-  const int kt0 = split * 4 + wave;
+  const int stride = n_splits * ATTN_WAVES;              // key tiles are dealt round-robin to all waves
+  const int kt0 = split * ATTN_WAVES + wave;
   // K rows and V^T rows of one key tile, loaded straight into MFMA operand registers
   struct TileRegs {
     vec k[DSTEPS];
@@ -135,14 +137,16 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     // the next tile's loads are issued before this tile is used (clamped, so the loop body has no branch
     // around loads and the compiler can count them; the last iteration re-reads its own tile)
     load_tile(min(kt + stride, n_ktiles - 1), nxt);
-    // ---- S^T = K . Q^T
+    // ---- S^T = K . Q^T  (the compiler barrier keeps the query reads inside the loop: hoisted, they would
+    // occupy the 64 registers that staging them in LDS is meant to free)
+    asm volatile("" ::: "memory");
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
     for (int s = 0; s < DSTEPS; ++s)
 #pragma unroll
-      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, cur.k[s], qv[s][pl]);
+      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, cur.k[s], qs[(s * NP + pl) * WAVE + lane]);
     float p[16];
     float mx = -INFINITY;
 #pragma unroll
@@ -188,53 +192,47 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
     cur = nxt;
   }
   TRACE_MARK(7, 2);
-  // ---- fold the four waves through LDS (lane-major, conflict free); wave 0 finishes
-  extern __shared__ float lds[];                       // [3 waves][DT*16 + 2][64 lanes]
-  constexpr int PW = (DT * 16 + 2) * WAVE;
-  const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
-  if (wave > 0) {
-    float* pb = lds + (wave - 1) * PW + lane;
+  // ---- fold the waves through LDS (lane-major, conflict free): every wave leaves its state, then wave w
+  // finishes RPW of the DT*16 accumulator registers, summed over the waves in wave order
+  extern __shared__ float lds[];                       // [ATTN_WAVES][DT*16 + 2][64 lanes]
+  constexpr int PW = (DT * 16 + 2) * WAVE, RPW = DT * 16 / ATTN_WAVES;
+  static_assert(RPW % 4 == 0, "a wave finishes whole groups of four accumulator registers");
+  {
+    float* pb = lds + wave * PW + lane;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) pb[(t * 16 + v) * WAVE] = o[t][v];
     pb[(DT * 16) * WAVE] = m_run;
-    pb[(DT * 16 + 1) * WAVE] = l_tot;
+    pb[(DT * 16 + 1) * WAVE] = l_run + __shfl_xor(l_run, 32, WAVE);
   }
   __syncthreads();
   TRACE_MARK(7, 3);
-  if (wave != 0) return;
-  float M = m_run;
+  float M = -INFINITY;
 #pragma unroll
-  for (int w = 0; w < 3; ++w) M = fmaxf(M, lds[w * PW + (DT * 16) * WAVE + lane]);
-  const float s0 = m_run > -INFINITY ? __expf(m_run - M) : 0.f;
-  float L = l_tot * s0;
+  for (int w = 0; w < ATTN_WAVES; ++w) M = fmaxf(M, lds[w * PW + (DT * 16) * WAVE + lane]);
+  float L = 0.f;
+  float r[RPW];
 #pragma unroll
-  for (int t = 0; t < DT; ++t)
+  for (int i = 0; i < RPW; ++i) r[i] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[t][v] *= s0;
-#pragma unroll
-  for (int w = 0; w < 3; ++w) {
+  for (int w = 0; w < ATTN_WAVES; ++w) {
     const float* pb = lds + w * PW + lane;
     const float mw = pb[(DT * 16) * WAVE];
-    if (mw > -INFINITY) {                               // a wave that saw no key tile contributes nothing
-      const float sw = __expf(mw - M);
-      L += sw * pb[(DT * 16 + 1) * WAVE];
+    const float sw = mw > -INFINITY ? __expf(mw - M) : 0.f;   // a wave that saw no key tile contributes nothing
+    L += sw * pb[(DT * 16 + 1) * WAVE];
 #pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[t][v] += sw * pb[(t * 16 + v) * WAVE];
-    }
+    for (int i = 0; i < RPW; ++i) r[i] += sw * pb[(wave * RPW + i) * WAVE];
   }
   if (n_splits == 1) {
     // the whole key range was here: normalise and write the attention output
     if (col < nvalid) {
       const float inv = 1.f / L;
 #pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          store_actk<E>(out, T_out, tok0 + col, head * HD + t * TILE + acc_row(v, half), o[t][v] * inv);
+      for (int i = 0; i < RPW; ++i) {
+        const int g = wave * RPW + i;
+        store_actk<E>(out, T_out, tok0 + col, head * HD + (g / 16) * TILE + acc_row(g % 16, half), r[i] * inv);
+      }
     }
     TRACE_MARK(7, 4);
     return;
@@ -243,15 +241,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const E* __restrict__ Q,
   const int pidx = (qt * geom.n_heads + head) * n_splits + split;
   float* pbase = part + (int64_t)pidx * TILE * (HD + 2);
 #pragma unroll
-  for (int t = 0; t < DT; ++t)
+  for (int i4 = 0; i4 < RPW / 4; ++i4) {
+    const int g = wave * RPW + 4 * i4;
+    f32x4 v4;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      f32x4 r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = o[t][4 * g + i];
-      *reinterpret_cast<f32x4*>(pbase + col * HD + t * TILE + acc_row(4 * g, half)) = r;
-    }
-  if (half == 0) {
+    for (int i = 0; i < 4; ++i) v4[i] = r[4 * i4 + i];
+    *reinterpret_cast<f32x4*>(pbase + col * HD + (g / 16) * TILE + acc_row(g % 16, half)) = v4;
+  }
+  if (wave == 0 && half == 0) {
     pbase[TILE * HD + col] = M;
     pbase[TILE * HD + TILE + col] = L;
   }
@@ -289,10 +286,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   }
 }
 
-template <int HD> constexpr size_t attn_lds() { return (size_t)3 * ((HD / TILE) * 16 + 2) * WAVE * 4; }
+template <int HD> constexpr size_t attn_lds() { return (size_t)ATTN_WAVES * ((HD / TILE) * 16 + 2) * WAVE * 4; }
 
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
-  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), 256, attn_lds<HD>(), st>>>(
+  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), ATTN_WAVES * WAVE, attn_lds<HD>(), st>>>(
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
       (E*)a.out, a.T);
   if (a.n_splits > 1)

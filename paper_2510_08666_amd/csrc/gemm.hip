@@ -38,17 +38,44 @@ template <typename E> struct QkvEpi {
   const float* rinv;   // [T] 1/rms of the token's residual row
   int D;               // n_heads * head_dim
 
+  // What the epilogue needs from memory besides the accumulators.  prefetch() runs before the weight stream
+  // starts and issues only loads whose addresses are known then; prefetch2() runs behind the stream and issues
+  // the loads that depend on the first ones, so that they are under way while the partial sums are folded.
+  template <int PER> struct Pre {
+    int pos, seq, page;
+    float r;
+    float c[PER], s[PER];
+  };
+  template <int PER> __device__ Pre<PER> prefetch(int, int tok, bool valid, int, int) const {
+    Pre<PER> p;
+    const int t = valid ? tok : 0;
+    p.pos = tok_pos[t];
+    p.seq = tok_seq[t];
+    p.r = rinv[t];
+    return p;
+  }
+  template <int PER> __device__ void prefetch2(Pre<PER>& p, int task, int half, int v0) const {
+    const int hd = geom.head_dim;
+    p.page = page_table[(int64_t)p.seq * pt_stride + p.pos / PAGE];
+    const int j0 = (task % (hd / 64)) * TILE + acc_row(v0, half);
+    const bool rot = task < 2 * geom.n_heads * (hd / 64);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      p.c[i] = rot ? cos_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 1.f;
+      p.s[i] = rot ? sin_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 0.f;
+    }
+  }
+
   template <int PER>
-  __device__ float apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+  __device__ float apply(const Pre<PER>& pre, int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
                          const float (&a1)[PER]) const {
     if (!valid) return 0.f;
     const int hd = geom.head_dim;
     const int per_head = hd / 64;
     const int qk_tasks = geom.n_heads * per_head;
-    const int pos = tok_pos[tok];
-    const int page = safe_page(geom, page_table[(int64_t)tok_seq[tok] * pt_stride + pos / PAGE]);
-    const int slot = pos % PAGE;
-    const float r = rinv[tok];
+    const int page = safe_page(geom, pre.page);
+    const int slot = pre.pos % PAGE;
+    const float r = pre.r;
     const int row0 = acc_row(v0, half);
     if (task < 2 * qk_tasks) {
       // rotary pair: a0 holds feature j of the head, a1 feature j + hd/2
@@ -59,11 +86,9 @@ template <typename E> struct QkvEpi {
       float lo[PER], hi[PER];
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        const float c = cos_tab[(int64_t)pos * (hd / 2) + j0 + i];
-        const float s = sin_tab[(int64_t)pos * (hd / 2) + j0 + i];
         const float a = a0[i] * r, b = a1[i] * r;
-        lo[i] = a * c - b * s;
-        hi[i] = b * c + a * s;
+        lo[i] = a * pre.c[i] - b * pre.s[i];
+        hi[i] = b * pre.c[i] + a * pre.s[i];
       }
       if (is_k) {
         E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
@@ -106,8 +131,26 @@ template <typename E> struct ResidualEpi {
   float* ssq;          // [H/64][T]
   int T;
 
+  template <int PER> struct Pre {
+    float x0[PER], x1[PER], g0[PER], g1[PER];
+  };
+  template <int PER> __device__ Pre<PER> prefetch(int task, int tok, bool valid, int half, int v0) const {
+    Pre<PER> p;
+    const int col = (2 * task) * TILE + acc_row(v0, half);
+    const float* p0 = x + (int64_t)(valid ? tok : 0) * H + col;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      p.x0[i] = p0[i];
+      p.x1[i] = p0[TILE + i];
+      p.g0[i] = gain[col + i];
+      p.g1[i] = gain[col + TILE + i];
+    }
+    return p;
+  }
+  template <int PER> __device__ void prefetch2(Pre<PER>&, int, int, int) const {}
+
   template <int PER>
-  __device__ float apply(int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
+  __device__ float apply(const Pre<PER>& pre, int task, int tok, bool valid, int half, int v0, const float (&a0)[PER],
                          const float (&a1)[PER]) const {
     if (!valid) return 0.f;
     const int col = (2 * task) * TILE + acc_row(v0, half);
@@ -115,11 +158,11 @@ template <typename E> struct ResidualEpi {
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const float n0 = p0[i] + a0[i], n1 = p0[TILE + i] + a1[i];
+      const float n0 = pre.x0[i] + a0[i], n1 = pre.x1[i] + a1[i];
       p0[i] = n0;
       p0[TILE + i] = n1;
-      store_actk<E>(xn, T, tok, col + i, n0 * gain[col + i]);
-      store_actk<E>(xn, T, tok, col + TILE + i, n1 * gain[col + TILE + i]);
+      store_actk<E>(xn, T, tok, col + i, n0 * pre.g0[i]);
+      store_actk<E>(xn, T, tok, col + TILE + i, n1 * pre.g1[i]);
       ss += n0 * n0 + n1 * n1;
     }
     return ss;
@@ -210,6 +253,13 @@ __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restr
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int tok0 = group * TT * TILE;
   TRACE_MARK(KID, 0);
+  const int v0 = wave * PER;
+  typename Epi::template Pre<PER> pre[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int tok = tok0 + t * TILE + (lane & 31);
+    pre[t] = epi.template prefetch<PER>(task, tok, tok < T, half, v0);
+  }
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
@@ -220,10 +270,11 @@ __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restr
   for (int t = 0; t < TT; ++t) ld.set(t, B, T, min(tok0 + t * TILE + (lane & 31), T - 1), half);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, ld, acc0, acc1);
   TRACE_MARK(KID, 1);
+#pragma unroll
+  for (int t = 0; t < TT; ++t) epi.template prefetch2<PER>(pre[t], task, half, v0);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
   __syncthreads();
   TRACE_MARK(KID, 2);
-  const int v0 = wave * PER;
   float a0[TT][PER], a1[TT][PER];
   fold_partials<TT, KW, PER>(red, lane, v0, a0, a1);
   if (n_slices > 1) {
@@ -237,7 +288,7 @@ __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restr
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int tok = tok0 + t * TILE + (lane & 31);
-    ss[t] = epi.template apply<PER>(task, tok, tok < T, half, v0, a0[t], a1[t]);
+    ss[t] = epi.template apply<PER>(pre[t], task, tok, tok < T, half, v0, a0[t], a1[t]);
   }
   if (Epi::ROWSUM) {
     // the task's row statistic: both half-waves of a column, then the KW waves in order
@@ -327,45 +378,75 @@ void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
 // through softmax and the k selection rounds (ties to the lower expert id).  With a single token group the same
 // workgroup goes on to build the token->expert permutation.
 // ------------------------------------------------------------------------------------------------
-// All-reduce over the 16 lanes of a group.
+// Cross-lane moves inside rows of 16 lanes on the data-parallel-primitive path (no LDS round trip).  The four
+// controls below form a butterfly: after them every lane of a 16-lane group holds the group's result, provided
+// the combining step is symmetric.
+template <int CTRL> __device__ inline int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+template <int CTRL> __device__ inline float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+constexpr int DPP_SWAP1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int DPP_SWAP2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <- lane 7-i of its group of 8
+constexpr int DPP_MIRROR = 0x140;       // lane i <- lane 15-i of its row
 __device__ inline float group16_max(float v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
+  v = fmaxf(v, dpp_f<DPP_SWAP1>(v));
+  v = fmaxf(v, dpp_f<DPP_SWAP2>(v));
+  v = fmaxf(v, dpp_f<DPP_HALF_MIRROR>(v));
+  return fmaxf(v, dpp_f<DPP_MIRROR>(v));
 }
+// Sum over the group in a fixed tree; every lane ends with the same bits (each step adds the same two values on
+// both sides, and float addition commutes).
 __device__ inline float group16_sum(float v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+  v += dpp_f<DPP_SWAP1>(v);
+  v += dpp_f<DPP_SWAP2>(v);
+  v += dpp_f<DPP_HALF_MIRROR>(v);
+  return v + dpp_f<DPP_MIRROR>(v);
+}
+// Largest value of the group and the lowest id that holds it.
+template <int CTRL> __device__ inline void argmax_step(float& bv, int& bi) {
+  const float ov = dpp_f<CTRL>(bv);
+  const int oi = dpp_i<CTRL>(bi);
+  if (ov > bv || (ov == bv && oi < bi)) {
+    bv = ov;
+    bi = oi;
+  }
+}
+__device__ inline void group16_argmax(float& bv, int& bi) {
+  argmax_step<DPP_SWAP1>(bv, bi);
+  argmax_step<DPP_SWAP2>(bv, bi);
+  argmax_step<DPP_HALF_MIRROR>(bv, bi);
+  argmax_step<DPP_MIRROR>(bv, bi);
 }
 
-// Token->expert permutation of at most 8*64 pairs whose expert ids sit in LDS (s_idx): a stable counting sort
-// by wavefront ballots.  A wave takes 64 consecutive pairs; for every expert e the ballot of "my pair goes to e"
-// gives that chunk's count (kept by lane e) and, through the bits below a lane, the pair's rank inside the
-// chunk.  Lane e of wave 0 then turns the per-chunk counts into offsets.  s_cc: [8][MAX_EXPERTS] ints.
+// Token->expert permutation of at most 8*64 pairs whose expert ids sit in LDS (s_idx): a stable counting sort.
+// A wave takes 64 consecutive pairs (a chunk).  The chunk's 64 ballots "which lanes go to expert e" are formed all
+// at once by OR-ing lane bits into s_ballot[chunk][e]; a pair's rank inside its chunk is the number of set bits
+// below its lane in its expert's ballot, the chunk's count for expert e the population of ballot e.  Lane e of
+// wave 0 then turns the per-chunk counts into offsets.  s_ballot: [8][MAX_EXPERTS] 64-bit words, s_cc:
+// [8][MAX_EXPERTS] ints.  A wave owns chunks wave and wave + n_waves (at least 4 waves, at most 8 chunks).
 __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, int n_exp, int32_t* __restrict__ cnt,
                                             int32_t* __restrict__ off, int32_t* __restrict__ perm,
-                                            int32_t* __restrict__ pos_of_pair, int32_t* s_cc) {
+                                            int32_t* __restrict__ pos_of_pair, unsigned long long* s_ballot,
+                                            int32_t* s_cc) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
   const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
   const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  int my_e[2], my_rank[2];   // a wave owns chunks wave and wave + n_waves (n_waves >= 4, n_chunks <= 8)
+  for (int i = threadIdx.x; i < n_chunks * MAX_EXPERTS; i += blockDim.x) s_ballot[i] = 0ull;
+  __syncthreads();
+  int my_e[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int c = wave + i * n_waves;
-    my_e[i] = -1;
-    my_rank[i] = 0;
-    if (c < n_chunks) {
-      const int p = c * WAVE + lane;
-      my_e[i] = p < n_pairs ? s_idx[p] : -1;
-      int mine_cnt = 0;
-      for (int e = 0; e < n_exp; ++e) {
-        const uint64_t b = __ballot(my_e[i] == e);
-        if (lane == e) mine_cnt = __popcll(b);
-        if (my_e[i] == e) my_rank[i] = __popcll(b & below);
-      }
-      s_cc[c * MAX_EXPERTS + lane] = mine_cnt;     // lane = expert id (n_exp <= 64)
-    }
+    const int p = c * WAVE + lane;
+    my_e[i] = (c < n_chunks && p < n_pairs) ? s_idx[p] : -1;
+    if (my_e[i] >= 0) atomicOr(&s_ballot[c * MAX_EXPERTS + my_e[i]], 1ull << lane);
+  }
+  __syncthreads();
+  int my_rank[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = wave + i * n_waves;
+    my_rank[i] = my_e[i] >= 0 ? __popcll(s_ballot[c * MAX_EXPERTS + my_e[i]] & below) : 0;
+    if (c < n_chunks) s_cc[c * MAX_EXPERTS + lane] = __popcll(s_ballot[c * MAX_EXPERTS + lane]);   // lane = expert id
   }
   __syncthreads();
   if (wave == 0) {
@@ -387,11 +468,11 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
     const uint64_t has_rows = __ballot(tot > 0);          // dense list of the experts with rows (ACTIVE_LIST)
     if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
     if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
-    int run = start;
+    int run = start;                                      // chunk c of expert `lane` starts at run
     for (int c = 0; c < n_chunks; ++c) {
-      const int here = s_cc[c * MAX_EXPERTS + lane];
-      s_cc[c * MAX_EXPERTS + lane] = run;          // becomes: first sorted position of (chunk c, expert lane)
-      run += here;
+      const int n = s_cc[c * MAX_EXPERTS + lane];
+      s_cc[c * MAX_EXPERTS + lane] = run;
+      run += n;
     }
   }
   __syncthreads();
@@ -419,10 +500,14 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
                                                             int32_t* __restrict__ tickets) {
   extern __shared__ float red[];   // [KW][2*TT*16][64] partials
   constexpr int ROWS = 2 * TT * 16, NTOK = TT * TILE, NTHREADS = KW * WAVE, PER = 16 / KW;
+  constexpr int SS_PARTS = NTHREADS / NTOK;                       // threads per token for the sums of squares
+  constexpr int SS_PER = (MAX_HIDDEN / 64 + SS_PARTS - 1) / SS_PARTS;
   constexpr int LOGIT_STRIDE = MAX_EXPERTS + 1;   // padded: the transposed writes spread over the banks
   __shared__ float s_logit[NTOK * LOGIT_STRIDE];
+  __shared__ float s_ssp[SS_PARTS * NTOK];
   __shared__ float s_rinv[NTOK];
   __shared__ int32_t s_idx[NTOK * MAX_TOPK];
+  __shared__ unsigned long long s_ballot[8 * MAX_EXPERTS];
   __shared__ int32_t s_cc[8 * MAX_EXPERTS];
   __shared__ int32_t s_flag;
   const int slice = blockIdx.x, n_slices = gridDim.x, group = blockIdx.y;
@@ -430,6 +515,16 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
   const int tok0 = group * NTOK;
   const int ksteps = H / ET<E>::KS;
   TRACE_MARK(3, 0);
+  // shares of the rows' sums of squares (one per 64-feature task of the producer), loaded before the stream
+  float ssv[SS_PER];
+  {
+    const int tok = min(tok0 + (int)threadIdx.x % NTOK, T - 1), part0 = threadIdx.x / NTOK;
+#pragma unroll
+    for (int i = 0; i < SS_PER; ++i) {
+      const int j = part0 + i * SS_PARTS;
+      ssv[i] = j < n_ssq ? ssq[(int64_t)j * T + tok] : 0.f;
+    }
+  }
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
   zero_acc<TT>(acc1);
@@ -441,11 +536,11 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
   TRACE_MARK(3, 1);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-  // the row's sum of squares = sum of the per-task shares, in task order
-  float row_ss = 0.f;
-  if (threadIdx.x < NTOK) {
-    const int tok = min(tok0 + (int)threadIdx.x, T - 1);
-    for (int j = 0; j < n_ssq; ++j) row_ss += ssq[(int64_t)j * T + tok];
+  {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < SS_PER; ++i) s += ssv[i];
+    s_ssp[threadIdx.x] = s;     // [part][token]
   }
   __syncthreads();
   TRACE_MARK(3, 2);
@@ -458,6 +553,8 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
     sum_slices<TT, PER>(part, group, n_slices, lane, v0, a0, a1);
   }
   if (threadIdx.x < NTOK) {
+    float row_ss = 0.f;
+    for (int q = 0; q < SS_PARTS; ++q) row_ss += s_ssp[q * NTOK + threadIdx.x];
     const float r = rsqrtf(row_ss / H + eps);
     s_rinv[threadIdx.x] = r;
     if (tok0 + (int)threadIdx.x < T) rinv[tok0 + threadIdx.x] = r;
@@ -506,15 +603,7 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
           bv = p[i];
           bi = 4 * sub + i;
         }
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) {
-        const float ov = __shfl_xor(bv, o, WAVE);
-        const int oi = __shfl_xor(bi, o, WAVE);
-        if (ov > bv || (ov == bv && oi < bi)) {
-          bv = ov;
-          bi = oi;
-        }
-      }
+      group16_argmax(bv, bi);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (4 * sub + i == bi) p[i] = -1.f;
@@ -536,24 +625,32 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
   TRACE_MARK(3, 4);
   if (!fuse_permute) return;
   __syncthreads();
-  ballot_permute_small(s_idx, T * top_k, n_exp, cnt, off, perm, pos_of_pair, s_cc);
+  ballot_permute_small(s_idx, T * top_k, n_exp, cnt, off, perm, pos_of_pair, s_ballot, s_cc);
   TRACE_MARK(3, 5);
+}
+
+// Workgroups that share the router's K range: as for the projections, with 8 waves per workgroup.
+static int router_slices(bool bf16, int K, int T) {
+  if (T > 2 * TILE) return 1;
+  const int ksteps = K / (bf16 ? 16 : 8);
+  const int burst = 8 * (T <= TILE ? 8 : 4);
+  return ksteps % burst == 0 ? ksteps / burst : 1;
 }
 
 template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a, hipStream_t st) {
   const E* W = (const E*)a.w;
-  const int slices = gemm_slices(bf16, a.H, a.T);
+  const int slices = router_slices(bf16, a.H, a.T);
   if (a.T <= 32) {
-    router_kernel<E, 1, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(
+    router_kernel<E, 1, 8><<<dim3(slices, 1), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else if (a.T <= 64) {
-    router_kernel<E, 2, 4><<<dim3(slices, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
+    router_kernel<E, 2, 8><<<dim3(slices, 1), 8 * WAVE, ksplit_lds<2, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else {
     const int groups = (a.T + 2 * TILE - 1) / (2 * TILE);
-    router_kernel<E, 2, 4><<<dim3(1, groups), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(
+    router_kernel<E, 2, 8><<<dim3(1, groups), 8 * WAVE, ksplit_lds<2, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
     launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, st);
@@ -884,8 +981,8 @@ void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
 bool configure_kernels() {
   bool ok = configure_ksplit<bf16_t, QkvEpi<bf16_t>>() && configure_ksplit<float, QkvEpi<float>>() &&
             configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>();
-  ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)router_kernel<float, 1, 4>) &&
-       opt_in_lds((const void*)router_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)router_kernel<float, 2, 4>);
+  ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
+       opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
   ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&
        opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>) &&
        opt_in_lds((const void*)lm_head_kernel<bf16_t, 4, 2>) && opt_in_lds((const void*)lm_head_kernel<float, 4, 2>);
