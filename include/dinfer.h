@@ -85,7 +85,7 @@ typedef struct dinfer_ctx dinfer_ctx;
 size_t dinfer_weights_bytes(const dinfer_config* cfg);
 size_t dinfer_kv_bytes(const dinfer_config* cfg, int32_t n_pages);
 /* max_seqs <= 64 sequences per call, max_tokens = most tokens one forward processes over all sequences
- * (the block for a step, the prompt for a prefill). */
+ * (the block for a step, the prompt for a prefill); max_tokens * top_k may not exceed 65535 routed pairs. */
 size_t dinfer_workspace_bytes(const dinfer_config* cfg, int32_t max_seqs, int32_t max_tokens);
 
 /* Validates the configuration, records the buffers, builds the rotary table in the workspace (enqueued on

@@ -248,7 +248,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
       launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a,
                    at<float>(c->weights, lw.attn_gain), xn, st);
     else
-      launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair), topk_w - (size_t)T * f.top_k, f.top_k,
+      launch_combine(bf, x, at<float>(ws, w.o), topk_w - (size_t)T * f.top_k, f.top_k,
                      f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, st);
     QkvArgs qa{c->weights + lw.wqkv, xn, rinv_a, ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table,
                pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H, tk_part, tickets};
@@ -291,7 +291,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     }
   }
   // the last layer's expert outputs are folded into the residual here; rinv_a then belongs to the final norm
-  launch_combine(bf, x, at<float>(ws, w.o), at<int32_t>(ws, w.pos_of_pair),
+  launch_combine(bf, x, at<float>(ws, w.o),
                  at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a,
                  at<float>(c->weights, c->wm.final_gain), ws + w.xn, st);
   (void)with_head;
@@ -339,6 +339,7 @@ size_t dinfer_kv_bytes(const dinfer_config* cfg, int32_t n_pages) {
 
 size_t dinfer_workspace_bytes(const dinfer_config* cfg, int32_t max_seqs, int32_t max_tokens) {
   if (check_config(cfg) != DINFER_OK || max_seqs < 1 || max_seqs > MAX_SEQS || max_tokens < 1) return 0;
+  if ((int64_t)max_tokens * cfg->top_k > permute_max_pairs()) return 0;
   return map_workspace(*cfg, max_seqs, max_tokens).total;
 }
 
@@ -355,6 +356,8 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   if (n_pages < 1) return fail(DINFER_EINVAL, "n_pages < 1");
   if (max_seqs < 1 || max_seqs > MAX_SEQS) return fail(DINFER_EINVAL, "max_seqs outside [1, %d]", MAX_SEQS);
   if (max_tokens < 1) return fail(DINFER_EINVAL, "max_tokens < 1");
+  if ((int64_t)max_tokens * cfg->top_k > permute_max_pairs())
+    return fail(DINFER_EUNSUPPORTED, "max_tokens * top_k exceeds %d routed pairs per forward", permute_max_pairs());
   dinfer_ctx* c = new (std::nothrow) dinfer_ctx();
   if (!c) return fail(DINFER_EINVAL, "out of host memory");
   c->cfg = *cfg;
@@ -388,7 +391,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     delete c;
     return fail(DINFER_EHIP, "hipHostMalloc failed");
   }
-  if (!configure_kernels() || !configure_attention()) {
+  if (!configure_kernels() || !configure_attention() || !configure_permute()) {
     (void)hipHostFree(c->h_mask_pinned);
     delete c;
     return fail(DINFER_EHIP, "the runtime refused the kernels' LDS sizes");

@@ -669,7 +669,7 @@ void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
 // finishes a share of the accumulator registers.  Experts without rows sit at the end of the grid and exit.
 //   GEMM 1: task = 32 gate features + the same 32 up features; input = normalised-input planes of the token rows,
 //           scaled by the row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
-//   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[sorted row][H]
+//   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[token*top_k + slot][H]
 // ------------------------------------------------------------------------------------------------
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
@@ -748,7 +748,8 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
 template <typename E, int TT, int EKS>
 __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                                    float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                                   const int32_t* __restrict__ off, int n_pairs, int H,
+                                                                   const int32_t* __restrict__ off,
+                                                                   const int32_t* __restrict__ perm, int n_pairs, int H,
                                                                    int I) {
   extern __shared__ float red[];   // [EKS][2*TT*16][64]
   constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
@@ -763,10 +764,11 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
   const int n_tasks = H / (2 * TILE);
   const int base = off[e];
   PlaneLoader<E, TT> ld;
-  int row[TT];
+  int row[TT], pair[TT];   // pair = token * top_k + slot: the output row (token order, no indirection for the reader)
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     row[t] = row0 + t * TILE + (lane & 31);
+    pair[t] = perm[base + min(row[t], n_rows - 1)];
     ld.set(t, Y, n_pairs, base + min(row[t], n_rows - 1), half);
   }
   f32x16 acc0[TT], acc1[TT];
@@ -799,7 +801,7 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
       }
     }
     if (row[t] < n_rows) {
-      float* orow = O + (int64_t)(base + row[t]) * H + (2 * task) * TILE;
+      float* orow = O + (int64_t)pair[t] * H + (2 * task) * TILE;
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         orow[acc_row(v0 + i, half)] = a0[i];
@@ -817,7 +819,7 @@ template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, 
 template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
   constexpr int EKS = ExpertSplit<TT>::EKS;
   expert_gemm2_kernel<E, TT, EKS><<<dim3(a.H / (2 * TILE), a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.T * a.top_k, a.H, a.I);
+      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.T * a.top_k, a.H, a.I);
 }
 template <typename E, int TT> static bool configure_experts() {
   constexpr int EKS = ExpertSplit<TT>::EKS;

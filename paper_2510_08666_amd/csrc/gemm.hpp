@@ -127,56 +127,4 @@ template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {
 // holes in the dispatch order.
 constexpr int ACTIVE_LIST = MAX_EXPERTS + 1;
 
-// Stable counting sort of n_pairs (token, slot) pairs by expert with wavefront ballots, by one workgroup: for
-// expert e the pairs are scanned 64 at a time; the ballot of "routed to e" gives the count (popcount) and,
-// through the bits below a lane, the stable rank of that lane's pair.  expert_of_pair may live in LDS or
-// global memory; s_cnt / s_off: LDS scratch of MAX_EXPERTS (+1) ints.  Every thread of the block must call.
-__device__ inline void ballot_permute(const int32_t* expert_of_pair, int n_pairs, int n_exp, int32_t* __restrict__ cnt,
-                                      int32_t* __restrict__ off, int32_t* __restrict__ perm,
-                                      int32_t* __restrict__ pos_of_pair, int32_t* s_cnt, int32_t* s_off) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
-  for (int e = wave; e < n_exp; e += n_waves) {
-    int c = 0;
-    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
-      const int p = p0 + lane;
-      c += __popcll(__ballot(p < n_pairs && expert_of_pair[p] == e));
-    }
-    if (lane == 0) s_cnt[e] = c;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < n_exp; ++e) {
-      s_off[e] = run;
-      run += s_cnt[e];
-    }
-    s_off[n_exp] = run;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < n_exp; e += blockDim.x) cnt[e] = s_cnt[e];
-  for (int e = threadIdx.x; e <= n_exp; e += blockDim.x) off[e] = s_off[e];
-  if (threadIdx.x == 0) {   // dense list of the experts that received rows (see ACTIVE_LIST)
-    int32_t* act = off + ACTIVE_LIST;
-    int n = 0;
-    for (int e = 0; e < n_exp; ++e)
-      if (s_cnt[e] > 0) act[n++] = e;
-    act[MAX_EXPERTS] = n;
-  }
-  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  for (int e = wave; e < n_exp; e += n_waves) {
-    int run = s_off[e];
-    for (int p0 = 0; p0 < n_pairs; p0 += WAVE) {
-      const int p = p0 + lane;
-      const bool mine = p < n_pairs && expert_of_pair[p] == e;
-      const uint64_t b = __ballot(mine);
-      if (mine) {
-        const int r = run + __popcll(b & below);
-        perm[r] = p;
-        pos_of_pair[p] = r;
-      }
-      run += __popcll(b);
-    }
-  }
-}
-
 }  // namespace dinfer

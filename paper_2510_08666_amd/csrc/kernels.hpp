@@ -32,8 +32,8 @@ void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_se
 // x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
                   float* rinv, const float* gain, void* xn, hipStream_t st);
-// x[t] += sum_j topk_w[t][j] * O[pos_of_pair[t*k+j]];  rinv[t] and xn[t] as above, of the updated row
-void launch_combine(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k,
+// x[t] += sum_j topk_w[t][j] * O[t*k+j];  rinv[t] and xn[t] as above, of the updated row
+void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
                     float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st);
 
 // Cross-workgroup split-K scratch shared by the projections and the router (see gemm.hip): `part` holds the
@@ -113,6 +113,8 @@ struct RouterArgs {
 void launch_router(bool bf16, const RouterArgs& a, hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st);
+int permute_max_pairs();      // most (token, slot) pairs one forward may route
+bool configure_permute();
 
 struct ExpertArgs {
   const void* w_gate_up;    // packed [E][I/32 tasks]
@@ -120,7 +122,7 @@ struct ExpertArgs {
   const void* xn;           // [T][H] normalised-input planes (FFN gain)
   const float* rinv;        // [T]
   void* y;                  // [T*k][I] k-major
-  float* o;                 // [T*k][H]
+  float* o;                 // [T*k][H], row = token*top_k + slot
   const int32_t* cnt;
   const int32_t* off;
   const int32_t* perm;

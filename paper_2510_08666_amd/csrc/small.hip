@@ -97,12 +97,11 @@ void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, 
     embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn, T);
 }
 
-// x[t] += sum_j w[t][j] * O[pos_of_pair[t*k+j]]  (j ascending: a fixed summation order);  rinv[t] and the
-// normalised-input planes of the new row.
+// x[t] += sum_j w[t][j] * O[t*k+j]  (j ascending: a fixed summation order);  rinv[t] and the normalised-input
+// planes of the new row.
 // Thread i owns columns 4*i + 1024*c .. +3 (hidden is a multiple of 64, so chunks are whole or absent).
 template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict__ x, const float* __restrict__ O,
-                                                               const int32_t* __restrict__ pos_of_pair,
                                                                const float* __restrict__ topk_w, int top_k, float eps,
                                                                int H, float* __restrict__ rinv,
                                                                const float* __restrict__ gain, E* __restrict__ xn,
@@ -110,13 +109,10 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
   __shared__ float sh[4];
   constexpr int CH = NORM_MAX_PER_THREAD / 4;
   const int t = blockIdx.x;
-  int64_t orow[MAX_TOPK];
   float w[MAX_TOPK];
 #pragma unroll
-  for (int j = 0; j < MAX_TOPK; ++j) {
-    orow[j] = j < top_k ? (int64_t)pos_of_pair[t * top_k + j] * H : 0;
-    w[j] = j < top_k ? topk_w[t * top_k + j] : 0.f;
-  }
+  for (int j = 0; j < MAX_TOPK; ++j) w[j] = j < top_k ? topk_w[t * top_k + j] : 0.f;
+  const float* orow = O + (int64_t)t * top_k * H;
   float ss = 0.f;
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
@@ -126,7 +122,7 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
 #pragma unroll
       for (int j = 0; j < MAX_TOPK; ++j)
         if (j < top_k) {
-          const f32x4 o = *reinterpret_cast<const f32x4*>(O + orow[j] + col);
+          const f32x4 o = *reinterpret_cast<const f32x4*>(orow + (int64_t)j * H + col);
 #pragma unroll
           for (int i = 0; i < 4; ++i) acc[i] += w[j] * o[i];
         }
@@ -146,25 +142,94 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
   ss = block_sum_256(ss, sh);
   if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
-void launch_combine(bool bf16, float* x, const float* O, const int32_t* pos_of_pair, const float* topk_w, int top_k,
+void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
                     float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st) {
   if (bf16)
-    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (bf16_t*)xn, T);
+    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, eps, H, rinv, gain, (bf16_t*)xn, T);
   else
-    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, pos_of_pair, topk_w, top_k, eps, H, rinv, gain, (float*)xn, T);
+    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, eps, H, rinv, gain, (float*)xn, T);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
-// Stand-alone form (many tokens); small forwards run the same routine inside the router kernel.
+// Stand-alone form (many tokens); small forwards run the same idea inside the router kernel.  Stable counting
+// sort of the (token, slot) pairs by expert, one workgroup.  A wave takes 64 consecutive pairs (a chunk) at a time
+// and forms the chunk's ballots "which lanes go to expert e" for all experts at once by OR-ing lane bits into its
+// own 64 LDS words; the population of ballot e is the chunk's count for e, the bits below a lane in its expert's
+// ballot the pair's rank inside the chunk.  pre[chunk][e] then becomes the number of pairs of e in earlier chunks
+// (a 16-bit count: at most 65535 pairs), and position = off[e] + pre[chunk][e] + rank.
+__device__ inline uint64_t chunk_ballots(unsigned long long* mine, int lane, int e) {
+  mine[lane] = 0ull;
+  __builtin_amdgcn_wave_barrier();     // LDS operations of one wave complete in order
+  if (e >= 0) atomicOr(&mine[e], 1ull << lane);
+  __builtin_amdgcn_wave_barrier();
+  return mine[lane];                   // ballot of expert `lane`
+}
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ expert_of_pair, int n_pairs,
                                                         int n_exp, int32_t* __restrict__ cnt, int32_t* __restrict__ off,
                                                         int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair) {
-  __shared__ int32_t s_cnt[MAX_EXPERTS], s_off[MAX_EXPERTS + 1];
-  ballot_permute(expert_of_pair, n_pairs, n_exp, cnt, off, perm, pos_of_pair, s_cnt, s_off);
+  extern __shared__ uint16_t s_pre[];                       // [n_chunks][MAX_EXPERTS]
+  __shared__ unsigned long long s_ballot[16 * MAX_EXPERTS];
+  __shared__ int32_t s_off[MAX_EXPERTS + 1];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  unsigned long long* mine = s_ballot + wave * MAX_EXPERTS;
+  for (int c = wave; c < n_chunks; c += n_waves) {
+    const int p = c * WAVE + lane;
+    const int e = p < n_pairs ? expert_of_pair[p] : -1;
+    s_pre[c * MAX_EXPERTS + lane] = (uint16_t)__popcll(chunk_ballots(mine, lane, e));
+    __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int run = 0;                                            // lane = expert: exclusive scan over the chunks
+    for (int c = 0; c < n_chunks; ++c) {
+      const int n = s_pre[c * MAX_EXPERTS + lane];
+      s_pre[c * MAX_EXPERTS + lane] = (uint16_t)run;
+      run += n;
+    }
+    const int tot = lane < n_exp ? run : 0;
+    int incl = tot;                                         // inclusive scan over the lanes (experts)
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += up;
+    }
+    s_off[lane] = incl - tot;
+    if (lane < n_exp) {
+      cnt[lane] = tot;
+      off[lane] = incl - tot;
+      if (lane == n_exp - 1) off[n_exp] = incl;
+    }
+    const uint64_t has_rows = __ballot(tot > 0);            // dense list of the experts that received rows
+    if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
+    if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+  }
+  __syncthreads();
+  for (int c = wave; c < n_chunks; c += n_waves) {
+    const int p = c * WAVE + lane;
+    const int e = p < n_pairs ? expert_of_pair[p] : -1;
+    chunk_ballots(mine, lane, e);
+    __builtin_amdgcn_wave_barrier();
+    if (e >= 0) {
+      const int r = s_off[e] + s_pre[c * MAX_EXPERTS + e] + __popcll(mine[e] & below);
+      perm[r] = p;
+      pos_of_pair[p] = r;
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
 }
+bool configure_permute() {
+  return hipFuncSetAttribute((const void*)permute_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) ==
+         hipSuccess;
+}
+constexpr int PERMUTE_MAX_PAIRS = 65535;
+int permute_max_pairs() { return PERMUTE_MAX_PAIRS; }
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
                     int32_t* pos_of_pair, hipStream_t st) {
-  permute_kernel<<<1, 1024, 0, st>>>(topk_idx, n_pairs, E, cnt, off, perm, pos_of_pair);
+  const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
+  permute_kernel<<<1, 1024, (size_t)n_chunks * MAX_EXPERTS * sizeof(uint16_t), st>>>(topk_idx, n_pairs, E, cnt, off, perm,
+                                                                                     pos_of_pair);
 }
 
 // ---------------------------------------------------------------- LM-head partial merge
