@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("DINFER_LIB_OUT") or os.path.join(HERE, "libdinfer.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "small.hip", "pack.hip"]
+SOURCES = ["api.hip", "gemm.hip", "wide.hip", "attention.hip", "small.hip", "pack.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

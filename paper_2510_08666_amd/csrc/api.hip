@@ -391,7 +391,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     delete c;
     return fail(DINFER_EHIP, "hipHostMalloc failed");
   }
-  if (!configure_kernels() || !configure_attention() || !configure_permute()) {
+  if (!configure_kernels() || !configure_attention() || !configure_permute() || !configure_wide()) {
     (void)hipHostFree(c->h_mask_pinned);
     delete c;
     return fail(DINFER_EHIP, "the runtime refused the kernels' LDS sizes");

@@ -104,6 +104,11 @@ __device__ inline int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half 
 template <typename E> __device__ inline typename ET<E>::vec load16(const E* p) {
   return *reinterpret_cast<const typename ET<E>::vec*>(p);
 }
+// Weights are read once per forward: a streaming (non-temporal) load keeps them from evicting the activations
+// that the same kernel re-reads from the L2 many times.
+template <typename E> __device__ inline typename ET<E>::vec load16_stream(const E* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const typename ET<E>::vec*>(p));
+}
 
 __device__ inline float wave_sum(float v) {
 #pragma unroll

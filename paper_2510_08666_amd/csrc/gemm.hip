@@ -826,19 +826,24 @@ template <typename E, int TT> static bool configure_experts() {
   return opt_in_lds((const void*)expert_gemm1_kernel<E, TT, EKS>) && opt_in_lds((const void*)expert_gemm2_kernel<E, TT, EKS>);
 }
 
-// An expert can receive at most T rows (a token selects an expert at most once): T fixes the row tiling.
-#define DINFER_EXPERT_DISPATCH(FN)                                                              \
-  if (a.T <= 32) {                                                                              \
-    if (bf16) FN<bf16_t, 1>(a, 1, st); else FN<float, 1>(a, 1, st);                             \
-  } else if (a.T <= 64) {                                                                       \
-    if (bf16) FN<bf16_t, 2>(a, 1, st); else FN<float, 2>(a, 1, st);                             \
-  } else {                                                                                      \
-    const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);                                       \
-    if (bf16) FN<bf16_t, 4>(a, groups, st); else FN<float, 4>(a, groups, st);                   \
+// An expert can receive at most T rows (a token selects an expert at most once): T fixes the row tiling.  Past
+// 64 tokens the many-token forms take over.
+void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) {
+  if (a.T > 2 * TILE) return launch_expert_gate_up_wide(bf16, a, st);
+  if (a.T <= TILE) {
+    if (bf16) launch_gate_up_t<bf16_t, 1>(a, 1, st); else launch_gate_up_t<float, 1>(a, 1, st);
+  } else {
+    if (bf16) launch_gate_up_t<bf16_t, 2>(a, 1, st); else launch_gate_up_t<float, 2>(a, 1, st);
   }
-
-void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER_EXPERT_DISPATCH(launch_gate_up_t) }
-void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { DINFER_EXPERT_DISPATCH(launch_down_t) }
+}
+void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) {
+  if (a.T > 2 * TILE) return launch_expert_down_wide(bf16, a, st);
+  if (a.T <= TILE) {
+    if (bf16) launch_down_t<bf16_t, 1>(a, 1, st); else launch_down_t<float, 1>(a, 1, st);
+  } else {
+    if (bf16) launch_down_t<bf16_t, 2>(a, 1, st); else launch_down_t<float, 2>(a, 1, st);
+  }
+}
 
 // ------------------------------------------------------------------------------------------------
 // LM head fused with the confidence reduction.  Workgroups of EKS waves walk the tasks (64 vocabulary ids each):
@@ -957,25 +962,22 @@ static int lm_head_wgs(int V) {
   return n_tasks < 768 ? n_tasks : 768;
 }
 // Partials per token row: upper bound (workspace sizing) and what a launch for T tokens writes.
-int lm_head_waves(int V) { return lm_head_wgs(V) * 4; }
-int lm_head_parts(int V, int T) { return lm_head_wgs(V) * (T <= 64 ? 4 : 2); }
+int lm_head_waves(int V) { return lm_head_wgs(V) * 4 > lm_head_wide_parts(V) ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
+int lm_head_parts(int V, int T) { return T <= 2 * TILE ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
 
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = lm_head_wgs(a.V);
   if (a.T <= 32) {
     lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
-  } else if (a.T <= 64) {
+  } else {
     lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
                                                                               a.scale, a.part, a.logits_out);
-  } else {
-    const int groups = (a.T + 4 * TILE - 1) / (4 * TILE);
-    lm_head_kernel<E, 4, 2><<<dim3(wgs, groups), 2 * WAVE, expert_lds<4, 2>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H,
-                                                                                   a.V, a.scale, a.part, a.logits_out);
   }
 }
 
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
+  if (a.T > 2 * TILE) return launch_lm_head_wide(bf16, a, st);
   if (bf16) launch_lm_t<bf16_t>(a, st);
   else launch_lm_t<float>(a, st);
 }
@@ -986,10 +988,9 @@ bool configure_kernels() {
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
   ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&
-       opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>) &&
-       opt_in_lds((const void*)lm_head_kernel<bf16_t, 4, 2>) && opt_in_lds((const void*)lm_head_kernel<float, 4, 2>);
-  ok = ok && configure_experts<bf16_t, 1>() && configure_experts<bf16_t, 2>() && configure_experts<bf16_t, 4>() &&
-       configure_experts<float, 1>() && configure_experts<float, 2>() && configure_experts<float, 4>();
+       opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>);
+  ok = ok && configure_experts<bf16_t, 1>() && configure_experts<bf16_t, 2>() && configure_experts<float, 1>() &&
+       configure_experts<float, 2>();
   (void)hipGetLastError();
   return ok;
 }

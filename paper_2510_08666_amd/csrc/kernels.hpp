@@ -128,8 +128,10 @@ struct ExpertArgs {
   const int32_t* perm;
   int T, H, I, E, top_k;
 };
-void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st);
+void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st);   // picks the form by a.T
 void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
+void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st);   // many-token forms (wide.hip)
+void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st);
 
 struct LmArgs {
   const void* w;            // packed LM head
@@ -142,7 +144,9 @@ struct LmArgs {
 };
 int lm_head_waves(int V);          // upper bound of partials per token row (workspace sizing)
 int lm_head_parts(int V, int T);   // partials per token row launch_lm_head writes for T tokens
-void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);
+void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);        // picks the form by a.T
+void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st);
+int lm_head_wide_parts(int V);
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st);
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
                    uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, hipStream_t st);
@@ -155,6 +159,7 @@ void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t 
 
 bool configure_kernels();     // one-time function attributes (dynamic LDS limits); false if the runtime refuses
 bool configure_attention();
+bool configure_wide();
 
 // In-kernel phase timestamps of builds with -DDINFER_TRACE (see common.hpp); return -1 in ordinary builds.
 int trace_read_gemm(void* h_out, size_t bytes);

@@ -1,0 +1,345 @@
+// Many-token forms (more than 64 tokens in a forward) of the weight-streaming contractions: routed-expert
+// grouped GEMMs and the LM head.  With hundreds of token rows a wave that fetched its own activation operands
+// would pull several times more bytes through the L2 than it streams weights from HBM, so here a workgroup of
+// four waves shares them: the workgroup covers 128 token rows (four 32-row tiles) and four tasks (256 output
+// features), each wave streams the weights of one task for the whole K range, and the activation fragments of the
+// four token tiles go through LDS, staged chunk by chunk (wave w stages tile w) and double buffered, so that
+// every fragment is fetched once per workgroup.  The accumulators of a wave (64 features x 128 rows) stay in
+// registers for the whole K range: there is no split of K and no fold.
+#include "gemm.hpp"
+#include "kernels.hpp"
+
+namespace dinfer {
+
+constexpr int WT = 4;      // token tiles per workgroup
+constexpr int WW = 4;      // waves = tasks per workgroup
+constexpr int WKC = 4;     // k-steps per staged chunk
+constexpr int WPRE = 2;    // weight chunks in flight per wave
+
+template <typename E> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * Planes<E>::N * WAVE * 16; }
+
+// Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow: the k-major
+// activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
+// sb: LDS [2][WKC][WT][planes][64] operand vectors.  NT: token tiles that hold rows.
+// Pipeline per chunk c: barrier; the fragments of chunk c+1 go from registers to LDS buffer (c+1)&1 and the
+// loads of chunk c+2 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
+// requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
+// around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
+// computes while the other waits at its barrier.
+template <typename E, int NT>
+__device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
+                                      int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
+                                      f32x16 (&acc1)[WT]) {
+  typedef typename ET<E>::vec vec;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  constexpr int64_t STEP = 2 * WAVE * G;
+  static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int last = n_chunks - 1;
+  vec wa0[WPRE][WKC], wa1[WPRE][WKC];
+  vec bnext[WKC][NP];
+  auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
+  // Prologue, in the order the loop keeps: weights of chunk 0, fragments of chunk 0 (to LDS) and chunk 1 (to
+  // registers), then the weights of the following chunks -- so that waiting for the fragments at the top of an
+  // iteration never includes waiting for weights requested after them.
+#pragma unroll
+  for (int ks = 0; ks < WKC; ++ks) {
+    wa0[0][ks] = load16_stream<E>(wp + (int64_t)ks * STEP);
+    wa1[0][ks] = load16_stream<E>(wp + (int64_t)ks * STEP + WAVE * G);
+  }
+  {
+    vec b0[WKC][NP];
+    const int c1 = min(1, last);
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) b0[ks][q] = load16<E>(brow + (int64_t)ks * bkstride + q * KS);
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) bnext[ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + ks) * bkstride + q * KS);
+#pragma unroll
+    for (int i = 1; i < WPRE; ++i) {
+      const int c = min(i, last);
+#pragma unroll
+      for (int ks = 0; ks < WKC; ++ks) {
+        wa0[i][ks] = load16_stream<E>(wp + (int64_t)(c * WKC + ks) * STEP);
+        wa1[i][ks] = load16_stream<E>(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) sb_at(0, ks, wave, q) = b0[ks][q];
+  }
+  for (int c0 = 0; c0 < n_chunks; c0 += WPRE) {
+#pragma unroll
+    for (int i = 0; i < WPRE; ++i) {
+      const int c = c0 + i;
+      if (c < n_chunks) {   // uniform over the workgroup
+        __syncthreads();
+        const int nb = (i + 1) & 1, cb = i & 1;   // c0 is even: parities of c+1 and c
+#pragma unroll
+        for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+          for (int q = 0; q < NP; ++q) sb_at(nb, ks, wave, q) = bnext[ks][q];
+        const int cn = min(c + 2, last);
+#pragma unroll
+        for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+          for (int q = 0; q < NP; ++q) bnext[ks][q] = load16<E>(brow + (int64_t)(cn * WKC + ks) * bkstride + q * KS);
+#pragma unroll
+        for (int ks = 0; ks < WKC; ++ks)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+              const vec b = sb_at(cb, ks, t, q);
+              mfma32(acc0[t], wa0[i][ks], b);
+              mfma32(acc1[t], wa1[i][ks], b);
+            }
+        const int cw = min(c + WPRE, last);
+#pragma unroll
+        for (int ks = 0; ks < WKC; ++ks) {
+          wa0[i][ks] = load16_stream<E>(wp + (int64_t)(cw * WKC + ks) * STEP);
+          wa1[i][ks] = load16_stream<E>(wp + (int64_t)(cw * WKC + ks) * STEP + WAVE * G);
+        }
+      }
+    }
+  }
+}
+
+// nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
+template <typename E>
+__device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
+                                   int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
+                                   f32x16 (&acc1)[WT]) {
+  if (nt >= 4) wide_stream_nt<E, 4>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 3) wide_stream_nt<E, 3>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 2) wide_stream_nt<E, 2>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else wide_stream_nt<E, 1>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+}
+
+__device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
+
+// ------------------------------------------------------------------------------------------------
+// Routed experts, rows of expert e = pairs perm[off[e] .. off[e]+cnt[e]).  Grid (tasks / 4, experts through the
+// active list, groups of 128 rows).
+//   GEMM 1: task = 32 gate features + the same 32 up features;  y = silu(gate) * up  -> Y[sorted row][I]
+//   GEMM 2: task = 64 adjacent output features of the down projection                -> O[token*top_k + slot][H]
+// ------------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                                       const float* __restrict__ rinv,
+                                                                       E* __restrict__ Y, const int32_t* __restrict__ cnt,
+                                                                       const int32_t* __restrict__ off,
+                                                                       const int32_t* __restrict__ perm, int T, int H,
+                                                                       int I, int top_k) {
+  typedef typename ET<E>::vec vec;
+  extern __shared__ char lds_raw[];
+  vec* sb = reinterpret_cast<vec*>(lds_raw);
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
+  const int e = off[ACTIVE_LIST + blockIdx.y];
+  const int n_rows = cnt[e], row0 = blockIdx.z * WT * TILE;
+  if (row0 >= n_rows) return;
+  const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int n_tasks = I / TILE, task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
+  const int base = off[e];
+  const int ksteps = H / KS;
+  int tok[WT];
+  float r[WT];
+#pragma unroll
+  for (int t = 0; t < WT; ++t) {
+    tok[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)] / top_k;
+    r[t] = rinv[tok[t]];
+  }
+  int stage_tok = tok[0];
+#pragma unroll
+  for (int t = 1; t < WT; ++t)
+    if (wave == t) stage_tok = tok[t];
+  const E* brow = xn + (int64_t)stage_tok * (NP * KS) + half * G;
+  f32x16 acc0[WT], acc1[WT];
+  zero_acc<WT>(acc0);
+  zero_acc<WT>(acc1);
+  wide_stream<E>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+                 (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
+  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
+#pragma unroll
+  for (int t = 0; t < WT; ++t) {
+    const int row = row0 + t * TILE + col;
+    if (t < nt && row < n_rows) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        store_actk<E>(Y, (int64_t)T * top_k, base + row, task * TILE + acc_row(v, half),
+                      silu_w(acc0[t][v] * r[t]) * (acc1[t][v] * r[t]));
+    }
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+                                                                       float* __restrict__ O, const int32_t* __restrict__ cnt,
+                                                                       const int32_t* __restrict__ off,
+                                                                       const int32_t* __restrict__ perm, int n_pairs, int H,
+                                                                       int I) {
+  typedef typename ET<E>::vec vec;
+  extern __shared__ char lds_raw[];
+  vec* sb = reinterpret_cast<vec*>(lds_raw);
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
+  const int e = off[ACTIVE_LIST + blockIdx.y];
+  const int n_rows = cnt[e], row0 = blockIdx.z * WT * TILE;
+  if (row0 >= n_rows) return;
+  const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
+  const int base = off[e];
+  const int ksteps = I / KS;
+  int pair[WT];
+#pragma unroll
+  for (int t = 0; t < WT; ++t) pair[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)];
+  const E* brow = Y + (int64_t)(base + min(row0 + wave * TILE + col, n_rows - 1)) * (NP * KS) + half * G;
+  f32x16 acc0[WT], acc1[WT];
+  zero_acc<WT>(acc0);
+  zero_acc<WT>(acc1);
+  wide_stream<E>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+                 (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
+  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
+#pragma unroll
+  for (int t = 0; t < WT; ++t) {
+    if (t < nt && row0 + t * TILE + col < n_rows) {
+      float* orow = O + (int64_t)pair[t] * H + (2 * task) * TILE;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 a, b;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[i] = acc0[t][4 * g + i];
+          b[i] = acc1[t][4 * g + i];
+        }
+        *reinterpret_cast<f32x4*>(orow + acc_row(4 * g, half)) = a;
+        *reinterpret_cast<f32x4*>(orow + TILE + acc_row(4 * g, half)) = b;
+      }
+    }
+  }
+}
+
+template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
+  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
+  const int n_tasks = a.I / TILE;
+  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + WW - 1) / WW, a.E, groups), WW * WAVE, wide_lds<E>(), st>>>(
+      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.T, a.H, a.I, a.top_k);
+}
+template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
+  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
+  const int n_tasks = a.H / (2 * TILE);
+  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + WW - 1) / WW, a.E, groups), WW * WAVE, wide_lds<E>(), st>>>(
+      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.T * a.top_k, a.H, a.I);
+}
+void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
+  if (bf16) launch_gate_up_wide_t<bf16_t>(a, st);
+  else launch_gate_up_wide_t<float>(a, st);
+}
+void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
+  if (bf16) launch_down_wide_t<bf16_t>(a, st);
+  else launch_down_wide_t<float>(a, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// LM head fused with the confidence reduction, many-token form.  Grid (task quads, groups of 128 tokens); a
+// wave turns its accumulators (64 vocabulary ids x 128 tokens) into one (max, sum-exp, lowest arg max) partial
+// per token: part[(quad * 4 + wave)][token].  Logits are never stored (unless the debug pointer is set).
+// ------------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(WW * WAVE, 2) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                                  const float* __restrict__ rinv, int T, int H, int V,
+                                                                  float scale, float* __restrict__ part,
+                                                                  float* __restrict__ logits_out) {
+  typedef typename ET<E>::vec vec;
+  extern __shared__ char lds_raw[];
+  vec* sb = reinterpret_cast<vec*>(lds_raw);
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int tok0 = blockIdx.y * WT * TILE;
+  const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
+  const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
+  const int slot = blockIdx.x * WW + wave, task = min(slot, n_tasks - 1);
+  const int ksteps = H / KS;
+  float zs[WT];
+#pragma unroll
+  for (int t = 0; t < WT; ++t) zs[t] = rinv[min(tok0 + t * TILE + col, T - 1)] * scale;
+  const E* brow = xn + (int64_t)min(tok0 + wave * TILE + col, T - 1) * (NP * KS) + half * G;
+  f32x16 acc0[WT], acc1[WT];
+  zero_acc<WT>(acc0);
+  zero_acc<WT>(acc1);
+  wide_stream<E>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+                 sb, nt, acc0, acc1);
+#pragma unroll
+  for (int t = 0; t < WT; ++t) {
+    const int tok = tok0 + t * TILE + col;
+    float m = -INFINITY, sum = 0.f;
+    int best = 0x7fffffff;
+    if (t < nt && slot < n_tasks) {
+      float z[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {   // ids ascend with i inside each tile; tile 1 follows tile 0
+        const int id = (2 * task + (i >> 4)) * TILE + acc_row(i & 15, half);
+        const float a = i < 16 ? acc0[t][i & 15] : acc1[t][i & 15];
+        z[i] = id < V ? a * zs[t] : -INFINITY;
+        if (z[i] > m) {                // strict '>' keeps the lowest id
+          m = z[i];
+          best = id;
+        }
+        if (logits_out && tok < T && id < V) logits_out[(int64_t)tok * V + id] = z[i];
+      }
+      if (m > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) sum += __expf(z[i] - m);
+      }
+    }
+    // fold the two half-waves (same token, other rows)
+    const float om = __shfl_xor(m, 32, WAVE), os = __shfl_xor(sum, 32, WAVE);
+    const int ob = __shfl_xor(best, 32, WAVE);
+    float M = m, S = sum;
+    int B = best;
+    if (om > M || (om == M && ob < B)) {
+      S = (M > -INFINITY ? S * __expf(M - om) : 0.f) + os;
+      M = om;
+      B = ob;
+    } else if (om > -INFINITY) {
+      S += os * __expf(om - M);
+    }
+    if (half == 0 && tok < T && t < nt) {
+      float* p = part + ((int64_t)slot * T + tok) * 4;
+      p[0] = M;
+      p[1] = S;
+      p[2] = __int_as_float(B);
+      p[3] = 0.f;
+    }
+  }
+}
+
+int lm_head_wide_parts(int V) { return ((V + 63) / 64 + WW - 1) / WW * WW; }
+
+template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
+  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
+  lm_head_wide_kernel<E><<<dim3(lm_head_wide_parts(a.V) / WW, groups), WW * WAVE, wide_lds<E>(), st>>>(
+      (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+}
+void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
+  if (bf16) launch_lm_wide_t<bf16_t>(a, st);
+  else launch_lm_wide_t<float>(a, st);
+}
+
+bool configure_wide() {
+  const void* fns[6] = {(const void*)expert_gemm1_wide_kernel<bf16_t>, (const void*)expert_gemm1_wide_kernel<float>,
+                        (const void*)expert_gemm2_wide_kernel<bf16_t>, (const void*)expert_gemm2_wide_kernel<float>,
+                        (const void*)lm_head_wide_kernel<bf16_t>,      (const void*)lm_head_wide_kernel<float>};
+  for (const void* f : fns)
+    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) return false;
+  return true;
+}
+
+}  // namespace dinfer
