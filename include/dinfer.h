@@ -182,7 +182,7 @@ int dinfer_stream_read(const void* d_buf, size_t bytes, float* d_sink, void* str
 
 /* Profiling aid of libraries built with -DDINFER_TRACE=<kernel id>: copies the phase timestamps (100 MHz wall
  * clock, [workgroup][8 slots] of uint64) that the chosen kernel's last launch left, to the HOST buffer h_out
- * (synchronous).  unit: 0 = GEMM kernels, 1 = attention.  Ordinary builds return DINFER_EINVAL. */
+ * (synchronous).  unit: 0 = GEMM kernels, 1 = attention, 2 = many-token GEMM forms.  Ordinary builds return DINFER_EINVAL. */
 int dinfer_debug_trace(int32_t unit, void* h_out, size_t bytes);
 
 #ifdef __cplusplus

@@ -648,7 +648,10 @@ int dinfer_debug_get(dinfer_ctx* c, int32_t what, void* d_out, size_t bytes, voi
 
 int dinfer_debug_trace(int32_t unit, void* h_out, size_t bytes) {
   if (!h_out) return fail(DINFER_EINVAL, "null argument");
-  const int r = unit == 0 ? trace_read_gemm(h_out, bytes) : unit == 1 ? trace_read_attention(h_out, bytes) : -2;
+  const int r = unit == 0   ? trace_read_gemm(h_out, bytes)
+                : unit == 1 ? trace_read_attention(h_out, bytes)
+                : unit == 2 ? trace_read_wide(h_out, bytes)
+                            : -2;
   if (r == -1) return fail(DINFER_EINVAL, "library built without DINFER_TRACE, or buffer too large");
   if (r != 0) return fail(DINFER_EINVAL, "trace read failed (%d)", r);
   return DINFER_OK;

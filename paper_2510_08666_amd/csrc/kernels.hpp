@@ -164,5 +164,6 @@ bool configure_wide();
 // In-kernel phase timestamps of builds with -DDINFER_TRACE (see common.hpp); return -1 in ordinary builds.
 int trace_read_gemm(void* h_out, size_t bytes);
 int trace_read_attention(void* h_out, size_t bytes);
+int trace_read_wide(void* h_out, size_t bytes);
 
 }  // namespace dinfer

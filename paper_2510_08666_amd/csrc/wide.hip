@@ -12,9 +12,13 @@
 namespace dinfer {
 
 constexpr int WT = 4;      // token tiles per workgroup
-constexpr int WW = 4;      // waves = tasks per workgroup
 constexpr int WKC = 4;     // k-steps per staged chunk
-constexpr int WPRE = 2;    // weight chunks in flight per wave
+// Waves (= tasks) per workgroup and weight chunks in flight per wave.  Eight waves put two on every SIMD, so one
+// computes while the other waits for LDS or memory, and the activation fragments are shared by eight tasks.
+// (Measured at 512 tokens: four waves with the whole register file behind a six-chunk weight prefetch are slower
+// for the expert GEMMs, 173 against 141 microseconds.)
+constexpr int EXPERT_WW = 8, EXPERT_PRE = 2;
+constexpr int LM_WW = 8, LM_PRE = 2;
 
 template <typename E> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * Planes<E>::N * WAVE * 16; }
 
@@ -22,11 +26,11 @@ template <typename E> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT 
 // activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
 // sb: LDS [2][WKC][WT][planes][64] operand vectors.  NT: token tiles that hold rows.
 // Pipeline per chunk c: barrier; the fragments of chunk c+1 go from registers to LDS buffer (c+1)&1 and the
-// loads of chunk c+2 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
+// loads of chunk c+3 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
 // requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
 // around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
 // computes while the other waits at its barrier.
-template <typename E, int NT>
+template <typename E, int NT, int WW, int WPRE>
 __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
                                       int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
                                       f32x16 (&acc1)[WT]) {
@@ -36,8 +40,11 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
   static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int last = n_chunks - 1;
+  TRACE_MARK(9, 0);
+  constexpr int SKS = WKC * WT / WW;               // k-steps of a chunk this wave stages (of token tile wave % WT)
+  const int st = wave % WT, sk0 = (wave / WT) * SKS;
   vec wa0[WPRE][WKC], wa1[WPRE][WKC];
-  vec bnext[WKC][NP];
+  vec bset[2][SKS][NP];                            // fragments of the next two chunks, on their way to LDS
   auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
   // Prologue, in the order the loop keeps: weights of chunk 0, fragments of chunk 0 (to LDS) and chunk 1 (to
   // registers), then the weights of the following chunks -- so that waiting for the fragments at the top of an
@@ -48,16 +55,19 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
     wa1[0][ks] = load16_stream<E>(wp + (int64_t)ks * STEP + WAVE * G);
   }
   {
-    vec b0[WKC][NP];
-    const int c1 = min(1, last);
+    vec b0[SKS][NP];
+    const int c1 = min(1, last), c2 = min(2, last);
 #pragma unroll
-    for (int ks = 0; ks < WKC; ++ks)
+    for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-      for (int q = 0; q < NP; ++q) b0[ks][q] = load16<E>(brow + (int64_t)ks * bkstride + q * KS);
+      for (int q = 0; q < NP; ++q) b0[ks][q] = load16<E>(brow + (int64_t)(sk0 + ks) * bkstride + q * KS);
 #pragma unroll
-    for (int ks = 0; ks < WKC; ++ks)
+    for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-      for (int q = 0; q < NP; ++q) bnext[ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + ks) * bkstride + q * KS);
+      for (int q = 0; q < NP; ++q) {
+        bset[1][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
+        bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
+      }
 #pragma unroll
     for (int i = 1; i < WPRE; ++i) {
       const int c = min(i, last);
@@ -68,9 +78,9 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       }
     }
 #pragma unroll
-    for (int ks = 0; ks < WKC; ++ks)
+    for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-      for (int q = 0; q < NP; ++q) sb_at(0, ks, wave, q) = b0[ks][q];
+      for (int q = 0; q < NP; ++q) sb_at(0, sk0 + ks, st, q) = b0[ks][q];
   }
   for (int c0 = 0; c0 < n_chunks; c0 += WPRE) {
 #pragma unroll
@@ -78,16 +88,22 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       const int c = c0 + i;
       if (c < n_chunks) {   // uniform over the workgroup
         __syncthreads();
+        if (c == 0) TRACE_MARK(9, 1);
+        if (c == 1) TRACE_MARK(9, 2);
+        if (c == 2) TRACE_MARK(9, 3);
+        if (c == 16) TRACE_MARK(9, 4);
+        if (c == 17) TRACE_MARK(9, 5);
         const int nb = (i + 1) & 1, cb = i & 1;   // c0 is even: parities of c+1 and c
 #pragma unroll
-        for (int ks = 0; ks < WKC; ++ks)
+        for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-          for (int q = 0; q < NP; ++q) sb_at(nb, ks, wave, q) = bnext[ks][q];
-        const int cn = min(c + 2, last);
+          for (int q = 0; q < NP; ++q) sb_at(nb, sk0 + ks, st, q) = bset[nb][ks][q];
+        const int cn = min(c + 3, last);
 #pragma unroll
-        for (int ks = 0; ks < WKC; ++ks)
+        for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-          for (int q = 0; q < NP; ++q) bnext[ks][q] = load16<E>(brow + (int64_t)(cn * WKC + ks) * bkstride + q * KS);
+          for (int q = 0; q < NP; ++q)
+            bset[nb][ks][q] = load16<E>(brow + (int64_t)(cn * WKC + sk0 + ks) * bkstride + q * KS);
 #pragma unroll
         for (int ks = 0; ks < WKC; ++ks)
 #pragma unroll
@@ -107,17 +123,18 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       }
     }
   }
+  TRACE_MARK(9, 6);
 }
 
 // nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
-template <typename E>
+template <typename E, int WW, int WPRE>
 __device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
                                    int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
                                    f32x16 (&acc1)[WT]) {
-  if (nt >= 4) wide_stream_nt<E, 4>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 3) wide_stream_nt<E, 3>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 2) wide_stream_nt<E, 2>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else wide_stream_nt<E, 1>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  if (nt >= 4) wide_stream_nt<E, 4, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 3) wide_stream_nt<E, 3, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 2) wide_stream_nt<E, 2, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else wide_stream_nt<E, 1, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
 }
 
 __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
@@ -129,7 +146,7 @@ __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
 //   GEMM 2: task = 64 adjacent output features of the down projection                -> O[token*top_k + slot][H]
 // ------------------------------------------------------------------------------------------------
 template <typename E>
-__global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+__global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                        const float* __restrict__ rinv,
                                                                        E* __restrict__ Y, const int32_t* __restrict__ cnt,
                                                                        const int32_t* __restrict__ off,
@@ -145,7 +162,7 @@ __global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm1_wide_kernel(const E
   if (row0 >= n_rows) return;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int n_tasks = I / TILE, task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
+  const int n_tasks = I / TILE, task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
   const int base = off[e];
   const int ksteps = H / KS;
   int tok[WT];
@@ -158,14 +175,14 @@ __global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm1_wide_kernel(const E
   int stage_tok = tok[0];
 #pragma unroll
   for (int t = 1; t < WT; ++t)
-    if (wave == t) stage_tok = tok[t];
+    if (wave % WT == t) stage_tok = tok[t];
   const E* brow = xn + (int64_t)stage_tok * (NP * KS) + half * G;
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, EXPERT_WW, EXPERT_PRE>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
-  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
+  if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
     const int row = row0 + t * TILE + col;
@@ -179,7 +196,7 @@ __global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm1_wide_kernel(const E
 }
 
 template <typename E>
-__global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+__global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                                        float* __restrict__ O, const int32_t* __restrict__ cnt,
                                                                        const int32_t* __restrict__ off,
                                                                        const int32_t* __restrict__ perm, int n_pairs, int H,
@@ -194,19 +211,19 @@ __global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm2_wide_kernel(const E
   if (row0 >= n_rows) return;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
+  const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
   const int base = off[e];
   const int ksteps = I / KS;
   int pair[WT];
 #pragma unroll
   for (int t = 0; t < WT; ++t) pair[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)];
-  const E* brow = Y + (int64_t)(base + min(row0 + wave * TILE + col, n_rows - 1)) * (NP * KS) + half * G;
+  const E* brow = Y + (int64_t)(base + min(row0 + (wave % WT) * TILE + col, n_rows - 1)) * (NP * KS) + half * G;
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, EXPERT_WW, EXPERT_PRE>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
-  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
+  if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
     if (t < nt && row0 + t * TILE + col < n_rows) {
@@ -229,13 +246,13 @@ __global__ __launch_bounds__(WW * WAVE, 2) void expert_gemm2_wide_kernel(const E
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   const int n_tasks = a.I / TILE;
-  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + WW - 1) / WW, a.E, groups), WW * WAVE, wide_lds<E>(), st>>>(
+  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, a.E, groups), EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
       (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.T, a.H, a.I, a.top_k);
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   const int n_tasks = a.H / (2 * TILE);
-  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + WW - 1) / WW, a.E, groups), WW * WAVE, wide_lds<E>(), st>>>(
+  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, a.E, groups), EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
       (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.T * a.top_k, a.H, a.I);
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
@@ -253,7 +270,7 @@ void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
 // per token: part[(quad * 4 + wave)][token].  Logits are never stored (unless the debug pointer is set).
 // ------------------------------------------------------------------------------------------------
 template <typename E>
-__global__ __launch_bounds__(WW * WAVE, 2) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+__global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                   const float* __restrict__ rinv, int T, int H, int V,
                                                                   float scale, float* __restrict__ part,
                                                                   float* __restrict__ logits_out) {
@@ -265,16 +282,16 @@ __global__ __launch_bounds__(WW * WAVE, 2) void lm_head_wide_kernel(const E* __r
   const int tok0 = blockIdx.y * WT * TILE;
   const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
-  const int slot = blockIdx.x * WW + wave, task = min(slot, n_tasks - 1);
+  const int slot = blockIdx.x * LM_WW + wave, task = min(slot, n_tasks - 1);
   const int ksteps = H / KS;
   float zs[WT];
 #pragma unroll
   for (int t = 0; t < WT; ++t) zs[t] = rinv[min(tok0 + t * TILE + col, T - 1)] * scale;
-  const E* brow = xn + (int64_t)min(tok0 + wave * TILE + col, T - 1) * (NP * KS) + half * G;
+  const E* brow = xn + (int64_t)min(tok0 + (wave % WT) * TILE + col, T - 1) * (NP * KS) + half * G;
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+  wide_stream<E, LM_WW, LM_PRE>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
@@ -321,11 +338,11 @@ __global__ __launch_bounds__(WW * WAVE, 2) void lm_head_wide_kernel(const E* __r
   }
 }
 
-int lm_head_wide_parts(int V) { return ((V + 63) / 64 + WW - 1) / WW * WW; }
+int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_WW; }
 
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
-  lm_head_wide_kernel<E><<<dim3(lm_head_wide_parts(a.V) / WW, groups), WW * WAVE, wide_lds<E>(), st>>>(
+  lm_head_wide_kernel<E><<<dim3(lm_head_wide_parts(a.V) / LM_WW, groups), LM_WW * WAVE, wide_lds<E>(), st>>>(
       (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
@@ -341,5 +358,7 @@ bool configure_wide() {
     if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) return false;
   return true;
 }
+
+TRACE_READER(trace_read_wide)
 
 }  // namespace dinfer
