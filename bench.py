@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the block-denoising step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4|5]
 
 A "step" is one dinfer_step: the whole hot path (embedding, 16 transformer layers with paged non-causal
 attention and the routed-expert grouped GEMMs, LM head fused with the confidence reduction, threshold
@@ -9,6 +9,10 @@ commit) over one batch of synthetic input.  Default workload: the LLaDA-MoE-shap
 cached prefix, 32-position fully masked block, threshold 0.9, bf16 random-init weights).  Every timed step
 starts from the same token / mask state, restored by two small device copies inside the timed region.
 Inputs are resident in HBM before timing starts.  Prints ONE JSON line.
+
+--workload 5 times the whole generation loop instead (256-token prompt, 1024 tokens in 16 blocks of 64, exactly
+8 steps of 8 commits per block, cache refresh of every decoded block): a "step" is still one denoising step, the
+value is end-to-end committed tokens/s (prefill excluded; the figure with prefill is reported beside it).
 """
 import argparse
 import json
@@ -55,12 +59,97 @@ def measured_traffic(kernel, workload):
     return None
 
 
+def generation_loop(args):
+    """Workload 5: prompt prefill, then blocks of (fixed number of denoising steps + cache refresh)."""
+    import torch
+    import dinfer_inputs as di
+    from paper_2510_08666_amd import binding
+
+    wl = di.workload_preset(5)
+    cfg = wl.model
+    seed = di.BASE_SEED + wl.seed_index
+    weights = di.make_weights(cfg, di.BASE_SEED + 2)
+    inp = di.make_workload_inputs(wl, seed)
+    S, P0 = wl.block_len, int(inp.prefix_len[0])
+    n_blocks = wl.gen_len // S
+    steps_per_block = S // wl.fixed_k
+    max_pos = P0 + wl.gen_len + 16
+    ctx = binding.Context(cfg, inp.n_pages, 1, max(P0, S), max_pos)
+    ctx.load_weights(weights)
+    dev = ctx.device
+    page_table = torch.from_numpy(inp.page_table).to(dev)
+    prompt = torch.from_numpy(inp.prefix_tokens[0].astype(np.int32)).to(dev)
+    tokens0 = torch.from_numpy(inp.block_tokens.copy()).to(dev)
+    mask0 = torch.from_numpy(inp.mask_bits.view(np.int64).copy()).to(dev)
+    tokens, mask = tokens0.clone(), mask0.clone()
+    prefix_len = torch.zeros(1, dtype=torch.int32, device=dev)
+    conf = torch.zeros((1, S), dtype=torch.float32, device=dev)
+    argmax = torch.zeros((1, S), dtype=torch.int32, device=dev)
+    n_committed = torch.zeros(1, dtype=torch.int32, device=dev)
+    out_tokens = torch.zeros((n_blocks, S), dtype=torch.int32, device=dev)
+
+    def generate():
+        """One whole generation; returns (seconds in prefill, seconds in the block loop)."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.prefill(prompt, [P0], page_table)
+        prefix_len.fill_(P0)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for b in range(n_blocks):
+            tokens.copy_(tokens0)
+            mask.copy_(mask0)
+            ctx.generate_block(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed,
+                               steps_per_block, masked_hint=S)
+            ctx.refresh_block(tokens, prefix_len, page_table)
+            out_tokens[b].copy_(tokens[0])
+        torch.cuda.synchronize()
+        return t1 - t0, time.perf_counter() - t1
+
+    for _ in range(max(args.warmup, 1) if args.warmup else 0):
+        generate()
+    n_gen = max(1, args.steps // (n_blocks * steps_per_block)) if args.steps >= n_blocks * steps_per_block else 1
+    t_pre = t_loop = 0.0
+    for _ in range(n_gen):
+        a, b = generate()
+        t_pre += a
+        t_loop += b
+    assert int(mask.item()) == 0 and int(prefix_len.item()) == P0 + wl.gen_len
+    n_steps = n_gen * n_blocks * steps_per_block
+    n_tok = n_gen * wl.gen_len
+    # algorithmic bytes of the loop: per step all weights of the touched experts (taken as all 64: a 64-token block
+    # with top-8 touches nearly all of them), per refresh the same without the LM head; KV of the growing prefix
+    es = 2
+    H, D, I, E, V, L = cfg.hidden, cfg.qkv_dim, cfg.moe_inter, cfg.n_experts, cfg.vocab, cfg.n_layers
+    fwd = L * ((3 * D * H + H * D + E * H) * es + E * 3 * I * H * es)
+    kv = sum(L * (P0 + b * S + S) * 2 * D * es * (steps_per_block + 1) for b in range(n_blocks))
+    total_bytes = n_blocks * ((steps_per_block + 1) * fwd + steps_per_block * V * H * es) + kv
+    out = {
+        "metric": "end-to-end committed tokens/s, block-diffusion generation loop, batch 1",
+        "value": round(n_tok / t_loop, 2), "unit": "tokens/s", "n_gpus": 1, "steps": n_steps, "warmup": args.warmup,
+        "ms_per_step": round(t_loop / n_steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "prompt_len": P0, "gen_len": wl.gen_len, "block_len": S,
+                   "steps_per_block": steps_per_block, "commits_per_step": wl.fixed_k,
+                   "refresh": "after every block, the last one included",
+                   "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2)},
+        "tokens_per_s_with_prefill": round(n_tok / (t_loop + t_pre), 2),
+        "prefill_ms": round(t_pre / n_gen * 1e3, 3), "generations_timed": n_gen,
+        "forwards_per_generation": n_blocks * (steps_per_block + 1),
+        "loop_GB_if_all_experts_touched": round(total_bytes / 1e9, 2),
+        "roofline": None, "cpu_baseline": None,
+        "note": "ms_per_step spreads the refresh forwards over the denoising steps",
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -76,6 +165,8 @@ def main():
     import dinfer_inputs as di
     from paper_2510_08666_amd import binding
 
+    if args.workload == 5:
+        return generation_loop(args)
     wl = di.workload_preset(args.workload)
     cfg = wl.model
     seed = di.BASE_SEED + wl.seed_index
