@@ -108,7 +108,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, y, o, lm_part, conf, argmax, total;
+      perm, pos_of_pair, work, y, o, lm_part, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -161,6 +161,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.off = cv.take((size_t)(2 * MAX_EXPERTS + 2) * 4);   // offsets, then the list of experts with rows
   w.perm = cv.take(T * K * 4);
   w.pos_of_pair = cv.take(T * K * 4);
+  w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
   w.lm_part = cv.take((size_t)lm_head_waves(c.vocab) * T * 4 * 4);
@@ -273,14 +274,14 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     }
     RouterArgs ra{c->weights + lw.router, xn, at<float>(ws, w.ssq), f.rms_eps, T, H, f.n_experts, f.top_k,
                   f.norm_topk, rinv_f, topk_idx, topk_w, at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
-                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), tk_part, tickets};
+                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.pos_of_pair), at<int32_t>(ws, w.work), tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_ROUTER, st);
       launch_router(bf, ra, st);
     }
     ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, xn, rinv_f,
                   ws + w.y, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
-                  at<int32_t>(ws, w.perm), T, H, f.moe_inter, f.n_experts, f.top_k};
+                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.work), T, H, f.moe_inter, f.n_experts, f.top_k};
     {
       StageTimer tm(c, DINFER_STAGE_EXPERT_GATE_UP, st);
       launch_expert_gate_up(bf, ea, st);

@@ -653,7 +653,7 @@ template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a
     router_kernel<E, 2, 8><<<dim3(1, groups), 8 * WAVE, ksplit_lds<2, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
-    launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, st);
+    launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, a.work, st);
   }
 }
 void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {

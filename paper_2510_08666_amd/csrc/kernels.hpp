@@ -107,12 +107,15 @@ struct RouterArgs {
   int32_t* off;
   int32_t* perm;
   int32_t* pos_of_pair;
+  int32_t* work;            // [1 + expert_work_items]: work list of the many-token expert GEMMs (T > 64 only)
   float* part;
   int32_t* tickets;
 };
 void launch_router(bool bf16, const RouterArgs& a, hipStream_t st);
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
-                    int32_t* pos_of_pair, hipStream_t st);
+                    int32_t* pos_of_pair, int32_t* work, hipStream_t st);
+// Work items (expert, group of 128 rows) the many-token expert GEMMs can be handed for n_pairs routed pairs.
+inline int expert_work_items(int E, int n_pairs) { return E + n_pairs / (4 * TILE); }
 int permute_max_pairs();      // most (token, slot) pairs one forward may route
 bool configure_permute();
 
@@ -126,6 +129,7 @@ struct ExpertArgs {
   const int32_t* cnt;
   const int32_t* off;
   const int32_t* perm;
+  const int32_t* work;      // see RouterArgs
   int T, H, I, E, top_k;
 };
 void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st);   // picks the form by a.T

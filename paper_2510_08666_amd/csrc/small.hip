@@ -166,7 +166,8 @@ __device__ inline uint64_t chunk_ballots(unsigned long long* mine, int lane, int
 }
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ expert_of_pair, int n_pairs,
                                                         int n_exp, int32_t* __restrict__ cnt, int32_t* __restrict__ off,
-                                                        int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair) {
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair,
+                                                        int32_t* __restrict__ work) {
   extern __shared__ uint16_t s_pre[];                       // [n_chunks][MAX_EXPERTS]
   __shared__ unsigned long long s_ballot[16 * MAX_EXPERTS];
   __shared__ int32_t s_off[MAX_EXPERTS + 1];
@@ -204,6 +205,28 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
     const uint64_t has_rows = __ballot(tot > 0);            // dense list of the experts that received rows
     if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
     if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+    // Work list of the many-token expert GEMMs: one item per (expert, group of up to 128 rows), the groups with
+    // the most 32-row tiles first, so that the long workgroups start first and the short ones fill the tail.
+    // work[0] = number of items, work[1 + i] = expert << 16 | group.
+    const int full = tot / (4 * TILE), rem_tiles = (tot % (4 * TILE) + TILE - 1) / TILE;
+    int at = 0;
+    for (int k = 4; k >= 1; --k) {
+      const int mine_k = (k == 4 ? full : 0) + (rem_tiles == k ? 1 : 0);   // the remainder group has index `full`
+      int incl_k = mine_k;
+#pragma unroll
+      for (int o = 1; o < WAVE; o <<= 1) {
+        const int up = __shfl_up(incl_k, o, WAVE);
+        if (lane >= o) incl_k += up;
+      }
+      const int first = at + incl_k - mine_k;
+      if (k == 4) {
+        for (int g = 0; g < mine_k; ++g) work[1 + first + g] = (lane << 16) | g;
+      } else if (mine_k) {
+        work[1 + first] = (lane << 16) | full;
+      }
+      at += __shfl(incl_k, WAVE - 1, WAVE);
+    }
+    if (lane == 0) work[0] = at;
   }
   __syncthreads();
   for (int c = wave; c < n_chunks; c += n_waves) {
@@ -226,10 +249,10 @@ bool configure_permute() {
 constexpr int PERMUTE_MAX_PAIRS = 65535;
 int permute_max_pairs() { return PERMUTE_MAX_PAIRS; }
 void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, int32_t* off, int32_t* perm,
-                    int32_t* pos_of_pair, hipStream_t st) {
+                    int32_t* pos_of_pair, int32_t* work, hipStream_t st) {
   const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
   permute_kernel<<<1, 1024, (size_t)n_chunks * MAX_EXPERTS * sizeof(uint16_t), st>>>(topk_idx, n_pairs, E, cnt, off, perm,
-                                                                                     pos_of_pair);
+                                                                                     pos_of_pair, work);
 }
 
 // ---------------------------------------------------------------- LM-head partial merge

@@ -30,7 +30,7 @@ template <typename E> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT 
 // requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
 // around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
 // computes while the other waits at its barrier.
-template <typename E, int NT, int WW, int WPRE>
+template <typename E, int NT, int WW, int WPRE, int KID>
 __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
                                       int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
                                       f32x16 (&acc1)[WT]) {
@@ -40,7 +40,7 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
   static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int last = n_chunks - 1;
-  TRACE_MARK(9, 0);
+  TRACE_MARK(KID, 0);
   constexpr int SKS = WKC * WT / WW;               // k-steps of a chunk this wave stages (of token tile wave % WT)
   const int st = wave % WT, sk0 = (wave / WT) * SKS;
   vec wa0[WPRE][WKC], wa1[WPRE][WKC];
@@ -88,11 +88,11 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       const int c = c0 + i;
       if (c < n_chunks) {   // uniform over the workgroup
         __syncthreads();
-        if (c == 0) TRACE_MARK(9, 1);
-        if (c == 1) TRACE_MARK(9, 2);
-        if (c == 2) TRACE_MARK(9, 3);
-        if (c == 16) TRACE_MARK(9, 4);
-        if (c == 17) TRACE_MARK(9, 5);
+        if (c == 0) TRACE_MARK(KID, 1);
+        if (c == 1) TRACE_MARK(KID, 2);
+        if (c == 2) TRACE_MARK(KID, 3);
+        if (c == 16) TRACE_MARK(KID, 4);
+        if (c == 17) TRACE_MARK(KID, 5);
         const int nb = (i + 1) & 1, cb = i & 1;   // c0 is even: parities of c+1 and c
 #pragma unroll
         for (int ks = 0; ks < SKS; ++ks)
@@ -123,25 +123,25 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       }
     }
   }
-  TRACE_MARK(9, 6);
+  TRACE_MARK(KID, 6);
 }
 
 // nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
-template <typename E, int WW, int WPRE>
+template <typename E, int WW, int WPRE, int KID>
 __device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
                                    int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
                                    f32x16 (&acc1)[WT]) {
-  if (nt >= 4) wide_stream_nt<E, 4, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 3) wide_stream_nt<E, 3, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 2) wide_stream_nt<E, 2, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else wide_stream_nt<E, 1, WW, WPRE>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  if (nt >= 4) wide_stream_nt<E, 4, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 3) wide_stream_nt<E, 3, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else if (nt == 2) wide_stream_nt<E, 2, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
+  else wide_stream_nt<E, 1, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
 }
 
 __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
 
 // ------------------------------------------------------------------------------------------------
-// Routed experts, rows of expert e = pairs perm[off[e] .. off[e]+cnt[e]).  Grid (tasks / 4, experts through the
-// active list, groups of 128 rows).
+// Routed experts, rows of expert e = pairs perm[off[e] .. off[e]+cnt[e]).  Grid (tasks / 8, work items): a work item
+// is an (expert, group of up to 128 rows) pair; the permutation kernel lists them heaviest first.
 //   GEMM 1: task = 32 gate features + the same 32 up features;  y = silu(gate) * up  -> Y[sorted row][I]
 //   GEMM 2: task = 64 adjacent output features of the down projection                -> O[token*top_k + slot][H]
 // ------------------------------------------------------------------------------------------------
@@ -150,16 +150,16 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(con
                                                                        const float* __restrict__ rinv,
                                                                        E* __restrict__ Y, const int32_t* __restrict__ cnt,
                                                                        const int32_t* __restrict__ off,
-                                                                       const int32_t* __restrict__ perm, int T, int H,
+                                                                       const int32_t* __restrict__ perm,
+                                                                       const int32_t* __restrict__ work, int T, int H,
                                                                        int I, int top_k) {
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
-  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
-  const int e = off[ACTIVE_LIST + blockIdx.y];
-  const int n_rows = cnt[e], row0 = blockIdx.z * WT * TILE;
-  if (row0 >= n_rows) return;
+  if ((int)blockIdx.y >= work[0]) return;   // uniform over the block
+  const int item = work[1 + blockIdx.y], e = item >> 16;
+  const int n_rows = cnt[e], row0 = (item & 0xffff) * WT * TILE;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int n_tasks = I / TILE, task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(con
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, EXPERT_WW, EXPERT_PRE>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, EXPERT_WW, EXPERT_PRE, 10>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
   if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
@@ -199,16 +199,16 @@ template <typename E>
 __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                                        float* __restrict__ O, const int32_t* __restrict__ cnt,
                                                                        const int32_t* __restrict__ off,
-                                                                       const int32_t* __restrict__ perm, int n_pairs, int H,
-                                                                       int I) {
+                                                                       const int32_t* __restrict__ perm,
+                                                                       const int32_t* __restrict__ work, int n_pairs,
+                                                                       int H, int I) {
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
-  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
-  const int e = off[ACTIVE_LIST + blockIdx.y];
-  const int n_rows = cnt[e], row0 = blockIdx.z * WT * TILE;
-  if (row0 >= n_rows) return;
+  if ((int)blockIdx.y >= work[0]) return;
+  const int item = work[1 + blockIdx.y], e = item >> 16;
+  const int n_rows = cnt[e], row0 = (item & 0xffff) * WT * TILE;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, EXPERT_WW, EXPERT_PRE>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, EXPERT_WW, EXPERT_PRE, 11>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
   if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
@@ -244,16 +244,16 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
 }
 
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
-  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   const int n_tasks = a.I / TILE;
-  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, a.E, groups), EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
-      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.T, a.H, a.I, a.top_k);
+  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
+                                EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
+      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
-  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   const int n_tasks = a.H / (2 * TILE);
-  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, a.E, groups), EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.T * a.top_k, a.H, a.I);
+  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
+                                EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
+      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.work, a.T * a.top_k, a.H, a.I);
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
   if (bf16) launch_gate_up_wide_t<bf16_t>(a, st);
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, LM_WW, LM_PRE>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+  wide_stream<E, LM_WW, LM_PRE, 9>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
