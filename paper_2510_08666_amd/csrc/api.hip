@@ -8,6 +8,7 @@
 #include <new>
 #include <vector>
 
+#include "gemm.hpp"
 #include "kernels.hpp"
 
 using namespace dinfer;
@@ -158,7 +159,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.topk_idx = cv.take((size_t)c.n_layers * T * K * 4);   // kept per layer (tests read the routing back)
   w.topk_w = cv.take((size_t)c.n_layers * T * K * 4);
   w.cnt = cv.take((size_t)MAX_EXPERTS * 4);
-  w.off = cv.take((size_t)(2 * MAX_EXPERTS + 2) * 4);   // offsets, then the list of experts with rows
+  w.off = cv.take((size_t)OFF_INTS * 4);   // offsets, then the lists of experts with rows (gemm.hpp)
   w.perm = cv.take(T * K * 4);
   w.pos_of_pair = cv.take(T * K * 4);
   w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);

@@ -466,7 +466,11 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
       if (lane == n_exp - 1) off[n_exp] = incl;
     }
     const uint64_t has_rows = __ballot(tot > 0);          // dense list of the experts with rows (ACTIVE_LIST)
-    if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
+    if (tot > 0) {
+      const int at = __popcll(has_rows & below);
+      off[ACTIVE_LIST + at] = lane;
+      *reinterpret_cast<int4*>(off + ACTIVE_RECORDS + 4 * at) = make_int4(lane, start, tot, 0);
+    }
     if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
     int run = start;                                      // chunk c of expert `lane` starts at run
     for (int c = 0; c < n_chunks; ++c) {
@@ -687,24 +691,26 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
   constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
   TRACE_MARK(4, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
-  const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
-  const int n_rows = cnt[e];
+  const int4 rec = *reinterpret_cast<const int4*>(off + ACTIVE_RECORDS + 4 * blockIdx.y);
+  const int e = rec.x, base = rec.y, n_rows = rec.z, group = blockIdx.z;
   const int row0 = group * TT * TILE;
   if (row0 >= n_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int task = blockIdx.x;
   const int n_tasks = I / TILE;
-  const int base = off[e];
   PlaneLoader<E, TT> ld;
   int row[TT];
   float r[TT];
+  // the token rows hang on the permutation: that chain is resolved while the first weights are in flight
+  auto prep = [&]() {
 #pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    row[t] = row0 + t * TILE + (lane & 31);
-    const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
-    ld.set(t, xn, T, tok, half);
-    r[t] = rinv[tok];
-  }
+    for (int t = 0; t < TT; ++t) {
+      row[t] = row0 + t * TILE + (lane & 31);
+      const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
+      ld.set(t, xn, T, tok, half);
+      r[t] = rinv[tok];
+    }
+  };
   TRACE_MARK(4, 1);
   f32x16 acc0[TT], acc1[TT];
   zero_acc<TT>(acc0);
@@ -713,7 +719,7 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
   const int per = (ksteps + EKS - 1) / EKS;
   const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
   stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
-                                        acc0, acc1);
+                                        acc0, acc1, prep);
   TRACE_MARK(4, 2);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
   __syncthreads();
@@ -755,14 +761,13 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __res
   constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
   TRACE_MARK(5, 0);
   if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
-  const int e = off[ACTIVE_LIST + blockIdx.y], group = blockIdx.z;
-  const int n_rows = cnt[e];
+  const int4 rec = *reinterpret_cast<const int4*>(off + ACTIVE_RECORDS + 4 * blockIdx.y);
+  const int e = rec.x, base = rec.y, n_rows = rec.z, group = blockIdx.z;
   const int row0 = group * TT * TILE;
   if (row0 >= n_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int task = blockIdx.x;
   const int n_tasks = H / (2 * TILE);
-  const int base = off[e];
   PlaneLoader<E, TT> ld;
   int row[TT], pair[TT];   // pair = token * top_k + slot: the output row (token order, no indirection for the reader)
 #pragma unroll

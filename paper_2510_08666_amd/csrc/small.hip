@@ -203,7 +203,11 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
       if (lane == n_exp - 1) off[n_exp] = incl;
     }
     const uint64_t has_rows = __ballot(tot > 0);            // dense list of the experts that received rows
-    if (tot > 0) off[ACTIVE_LIST + __popcll(has_rows & below)] = lane;
+    if (tot > 0) {
+      const int at = __popcll(has_rows & below);
+      off[ACTIVE_LIST + at] = lane;
+      *reinterpret_cast<int4*>(off + ACTIVE_RECORDS + 4 * at) = make_int4(lane, incl - tot, tot, 0);
+    }
     if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
     // Work list of the many-token expert GEMMs: one item per (expert, group of up to 128 rows), the groups with
     // the most 32-row tiles first, so that the long workgroups start first and the short ones fill the tail.
