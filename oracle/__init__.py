@@ -71,6 +71,9 @@ def lib():
         L.oracle_step.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
                                   c_i32, c_vp, c_vp, c_vp, P(CTrace)]
         L.oracle_step.restype = c_i32
+        L.oracle_step_vicinity.argtypes = [P(CConfig), P(CWeights), c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_vp,
+                                           c_i32, c_f64, c_i32, c_vp, c_vp, c_vp, P(CTrace)]
+        L.oracle_step_vicinity.restype = c_i32
         L.oracle_generate_block.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp,
                                             c_i32, c_f64, c_i32, c_i32, c_vp]
         L.oracle_generate_block.restype = c_i32
@@ -179,6 +182,27 @@ class Oracle:
                               trace.c if trace else None)
         if n < 0:
             raise ValueError("oracle_step failed")
+        r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
+        if want_logits:
+            r["logits"] = logits
+        return r
+
+    def step_vicinity(self, block_tokens, vicinity_tokens, mask, prefix_len, kc, vc, threshold, fixed_k=0,
+                      want_logits=False, trace=None):
+        """One denoising step that also recomputes K,V of the len(vicinity_tokens) cached positions before the
+        block (vicinity KV-cache refresh).  Returns the same dict as step()."""
+        tok = np.array(block_tokens, dtype=np.int32)
+        vic = np.ascontiguousarray(vicinity_tokens, dtype=np.int32)
+        S = tok.shape[0]
+        m = np.array([mask], dtype=np.uint64)
+        conf = np.zeros(S, dtype=np.float64)
+        am = np.zeros(S, dtype=np.int32)
+        logits = np.zeros((S, self.cfg.vocab), dtype=np.float64) if want_logits else None
+        n = lib().oracle_step_vicinity(self.ccfg, self.cw, S, int(vic.shape[0]), _p(tok), _p(vic), _p(m),
+                                       int(prefix_len), _p(kc), _p(vc), kc.shape[1], float(threshold), int(fixed_k),
+                                       _p(conf), _p(am), _p(logits), trace.c if trace else None)
+        if n < 0:
+            raise ValueError("oracle_step_vicinity failed")
         r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
         if want_logits:
             r["logits"] = logits

@@ -342,6 +342,30 @@ int32_t oracle_step(const oracle_config* c, const oracle_weights* w, int block_l
   return n;
 }
 
+int32_t oracle_step_vicinity(const oracle_config* c, const oracle_weights* w, int block_len, int look_back,
+                             int32_t* block_tokens, const int32_t* vicinity_tokens, uint64_t* mask, int prefix_len,
+                             double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k,
+                             double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace) {
+  if (look_back < 0 || look_back > prefix_len) return -1;
+  const int V = c->vocab, n = look_back + block_len;
+  int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)n);
+  double* hidden = (double*)malloc(sizeof(double) * (size_t)n * c->hidden);
+  double* logits = logits_out ? logits_out : (double*)malloc(sizeof(double) * (size_t)block_len * V);
+  for (int i = 0; i < look_back; ++i) tokens[i] = vicinity_tokens[i];
+  for (int i = 0; i < block_len; ++i) tokens[look_back + i] = block_tokens[i];
+  int32_t committed = -1;
+  /* the neighbours are simply the first tokens of a longer forward that starts look_back positions earlier */
+  if (oracle_forward(c, w, n, tokens, prefix_len - look_back, kcache, vcache, cache_cap, hidden, trace) == 0) {
+    oracle_logits(c, w, hidden + (size_t)look_back * c->hidden, block_len, logits);
+    for (int i = 0; i < block_len; ++i) oracle_confidence(logits + (size_t)i * V, V, &conf[i], &argmax[i]);
+    committed = oracle_commit(conf, argmax, block_len, mask, block_tokens, threshold, fixed_k);
+  }
+  if (!logits_out) free(logits);
+  free(hidden);
+  free(tokens);
+  return committed;
+}
+
 int32_t oracle_generate_block(const oracle_config* c, const oracle_weights* w, int block_len,
                               int32_t* block_tokens, uint64_t* mask, int prefix_len, double* kcache,
                               double* vcache, int cache_cap, double threshold, int fixed_k, int max_steps,

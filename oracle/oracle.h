@@ -107,6 +107,18 @@ int32_t oracle_step(const oracle_config* c, const oracle_weights* w, int block_l
                     double threshold, int fixed_k, double* conf, int32_t* argmax, double* logits_out,
                     const oracle_trace* trace);
 
+/* The step with vicinity KV-cache refresh (Section 2, KV-cache management: during denoising K and V are recomputed
+ * for the masked tokens and for their immediate neighbours).  The look_back cached positions before the block
+ * (ids in vicinity_tokens[look_back], positions prefix_len-look_back .. prefix_len-1) join the forward: they
+ * are embedded again, attend to every key like the block's positions, and their K,V rows in the cache are
+ * overwritten.  Logits, confidence and the commit concern the block's positions only.  Positions after the block
+ * do not exist in this formulation (the block attends to the prefix and itself), so there is no look-ahead part.
+ * Requires 0 <= look_back <= prefix_len.  The trace (if any) covers look_back + block_len tokens. */
+int32_t oracle_step_vicinity(const oracle_config* c, const oracle_weights* w, int block_len, int look_back,
+                             int32_t* block_tokens, const int32_t* vicinity_tokens, uint64_t* mask, int prefix_len,
+                             double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k,
+                             double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace);
+
 /* Repeats oracle_step until the mask is empty (at most max_steps); returns steps taken.
  * committed_per_step (may be NULL): [max_steps]. */
 int32_t oracle_generate_block(const oracle_config* c, const oracle_weights* w, int block_len,

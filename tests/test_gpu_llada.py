@@ -136,21 +136,17 @@ def test_c3_long_prefix_half_committed(model):
 
 
 def test_c4_batch16_paged(model):
-    """Configuration 4: 16 sequences, prefixes 256..2048 on scattered pages.  Every sequence's decisions and
-    invariants are checked on the GPU side; three sequences (shortest, longest prefix, and one more) are
-    compared element by element against the oracle."""
+    """Configuration 4: 16 sequences, prefixes 256..2048 on scattered pages (512 block tokens: the many-token
+    forms of the expert GEMMs and the LM head).  Every sequence is compared element by element against the
+    oracle."""
     c = BigCase(model, di.workload_preset(4))
     inp = c.inp
     got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold)
-    order = np.argsort(inp.prefix_len)
-    seqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])})
-    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0, seqs)
+    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0)
     for s in range(c.ns):
         assert got["n_committed"][s] == 1 and bin(int(got["mask"][s])).count("1") == c.S - 1
         i = int(np.argmax(got["conf"][s]))
         assert got["tokens"][s][i] == got["argmax"][s][i]
-    # a sequence computed alone equals the same sequence inside the batch (logits bit-identical is not
-    # required: the row tiling differs; the bars are)
     cnt = c.gpu.ctx.debug_get(3, (c.cfg.n_experts,), c.gpu.torch.int32).cpu().numpy()
     log("C4 last-layer expert rows: min %d max %d mean %.1f" % (cnt.min(), cnt.max(), cnt.mean()))
     assert cnt.sum() == c.ns * c.S * c.cfg.top_k
@@ -168,8 +164,7 @@ def test_c5_first_block_fixed_k_and_refresh(model):
     n_steps = 0
     while masks.any():
         got, logits, routing = c.gpu_step(tokens, masks, inp.prefix_len, wl.threshold, wl.fixed_k)
-        if n_steps in (0, 7):      # the oracle takes ~15 s a step: first and last step are compared in full
-            c.check_step(got, logits, routing, tokens, masks, inp.prefix_len, wl.threshold, wl.fixed_k)
+        c.check_step(got, logits, routing, tokens, masks, inp.prefix_len, wl.threshold, wl.fixed_k)
         assert got["n_committed"][0] == 8
         assert int(got["mask"][0]) & ~int(masks[0]) == 0
         tokens, masks = got["tokens"].copy(), got["mask"].copy()
