@@ -151,6 +151,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vicinity", type=int, default=0,
+                    help="time the step with vicinity KV-cache refresh over this many cached positions before the "
+                         "block (the paper's experiments use 16); 0 = the plain step")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device-to-device copy kernel (known traffic: "
@@ -176,7 +179,8 @@ def main():
     ns, S = inp.block_tokens.shape
     T = ns * S
     max_pos = int(inp.prefix_len.max()) + S + 16
-    ctx = binding.Context(cfg, inp.n_pages, ns, max(T, 64), max_pos)
+    lb = args.vicinity
+    ctx = binding.Context(cfg, inp.n_pages, ns, max(ns * (S + lb), 64), max_pos)
     ctx.load_weights(weights)
     dev = ctx.device
     page_table = torch.from_numpy(inp.page_table).to(dev)
@@ -198,10 +202,19 @@ def main():
     argmax = torch.zeros((ns, S), dtype=torch.int32, device=dev)
     n_committed = torch.zeros(ns, dtype=torch.int32, device=dev)
 
+    vic = None
+    if lb:
+        vic = torch.from_numpy(np.stack([inp.prefix_tokens[s][int(inp.prefix_len[s]) - lb:] for s in range(ns)])
+                               .astype(np.int32)).to(dev)
+
     def one_step():
         tokens.copy_(tokens0)
         mask.copy_(mask0)
-        ctx.step(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed)
+        if lb:
+            ctx.step_vicinity(tokens, vic, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax,
+                              n_committed)
+        else:
+            ctx.step(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed)
 
     # practical HBM read ceiling: the streaming-read probe over the weight buffer, and over one launch's worth
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -242,9 +255,10 @@ def main():
         del src, dst
 
     committed = float(n_committed.sum().item())
+    T = ns * (S + lb)      # tokens of one forward
     routing = ctx.debug_get(1, (cfg.n_layers, T, cfg.top_k), torch.int32).cpu().numpy()
     touched = [len(np.unique(routing[l])) for l in range(cfg.n_layers)]
-    total_bytes, stages = step_bytes(cfg, T, [int(p) for p in inp.prefix_len], S, touched)
+    total_bytes, stages = step_bytes(cfg, T, [int(p) - lb for p in inp.prefix_len], S + lb, touched)
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
 
@@ -275,7 +289,11 @@ def main():
         # a bounded sample: whole oracle steps of sequence 0, repeated until about 10 s of CPU work are done
         n_done, tc = 0, time.perf_counter()
         while n_done == 0 or (time.perf_counter() - tc < 10.0 and n_done < 200):
-            o.step(inp.block_tokens[0], int(inp.mask_bits[0]), P, kc, vc, wl.threshold, wl.fixed_k)
+            if lb:
+                o.step_vicinity(inp.block_tokens[0], inp.prefix_tokens[0][P - lb:], int(inp.mask_bits[0]), P, kc, vc,
+                                wl.threshold, wl.fixed_k)
+            else:
+                o.step(inp.block_tokens[0], int(inp.mask_bits[0]), P, kc, vc, wl.threshold, wl.fixed_k)
             n_done += 1
         cdt = (time.perf_counter() - tc) / n_done
         cpu = {"value": round(1.0 / (cdt * ns), 5), "unit": "steps/s", "cores": oracle.num_threads(),
@@ -287,7 +305,8 @@ def main():
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "n_seq": ns, "block_len": S, "prefix_len": [int(p) for p in inp.prefix_len][:4],
+        "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else ""), "n_seq": ns, "block_len": S,
+                   "vicinity_look_back": lb, "prefix_len": [int(p) for p in inp.prefix_len][:4],
                    "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),
                    "prefix_kv": "seeded synthetic N(0,0.9)"},
         "committed_tokens_per_s": round(steps_per_s * committed, 2),

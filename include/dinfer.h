@@ -125,6 +125,22 @@ int dinfer_step(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_bl
                 const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
                 void* stream);
 
+/* The step with vicinity KV-cache refresh (Section 2, KV-cache management: during denoising K and V are
+ * recomputed for the masked tokens and their immediate neighbours; the paper's experiments use a window of 16).
+ * The look_back cached positions before each block join the forward: d_vicinity_tokens [n_seq][look_back] holds
+ * their ids (positions prefix_len-look_back .. prefix_len-1); they are embedded again, attend to every key like
+ * the block's positions, and their K,V rows in the prefix pages are OVERWRITTEN.  Logits, confidence and the
+ * commit concern the block only; every other argument is as in dinfer_step.  There is no look-ahead part: the
+ * block attends to its prefix and itself, positions after it do not exist here.
+ * 0 <= look_back <= 64; the caller guarantees d_prefix_len[s] >= look_back for every sequence (a shorter prefix
+ * keeps all accesses in bounds but misplaces the block); n_seq * (look_back + block_len) <= max_tokens.
+ * look_back = 0 is dinfer_step. */
+int dinfer_step_vicinity(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t look_back,
+                         int32_t* d_block_tokens, const int32_t* d_vicinity_tokens, uint64_t* d_mask,
+                         const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                         const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
+                         void* stream);
+
 /* Cache update of a decoded block: the same forward without LM head and decoder over the block's final
  * ids, leaving the block's K,V final, then d_prefix_len[s] += block_len. */
 int dinfer_refresh_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, const int32_t* d_block_tokens,

@@ -22,7 +22,8 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
               "w_up": T_UP, "w_down": T_DOWN}
 
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
-           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_refresh_block",
+           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity",
+           "dinfer_refresh_block",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
            "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
@@ -69,6 +70,9 @@ def _load():
     L.dinfer_prefill.argtypes = [c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp]
     L.dinfer_step.restype = c_i32
     L.dinfer_step.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp, c_vp, c_vp, c_vp]
+    L.dinfer_step_vicinity.restype = c_i32
+    L.dinfer_step_vicinity.argtypes = [c_vp, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp,
+                                       c_vp, c_vp, c_vp]
     L.dinfer_refresh_block.restype = c_i32
     L.dinfer_refresh_block.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp]
     L.dinfer_generate_block.restype = c_i32
@@ -201,6 +205,16 @@ class Context:
         _check(lib.dinfer_step(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
                                _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), _ptr(d_conf),
                                _ptr(d_argmax), _ptr(d_n_committed), _stream()))
+
+    def step_vicinity(self, d_block_tokens, d_vicinity_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k,
+                      d_conf, d_argmax, d_n_committed):
+        n_seq, block_len = d_block_tokens.shape
+        look_back = d_vicinity_tokens.shape[1]
+        dec = Decode(float(threshold), int(fixed_k))
+        _check(lib.dinfer_step_vicinity(self.h, n_seq, block_len, look_back, _ptr(d_block_tokens),
+                                        _ptr(d_vicinity_tokens), _ptr(d_mask), _ptr(d_prefix_len), _ptr(d_page_table),
+                                        d_page_table.shape[1], ctypes.byref(dec), _ptr(d_conf), _ptr(d_argmax),
+                                        _ptr(d_n_committed), _stream()))
 
     def refresh_block(self, d_block_tokens, d_prefix_len, d_page_table):
         n_seq, block_len = d_block_tokens.shape

@@ -109,7 +109,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, work, y, o, lm_part, conf, argmax, total;
+      perm, pos_of_pair, work, run_tokens, run_base, y, o, lm_part, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -162,6 +162,8 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.off = cv.take((size_t)OFF_INTS * 4);   // offsets, then the lists of experts with rows (gemm.hpp)
   w.perm = cv.take(T * K * 4);
   w.pos_of_pair = cv.take(T * K * 4);
+  w.run_tokens = cv.take(T * 4);                 // token run and start positions of a vicinity-refresh forward
+  w.run_base = cv.take((size_t)max_seqs * 4);
   w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
@@ -506,8 +508,46 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, d_block_tokens, d_mask, decode->threshold, decode->fixed_k,
-                d_n_committed, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
+                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t look_back, int32_t* d_block_tokens,
+                         const int32_t* d_vicinity_tokens, uint64_t* d_mask, const int32_t* d_prefix_len,
+                         const int32_t* d_page_table, int32_t pt_stride, const dinfer_decode* decode, float* d_conf,
+                         int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
+  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if (look_back < 0 || look_back > 64) return fail(DINFER_EINVAL, "look_back %d outside [0, 64]", look_back);
+  if (look_back > 0 && !d_vicinity_tokens) return fail(DINFER_EINVAL, "null pointer");
+  const int run = look_back + block_len;
+  if ((int64_t)n_seq * run > c->max_tokens)
+    return fail(DINFER_ENOSPACE, "n_seq*(look_back+block_len) %d exceeds max_tokens %d", n_seq * run, c->max_tokens);
+  hipStream_t st = (hipStream_t)stream;
+  const dinfer_config& f = c->cfg;
+  int32_t* run_tokens = at<int32_t>(c->ws, c->wsm.run_tokens);
+  int32_t* run_base = at<int32_t>(c->ws, c->wsm.run_base);
+  launch_vicinity_pack(n_seq, block_len, look_back, d_block_tokens, d_vicinity_tokens, d_prefix_len, run_tokens, run_base,
+                       st);
+  rc = forward(c, uniform_span(n_seq, run), run_tokens, run_base, d_page_table, pt_stride, true, st);
+  if (rc != DINFER_OK) return rc;
+  const int T = n_seq * run;
+  float* conf_rows = at<float>(c->ws, c->wsm.conf);
+  int32_t* argmax_rows = at<int32_t>(c->ws, c->wsm.argmax);
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
+            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            at<float>(c->ws, c->wsm.lm_part), nullptr};
+  {
+    StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
+    launch_lm_head(c->bf16, la, st);
+  }
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, conf_rows, argmax_rows, st);
+  launch_commit(conf_rows, argmax_rows, n_seq, block_len, run, look_back, d_block_tokens, d_mask, decode->threshold,
+                decode->fixed_k, d_n_committed, d_conf, d_argmax, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
 }

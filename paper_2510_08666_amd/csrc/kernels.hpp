@@ -152,8 +152,14 @@ void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);        // picks
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st);
 int lm_head_wide_parts(int V);
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st);
-void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
-                   uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, hipStream_t st);
+// conf / argmax: one row per forward token, position i of sequence s at row s*row_stride + row_off + i;
+// conf_out / argmax_out (may be null): the block's values, compact [n_seq][block_len].
+void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
+                   int32_t* tokens, uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, float* conf_out,
+                   int32_t* argmax_out, hipStream_t st);
+void launch_vicinity_pack(int n_seq, int block_len, int look_back, const int32_t* block_tokens,
+                          const int32_t* vicinity_tokens, const int32_t* prefix_len, int32_t* run_tokens,
+                          int32_t* run_base, hipStream_t st);
 void launch_add_i32(int32_t* a, int n, int v, hipStream_t st);
 
 void launch_kv_copy(bool bf16, bool to_pool, void* kv_layer, KvGeom geom, const int32_t* page_row, int first_pos,

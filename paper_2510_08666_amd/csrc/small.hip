@@ -303,14 +303,24 @@ void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int3
 
 // ---------------------------------------------------------------- decoder: threshold commit
 // One wavefront per sequence, lane = block position.  The set of lanes to commit is a 64-bit ballot.
+// conf / argmax hold one row per forward token: position i of sequence s is row s*row_stride + row_off + i (the
+// rows before row_off are the neighbours a vicinity-refresh forward carries along).  When conf_out / argmax_out
+// are given, the block's values are also stored compactly as [sequence][block_len].
 __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ conf, const int32_t* __restrict__ argmax,
-                                                     int block_len, int32_t* __restrict__ tokens,
-                                                     uint64_t* __restrict__ mask, float threshold, int fixed_k,
-                                                     int32_t* __restrict__ n_committed) {
+                                                     int block_len, int row_stride, int row_off,
+                                                     int32_t* __restrict__ tokens, uint64_t* __restrict__ mask,
+                                                     float threshold, int fixed_k, int32_t* __restrict__ n_committed,
+                                                     float* __restrict__ conf_out, int32_t* __restrict__ argmax_out) {
   const int s = blockIdx.x, lane = threadIdx.x;
   const uint64_t old = mask[s];
   const bool masked = lane < block_len && ((old >> lane) & 1ull);
-  const float c = lane < block_len ? conf[s * block_len + lane] : -1.f;
+  const int row = s * row_stride + row_off + lane;
+  const float c = lane < block_len ? conf[row] : -1.f;
+  const int am = lane < block_len ? argmax[row] : 0;
+  if (conf_out && lane < block_len) {
+    conf_out[s * block_len + lane] = c;
+    argmax_out[s * block_len + lane] = am;
+  }
   uint64_t sel = 0;
   if (fixed_k > 0) {
     float val = masked ? c : -1.f;
@@ -331,15 +341,34 @@ __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ co
       if (hit) sel = 1ull << (__ffsll((unsigned long long)hit) - 1);
     }
   }
-  if ((sel >> lane) & 1ull) tokens[s * block_len + lane] = argmax[s * block_len + lane];
+  if ((sel >> lane) & 1ull) tokens[s * block_len + lane] = am;
   if (lane == 0) {
     mask[s] = old & ~sel;
     n_committed[s] = __popcll(sel);
   }
 }
-void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int32_t* tokens,
-                   uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, hipStream_t st) {
-  commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, tokens, mask, threshold, fixed_k, n_committed);
+void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
+                   int32_t* tokens, uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, float* conf_out,
+                   int32_t* argmax_out, hipStream_t st) {
+  commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, row_stride, row_off, tokens, mask, threshold, fixed_k,
+                                      n_committed, conf_out, argmax_out);
+}
+
+// Token run of a vicinity-refresh forward: per sequence the look_back neighbour ids, then the block's ids; the run
+// starts look_back positions before the block (never before position 0).
+__global__ void vicinity_pack_kernel(int block_len, int look_back, const int32_t* __restrict__ block_tokens,
+                                     const int32_t* __restrict__ vicinity_tokens, const int32_t* __restrict__ prefix_len,
+                                     int32_t* __restrict__ run_tokens, int32_t* __restrict__ run_base) {
+  const int s = blockIdx.x, n = look_back + block_len;
+  for (int i = threadIdx.x; i < n; i += blockDim.x)
+    run_tokens[s * n + i] = i < look_back ? vicinity_tokens[s * look_back + i] : block_tokens[s * block_len + i - look_back];
+  if (threadIdx.x == 0) run_base[s] = max(0, prefix_len[s] - look_back);
+}
+void launch_vicinity_pack(int n_seq, int block_len, int look_back, const int32_t* block_tokens,
+                          const int32_t* vicinity_tokens, const int32_t* prefix_len, int32_t* run_tokens,
+                          int32_t* run_base, hipStream_t st) {
+  vicinity_pack_kernel<<<n_seq, 128, 0, st>>>(block_len, look_back, block_tokens, vicinity_tokens, prefix_len, run_tokens,
+                                              run_base);
 }
 
 __global__ void add_i32_kernel(int32_t* a, int n, int v) {

@@ -58,6 +58,14 @@ class OracleRun:
         ref = self.step(s, tokens, mask, prefix_len, threshold, fixed_k, want_logits, tr)
         return ref, check_routing(tr, gpu_routing, self.cfg.top_k, bars)
 
+    def step_vicinity_following(self, s, tokens, vicinity_tokens, mask, prefix_len, threshold, fixed_k, gpu_routing,
+                                bars):
+        """step_following for the vicinity-refresh step; gpu_routing: [L][look_back + S][k]."""
+        kc, vc = self.caches[s]
+        tr = oracle.Trace(self.cfg, len(vicinity_tokens) + len(tokens), forced_idx=gpu_routing)
+        ref = self.o.step_vicinity(tokens, vicinity_tokens, mask, prefix_len, kc, vc, threshold, fixed_k, True, tr)
+        return ref, check_routing(tr, gpu_routing, self.cfg.top_k, bars)
+
     def forward_following(self, s, tokens, prefix_len, gpu_routing, bars):
         """A forward without decoder (prefill, or the refresh of a decoded block) that follows the GPU's
         expert sets through router near-ties, as step_following does.  Writes K,V into sequence s's cache."""
@@ -125,6 +133,14 @@ class GpuRun:
         self.torch.cuda.synchronize()
         return self.state()
 
+    def step_vicinity(self, vicinity_tokens, threshold, fixed_k=0):
+        """vicinity_tokens: [n_seq][look_back] ids of the cached positions right before each block."""
+        vic = self.torch.from_numpy(np.ascontiguousarray(vicinity_tokens, dtype=np.int32)).to(self.dev)
+        self.ctx.step_vicinity(self.tokens, vic, self.mask, self.prefix_len, self.page_table, threshold, fixed_k,
+                               self.conf, self.argmax, self.n_committed)
+        self.torch.cuda.synchronize()
+        return self.state()
+
     def state(self):
         return dict(tokens=self.tokens.cpu().numpy(), mask=self.mask.cpu().numpy().view(np.uint64),
                     conf=self.conf.cpu().numpy(), argmax=self.argmax.cpu().numpy(),
@@ -186,6 +202,18 @@ def check_routing(trace, gpu_routing, top_k, bars, stats=None):
 
 def max_abs_err(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max()) if np.size(ref) else 0.0
+
+
+def kv_close(got, ref, bars):
+    """Cached K or V rows [n][D] against the oracle's.  They are outputs of a linear layer computed with the same
+    arithmetic as the logits (bf16 inputs, float32 accumulation), so they get the same relative bar, per row:
+    max |got - ref| <= max(kv_abs, logit_rel * max |ref row|).  The absolute floor alone is too tight once a row
+    holds values beyond 4, where bf16 storage and a 0.5 % activation error already add up to 0.03."""
+    if not np.size(ref):
+        return True
+    err = np.abs(np.asarray(got, dtype=np.float64) - ref).max(axis=-1)
+    allowed = np.maximum(bars.kv_abs, bars.logit_rel * np.abs(ref).max(axis=-1))
+    return bool(np.all(err <= allowed))
 
 
 def compare_logits(ref, got, bars):

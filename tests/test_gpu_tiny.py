@@ -6,7 +6,7 @@ import pytest
 
 import dinfer_inputs as di
 import oracle
-from harness import GpuRun, OracleRun, bars_for, compare_logits, compare_step, make_case, max_abs_err
+from harness import kv_close, GpuRun, OracleRun, bars_for, compare_logits, compare_step, make_case, max_abs_err
 
 pytestmark = pytest.mark.gpu
 
@@ -98,8 +98,8 @@ def test_prefill_matches_oracle(case):
         at += P
         for l in range(case.cfg.n_layers):
             k, v = g.read_kv(s, l, 0, P)
-            assert max_abs_err(k, kc[l, :P]) <= case.bars.kv_abs, (s, l)
-            assert max_abs_err(v, vc[l, :P]) <= case.bars.kv_abs, (s, l)
+            assert kv_close(k, kc[l, :P], case.bars), (s, l)
+            assert kv_close(v, vc[l, :P], case.bars), (s, l)
         kc[...], vc[...] = keep
 
 
@@ -127,8 +127,8 @@ def _run_step(case, threshold, fixed_k=0, tokens=None, masks=None):
         # K,V of the block positions as the step wrote them; prefix rows untouched
         for l in range(case.cfg.n_layers):
             k, v = g.read_kv(s, l, 0, P + case.S)
-            assert max_abs_err(k[P:], kc[l, P:P + case.S]) <= case.bars.kv_abs
-            assert max_abs_err(v[P:], vc[l, P:P + case.S]) <= case.bars.kv_abs
+            assert kv_close(k[P:], kc[l, P:P + case.S], case.bars)
+            assert kv_close(v[P:], vc[l, P:P + case.S], case.bars)
             if P:
                 ref_k = keep_k[l, :P].astype(np.float32)
                 ref_v = keep_v[l, :P].astype(np.float32)
@@ -267,8 +267,8 @@ def test_generate_block_teacher_forced(case):
         kc, vc = case.ora.caches[s]
         for l in range(case.cfg.n_layers):
             k, v = g.read_kv(s, l, P, case.S)
-            assert max_abs_err(k, kc[l, P:P + case.S]) <= case.bars.kv_abs
-            assert max_abs_err(v, vc[l, P:P + case.S]) <= case.bars.kv_abs
+            assert kv_close(k, kc[l, P:P + case.S], case.bars)
+            assert kv_close(v, vc[l, P:P + case.S], case.bars)
 
 
 def test_fixed_k_generation_takes_ceil_steps(case):
