@@ -71,6 +71,11 @@ def lib():
         L.oracle_step.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
                                   c_i32, c_vp, c_vp, c_vp, P(CTrace)]
         L.oracle_step.restype = c_i32
+        L.oracle_credit_position.argtypes = [c_vp, c_i32, c_vp, c_f64, c_f64, c_f64, c_vp, c_vp, c_vp]
+        L.oracle_credit_position.restype = None
+        L.oracle_step_credit.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
+                                         c_i32, c_vp, c_f64, c_f64, c_f64, c_vp, c_vp, c_vp, P(CTrace)]
+        L.oracle_step_credit.restype = c_i32
         L.oracle_step_vicinity.argtypes = [P(CConfig), P(CWeights), c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_vp,
                                            c_i32, c_f64, c_i32, c_vp, c_vp, c_vp, P(CTrace)]
         L.oracle_step_vicinity.restype = c_i32
@@ -187,6 +192,29 @@ class Oracle:
             r["logits"] = logits
         return r
 
+    def step_credit(self, block_tokens, mask, prefix_len, kc, vc, threshold, credit, alpha, beta, gamma, fixed_k=0,
+                    want_logits=False, trace=None):
+        """One denoising step with credit decoding.  credit: float64 [S][V], updated in place (rows of positions
+        masked at the start of the step).  Returns the dict of step(); conf / argmax are those of the enhanced
+        distribution, logits (if wanted) the fused logits of the masked rows."""
+        tok = np.array(block_tokens, dtype=np.int32)
+        S = tok.shape[0]
+        assert credit.dtype == np.float64 and credit.shape == (S, self.cfg.vocab) and credit.flags.c_contiguous
+        m = np.array([mask], dtype=np.uint64)
+        conf = np.zeros(S, dtype=np.float64)
+        am = np.zeros(S, dtype=np.int32)
+        logits = np.zeros((S, self.cfg.vocab), dtype=np.float64) if want_logits else None
+        n = lib().oracle_step_credit(self.ccfg, self.cw, S, _p(tok), _p(m), int(prefix_len), _p(kc), _p(vc),
+                                     kc.shape[1], float(threshold), int(fixed_k), _p(credit), float(alpha),
+                                     float(beta), float(gamma), _p(conf), _p(am), _p(logits),
+                                     trace.c if trace else None)
+        if n < 0:
+            raise ValueError("oracle_step_credit failed")
+        r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
+        if want_logits:
+            r["logits"] = logits
+        return r
+
     def step_vicinity(self, block_tokens, vicinity_tokens, mask, prefix_len, kc, vc, threshold, fixed_k=0,
                       want_logits=False, trace=None):
         """One denoising step that also recomputes K,V of the len(vicinity_tokens) cached positions before the
@@ -221,6 +249,18 @@ class Oracle:
 
 
 # ---- building blocks, for the pins ----
+
+def credit_position(logits, credit, alpha, beta, gamma):
+    """Credit decoding of one position; credit (float64 [V]) is updated in place.  Returns (conf, argmax, fused)."""
+    logits = f64(logits)
+    assert credit.dtype == np.float64 and credit.flags.c_contiguous
+    conf = np.zeros(1)
+    am = np.zeros(1, dtype=np.int32)
+    fused = np.zeros_like(logits)
+    lib().oracle_credit_position(_p(logits), logits.shape[0], _p(credit), float(alpha), float(beta), float(gamma),
+                                 _p(conf), _p(am), _p(fused))
+    return float(conf[0]), int(am[0]), fused
+
 
 def rmsnorm(x, gain, eps):
     x = f64(x)

@@ -286,6 +286,22 @@ void oracle_confidence(const double* logits, int vocab, double* conf, int32_t* a
   *argmax = best;
 }
 
+/* Credit decoding for one position (Appendix "Credit decoding", equations 1 and 2), written out densely over the
+ * vocabulary: discount every credit, reward the current top-1 token with its probability to the power gamma, add
+ * alpha * log(1 + credit) to the logits and take the softmax of that. */
+void oracle_credit_position(const double* logits, int vocab, double* credit, double alpha, double beta, double gamma,
+                            double* conf, int32_t* argmax, double* fused_out) {
+  double p_top;
+  int32_t v_top;
+  oracle_confidence(logits, vocab, &p_top, &v_top);               /* p = softmax(logits), v* and p[v*] */
+  for (int v = 0; v < vocab; ++v) credit[v] *= beta;              /* equation 1 */
+  credit[v_top] += pow(p_top, gamma);
+  double* fused = fused_out ? fused_out : (double*)malloc(sizeof(double) * (size_t)vocab);
+  for (int v = 0; v < vocab; ++v) fused[v] = logits[v] + alpha * log(1.0 + credit[v]);   /* equation 2 */
+  oracle_confidence(fused, vocab, conf, argmax);                  /* largest enhanced probability */
+  if (!fused_out) free(fused);
+}
+
 /* Decoder (Section 2, threshold decoding): among masked positions commit those whose confidence
  * reaches the threshold; if there is none, commit the single most confident one (lowest position on
  * ties) so that every step makes progress.  fixed_k > 0 instead commits the fixed_k most confident
@@ -337,6 +353,34 @@ int32_t oracle_step(const oracle_config* c, const oracle_weights* w, int block_l
     for (int i = 0; i < block_len; ++i) oracle_confidence(logits + (size_t)i * V, V, &conf[i], &argmax[i]);
     n = oracle_commit(conf, argmax, block_len, mask, block_tokens, threshold, fixed_k);
   }
+  if (!logits_out) free(logits);
+  free(hidden);
+  return n;
+}
+
+int32_t oracle_step_credit(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                           uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                           double threshold, int fixed_k, double* credit, double alpha, double beta, double gamma,
+                           double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace) {
+  const int V = c->vocab;
+  double* hidden = (double*)malloc(sizeof(double) * (size_t)block_len * c->hidden);
+  double* logits = logits_out ? logits_out : (double*)malloc(sizeof(double) * (size_t)block_len * V);
+  double* fused = (double*)malloc(sizeof(double) * (size_t)V);
+  int32_t n = -1;
+  if (oracle_forward(c, w, block_len, block_tokens, prefix_len, kcache, vcache, cache_cap, hidden, trace) == 0) {
+    oracle_logits(c, w, hidden, block_len, logits);
+    for (int i = 0; i < block_len; ++i) {
+      double* row = logits + (size_t)i * V;
+      if ((*mask >> i) & 1) {
+        oracle_credit_position(row, V, credit + (size_t)i * V, alpha, beta, gamma, &conf[i], &argmax[i], fused);
+        for (int v = 0; v < V; ++v) row[v] = fused[v];
+      } else {
+        oracle_confidence(row, V, &conf[i], &argmax[i]);
+      }
+    }
+    n = oracle_commit(conf, argmax, block_len, mask, block_tokens, threshold, fixed_k);
+  }
+  free(fused);
   if (!logits_out) free(logits);
   free(hidden);
   return n;

@@ -86,6 +86,15 @@ void oracle_confidence(const double* logits, int vocab, double* conf, int32_t* a
 int32_t oracle_commit(const double* conf, const int32_t* argmax, int block_len, uint64_t* mask,
                       int32_t* tokens, double threshold, int fixed_k);
 
+/* Credit decoding (Appendix, "Credit decoding", equations 1 and 2) for ONE position.  logits [V] are the model's;
+ * credit [V] is C_{t-1} on entry and C_t on return:
+ *   p = softmax(logits),  v* = arg max p (lowest id on ties),
+ *   C_t[v] = beta * C_{t-1}[v] + (v == v* ? p[v*]^gamma : 0),
+ *   fused[v] = logits[v] + alpha * log(1 + C_t[v]),  enhanced distribution = softmax(fused).
+ * conf / argmax: the largest enhanced probability and its id (lowest id on ties).  fused_out may be NULL. */
+void oracle_credit_position(const double* logits, int vocab, double* credit, double alpha, double beta, double gamma,
+                            double* conf, int32_t* argmax, double* fused_out);
+
 /* ---- the step ---- */
 
 /* Forward of n_tok tokens placed at positions prefix_len .. prefix_len+n_tok-1 of one sequence.
@@ -118,6 +127,16 @@ int32_t oracle_step_vicinity(const oracle_config* c, const oracle_weights* w, in
                              int32_t* block_tokens, const int32_t* vicinity_tokens, uint64_t* mask, int prefix_len,
                              double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k,
                              double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace);
+
+/* One denoising step with credit decoding: as oracle_step, but the decoder sees the enhanced distribution.
+ * credit: [block_len][V], kept by the caller across the steps of one block (zero at its start); only the rows of
+ * positions that are still masked when the step begins are updated and fused, the other positions report the
+ * plain confidence and arg max.  logits_out (may be NULL) receives the FUSED logits of the masked rows and the
+ * plain logits of the others. */
+int32_t oracle_step_credit(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                           uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                           double threshold, int fixed_k, double* credit, double alpha, double beta, double gamma,
+                           double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace);
 
 /* Repeats oracle_step until the mask is empty (at most max_steps); returns steps taken.
  * committed_per_step (may be NULL): [max_steps]. */
