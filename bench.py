@@ -151,6 +151,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--credit", action="store_true",
+                    help="time the step with credit decoding (alpha 0.65, beta 0.7, gamma 0.5); the credit lists "
+                         "carry over between the timed steps, as inside a block")
     ap.add_argument("--vicinity", type=int, default=0,
                     help="time the step with vicinity KV-cache refresh over this many cached positions before the "
                          "block (the paper's experiments use 16); 0 = the plain step")
@@ -207,10 +210,20 @@ def main():
         vic = torch.from_numpy(np.stack([inp.prefix_tokens[s][int(inp.prefix_len[s]) - lb:] for s in range(ns)])
                                .astype(np.int32)).to(dev)
 
+    credit = None
+    if args.credit:
+        cap = binding.CREDIT_CAP
+        credit = (torch.zeros((ns, S, cap), dtype=torch.int32, device=dev),
+                  torch.zeros((ns, S, cap), dtype=torch.float32, device=dev),
+                  torch.zeros((ns, S), dtype=torch.int32, device=dev))
+
     def one_step():
         tokens.copy_(tokens0)
         mask.copy_(mask0)
-        if lb:
+        if credit is not None:
+            ctx.step_credit(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, 0.65, 0.7, 0.5, credit[0],
+                            credit[1], credit[2], conf, argmax, n_committed)
+        elif lb:
             ctx.step_vicinity(tokens, vic, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax,
                               n_committed)
         else:
@@ -305,7 +318,8 @@ def main():
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else ""), "n_seq": ns, "block_len": S,
+        "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else ""),
+                   "n_seq": ns, "block_len": S,
                    "vicinity_look_back": lb, "prefix_len": [int(p) for p in inp.prefix_len][:4],
                    "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),
                    "prefix_kv": "seeded synthetic N(0,0.9)"},

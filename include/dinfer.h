@@ -125,6 +125,30 @@ int dinfer_step(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_bl
                 const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
                 void* stream);
 
+/* The step with credit decoding (Appendix "Credit decoding").  Every undecided position keeps a credit per token,
+ * C_t[v] = beta * C_{t-1}[v] + (v == top-1 candidate of step t ? p_t(v)^gamma : 0)          (equation 1)
+ * and the decoder sees softmax(logits + alpha * log(1 + C_t)) instead of softmax(logits)     (equation 2):
+ * d_conf / d_argmax report the largest probability of that enhanced distribution and its id (lowest id on
+ * ties), and the threshold / fixed-k rule of `decode` acts on them.  Positions already decided report the
+ * plain values and their credits are left alone.
+ * Credit state, device memory owned by the caller and carried across the steps of one block: a token can only
+ * hold credit if it was the top-1 candidate at some step, so a position stores a list of at most
+ * DINFER_CREDIT_CAP (id, credit) entries:
+ *   d_credit_ids [n_seq][block_len][DINFER_CREDIT_CAP] int32, d_credit_val same shape float32,
+ *   d_credit_n   [n_seq][block_len] int32 entries in use.  Zero d_credit_n to start a block.
+ * A block takes at most block_len <= 64 steps, so the list cannot overflow inside one; if a caller keeps state
+ * longer, the entry with the smallest credit is replaced.
+ * alpha >= 0, 0 <= beta <= 1, 0 < gamma <= 1.  Everything else as in dinfer_step. */
+#define DINFER_CREDIT_CAP 64
+typedef struct {
+  float alpha, beta, gamma;
+} dinfer_credit;
+int dinfer_step_credit(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                       const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                       const dinfer_decode* decode, const dinfer_credit* credit, int32_t* d_credit_ids,
+                       float* d_credit_val, int32_t* d_credit_n, float* d_conf, int32_t* d_argmax,
+                       int32_t* d_n_committed, void* stream);
+
 /* The step with vicinity KV-cache refresh (Section 2, KV-cache management: during denoising K and V are
  * recomputed for the masked tokens and their immediate neighbours; the paper's experiments use a window of 16).
  * The look_back cached positions before each block join the forward: d_vicinity_tokens [n_seq][look_back] holds

@@ -22,7 +22,7 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
               "w_up": T_UP, "w_down": T_DOWN}
 
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
-           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity",
+           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit",
            "dinfer_refresh_block",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
            "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
@@ -38,6 +38,13 @@ class Config(ctypes.Structure):
 
 class Decode(ctypes.Structure):
     _fields_ = [("threshold", c_f32), ("fixed_k", c_i32)]
+
+
+class Credit(ctypes.Structure):
+    _fields_ = [("alpha", c_f32), ("beta", c_f32), ("gamma", c_f32)]
+
+
+CREDIT_CAP = 64
 
 
 class DinferError(RuntimeError):
@@ -70,6 +77,9 @@ def _load():
     L.dinfer_prefill.argtypes = [c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp]
     L.dinfer_step.restype = c_i32
     L.dinfer_step.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp, c_vp, c_vp, c_vp]
+    L.dinfer_step_credit.restype = c_i32
+    L.dinfer_step_credit.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), P(Credit), c_vp, c_vp,
+                                     c_vp, c_vp, c_vp, c_vp, c_vp]
     L.dinfer_step_vicinity.restype = c_i32
     L.dinfer_step_vicinity.argtypes = [c_vp, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp,
                                        c_vp, c_vp, c_vp]
@@ -205,6 +215,16 @@ class Context:
         _check(lib.dinfer_step(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
                                _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), _ptr(d_conf),
                                _ptr(d_argmax), _ptr(d_n_committed), _stream()))
+
+    def step_credit(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, alpha, beta, gamma,
+                    d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, d_n_committed):
+        n_seq, block_len = d_block_tokens.shape
+        dec = Decode(float(threshold), int(fixed_k))
+        cr = Credit(float(alpha), float(beta), float(gamma))
+        _check(lib.dinfer_step_credit(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
+                                      _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), ctypes.byref(cr),
+                                      _ptr(d_credit_ids), _ptr(d_credit_val), _ptr(d_credit_n), _ptr(d_conf),
+                                      _ptr(d_argmax), _ptr(d_n_committed), _stream()))
 
     def step_vicinity(self, d_block_tokens, d_vicinity_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k,
                       d_conf, d_argmax, d_n_committed):

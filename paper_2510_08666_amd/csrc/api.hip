@@ -109,7 +109,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, work, run_tokens, run_base, y, o, lm_part, conf, argmax, total;
+      perm, pos_of_pair, work, run_tokens, run_base, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -168,6 +168,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
   w.lm_part = cv.take((size_t)lm_head_waves(c.vocab) * T * 4 * 4);
+  w.lm_stats = cv.take(T * 2 * 4);
   w.conf = cv.take(T * 4);
   w.argmax = cv.take(T * 4);
   w.total = cv.at;
@@ -507,7 +508,42 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
     launch_lm_head(c->bf16, la, st);
   }
-  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, st);
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
+                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_step_credit(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                       const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                       const dinfer_decode* decode, const dinfer_credit* credit, int32_t* d_credit_ids,
+                       float* d_credit_val, int32_t* d_credit_n, float* d_conf, int32_t* d_argmax,
+                       int32_t* d_n_committed, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
+  if (!credit || !d_credit_ids || !d_credit_val || !d_credit_n) return fail(DINFER_EINVAL, "null pointer");
+  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if (!(credit->alpha >= 0.f) || !(credit->beta >= 0.f && credit->beta <= 1.f) ||
+      !(credit->gamma > 0.f && credit->gamma <= 1.f))
+    return fail(DINFER_EINVAL, "credit parameters: alpha >= 0, 0 <= beta <= 1, 0 < gamma <= 1");
+  hipStream_t st = (hipStream_t)stream;
+  rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, true, st);
+  if (rc != DINFER_OK) return rc;
+  const dinfer_config& f = c->cfg;
+  const int T = n_seq * block_len;
+  float* stats = at<float>(c->ws, c->wsm.lm_stats);
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
+            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            at<float>(c->ws, c->wsm.lm_part), nullptr};
+  {
+    StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
+    launch_lm_head(c->bf16, la, st);
+  }
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, stats, st);
+  launch_credit(c->bf16, la.w, la.xn, la.rinv, T, f.hidden, f.vocab, f.logit_scale, stats, d_mask, block_len,
+                credit->alpha, credit->beta, credit->gamma, d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, st);
   launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
                 decode->fixed_k, d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
@@ -545,7 +581,7 @@ int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
     launch_lm_head(c->bf16, la, st);
   }
-  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, conf_rows, argmax_rows, st);
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, conf_rows, argmax_rows, nullptr, st);
   launch_commit(conf_rows, argmax_rows, n_seq, block_len, run, look_back, d_block_tokens, d_mask, decode->threshold,
                 decode->fixed_k, d_n_committed, d_conf, d_argmax, st);
   HIP_TRY(hipGetLastError());

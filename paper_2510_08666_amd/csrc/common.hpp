@@ -21,6 +21,7 @@ constexpr int MAX_SEQS = 64;
 constexpr int MAX_TOPK = 8;
 constexpr int MAX_EXPERTS = 64;
 constexpr int MAX_HIDDEN = 4096;
+constexpr int CREDIT_CAP = 64;   // credited tokens a position can hold (= DINFER_CREDIT_CAP of the C header)
 constexpr int ATTN_MAX_PAGES = 2048;   // pages of one sequence the attention kernel stages in LDS (32768 positions)
 
 // Per element type: G = elements in one 16-byte lane chunk; one MFMA k-step covers KS = 2*G input features.

@@ -151,7 +151,13 @@ int lm_head_parts(int V, int T);   // partials per token row launch_lm_head writ
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);        // picks the form by a.T
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st);
 int lm_head_wide_parts(int V);
-void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st);
+// stats (may be null): [T][2] = the row's largest logit and sum exp(z - max)
+void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
+                     hipStream_t st);
+// Credit decoding of the masked rows: conf / argmax hold the plain values on entry and the enhanced ones on return.
+void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rinv, int T, int H, int V, float scale,
+                   const float* stats, const uint64_t* mask, int block_len, float alpha, float beta, float gamma,
+                   int32_t* cred_ids, float* cred_val, int32_t* cred_n, float* conf, int32_t* argmax, hipStream_t st);
 // conf / argmax: one row per forward token, position i of sequence s at row s*row_stride + row_off + i;
 // conf_out / argmax_out (may be null): the block's values, compact [n_seq][block_len].
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,

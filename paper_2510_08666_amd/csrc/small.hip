@@ -276,7 +276,8 @@ __device__ inline LmStat lm_combine(LmStat a, LmStat b) {
   return a;
 }
 __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__ part, int n_waves, int T,
-                                                        float* __restrict__ conf, int32_t* __restrict__ argmax) {
+                                                        float* __restrict__ conf, int32_t* __restrict__ argmax,
+                                                        float* __restrict__ stats) {
   __shared__ LmStat sh[4];
   const int t = blockIdx.x;
   LmStat a{-INFINITY, 0.f, 0x7fffffff};
@@ -295,10 +296,130 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__
     a = lm_combine(lm_combine(sh[0], sh[1]), lm_combine(sh[2], sh[3]));
     conf[t] = 1.f / a.s;
     argmax[t] = a.id;
+    if (stats) {            // the row's largest logit and sum exp(z - max): what a later correction of the softmax needs
+      stats[2 * t] = a.m;
+      stats[2 * t + 1] = a.s;
+    }
   }
 }
-void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, hipStream_t st) {
-  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax);
+void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
+                     hipStream_t st) {
+  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax, stats);
+}
+
+// ---------------------------------------------------------------- decoder: credit decoding
+// Credits are sparse: a (position, token) pair can only ever hold credit if the token was the position's top-1
+// candidate at some step, so a position keeps a short list of (token id, credit).  Fusing alpha*log(1 + credit) into
+// the logits then changes only the listed logits of the row, and the enhanced softmax follows from the row's plain
+// (max, sum exp) by exchanging those few terms -- for which the listed logits are recomputed here as dot products
+// of the row's normalised-input planes with the listed rows of the packed LM head.  One workgroup per position.
+template <typename E>
+__global__ __launch_bounds__(256) void credit_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                      const float* __restrict__ rinv, int T, int H, int V, float scale,
+                                                      const float* __restrict__ stats, const uint64_t* __restrict__ mask,
+                                                      int block_len, float alpha, float beta, float gamma,
+                                                      int32_t* __restrict__ cred_ids, float* __restrict__ cred_val,
+                                                      int32_t* __restrict__ cred_n, float* __restrict__ conf,
+                                                      int32_t* __restrict__ argmax) {
+  typedef typename ET<E>::vec vec;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  __shared__ int32_t s_ids[CREDIT_CAP];
+  __shared__ float s_val[CREDIT_CAP], s_z[CREDIT_CAP];
+  __shared__ int32_t s_n;
+  const int row = blockIdx.x, seq = row / block_len, pos = row % block_len;
+  if (!((mask[seq] >> pos) & 1ull)) return;            // decided positions keep their plain values
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const float M = stats[2 * row], S = stats[2 * row + 1];
+  const int v_top = argmax[row];
+  const float p_top = conf[row];
+  if (wave == 0) {
+    // equation 1: discount every credit, reward the current top-1 candidate with p^gamma
+    int n = cred_n[row];
+    n = min(max(n, 0), CREDIT_CAP);
+    int id = lane < n ? cred_ids[(int64_t)row * CREDIT_CAP + lane] : -1;
+    float val = lane < n ? cred_val[(int64_t)row * CREDIT_CAP + lane] * beta : INFINITY;
+    const float reward = powf(p_top, gamma);
+    const uint64_t hit = __ballot(lane < n && id == v_top);
+    int slot;
+    if (hit) {
+      slot = __ffsll((unsigned long long)hit) - 1;
+      if (lane == slot) val += reward;
+    } else {
+      if (n < CREDIT_CAP) {
+        slot = n++;
+      } else {                                          // list full: the smallest credit makes room
+        const float smallest = -wave_max(-val);
+        slot = __ffsll((unsigned long long)__ballot(val == smallest)) - 1;
+      }
+      if (lane == slot) {
+        id = v_top;
+        val = reward;
+      }
+    }
+    if (lane < n) {
+      cred_ids[(int64_t)row * CREDIT_CAP + lane] = id;
+      cred_val[(int64_t)row * CREDIT_CAP + lane] = val;
+      s_ids[lane] = id;
+      s_val[lane] = val;
+    }
+    if (lane == 0) {
+      cred_n[row] = n;
+      s_n = n;
+    }
+  }
+  __syncthreads();
+  const int n = s_n;
+  const int ksteps = H / KS;
+  const float zs = rinv[row] * scale;
+  for (int k = wave; k < n; k += 4) {
+    const int v = s_ids[k];
+    float z;
+    if (v == v_top) {
+      z = M;                                           // exactly the value the plain sum was built around
+    } else {
+      const int task = v / (2 * TILE), which = (v / TILE) & 1, r = v % TILE;
+      float acc = 0.f;
+      for (int j = lane; j < H / G; j += WAVE) {       // one 16-byte chunk of the row per lane and round
+        const int k0 = j * G, ks = k0 / KS, h = (k0 % KS) / G;
+        const vec wv = load16<E>(W + ((((int64_t)task * ksteps + ks) * 2 + which) * WAVE + h * TILE + r) * G);
+        const E* xp = xn + act_index<E>(T, row, k0);
+        const vec hi = load16<E>(xp);
+#pragma unroll
+        for (int e = 0; e < G; ++e) {
+          float x = to_f32(hi[e]);
+          if (NP == 2) x += to_f32(xp[KS + e]);
+          acc += to_f32(wv[e]) * x;
+        }
+      }
+      z = wave_sum(acc) * zs;
+    }
+    if (lane == 0) s_z[k] = z;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    // equation 2 on the listed logits; every other term of the softmax is unchanged
+    float Mt = M;
+    for (int k = 0; k < n; ++k) Mt = fmaxf(Mt, s_z[k] + alpha * log1pf(s_val[k]));
+    float St = S * __expf(M - Mt);
+    int best = 0x7fffffff;
+    for (int k = 0; k < n; ++k) {
+      const float zt = s_z[k] + alpha * log1pf(s_val[k]);
+      St += __expf(zt - Mt) - __expf(s_z[k] - Mt);
+      if (zt == Mt && s_ids[k] < best) best = s_ids[k];
+    }
+    conf[row] = 1.f / St;
+    argmax[row] = best;
+  }
+}
+void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rinv, int T, int H, int V, float scale,
+                   const float* stats, const uint64_t* mask, int block_len, float alpha, float beta, float gamma,
+                   int32_t* cred_ids, float* cred_val, int32_t* cred_n, float* conf, int32_t* argmax, hipStream_t st) {
+  if (bf16)
+    credit_kernel<bf16_t><<<T, 256, 0, st>>>((const bf16_t*)w_lm, (const bf16_t*)xn, rinv, T, H, V, scale, stats, mask,
+                                             block_len, alpha, beta, gamma, cred_ids, cred_val, cred_n, conf, argmax);
+  else
+    credit_kernel<float><<<T, 256, 0, st>>>((const float*)w_lm, (const float*)xn, rinv, T, H, V, scale, stats, mask,
+                                            block_len, alpha, beta, gamma, cred_ids, cred_val, cred_n, conf, argmax);
 }
 
 // ---------------------------------------------------------------- decoder: threshold commit

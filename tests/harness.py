@@ -133,6 +133,20 @@ class GpuRun:
         self.torch.cuda.synchronize()
         return self.state()
 
+    def credit_state(self):
+        """Fresh (empty) credit lists for every position of the block."""
+        torch, cap = self.torch, self.binding.CREDIT_CAP
+        ns, S = self.tokens.shape
+        return dict(ids=torch.zeros((ns, S, cap), dtype=torch.int32, device=self.dev),
+                    val=torch.zeros((ns, S, cap), dtype=torch.float32, device=self.dev),
+                    n=torch.zeros((ns, S), dtype=torch.int32, device=self.dev))
+
+    def step_credit(self, credit, threshold, alpha, beta, gamma, fixed_k=0):
+        self.ctx.step_credit(self.tokens, self.mask, self.prefix_len, self.page_table, threshold, fixed_k, alpha, beta,
+                             gamma, credit["ids"], credit["val"], credit["n"], self.conf, self.argmax, self.n_committed)
+        self.torch.cuda.synchronize()
+        return self.state()
+
     def step_vicinity(self, vicinity_tokens, threshold, fixed_k=0):
         """vicinity_tokens: [n_seq][look_back] ids of the cached positions right before each block."""
         vic = self.torch.from_numpy(np.ascontiguousarray(vicinity_tokens, dtype=np.int32)).to(self.dev)

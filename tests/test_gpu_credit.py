@@ -1,0 +1,120 @@
+"""GPU parity of the step with credit decoding over several steps of a block, through the C-ABI, against the
+oracle's dense credits.  The oracle is teacher-forced: after every step it continues from the GPU's tokens, mask
+and credit lists, so that one flagged near-tie does not make every later step incomparable."""
+import numpy as np
+import pytest
+
+import dinfer_inputs as di
+import oracle
+from harness import GpuRun, OracleRun, bars_for, compare_step, make_case
+
+pytestmark = pytest.mark.gpu
+
+ALPHA, BETA, GAMMA = 0.65, 0.7, 0.5
+
+
+def _variant(name):
+    tiny = di.model_preset("tiny")
+    W = di.Workload
+    sc = di.configs.scaled
+    return {
+        "c1": W("c1", tiny, 1, 32, 64, 64, threshold=0.9, seed_index=1),
+        # bf16 storage with the tiny configuration's logit scale, so that confidences (and the boosts) are sizeable
+        "c1_bf16": W("c1_bf16", sc(tiny, dtype="bf16"), 1, 32, 64, 64, threshold=0.9, seed_index=1),
+        "batch": W("batch", tiny, 3, 64, 17, 140, precommit=True, threshold=0.9, seed_index=7),
+    }[name]
+
+
+@pytest.fixture(scope="module", params=["c1", "c1_bf16", "batch"])
+def case(request):
+    wl = _variant(request.param)
+    cfg, w, inp = make_case(wl)
+    ns, S = inp.block_tokens.shape
+    cap = int(inp.prefix_len.max()) + 2 * S + 16
+    ora = OracleRun(cfg, w, inp, cap)
+    gpu = GpuRun(cfg, w, inp, ns * S, cap)
+    yield wl, cfg, inp, ora, gpu, bars_for(cfg)
+    gpu.close()
+
+
+def dense(credit, s, V):
+    """The GPU's credit lists of sequence s as the oracle's dense [S][V] array."""
+    ids, val, n = (credit[k][s].cpu().numpy() for k in ("ids", "val", "n"))
+    out = np.zeros((ids.shape[0], V))
+    for i in range(ids.shape[0]):
+        assert 0 <= n[i] <= ids.shape[1]
+        assert len(set(ids[i, :n[i]].tolist())) == n[i], "a token is listed twice"
+        out[i, ids[i, :n[i]]] = val[i, :n[i]]
+    return out
+
+
+def test_credit_steps_match_oracle(case):
+    wl, cfg, inp, ora, g, bars = case
+    ns, S = inp.block_tokens.shape
+    V = cfg.vocab
+    g.inject_prefix(ora.caches)
+    credit = g.credit_state()
+    tokens, masks = inp.block_tokens.copy(), inp.mask_bits.copy()
+    ora_credit = [np.zeros((S, V)) for _ in range(ns)]
+    # three commits per step (fixed-k mode), so that the block lives for several steps and credits accumulate
+    fixed_k, tau = 3, 0.5
+    enhanced_differs = False
+    for step in range(5):
+        g.set_state(tokens, masks, inp.prefix_len)
+        got = g.step_credit(credit, tau, ALPHA, BETA, GAMMA, fixed_k)
+        routing = g.routing().reshape(cfg.n_layers, ns, S, cfg.top_k)
+        for s in range(ns):
+            kc, vc = ora.caches[s]
+            keep = kc.copy(), vc.copy()
+            P = int(inp.prefix_len[s])
+            tr = oracle.Trace(cfg, S, forced_idx=routing[:, s])
+            ref = ora.o.step_credit(tokens[s], int(masks[s]), P, kc, vc, tau, ora_credit[s], ALPHA, BETA, GAMMA, fixed_k,
+                                    want_logits=True, trace=tr)
+            rep = compare_step(ref, got["tokens"][s], got["mask"][s], got["conf"][s], got["argmax"][s],
+                               got["n_committed"][s], tokens[s], masks[s], tau, fixed_k, bars, ref["logits"])
+            # the credit lists against the dense credits
+            mine = dense(credit, s, V)
+            tol = 1e-4 if cfg.dtype == "f32" else 5e-2
+            masked = [i for i in range(S) if (int(masks[s]) >> i) & 1]
+            for i in masked:
+                if set(np.nonzero(mine[i])[0]) != set(np.nonzero(ora_credit[s][i])[0]):
+                    # the two sides rewarded different top-1 candidates: only a near-tie of the plain logits allows it
+                    assert i in rep["flagged"] or got["argmax"][s][i] == ref["argmax"][i], (step, s, i)
+                    continue
+                nz = np.nonzero(mine[i])[0]
+                assert np.allclose(mine[i, nz], ora_credit[s][i, nz], rtol=tol), (step, s, i)
+            assert not mine[[i for i in range(S) if i not in masked]].any() or step > 0
+            # the fusion is really at work: from the second step on the enhanced confidences sit well above the plain ones
+            kc[...], vc[...] = keep
+            plain = ora.o.step(tokens[s], int(masks[s]), P, kc, vc, 2.0)["conf"]
+            kc[...], vc[...] = keep
+            if step > 0 and masked and np.all(ref["conf"][masked] > plain[masked] * 1.05):
+                enhanced_differs = True
+            ora_credit[s] = mine                              # teacher forcing
+        tokens, masks = got["tokens"].copy(), got["mask"].copy()
+    assert enhanced_differs, "the credits never changed a confidence: the test does not exercise the fusion"
+
+
+def test_alpha_zero_equals_the_plain_step(case):
+    wl, cfg, inp, ora, g, bars = case
+    g.inject_prefix(ora.caches)
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    a = g.step(0.05)
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    credit = g.credit_state()
+    b = g.step_credit(credit, 0.05, 0.0, BETA, GAMMA)
+    for key in ("tokens", "mask", "argmax", "n_committed"):
+        assert np.array_equal(a[key], b[key]), key
+    assert np.allclose(a["conf"], b["conf"], rtol=1e-6)
+    n = credit["n"].cpu().numpy()
+    masked = np.array([[(int(inp.mask_bits[s]) >> i) & 1 for i in range(n.shape[1])] for s in range(n.shape[0])])
+    assert np.array_equal(n, masked)                          # one entry per position that was masked
+
+
+def test_bad_parameters(case):
+    wl, cfg, inp, ora, g, bars = case
+    from paper_2510_08666_amd.binding import DinferError
+    credit = g.credit_state()
+    for a, b, c in ((-1.0, 0.5, 0.5), (0.5, 1.5, 0.5), (0.5, 0.5, 0.0)):
+        with pytest.raises(DinferError):
+            g.step_credit(credit, 0.5, a, b, c)

@@ -226,6 +226,53 @@ def test_c2_vicinity_refresh_step(model):
     c.gpu.close()
 
 
+def test_c2_credit_decoding_steps(model):
+    """Configuration 2 with credit decoding over three steps of a block (fixed 4 commits per step), teacher-forced
+    like the tiny credit test.  With random-init weights the confidences are ~3e-4, so a boost is about one per
+    cent: the case checks the credit lists, the recomputed listed logits and the exchanged softmax terms at the
+    full vocabulary; the tiny cases check large boosts."""
+    cfg, w, o = model
+    wl = di.workload_preset(2)
+    c = BigCase((cfg, w, o), wl)
+    inp, g = c.inp, c.gpu
+    S, P, V = c.S, int(inp.prefix_len[0]), cfg.vocab
+    alpha, beta, gamma, fixed_k = 0.65, 0.7, 0.5, 4
+    credit = g.credit_state()
+    ora_credit = np.zeros((S, V))
+    tokens, masks = inp.block_tokens.copy(), inp.mask_bits.copy()
+    kc, vc = c.caches[0]
+    boosted = False
+    for step in range(3):
+        g.set_state(tokens, masks, inp.prefix_len)
+        got = g.step_credit(credit, 0.5, alpha, beta, gamma, fixed_k)
+        routing = g.routing().reshape(cfg.n_layers, S, cfg.top_k)
+        tr = oracle.Trace(cfg, S, forced_idx=routing)
+        ref = o.step_credit(tokens[0], int(masks[0]), P, kc, vc, 0.5, ora_credit, alpha, beta, gamma, fixed_k,
+                            want_logits=True, trace=tr)
+        near = check_routing(tr, routing, cfg.top_k, c.bars)
+        rep = compare_step(ref, got["tokens"][0], got["mask"][0], got["conf"][0], got["argmax"][0],
+                           got["n_committed"][0], tokens[0], masks[0], 0.5, fixed_k, c.bars, ref["logits"])
+        ids, val, n = (credit[k][0].cpu().numpy() for k in ("ids", "val", "n"))
+        mine = np.zeros((S, V))
+        for i in range(S):
+            mine[i, ids[i, :n[i]]] = val[i, :n[i]]
+        for i in range(S):
+            if (int(masks[0]) >> i) & 1 and set(np.nonzero(mine[i])[0]) == set(np.nonzero(ora_credit[i])[0]):
+                nz = np.nonzero(mine[i])[0]
+                assert np.allclose(mine[i, nz], ora_credit[i, nz], rtol=5e-2), (step, i)
+        plain = o.step(tokens[0], int(masks[0]), P, kc, vc, 2.0)["conf"]
+        masked = [i for i in range(S) if (int(masks[0]) >> i) & 1]
+        if step > 0 and np.median(ref["conf"][masked] / plain[masked]) > 1.005:
+            boosted = True
+        log("C2 credit step %d: conf rel err %.1e, flagged %s, near-ties %d, median enhanced/plain conf %.3f, "
+            "max list length %d" % (step, rep["conf_rel_err"], rep["flagged"], near,
+                                    float(np.median(ref["conf"][masked] / plain[masked])), int(n.max())))
+        ora_credit = mine
+        tokens, masks = got["tokens"].copy(), got["mask"].copy()
+    assert boosted
+    c.gpu.close()
+
+
 def test_prefill_at_full_shapes(model):
     """A real prefill (bidirectional forward over the prompt) of 100 tokens at the full model shapes."""
     cfg, w, o = model
