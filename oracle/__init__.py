@@ -71,6 +71,14 @@ def lib():
         L.oracle_step.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
                                   c_i32, c_vp, c_vp, c_vp, P(CTrace)]
         L.oracle_step.restype = c_i32
+        L.oracle_expected_embedding.argtypes = [P(CConfig), P(CWeights), c_vp, c_vp]
+        L.oracle_expected_embedding.restype = None
+        L.oracle_forward_embedded.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_vp,
+                                              P(CTrace)]
+        L.oracle_forward_embedded.restype = c_i32
+        L.oracle_step_smooth.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
+                                         c_i32, c_f64, c_vp, c_vp, c_vp, c_vp, P(CTrace)]
+        L.oracle_step_smooth.restype = c_i32
         L.oracle_credit_position.argtypes = [c_vp, c_i32, c_vp, c_f64, c_f64, c_f64, c_vp, c_vp, c_vp]
         L.oracle_credit_position.restype = None
         L.oracle_step_credit.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
@@ -187,6 +195,45 @@ class Oracle:
                               trace.c if trace else None)
         if n < 0:
             raise ValueError("oracle_step failed")
+        r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
+        if want_logits:
+            r["logits"] = logits
+        return r
+
+    def expected_embedding(self, logits):
+        """softmax(logits) . W_emb for one position: float64 [H]."""
+        logits = f64(logits)
+        out = np.zeros(self.cfg.hidden)
+        lib().oracle_expected_embedding(self.ccfg, self.cw, _p(logits), _p(out))
+        return out
+
+    def forward_embedded(self, tokens, emb_add, prefix_len, kc, vc, trace=None):
+        """forward() with emb_add [n_tok][H] added to the token embeddings."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        add = f64(emb_add)
+        hidden = np.zeros((tok.shape[0], self.cfg.hidden))
+        rc = lib().oracle_forward_embedded(self.ccfg, self.cw, tok.shape[0], _p(tok), _p(add), int(prefix_len), _p(kc),
+                                           _p(vc), kc.shape[1], _p(hidden), trace.c if trace else None)
+        if rc != 0:
+            raise ValueError("oracle_forward_embedded failed (%d)" % rc)
+        return hidden
+
+    def step_smooth(self, block_tokens, mask, prefix_len, kc, vc, threshold, alpha, delta, fixed_k=0, want_logits=False,
+                    trace=None):
+        """One denoising step with iteration smoothing.  delta: float64 [S][H], in (previous step's expected
+        embeddings) and out (this step's, rows of the positions masked at the start)."""
+        tok = np.array(block_tokens, dtype=np.int32)
+        S = tok.shape[0]
+        assert delta.dtype == np.float64 and delta.shape == (S, self.cfg.hidden) and delta.flags.c_contiguous
+        m = np.array([mask], dtype=np.uint64)
+        conf = np.zeros(S, dtype=np.float64)
+        am = np.zeros(S, dtype=np.int32)
+        logits = np.zeros((S, self.cfg.vocab), dtype=np.float64) if want_logits else None
+        n = lib().oracle_step_smooth(self.ccfg, self.cw, S, _p(tok), _p(m), int(prefix_len), _p(kc), _p(vc),
+                                     kc.shape[1], float(threshold), int(fixed_k), float(alpha), _p(delta), _p(conf),
+                                     _p(am), _p(logits), trace.c if trace else None)
+        if n < 0:
+            raise ValueError("oracle_step_smooth failed")
         r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
         if want_logits:
             r["logits"] = logits

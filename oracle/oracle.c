@@ -187,6 +187,12 @@ void oracle_permutation(const int32_t* expert_of_pair, int n_pairs, int n_expert
 int oracle_forward(const oracle_config* c, const oracle_weights* w, int n_tok, const int32_t* tokens,
                    int prefix_len, double* kcache, double* vcache, int cache_cap, double* hidden_out,
                    const oracle_trace* trace) {
+  return oracle_forward_embedded(c, w, n_tok, tokens, NULL, prefix_len, kcache, vcache, cache_cap, hidden_out, trace);
+}
+
+int oracle_forward_embedded(const oracle_config* c, const oracle_weights* w, int n_tok, const int32_t* tokens,
+                            const double* emb_add, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                            double* hidden_out, const oracle_trace* trace) {
   const int H = c->hidden, D = c->n_heads * c->head_dim, hd = c->head_dim, K = c->top_k;
   if (prefix_len < 0 || n_tok <= 0 || prefix_len + n_tok > cache_cap) return -1;
   for (int t = 0; t < n_tok; ++t)
@@ -202,6 +208,9 @@ int oracle_forward(const oracle_config* c, const oracle_weights* w, int n_tok, c
   /* the sequence is first embedded (masked positions carry the mask id and embed its row) */
   for (int t = 0; t < n_tok; ++t)
     for (int i = 0; i < H; ++i) x[(size_t)t * H + i] = wval(c->wdtype, w->emb, (size_t)tokens[t] * H + i);
+  /* iteration smoothing: what the previous iteration retained for a position is added to its embedding */
+  if (emb_add)
+    for (size_t i = 0; i < (size_t)n_tok * H; ++i) x[i] += emb_add[i];
 
   for (int l = 0; l < c->n_layers; ++l) {
     const oracle_layer* L = &w->layers[l];
@@ -354,6 +363,48 @@ int32_t oracle_step(const oracle_config* c, const oracle_weights* w, int block_l
     n = oracle_commit(conf, argmax, block_len, mask, block_tokens, threshold, fixed_k);
   }
   if (!logits_out) free(logits);
+  free(hidden);
+  return n;
+}
+
+/* Expected embedding of one position (Appendix "IterSmooth"): p = softmax(logits), delta = p . W_emb. */
+void oracle_expected_embedding(const oracle_config* c, const oracle_weights* w, const double* logits, double* delta) {
+  const int V = c->vocab, H = c->hidden;
+  double m = logits[0];
+  for (int v = 1; v < V; ++v)
+    if (logits[v] > m) m = logits[v];
+  double z = 0.0;
+  for (int v = 0; v < V; ++v) z += exp(logits[v] - m);
+  for (int i = 0; i < H; ++i) delta[i] = 0.0;
+  for (int v = 0; v < V; ++v) {
+    const double p = exp(logits[v] - m) / z;
+    for (int i = 0; i < H; ++i) delta[i] += p * wval(c->wdtype, w->emb, (size_t)v * H + i);
+  }
+}
+
+int32_t oracle_step_smooth(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                           uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                           double threshold, int fixed_k, double alpha, double* delta, double* conf, int32_t* argmax,
+                           double* logits_out, const oracle_trace* trace) {
+  const int V = c->vocab, H = c->hidden;
+  double* hidden = (double*)malloc(sizeof(double) * (size_t)block_len * H);
+  double* add = (double*)calloc((size_t)block_len * H, sizeof(double));
+  double* logits = logits_out ? logits_out : (double*)malloc(sizeof(double) * (size_t)block_len * V);
+  /* e_t[i] = e_mask + alpha_t * delta_{t-1}[i] on the positions that are still masked, plain embeddings elsewhere */
+  for (int i = 0; i < block_len; ++i)
+    if ((*mask >> i) & 1)
+      for (int j = 0; j < H; ++j) add[(size_t)i * H + j] = alpha * delta[(size_t)i * H + j];
+  int32_t n = -1;
+  if (oracle_forward_embedded(c, w, block_len, block_tokens, add, prefix_len, kcache, vcache, cache_cap, hidden, trace) == 0) {
+    oracle_logits(c, w, hidden, block_len, logits);
+    for (int i = 0; i < block_len; ++i) oracle_confidence(logits + (size_t)i * V, V, &conf[i], &argmax[i]);
+    /* what this iteration retains for the next one: the expected embedding of every position that was masked */
+    for (int i = 0; i < block_len; ++i)
+      if ((*mask >> i) & 1) oracle_expected_embedding(c, w, logits + (size_t)i * V, delta + (size_t)i * H);
+    n = oracle_commit(conf, argmax, block_len, mask, block_tokens, threshold, fixed_k);
+  }
+  if (!logits_out) free(logits);
+  free(add);
   free(hidden);
   return n;
 }

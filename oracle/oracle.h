@@ -104,6 +104,11 @@ int oracle_forward(const oracle_config* c, const oracle_weights* w, int n_tok, c
                    int prefix_len, double* kcache, double* vcache, int cache_cap, double* hidden_out,
                    const oracle_trace* trace);
 
+/* The same forward with emb_add [n_tok][H] (may be NULL) added to the token embeddings before the first layer. */
+int oracle_forward_embedded(const oracle_config* c, const oracle_weights* w, int n_tok, const int32_t* tokens,
+                            const double* emb_add, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                            double* hidden_out, const oracle_trace* trace);
+
 /* logits[t][v] = logit_scale * RMSNorm(hidden[t]; final_gain) . lm_head[v] */
 void oracle_logits(const oracle_config* c, const oracle_weights* w, const double* hidden, int n_tok,
                    double* logits);
@@ -127,6 +132,21 @@ int32_t oracle_step_vicinity(const oracle_config* c, const oracle_weights* w, in
                              int32_t* block_tokens, const int32_t* vicinity_tokens, uint64_t* mask, int prefix_len,
                              double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k,
                              double* conf, int32_t* argmax, double* logits_out, const oracle_trace* trace);
+
+/* Iteration smoothing (Appendix "IterSmooth").  delta [H] = softmax(logits) . W_emb: the expected input embedding
+ * under the position's predicted distribution (the input embedding matrix is used: it is not tied to the LM head). */
+void oracle_expected_embedding(const oracle_config* c, const oracle_weights* w, const double* logits, double* delta);
+
+/* One denoising step with iteration smoothing.  delta: [block_len][H], kept by the caller across the steps of a
+ * block (zero at its start).  On entry it holds the expected embeddings the previous step retained; a position that
+ * is still masked is embedded as e_mask + alpha * delta[i] (alpha = this step's mixing weight
+ * min(alpha_init + alpha_growth * t, alpha_preset), computed by the caller), every other position as its token's
+ * embedding.  On return the rows of the positions that were masked at the start of the step hold the expected
+ * embeddings of this step's logits.  Everything else as oracle_step. */
+int32_t oracle_step_smooth(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                           uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                           double threshold, int fixed_k, double alpha, double* delta, double* conf, int32_t* argmax,
+                           double* logits_out, const oracle_trace* trace);
 
 /* One denoising step with credit decoding: as oracle_step, but the decoder sees the enhanced distribution.
  * credit: [block_len][V], kept by the caller across the steps of one block (zero at its start); only the rows of
