@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--credit", action="store_true",
                     help="time the step with credit decoding (alpha 0.65, beta 0.7, gamma 0.5); the credit lists "
                          "carry over between the timed steps, as inside a block")
+    ap.add_argument("--smooth", action="store_true",
+                    help="time the step with iteration smoothing (alpha 0.2); the expected embeddings carry over "
+                         "between the timed steps, as inside a block (single-block workloads with at most 64 tokens)")
     ap.add_argument("--vicinity", type=int, default=0,
                     help="time the step with vicinity KV-cache refresh over this many cached positions before the "
                          "block (the paper's experiments use 16); 0 = the plain step")
@@ -217,10 +220,17 @@ def main():
                   torch.zeros((ns, S, cap), dtype=torch.float32, device=dev),
                   torch.zeros((ns, S), dtype=torch.int32, device=dev))
 
+    smooth = None
+    if args.smooth:
+        smooth = (torch.zeros((ns, S, cfg.hidden), dtype=torch.float32, device=dev), ctx.smooth_scratch(ns * S))
+
     def one_step():
         tokens.copy_(tokens0)
         mask.copy_(mask0)
-        if credit is not None:
+        if smooth is not None:
+            ctx.step_smooth(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, 0.2, smooth[0], smooth[1],
+                            conf, argmax, n_committed)
+        elif credit is not None:
             ctx.step_credit(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, 0.65, 0.7, 0.5, credit[0],
                             credit[1], credit[2], conf, argmax, n_committed)
         elif lb:
@@ -318,7 +328,8 @@ def main():
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else ""),
+        "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else "")
+                   + ("-smooth" if args.smooth else ""),
                    "n_seq": ns, "block_len": S,
                    "vicinity_look_back": lb, "prefix_len": [int(p) for p in inp.prefix_len][:4],
                    "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),

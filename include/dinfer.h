@@ -125,6 +125,24 @@ int dinfer_step(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_bl
                 const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
                 void* stream);
 
+/* The step with iteration smoothing (Appendix "IterSmooth").  Positions that are still masked are not embedded as
+ * the bare mask token: e_t[i] = e_mask + alpha * delta[i], where delta[i] = softmax(z_{t-1}[i]) . W_emb is the
+ * expected INPUT embedding under the distribution the previous step predicted for the position (the embedding
+ * matrix is not tied to the LM head).  alpha is this step's mixing weight min(alpha_init + alpha_growth * t,
+ * alpha_preset), computed by the caller (0 on the first step of a block, or to ignore what was retained).
+ *   d_delta   [n_seq][block_len][hidden] float32, in/out, kept by the caller across the steps of a block: on return
+ *             the rows of the positions that were masked when the step began hold this step's expected embeddings;
+ *             other rows are left alone.
+ *   d_scratch device buffer of at least dinfer_smooth_scratch_bytes(cfg, n_seq * block_len) bytes, 256-byte
+ *             aligned, contents irrelevant: this variant stores the block's logits there (the second contraction
+ *             over the vocabulary needs normalised probabilities).
+ * n_seq * block_len <= 64.  Everything else as in dinfer_step. */
+size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens);
+int dinfer_step_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                       const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                       const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch,
+                       size_t scratch_bytes, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream);
+
 /* The step with credit decoding (Appendix "Credit decoding").  Every undecided position keeps a credit per token,
  * C_t[v] = beta * C_{t-1}[v] + (v == top-1 candidate of step t ? p_t(v)^gamma : 0)          (equation 1)
  * and the decoder sees softmax(logits + alpha * log(1 + C_t)) instead of softmax(logits)     (equation 2):

@@ -37,7 +37,7 @@ struct LayerW {
   size_t attn_gain, wqkv, wo, ffn_gain, router, gate_up, down;   // byte offsets into d_weights
 };
 struct WeightMap {
-  size_t emb, lm_head, final_gain;
+  size_t emb, emb_t, lm_head, final_gain;   // emb_t: the embedding matrix transposed and packed (iteration smoothing)
   std::vector<LayerW> layers;
   size_t total;
 };
@@ -77,6 +77,7 @@ WeightMap map_weights(const dinfer_config& c) {
   WeightMap m;
   Carve cv;
   m.emb = cv.take((size_t)V * H * es);
+  m.emb_t = cv.take((size_t)packed_bytes(bf, H / 64, smooth_kpad(bf, V)));
   m.lm_head = cv.take((size_t)packed_bytes(bf, (V + 63) / 64, H));
   m.final_gain = cv.take((size_t)H * 4);
   m.layers.resize(c.n_layers);
@@ -140,8 +141,10 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
       const size_t tile = (size_t)2 * tt * 16 * WAVE * 4;
       const size_t qkv = (size_t)(3 * D / 64) * gemm_slices(bf, H, tt * TILE) * tile;
       const size_t opr = (size_t)(H / 64) * gemm_slices(bf, D, tt * TILE) * tile;
+      const size_t smooth = (size_t)(H / 64) * SMOOTH_SLICES * tile;   // expected-embedding contraction
       most = qkv > most ? qkv : most;
       most = opr > most ? opr : most;
+      most = smooth > most ? smooth : most;
     }
     w.tk_part = cv.take(most);
     const int units = 3 * D / 64 > H / 64 ? 3 * D / 64 : H / 64;
@@ -223,7 +226,8 @@ struct StageTimer {
 
 // One forward over the packed tokens of `span`.  with_head: final norm into h (ready for the LM head).
 int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const int32_t* d_base,
-            const int32_t* d_page_table, int pt_stride, bool with_head, hipStream_t st) {
+            const int32_t* d_page_table, int pt_stride, bool with_head, hipStream_t st,
+            const SmoothIn* smooth = nullptr) {
   const dinfer_config& f = c->cfg;
   const bool bf = c->bf16;
   const int T = span.off[span.n_seq];
@@ -251,7 +255,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     int32_t* tickets = at<int32_t>(ws, w.tickets);
     if (l == 0)
       launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a,
-                   at<float>(c->weights, lw.attn_gain), xn, st);
+                   at<float>(c->weights, lw.attn_gain), xn, smooth, st);
     else
       launch_combine(bf, x, at<float>(ws, w.o), topk_w - (size_t)T * f.top_k, f.top_k,
                      f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, st);
@@ -451,7 +455,10 @@ int dinfer_set_tensor(dinfer_ctx* c, int32_t tensor_id, int32_t layer, const voi
   char* W = c->weights;
   const size_t qk_bytes = (size_t)packed_bytes(bf, D / 64, H);
   switch (tensor_id) {
-    case DINFER_T_EMB: HIP_TRY(hipMemcpyAsync(W + c->wm.emb, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
+    case DINFER_T_EMB:
+      HIP_TRY(hipMemcpyAsync(W + c->wm.emb, d_src, bytes, hipMemcpyDeviceToDevice, st));
+      launch_pack_transposed(bf, d_src, W + c->wm.emb_t, V, H, smooth_kpad(bf, V), st);
+      break;
     case DINFER_T_LM_HEAD: launch_pack(bf, d_src, W + c->wm.lm_head, 1, V, H, (V + 63) / 64, PACK_ADJACENT, 0, st); break;
     case DINFER_T_FINAL_GAIN: HIP_TRY(hipMemcpyAsync(W + c->wm.final_gain, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
     case DINFER_T_ATTN_GAIN: HIP_TRY(hipMemcpyAsync(W + lw->attn_gain, d_src, bytes, hipMemcpyDeviceToDevice, st)); break;
@@ -509,6 +516,56 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
+                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens) {
+  if (check_config(cfg) != DINFER_OK || max_tokens < 1 || max_tokens > 2 * TILE) return 0;
+  const bool bf = cfg->dtype == DINFER_BF16;
+  const size_t planes = bf ? 2 : 1, es = bf ? 2 : 4;
+  return align_up((size_t)max_tokens * cfg->vocab * 4) + align_up(planes * max_tokens * smooth_kpad(bf, cfg->vocab) * es);
+}
+
+int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                       const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                       const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch, size_t scratch_bytes,
+                       float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed || !d_delta || !d_scratch)
+    return fail(DINFER_EINVAL, "null pointer");
+  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if (!(alpha >= 0.f)) return fail(DINFER_EINVAL, "alpha must be >= 0");
+  const dinfer_config& f = c->cfg;
+  const int T = n_seq * block_len;
+  if (T > 2 * TILE) return fail(DINFER_EUNSUPPORTED, "iteration smoothing handles at most %d block tokens per call", 2 * TILE);
+  if ((uintptr_t)d_scratch & 255) return fail(DINFER_EINVAL, "scratch must be 256-byte aligned");
+  const size_t need = dinfer_smooth_scratch_bytes(&f, T);
+  if (scratch_bytes < need) return fail(DINFER_ENOSPACE, "smoothing scratch %zu < %zu bytes", scratch_bytes, need);
+  hipStream_t st = (hipStream_t)stream;
+  float* logits = (float*)d_scratch;
+  void* probs = (char*)d_scratch + align_up((size_t)T * f.vocab * 4);
+  SmoothIn sin{d_delta, alpha, d_mask, block_len};
+  rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, true, st,
+               alpha > 0.f ? &sin : nullptr);
+  if (rc != DINFER_OK) return rc;
+  float* stats = at<float>(c->ws, c->wsm.lm_stats);
+  // this variant keeps the logits of the block (T x vocab float32): the second contraction over the vocabulary
+  // needs the normalised probabilities, which exist only once the row's maximum and sum are known
+  LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
+            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            at<float>(c->ws, c->wsm.lm_part), logits};
+  {
+    StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
+    launch_lm_head(c->bf16, la, st);
+  }
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, stats, st);
+  SmoothArgs sa{c->weights + c->wm.emb_t, logits, stats, probs, d_mask, block_len, d_delta, T, f.hidden, f.vocab,
+                at<float>(c->ws, c->wsm.tk_part), at<int32_t>(c->ws, c->wsm.tickets)};
+  launch_expected_embedding(c->bf16, sa, st);
   launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
                 decode->fixed_k, d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());

@@ -170,6 +170,38 @@ template <typename E> struct ResidualEpi {
   __device__ void row_sum(int task, int tok, float s) const { ssq[(int64_t)task * T + tok] = s; }
 };
 
+// Iteration smoothing: the contraction of the probabilities with the embedding matrix; a row of a position that
+// is still masked receives the expected embedding, the other rows are left alone.
+struct SmoothEpi {
+  static constexpr bool ROWSUM = false;
+  float* delta;         // [T][H]
+  int H;
+  const uint64_t* mask;
+  int block_len;
+  template <int PER> struct Pre {
+    bool on;
+  };
+  template <int PER> __device__ Pre<PER> prefetch(int, int tok, bool valid, int, int) const {
+    Pre<PER> p;
+    p.on = valid && ((mask[tok / block_len] >> (tok % block_len)) & 1ull);
+    return p;
+  }
+  template <int PER> __device__ void prefetch2(Pre<PER>&, int, int, int) const {}
+  template <int PER>
+  __device__ float apply(const Pre<PER>& pre, int task, int tok, bool, int half, int v0, const float (&a0)[PER],
+                         const float (&a1)[PER]) const {
+    if (!pre.on) return 0.f;
+    float* p0 = delta + (int64_t)tok * H + (2 * task) * TILE + acc_row(v0, half);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      p0[i] = a0[i];
+      p0[TILE + i] = a1[i];
+    }
+    return 0.f;
+  }
+  __device__ void row_sum(int, int, float) const {}
+};
+
 // Every wave leaves its partial accumulators in LDS: red[wave][t*32 + tile*16 + v][lane].
 template <int TT, int ROWS>
 __device__ inline void spill_partials(float* red, int wave, int lane, const f32x16 (&acc0)[TT], const f32x16 (&acc1)[TT]) {
@@ -322,15 +354,15 @@ int gemm_slices(bool bf16, int K, int T) {
 
 template <typename E, class Epi>
 static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int T, int K, int n_tasks,
-                          float* part, int32_t* tickets, const Epi& epi, hipStream_t st) {
-  const int slices = gemm_slices(bf16, K, T);
+                          float* part, int32_t* tickets, const Epi& epi, hipStream_t st, int forced_slices = 0) {
+  const int slices = forced_slices ? forced_slices : gemm_slices(bf16, K, T);
   if (T <= 32) {
     gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   } else if (T <= 64) {
     gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(forced_slices ? forced_slices : 1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
   }
 }
 
@@ -368,6 +400,22 @@ template <typename E> static void launch_oproj_t(bool bf16, const OprojArgs& a, 
 void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
   if (bf16) launch_oproj_t<bf16_t>(true, a, st);
   else launch_oproj_t<float>(false, a, st);
+}
+
+int smooth_kpad(bool bf16, int V) {
+  const int unit = (bf16 ? 16 : 8) * 4 * 8 * SMOOTH_SLICES;   // k-step x waves x burst x slices
+  return (V + unit - 1) / unit * unit;
+}
+template <typename E> static void launch_smooth_t(bool bf16, const SmoothArgs& a, hipStream_t st) {
+  const int Kpad = smooth_kpad(bf16, a.V);
+  SmoothEpi epi{a.delta, a.H, a.mask, a.block_len};
+  launch_ksplit<E>(bf16, (const E*)a.w_emb_t, Kpad / ET<E>::KS, (const E*)a.probs, a.T, Kpad, a.H / 64, a.part, a.tickets,
+                   epi, st, SMOOTH_SLICES);
+}
+void launch_expected_embedding(bool bf16, const SmoothArgs& a, hipStream_t st) {
+  launch_prob_planes(bf16, a.logits, a.stats, a.T, a.V, smooth_kpad(bf16, a.V), a.probs, st);
+  if (bf16) launch_smooth_t<bf16_t>(true, a, st);
+  else launch_smooth_t<float>(false, a, st);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -989,7 +1037,8 @@ void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
 
 bool configure_kernels() {
   bool ok = configure_ksplit<bf16_t, QkvEpi<bf16_t>>() && configure_ksplit<float, QkvEpi<float>>() &&
-            configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>();
+            configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>() &&
+            configure_ksplit<bf16_t, SmoothEpi>() && configure_ksplit<float, SmoothEpi>();
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
   ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&

@@ -14,6 +14,8 @@ enum PackMode { PACK_ADJACENT = 0, PACK_ROPE_PAIR = 1, PACK_HALF0 = 2, PACK_HALF
 void launch_pack(bool bf16, const void* src, void* dst, int batch, int N, int K, int n_tasks, int mode,
                  int head_dim, hipStream_t st);
 int64_t packed_bytes(bool bf16, int n_tasks, int K);
+// src [V][H] row-major -> the packed layout of its transpose ([H] output features, contraction over V padded to Kpad)
+void launch_pack_transposed(bool bf16, const void* src, void* dst, int V, int H, int Kpad, hipStream_t st);
 
 // ---- forward pieces ----
 struct FwdMeta {            // device arrays describing the tokens of one forward
@@ -30,8 +32,16 @@ void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_se
 // that follows; the row's 1/rms factor is NOT applied) as a k-major activation matrix [T][H] (act_index in
 // common.hpp).  The consumers feed it to the matrix cores and apply 1/rms in their epilogues.
 // x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
+// Iteration smoothing: a position that is still masked (bit of its sequence's mask, uniform blocks of block_len
+// tokens) is embedded as emb[token] + alpha * delta[t].  Pass null for a plain embedding.
+struct SmoothIn {
+  const float* delta;       // [T][H]
+  float alpha;
+  const uint64_t* mask;     // [n_seq]
+  int block_len;
+};
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, hipStream_t st);
+                  float* rinv, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st);
 // x[t] += sum_j topk_w[t][j] * O[t*k+j];  rinv[t] and xn[t] as above, of the updated row
 void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
                     float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st);
@@ -91,6 +101,27 @@ struct OprojArgs {
   int32_t* tickets;
 };
 void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st);
+
+// Iteration smoothing: delta[t] = softmax(logits[t]) . W_emb for the rows of positions that are still masked.
+//   probs: scratch for the probabilities as a k-major activation matrix [T][Kpad]; logits [T][V] float32;
+//   stats [T][2] = (largest logit, sum exp(z - max)) of every row; w_emb_t: launch_pack_transposed's layout.
+constexpr int SMOOTH_SLICES = 16;     // workgroups that share the vocabulary range of one 64-column task
+int smooth_kpad(bool bf16, int V);    // the vocabulary rounded up so that every wave of every slice gets whole bursts
+struct SmoothArgs {
+  const void* w_emb_t;
+  const float* logits;
+  const float* stats;
+  void* probs;
+  const uint64_t* mask;
+  int block_len;
+  float* delta;             // [T][H] in/out
+  int T, H, V;
+  float* part;
+  int32_t* tickets;
+};
+void launch_expected_embedding(bool bf16, const SmoothArgs& a, hipStream_t st);
+void launch_prob_planes(bool bf16, const float* logits, const float* stats, int T, int V, int Kpad, void* probs,
+                        hipStream_t st);
 // Router logits on the matrix cores + softmax + top-k (ties to the lower expert id, weights renormalised when
 // norm_topk); rinv[t] from the sums of squares above; for T <= 64 also the token->expert permutation
 // (otherwise launch_permute is issued behind it).

@@ -45,6 +45,35 @@ __global__ __launch_bounds__(256) void pack_kernel(const E* __restrict__ src, E*
   *reinterpret_cast<typename ET<E>::vec*>(d) = v;
 }
 
+// The embedding matrix [V][H] as the A operand of (probabilities) . W_emb: output features are the H embedding
+// columns, the contraction runs over the vocabulary, padded with zeros to Kpad.  dst: [H/64][Kpad/KS][2][64][16 B].
+template <typename E>
+__global__ __launch_bounds__(256) void pack_transposed_kernel(const E* __restrict__ src, E* __restrict__ dst, int V, int H,
+                                                               int Kpad) {
+  constexpr int G = ET<E>::G, KS = ET<E>::KS;
+  const int ksteps = Kpad / KS;
+  const int lane = threadIdx.x & 63;
+  const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // (task, kstep, which)
+  if (chunk >= (int64_t)(H / 64) * ksteps * 2) return;
+  const int which = (int)(chunk & 1);
+  const int ks = (int)((chunk >> 1) % ksteps);
+  const int task = (int)((chunk >> 1) / ksteps);
+  const int feature = (2 * task + which) * TILE + (lane & 31);
+  const int k = ks * KS + (lane >> 5) * G;
+  typename ET<E>::vec v;
+#pragma unroll
+  for (int i = 0; i < G; ++i) v[i] = k + i < V ? src[(int64_t)(k + i) * H + feature] : (E)0.f;
+  *reinterpret_cast<typename ET<E>::vec*>(dst + (chunk * WAVE + lane) * G) = v;
+}
+void launch_pack_transposed(bool bf16, const void* src, void* dst, int V, int H, int Kpad, hipStream_t st) {
+  const int ks = bf16 ? 16 : 8;
+  const int64_t chunks = (int64_t)(H / 64) * (Kpad / ks) * 2;
+  if (bf16)
+    pack_transposed_kernel<bf16_t><<<(unsigned)((chunks + 3) / 4), 256, 0, st>>>((const bf16_t*)src, (bf16_t*)dst, V, H, Kpad);
+  else
+    pack_transposed_kernel<float><<<(unsigned)((chunks + 3) / 4), 256, 0, st>>>((const float*)src, (float*)dst, V, H, Kpad);
+}
+
 int64_t packed_bytes(bool bf16, int n_tasks, int K) {
   const int ks = bf16 ? 16 : 8;
   return (int64_t)n_tasks * (K / ks) * 2 * WAVE * 16;

@@ -75,13 +75,16 @@ template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
                                                              float eps, int H, int V, float* __restrict__ x,
                                                              float* __restrict__ rinv, const float* __restrict__ gain,
-                                                             E* __restrict__ xn, int T) {
+                                                             E* __restrict__ xn, int T, SmoothIn sm) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
+  // iteration smoothing: a still-masked position adds alpha times what the previous iteration retained for it
+  const bool smooth = sm.delta && ((sm.mask[t / sm.block_len] >> (t % sm.block_len)) & 1ull);
   float ss = 0.f;
   for (int c = threadIdx.x; c < H; c += NORM_THREADS) {
-    const float v = to_f32(row[c]);
+    float v = to_f32(row[c]);
+    if (smooth) v += sm.alpha * sm.delta[(int64_t)t * H + c];
     x[(int64_t)t * H + c] = v;
     store_actk<E>(xn, T, t, c, v * gain[c]);
     ss += v * v;
@@ -90,11 +93,36 @@ __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __re
   if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
 }
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, hipStream_t st) {
+                  float* rinv, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st) {
+  const SmoothIn sm = smooth ? *smooth : SmoothIn{nullptr, 0.f, nullptr, 1};
   if (bf16)
-    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv, gain, (bf16_t*)xn, T);
+    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv, gain, (bf16_t*)xn,
+                                                    T, sm);
   else
-    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn, T);
+    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn,
+                                                   T, sm);
+}
+
+// ---------------------------------------------------------------- iteration smoothing: probabilities
+// p[t][v] = exp(z[t][v] - max_t) / sum_t as a k-major activation matrix [T][Kpad] (zero past the vocabulary):
+// the B operand of the expected-embedding contraction.
+template <typename E>
+__global__ __launch_bounds__(256) void prob_planes_kernel(const float* __restrict__ logits, const float* __restrict__ stats,
+                                                           int T, int V, int Kpad, E* __restrict__ probs) {
+  const int t = blockIdx.y;
+  const float m = stats[2 * t], inv = 1.f / stats[2 * t + 1];
+  for (int v0 = (blockIdx.x * 256 + threadIdx.x) * 4; v0 < Kpad; v0 += gridDim.x * 256 * 4) {
+    f32x4 p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = v0 + i < V ? __expf(logits[(int64_t)t * V + v0 + i] - m) * inv : 0.f;
+    store_actk4<E>(probs, T, t, v0, p);
+  }
+}
+void launch_prob_planes(bool bf16, const float* logits, const float* stats, int T, int V, int Kpad, void* probs,
+                        hipStream_t st) {
+  dim3 grid(64, T);
+  if (bf16) prob_planes_kernel<bf16_t><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (bf16_t*)probs);
+  else prob_planes_kernel<float><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (float*)probs);
 }
 
 // x[t] += sum_j w[t][j] * O[t*k+j]  (j ascending: a fixed summation order);  rinv[t] and the normalised-input

@@ -147,6 +147,18 @@ class GpuRun:
         self.torch.cuda.synchronize()
         return self.state()
 
+    def smooth_state(self):
+        """Zero expected embeddings [n_seq][S][H] and the scratch buffer of the smoothing step."""
+        ns, S = self.tokens.shape
+        return dict(delta=self.torch.zeros((ns, S, self.cfg.hidden), dtype=self.torch.float32, device=self.dev),
+                    scratch=self.ctx.smooth_scratch(ns * S))
+
+    def step_smooth(self, smooth, alpha, threshold, fixed_k=0):
+        self.ctx.step_smooth(self.tokens, self.mask, self.prefix_len, self.page_table, threshold, fixed_k, alpha,
+                             smooth["delta"], smooth["scratch"], self.conf, self.argmax, self.n_committed)
+        self.torch.cuda.synchronize()
+        return self.state()
+
     def step_vicinity(self, vicinity_tokens, threshold, fixed_k=0):
         """vicinity_tokens: [n_seq][look_back] ids of the cached positions right before each block."""
         vic = self.torch.from_numpy(np.ascontiguousarray(vicinity_tokens, dtype=np.int32)).to(self.dev)
