@@ -90,6 +90,14 @@ def lib():
         L.oracle_generate_block.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp,
                                             c_i32, c_f64, c_i32, c_i32, c_vp]
         L.oracle_generate_block.restype = c_i32
+        L.oracle_commit_hier.argtypes = [c_vp, c_vp, c_i32, c_vp, c_vp, c_f64, c_f64]
+        L.oracle_commit_hier.restype = c_i32
+        L.oracle_step_hier.argtypes = [P(CConfig), P(CWeights), c_i32, c_vp, c_vp, c_i32, c_vp, c_vp, c_i32, c_f64,
+                                       c_f64, c_vp, c_vp, c_vp, P(CTrace)]
+        L.oracle_step_hier.restype = c_i32
+        L.oracle_generate.argtypes = [P(CConfig), P(CWeights), c_i32, c_i32, c_i32, c_vp, c_vp, c_i32, c_f64, c_i32,
+                                      c_i32, c_i32, c_vp, c_vp]
+        L.oracle_generate.restype = c_i32
         L.oracle_num_threads.restype = c_i32
         for f in (L.oracle_rmsnorm, L.oracle_rope, L.oracle_linear, L.oracle_attention, L.oracle_router,
                   L.oracle_moe_ffn, L.oracle_permutation, L.oracle_confidence, L.oracle_logits):
@@ -283,6 +291,35 @@ class Oracle:
             r["logits"] = logits
         return r
 
+    def step_hier(self, block_tokens, mask, prefix_len, kc, vc, tau_high, tau_low, want_logits=False, trace=None):
+        """One denoising step with the hierarchical decoder.  Returns what step() returns."""
+        tok = np.array(block_tokens, dtype=np.int32)
+        S = tok.shape[0]
+        m = np.array([mask], dtype=np.uint64)
+        conf = np.zeros(S, dtype=np.float64)
+        am = np.zeros(S, dtype=np.int32)
+        logits = np.zeros((S, self.cfg.vocab), dtype=np.float64) if want_logits else None
+        n = lib().oracle_step_hier(self.ccfg, self.cw, S, _p(tok), _p(m), int(prefix_len), _p(kc), _p(vc), kc.shape[1],
+                                   float(tau_high), float(tau_low), _p(conf), _p(am), _p(logits),
+                                   trace.c if trace else None)
+        if n < 0:
+            raise ValueError("oracle_step_hier failed")
+        r = dict(tokens=tok, mask=int(m[0]), n_committed=int(n), conf=conf, argmax=am)
+        if want_logits:
+            r["logits"] = logits
+        return r
+
+    def generate(self, block_len, n_blocks, prefix_len, kc, vc, threshold, fixed_k=0, eos_id=-1):
+        """Outer loop over blocks with early termination.  Returns dict(tokens [n_blocks*block_len], blocks, steps)."""
+        out = np.zeros(n_blocks * block_len, dtype=np.int32)
+        steps = np.zeros(n_blocks, dtype=np.int32)
+        done = lib().oracle_generate(self.ccfg, self.cw, int(block_len), int(n_blocks), int(prefix_len), _p(kc), _p(vc),
+                                     kc.shape[1], float(threshold), int(fixed_k), int(self.cfg.mask_id), int(eos_id),
+                                     _p(out), _p(steps))
+        if done < 0:
+            raise ValueError("oracle_generate failed")
+        return dict(tokens=out, blocks=int(done), steps=steps[:done].copy())
+
     def generate_block(self, block_tokens, mask, prefix_len, kc, vc, threshold, fixed_k=0, max_steps=64):
         tok = np.array(block_tokens, dtype=np.int32)
         m = np.array([mask], dtype=np.uint64)
@@ -380,6 +417,15 @@ def commit(conf, argmax, mask, tokens, threshold, fixed_k=0):
     tok = np.array(tokens, dtype=np.int32)
     m = np.array([mask], dtype=np.uint64)
     n = lib().oracle_commit(_p(conf), _p(am), conf.shape[0], _p(m), _p(tok), float(threshold), int(fixed_k))
+    return int(n), int(m[0]), tok
+
+
+def commit_hier(conf, argmax, mask, tokens, tau_high, tau_low):
+    conf = f64(conf)
+    am = np.ascontiguousarray(argmax, dtype=np.int32)
+    tok = np.array(tokens, dtype=np.int32)
+    m = np.array([mask], dtype=np.uint64)
+    n = lib().oracle_commit_hier(_p(conf), _p(am), conf.shape[0], _p(m), _p(tok), float(tau_high), float(tau_low))
     return int(n), int(m[0]), tok
 
 

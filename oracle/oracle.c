@@ -349,6 +349,83 @@ int32_t oracle_commit(const double* conf, const int32_t* argmax, int block_len, 
   return n;
 }
 
+/* Decoder (Appendix "Hierarchical decoding"; thresholds from the experimental configuration: decoding
+ * threshold 0.92, lower boundary 0.62).  The paper gives the method in prose only; this is the reading taken:
+ *   1. every masked position whose confidence reaches tau_high is committed;
+ *   2. the regions of a step are the maximal runs of consecutive masked positions (as masked when the step
+ *      starts).  A region in which step 1 committed nothing tries to resolve one position: among its positions
+ *      whose confidence reaches tau_low, the one closest to the centre of the run (on equal distance the more
+ *      confident one, then the lower position).  Committing near the centre splits the run, so the regions of the
+ *      next step are the halves: the recursion runs over the forward passes;
+ *   3. if steps 1 and 2 committed nothing at all, the single most confident masked position is committed (lowest
+ *      position on ties), as in oracle_commit, so that the loop of Algorithm 1 ends. */
+int32_t oracle_commit_hier(const double* conf, const int32_t* argmax, int block_len, uint64_t* mask,
+                           int32_t* tokens, double tau_high, double tau_low) {
+  const uint64_t old = *mask;
+  uint64_t sel = 0;
+  int a = 0;
+  while (a < block_len) {
+    if (!((old >> a) & 1)) {
+      ++a;
+      continue;
+    }
+    int b = a;                                     /* the run is a .. b inclusive */
+    while (b + 1 < block_len && ((old >> (b + 1)) & 1)) ++b;
+    int high = 0;
+    for (int i = a; i <= b; ++i)
+      if (conf[i] >= tau_high) {
+        sel |= (uint64_t)1 << i;
+        high = 1;
+      }
+    if (!high) {
+      int best = -1, best_dist = 0;
+      for (int i = a; i <= b; ++i) {
+        if (conf[i] < tau_low) continue;
+        int dist = 2 * i - (a + b);                /* twice the distance to the centre (a + b) / 2 */
+        if (dist < 0) dist = -dist;
+        if (best < 0 || dist < best_dist || (dist == best_dist && conf[i] > conf[best])) {
+          best = i;
+          best_dist = dist;
+        }
+      }
+      if (best >= 0) sel |= (uint64_t)1 << best;
+    }
+    a = b + 1;
+  }
+  if (sel == 0) {
+    int best = -1;
+    for (int i = 0; i < block_len; ++i)
+      if (((old >> i) & 1) && (best < 0 || conf[i] > conf[best])) best = i;
+    if (best >= 0) sel = (uint64_t)1 << best;
+  }
+  int32_t n = 0;
+  for (int i = 0; i < block_len; ++i)
+    if ((sel >> i) & 1) {
+      tokens[i] = argmax[i];
+      ++n;
+    }
+  *mask = old & ~sel;
+  return n;
+}
+
+int32_t oracle_step_hier(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                         uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                         double tau_high, double tau_low, double* conf, int32_t* argmax, double* logits_out,
+                         const oracle_trace* trace) {
+  const int V = c->vocab;
+  double* hidden = (double*)malloc(sizeof(double) * (size_t)block_len * c->hidden);
+  double* logits = logits_out ? logits_out : (double*)malloc(sizeof(double) * (size_t)block_len * V);
+  int32_t n = -1;
+  if (oracle_forward(c, w, block_len, block_tokens, prefix_len, kcache, vcache, cache_cap, hidden, trace) == 0) {
+    oracle_logits(c, w, hidden, block_len, logits);
+    for (int i = 0; i < block_len; ++i) oracle_confidence(logits + (size_t)i * V, V, &conf[i], &argmax[i]);
+    n = oracle_commit_hier(conf, argmax, block_len, mask, block_tokens, tau_high, tau_low);
+  }
+  if (!logits_out) free(logits);
+  free(hidden);
+  return n;
+}
+
 int32_t oracle_step(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
                     uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
                     double threshold, int fixed_k, double* conf, int32_t* argmax, double* logits_out,
@@ -481,4 +558,39 @@ int32_t oracle_generate_block(const oracle_config* c, const oracle_weights* w, i
   free(conf);
   free(am);
   return steps;
+}
+
+/* The outer loop of Algorithm 1 for one sequence whose prompt is cached: block after block starts fully masked,
+ * is denoised by oracle_generate_block and, once decoded, is run through the forward again so that its K,V are
+ * those of its final ids.  Early termination (Section 3, system optimisations, diffusion iterations): once a
+ * decoded block contains eos_id the loop stops and the remaining blocks are filled with eos_id (eos_id < 0: never).
+ * out [n_blocks * block_len]; returns the number of blocks that were decoded, -1 on failure. */
+int32_t oracle_generate(const oracle_config* c, const oracle_weights* w, int block_len, int n_blocks, int prefix_len,
+                        double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k, int32_t mask_id,
+                        int32_t eos_id, int32_t* out, int32_t* steps_per_block) {
+  double* hidden = (double*)malloc(sizeof(double) * (size_t)block_len * c->hidden);
+  int32_t done = 0;
+  int stop = 0;
+  for (int b = 0; b < n_blocks; ++b) {
+    int32_t* blk = out + (size_t)b * block_len;
+    if (stop) {
+      for (int i = 0; i < block_len; ++i) blk[i] = eos_id;
+      continue;
+    }
+    for (int i = 0; i < block_len; ++i) blk[i] = mask_id;
+    uint64_t mask = block_len == 64 ? ~(uint64_t)0 : (((uint64_t)1 << block_len) - 1);
+    const int P = prefix_len + b * block_len;
+    const int32_t steps = oracle_generate_block(c, w, block_len, blk, &mask, P, kcache, vcache, cache_cap, threshold,
+                                                fixed_k, block_len, NULL);
+    if (steps < 0 || mask != 0 || oracle_forward(c, w, block_len, blk, P, kcache, vcache, cache_cap, hidden, NULL) != 0) {
+      done = -1;
+      break;
+    }
+    if (steps_per_block) steps_per_block[b] = steps;
+    ++done;
+    for (int i = 0; i < block_len; ++i)
+      if (eos_id >= 0 && blk[i] == eos_id) stop = 1;
+  }
+  free(hidden);
+  return done;
 }

@@ -165,6 +165,22 @@ int32_t oracle_generate_block(const oracle_config* c, const oracle_weights* w, i
                               double* vcache, int cache_cap, double threshold, int fixed_k, int max_steps,
                               int32_t* committed_per_step);
 
+/* Hierarchical decoding (Appendix "Hierarchical decoding"): the commit rule on given confidences, and the step
+ * that uses it in place of oracle_commit.  See oracle.c for the reading of the paper's prose. */
+int32_t oracle_commit_hier(const double* conf, const int32_t* argmax, int block_len, uint64_t* mask,
+                           int32_t* tokens, double tau_high, double tau_low);
+int32_t oracle_step_hier(const oracle_config* c, const oracle_weights* w, int block_len, int32_t* block_tokens,
+                         uint64_t* mask, int prefix_len, double* kcache, double* vcache, int cache_cap,
+                         double tau_high, double tau_low, double* conf, int32_t* argmax, double* logits_out,
+                         const oracle_trace* trace);
+
+/* Outer loop of Algorithm 1 over n_blocks blocks (each starts as block_len times mask_id) with early termination
+ * at eos_id (Section 3, system optimisations; negative: none); out
+ * [n_blocks * block_len]; steps_per_block (may be NULL) [n_blocks]; returns the blocks decoded. */
+int32_t oracle_generate(const oracle_config* c, const oracle_weights* w, int block_len, int n_blocks, int prefix_len,
+                        double* kcache, double* vcache, int cache_cap, double threshold, int fixed_k, int32_t mask_id,
+                        int32_t eos_id, int32_t* out, int32_t* steps_per_block);
+
 int oracle_num_threads(void);
 
 #ifdef __cplusplus
