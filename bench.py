@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--credit", action="store_true",
                     help="time the step with credit decoding (alpha 0.65, beta 0.7, gamma 0.5); the credit lists "
                          "carry over between the timed steps, as inside a block")
+    ap.add_argument("--hier", action="store_true",
+                    help="decode with the hierarchical rule (threshold 0.92, lower boundary 0.62, the paper's settings) "
+                         "instead of the workload's threshold, in whichever step variant is timed")
     ap.add_argument("--smooth", action="store_true",
                     help="time the step with iteration smoothing (alpha 0.2); the expected embeddings carry over "
                          "between the timed steps, as inside a block (single-block workloads with at most 64 tokens)")
@@ -224,20 +227,22 @@ def main():
     if args.smooth:
         smooth = (torch.zeros((ns, S, cfg.hidden), dtype=torch.float32, device=dev), ctx.smooth_scratch(ns * S))
 
+    thr = binding.hierarchical(0.92, 0.62) if args.hier else wl.threshold
+
     def one_step():
         tokens.copy_(tokens0)
         mask.copy_(mask0)
         if smooth is not None:
-            ctx.step_smooth(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, 0.2, smooth[0], smooth[1],
+            ctx.step_smooth(tokens, mask, prefix_len, page_table, thr, wl.fixed_k, 0.2, smooth[0], smooth[1],
                             conf, argmax, n_committed)
         elif credit is not None:
-            ctx.step_credit(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, 0.65, 0.7, 0.5, credit[0],
+            ctx.step_credit(tokens, mask, prefix_len, page_table, thr, wl.fixed_k, 0.65, 0.7, 0.5, credit[0],
                             credit[1], credit[2], conf, argmax, n_committed)
         elif lb:
-            ctx.step_vicinity(tokens, vic, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax,
+            ctx.step_vicinity(tokens, vic, mask, prefix_len, page_table, thr, wl.fixed_k, conf, argmax,
                               n_committed)
         else:
-            ctx.step(tokens, mask, prefix_len, page_table, wl.threshold, wl.fixed_k, conf, argmax, n_committed)
+            ctx.step(tokens, mask, prefix_len, page_table, thr, wl.fixed_k, conf, argmax, n_committed)
 
     # practical HBM read ceiling: the streaming-read probe over the weight buffer, and over one launch's worth
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -329,7 +334,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else "")
-                   + ("-smooth" if args.smooth else ""),
+                   + ("-smooth" if args.smooth else "") + ("-hier" if args.hier else ""),
                    "n_seq": ns, "block_len": S,
                    "vicinity_look_back": lb, "prefix_len": [int(p) for p in inp.prefix_len][:4],
                    "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),

@@ -73,10 +73,20 @@ typedef struct dinfer_config {
 
 /* Decoder settings.  fixed_k == 0: commit every masked position whose confidence is at or above
  * `threshold`, or the single most confident one if none is.  fixed_k > 0: commit the fixed_k most confident
- * masked positions (all that remain if fewer).  Ties go to the lower position. */
+ * masked positions (all that remain if fewer).  Ties go to the lower position.
+ *
+ * hierarchical != 0 (with fixed_k == 0) selects hierarchical decoding (Appendix "Hierarchical decoding"; the
+ * experiments use threshold 0.92 and lower boundary 0.62).  The paper describes it in prose; this library takes it
+ * as: (1) every masked position at or above `threshold` is committed; (2) in every maximal run of consecutive
+ * masked positions in which (1) committed nothing, the position closest to the centre of the run among those at
+ * or above `lower_bound` is committed (at equal distance the more confident one, then the lower position), so
+ * that runs are split near their middle and the next step works on the halves; (3) if nothing was committed at
+ * all, the single most confident masked position is.  lower_bound <= threshold. */
 typedef struct dinfer_decode {
   float threshold;
   int32_t fixed_k;
+  int32_t hierarchical;
+  float lower_bound;
 } dinfer_decode;
 
 typedef struct dinfer_ctx dinfer_ctx;
@@ -124,6 +134,13 @@ int dinfer_step(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_bl
                 const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
                 const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
                 void* stream);
+
+/* The decoder alone, on confidences and candidate ids the caller provides (all device pointers, [n_seq][block_len];
+ * block_len <= 64, n_seq >= 1): applies `decode` to d_block_tokens / d_mask as the last stage of dinfer_step does
+ * and writes d_n_committed [n_seq].  Needs no context. */
+int dinfer_commit(const float* d_conf, const int32_t* d_argmax, int32_t n_seq, int32_t block_len,
+                  int32_t* d_block_tokens, uint64_t* d_mask, const dinfer_decode* decode, int32_t* d_n_committed,
+                  void* stream);
 
 /* The step with iteration smoothing (Appendix "IterSmooth").  Positions that are still masked are not embedded as
  * the bare mask token: e_t[i] = e_mask + alpha * delta[i], where delta[i] = softmax(z_{t-1}[i]) . W_emb is the
@@ -187,6 +204,25 @@ int dinfer_step_vicinity(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int3
  * ids, leaving the block's K,V final, then d_prefix_len[s] += block_len. */
 int dinfer_refresh_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, const int32_t* d_block_tokens,
                          int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, void* stream);
+
+/* The outer loop of Algorithm 1 with early termination (Section 3, system optimisations, diffusion iterations):
+ * n_blocks blocks of block_len positions are generated one after the other behind the cached prefix; every block
+ * starts fully masked, is denoised by the inner loop (dinfer_generate_block: with decode->fixed_k > 0 its
+ * ceil(block_len / fixed_k) steps are enqueued without waiting) and is then run through dinfer_refresh_block.
+ * Once a decoded block of a sequence contains eos_id (negative: never) the sequence is finished: its remaining
+ * blocks are filled with eos_id and commit nothing; when every sequence is finished the loop stops.  The host
+ * waits once per block to read the count of finished sequences.
+ *   d_out          [n_seq][n_blocks * block_len] out: the generated ids.
+ *   d_block_tokens [n_seq][block_len], d_mask [n_seq], d_conf, d_argmax, d_n_committed: working buffers as in
+ *                  dinfer_step (contents on return: those of the last step).
+ *   d_finished     [n_seq] int32 out: 1 for a sequence that produced eos_id.
+ *   d_prefix_len   [n_seq] in/out: advanced by block_len for every block that was run, for every sequence (a
+ *                  finished sequence rides along in the batch; its rows of eos_id are cached like any others).
+ *   *h_blocks_run  (host, may be NULL): blocks that were run before the loop stopped. */
+int dinfer_generate(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t n_blocks, int32_t* d_out,
+                    int32_t* d_block_tokens, uint64_t* d_mask, int32_t* d_prefix_len, const int32_t* d_page_table,
+                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t* d_finished,
+                    float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run, void* stream);
 
 /* The inner loop of Algorithm 1: steps until every mask is empty or max_steps were taken.  With
  * fixed_k > 0 and h_masked_hint > 0 (the caller's count of undecided positions per sequence, the same for

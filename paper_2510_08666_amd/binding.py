@@ -23,7 +23,7 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
 
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit", "dinfer_step_smooth", "dinfer_smooth_scratch_bytes",
-           "dinfer_refresh_block",
+           "dinfer_refresh_block", "dinfer_commit", "dinfer_generate",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
            "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
@@ -37,7 +37,19 @@ class Config(ctypes.Structure):
 
 
 class Decode(ctypes.Structure):
-    _fields_ = [("threshold", c_f32), ("fixed_k", c_i32)]
+    _fields_ = [("threshold", c_f32), ("fixed_k", c_i32), ("hierarchical", c_i32), ("lower_bound", c_f32)]
+
+
+def _decode(threshold, fixed_k):
+    """A Decode passes through; otherwise threshold decoding (or fixed-k when fixed_k > 0)."""
+    if isinstance(threshold, Decode):
+        return threshold
+    return Decode(float(threshold), int(fixed_k), 0, 0.0)
+
+
+def hierarchical(threshold, lower_bound):
+    """Decoder settings of hierarchical decoding."""
+    return Decode(float(threshold), 0, 1, float(lower_bound))
 
 
 class Credit(ctypes.Structure):
@@ -45,6 +57,13 @@ class Credit(ctypes.Structure):
 
 
 CREDIT_CAP = 64
+
+
+def commit(d_conf, d_argmax, d_block_tokens, d_mask, decode, d_n_committed):
+    """The decoder alone on given confidences and candidate ids ([n_seq][block_len] device tensors)."""
+    n_seq, block_len = d_block_tokens.shape
+    _check(lib.dinfer_commit(_ptr(d_conf), _ptr(d_argmax), n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask),
+                             ctypes.byref(decode), _ptr(d_n_committed), _stream()))
 
 
 class DinferError(RuntimeError):
@@ -93,6 +112,11 @@ def _load():
     L.dinfer_generate_block.restype = c_i32
     L.dinfer_generate_block.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp, c_vp, c_vp,
                                         c_i32, c_i32, P(c_i32), c_vp]
+    L.dinfer_commit.restype = c_i32
+    L.dinfer_commit.argtypes = [c_vp, c_vp, c_i32, c_i32, c_vp, c_vp, P(Decode), c_vp, c_vp]
+    L.dinfer_generate.restype = c_i32
+    L.dinfer_generate.argtypes = [c_vp, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_i32, c_vp,
+                                  c_vp, c_vp, c_vp, P(c_i32), c_vp]
     L.dinfer_kv_write.restype = c_i32
     L.dinfer_kv_write.argtypes = [c_vp, c_i32, c_vp, c_i32, c_i32, c_vp, c_vp, c_vp]
     L.dinfer_kv_read.restype = c_i32
@@ -216,7 +240,7 @@ class Context:
     def step(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, d_conf, d_argmax,
              d_n_committed):
         n_seq, block_len = d_block_tokens.shape
-        dec = Decode(float(threshold), int(fixed_k))
+        dec = _decode(threshold, fixed_k)
         _check(lib.dinfer_step(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
                                _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), _ptr(d_conf),
                                _ptr(d_argmax), _ptr(d_n_committed), _stream()))
@@ -231,7 +255,7 @@ class Context:
     def step_smooth(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, alpha, d_delta,
                     d_scratch, d_conf, d_argmax, d_n_committed):
         n_seq, block_len = d_block_tokens.shape
-        dec = Decode(float(threshold), int(fixed_k))
+        dec = _decode(threshold, fixed_k)
         _check(lib.dinfer_step_smooth(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
                                       _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), float(alpha),
                                       _ptr(d_delta), _ptr(d_scratch), d_scratch.numel(), _ptr(d_conf), _ptr(d_argmax),
@@ -240,7 +264,7 @@ class Context:
     def step_credit(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, alpha, beta, gamma,
                     d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, d_n_committed):
         n_seq, block_len = d_block_tokens.shape
-        dec = Decode(float(threshold), int(fixed_k))
+        dec = _decode(threshold, fixed_k)
         cr = Credit(float(alpha), float(beta), float(gamma))
         _check(lib.dinfer_step_credit(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask), _ptr(d_prefix_len),
                                       _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), ctypes.byref(cr),
@@ -251,7 +275,7 @@ class Context:
                       d_conf, d_argmax, d_n_committed):
         n_seq, block_len = d_block_tokens.shape
         look_back = d_vicinity_tokens.shape[1]
-        dec = Decode(float(threshold), int(fixed_k))
+        dec = _decode(threshold, fixed_k)
         _check(lib.dinfer_step_vicinity(self.h, n_seq, block_len, look_back, _ptr(d_block_tokens),
                                         _ptr(d_vicinity_tokens), _ptr(d_mask), _ptr(d_prefix_len), _ptr(d_page_table),
                                         d_page_table.shape[1], ctypes.byref(dec), _ptr(d_conf), _ptr(d_argmax),
@@ -265,13 +289,27 @@ class Context:
     def generate_block(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, d_conf, d_argmax,
                        d_n_committed, max_steps, masked_hint=0):
         n_seq, block_len = d_block_tokens.shape
-        dec = Decode(float(threshold), int(fixed_k))
+        dec = _decode(threshold, fixed_k)
         steps = c_i32(0)
         _check(lib.dinfer_generate_block(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask),
                                          _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1],
                                          ctypes.byref(dec), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
                                          int(max_steps), int(masked_hint), ctypes.byref(steps), _stream()))
         return steps.value
+
+    def generate(self, d_out, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, eos_id,
+                 d_finished, d_conf, d_argmax, d_n_committed):
+        """Outer loop over the blocks of d_out [n_seq][n_blocks * block_len]; returns the blocks that were run."""
+        n_seq, block_len = d_block_tokens.shape
+        n_blocks = d_out.shape[1] // block_len
+        assert d_out.shape[1] == n_blocks * block_len and d_out.is_contiguous()
+        dec = _decode(threshold, fixed_k)
+        run = c_i32(0)
+        _check(lib.dinfer_generate(self.h, n_seq, block_len, n_blocks, _ptr(d_out), _ptr(d_block_tokens), _ptr(d_mask),
+                                   _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec),
+                                   int(eos_id), _ptr(d_finished), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
+                                   ctypes.byref(run), _stream()))
+        return run.value
 
     # ---- KV rows in and out, test hooks
     def kv_write(self, layer, d_page_row, first_pos, d_k, d_v):

@@ -110,7 +110,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, work, run_tokens, run_base, y, o, lm_part, lm_stats, conf, argmax, total;
+      perm, pos_of_pair, work, run_tokens, run_base, n_finished, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -167,6 +167,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.pos_of_pair = cv.take(T * K * 4);
   w.run_tokens = cv.take(T * 4);                 // token run and start positions of a vicinity-refresh forward
   w.run_base = cv.take((size_t)max_seqs * 4);
+  w.n_finished = cv.take(4);                     // generation loop: sequences that have produced the end-of-sequence id
   w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
@@ -204,6 +205,20 @@ namespace {
 template <typename T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
 
 constexpr size_t PROF_MAX_LAUNCHES = 8192;
+
+int check_decode(const dinfer_decode* d) {
+  if (!d) return fail(DINFER_EINVAL, "decode is null");
+  if (d->fixed_k < 0 || d->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", d->fixed_k);
+  if (d->hierarchical) {
+    if (d->fixed_k > 0) return fail(DINFER_EINVAL, "hierarchical decoding with fixed_k %d", d->fixed_k);
+    if (!(d->lower_bound <= d->threshold)) return fail(DINFER_EINVAL, "lower_bound %g above threshold %g",
+                                                        (double)d->lower_bound, (double)d->threshold);
+  }
+  return DINFER_OK;
+}
+CommitRule commit_rule(const dinfer_decode* d) {
+  return CommitRule{d->threshold, d->fixed_k, d->hierarchical != 0 ? 1 : 0, d->lower_bound};
+}
 
 // Brackets the launches of one stage with an event pair when that stage is being profiled.
 struct StageTimer {
@@ -502,7 +517,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
-  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if ((rc = check_decode(decode)) != DINFER_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, true, st);
   if (rc != DINFER_OK) return rc;
@@ -516,8 +531,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
-                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
 }
@@ -537,7 +551,7 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed || !d_delta || !d_scratch)
     return fail(DINFER_EINVAL, "null pointer");
-  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if ((rc = check_decode(decode)) != DINFER_OK) return rc;
   if (!(alpha >= 0.f)) return fail(DINFER_EINVAL, "alpha must be >= 0");
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
@@ -566,8 +580,7 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   SmoothArgs sa{c->weights + c->wm.emb_t, logits, stats, probs, d_mask, block_len, d_delta, T, f.hidden, f.vocab,
                 at<float>(c->ws, c->wsm.tk_part), at<int32_t>(c->ws, c->wsm.tickets)};
   launch_expected_embedding(c->bf16, sa, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
-                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
 }
@@ -581,7 +594,7 @@ int dinfer_step_credit(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
   if (!credit || !d_credit_ids || !d_credit_val || !d_credit_n) return fail(DINFER_EINVAL, "null pointer");
-  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if ((rc = check_decode(decode)) != DINFER_OK) return rc;
   if (!(credit->alpha >= 0.f) || !(credit->beta >= 0.f && credit->beta <= 1.f) ||
       !(credit->gamma > 0.f && credit->gamma <= 1.f))
     return fail(DINFER_EINVAL, "credit parameters: alpha >= 0, 0 <= beta <= 1, 0 < gamma <= 1");
@@ -601,8 +614,7 @@ int dinfer_step_credit(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, stats, st);
   launch_credit(c->bf16, la.w, la.xn, la.rinv, T, f.hidden, f.vocab, f.logit_scale, stats, d_mask, block_len,
                 credit->alpha, credit->beta, credit->gamma, d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, decode->threshold,
-                decode->fixed_k, d_n_committed, nullptr, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
 }
@@ -614,7 +626,7 @@ int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
-  if (decode->fixed_k < 0 || decode->fixed_k > 64) return fail(DINFER_EINVAL, "fixed_k %d", decode->fixed_k);
+  if ((rc = check_decode(decode)) != DINFER_OK) return rc;
   if (look_back < 0 || look_back > 64) return fail(DINFER_EINVAL, "look_back %d outside [0, 64]", look_back);
   if (look_back > 0 && !d_vicinity_tokens) return fail(DINFER_EINVAL, "null pointer");
   const int run = look_back + block_len;
@@ -639,8 +651,7 @@ int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, conf_rows, argmax_rows, nullptr, st);
-  launch_commit(conf_rows, argmax_rows, n_seq, block_len, run, look_back, d_block_tokens, d_mask, decode->threshold,
-                decode->fixed_k, d_n_committed, d_conf, d_argmax, st);
+  launch_commit(conf_rows, argmax_rows, n_seq, block_len, run, look_back, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, d_conf, d_argmax, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
 }
@@ -688,6 +699,56 @@ int dinfer_generate_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32
     }
   }
   if (h_steps_taken) *h_steps_taken = steps;
+  return DINFER_OK;
+}
+
+int dinfer_commit(const float* d_conf, const int32_t* d_argmax, int32_t n_seq, int32_t block_len,
+                  int32_t* d_block_tokens, uint64_t* d_mask, const dinfer_decode* decode, int32_t* d_n_committed,
+                  void* stream) {
+  if (!d_conf || !d_argmax || !d_block_tokens || !d_mask || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
+  if (n_seq < 1 || block_len < 1 || block_len > 64) return fail(DINFER_EINVAL, "n_seq %d block_len %d", n_seq, block_len);
+  int rc = check_decode(decode);
+  if (rc != DINFER_OK) return rc;
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode),
+                d_n_committed, nullptr, nullptr, (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return DINFER_OK;
+}
+
+int dinfer_generate(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t n_blocks, int32_t* d_out,
+                    int32_t* d_block_tokens, uint64_t* d_mask, int32_t* d_prefix_len, const int32_t* d_page_table,
+                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t* d_finished, float* d_conf,
+                    int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  if (!d_out || !d_mask || !d_finished || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
+  if (n_blocks < 1) return fail(DINFER_EINVAL, "n_blocks %d", n_blocks);
+  if (eos_id >= c->cfg.vocab) return fail(DINFER_EINVAL, "eos_id %d outside the vocabulary", eos_id);
+  if ((rc = check_decode(decode)) != DINFER_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* d_count = at<int32_t>(c->ws, c->wsm.n_finished);
+  int32_t* h_count = reinterpret_cast<int32_t*>(c->h_mask_pinned);
+  int b = 0;
+  for (; b < n_blocks; ++b) {
+    launch_block_begin(n_seq, block_len, c->cfg.mask_id, eos_id, d_finished, b == 0, d_block_tokens, d_mask, st);
+    rc = dinfer_generate_block(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
+                               d_conf, d_argmax, d_n_committed, block_len, block_len, nullptr, stream);
+    if (rc != DINFER_OK) return rc;
+    rc = dinfer_refresh_block(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride, stream);
+    if (rc != DINFER_OK) return rc;
+    launch_block_end(n_seq, block_len, n_blocks, b, eos_id, d_block_tokens, d_out, d_finished, d_count, st);
+    if (eos_id >= 0) {   // without an end-of-sequence id nothing can stop the loop: no wait at all
+      HIP_TRY(hipMemcpyAsync(h_count, d_count, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      if (*h_count >= n_seq) {
+        ++b;
+        break;
+      }
+    }
+  }
+  launch_fill_blocks(n_seq, block_len, n_blocks, b, eos_id, d_out, st);
+  HIP_TRY(hipGetLastError());
+  if (h_blocks_run) *h_blocks_run = b;
   return DINFER_OK;
 }
 

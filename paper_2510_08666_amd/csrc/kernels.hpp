@@ -191,9 +191,26 @@ void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rin
                    int32_t* cred_ids, float* cred_val, int32_t* cred_n, float* conf, int32_t* argmax, hipStream_t st);
 // conf / argmax: one row per forward token, position i of sequence s at row s*row_stride + row_off + i;
 // conf_out / argmax_out (may be null): the block's values, compact [n_seq][block_len].
+// rule: threshold / fixed_k as in the decoder settings of the C interface; hier != 0 selects the hierarchical
+// rule with lower boundary tau_low.
+struct CommitRule {
+  float threshold;
+  int fixed_k;
+  int hier;
+  float tau_low;
+};
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
-                   int32_t* tokens, uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, float* conf_out,
+                   int32_t* tokens, uint64_t* mask, CommitRule rule, int32_t* n_committed, float* conf_out,
                    int32_t* argmax_out, hipStream_t st);
+// Generation loop over blocks: start of a block (ids = mask_id and a full mask, or eos_id and an empty mask for a
+// finished sequence; `first` clears the finished flags instead of reading them); end of a block (copy into out[s][block_index], mark sequences whose block holds eos_id,
+// count the finished ones into n_finished[0]); fill of the blocks from first_block on with eos_id.
+void launch_block_begin(int n_seq, int block_len, int mask_id, int eos_id, int32_t* finished, bool first,
+                        int32_t* block_tokens, uint64_t* mask, hipStream_t st);
+void launch_block_end(int n_seq, int block_len, int n_blocks, int block_index, int eos_id, const int32_t* block_tokens,
+                      int32_t* out, int32_t* finished, int32_t* n_finished, hipStream_t st);
+void launch_fill_blocks(int n_seq, int block_len, int n_blocks, int first_block, int eos_id, int32_t* out,
+                        hipStream_t st);
 void launch_vicinity_pack(int n_seq, int block_len, int look_back, const int32_t* block_tokens,
                           const int32_t* vicinity_tokens, const int32_t* prefix_len, int32_t* run_tokens,
                           int32_t* run_base, hipStream_t st);

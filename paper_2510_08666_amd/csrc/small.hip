@@ -458,10 +458,13 @@ void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rin
 __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ conf, const int32_t* __restrict__ argmax,
                                                      int block_len, int row_stride, int row_off,
                                                      int32_t* __restrict__ tokens, uint64_t* __restrict__ mask,
-                                                     float threshold, int fixed_k, int32_t* __restrict__ n_committed,
+                                                     CommitRule rule, int32_t* __restrict__ n_committed,
                                                      float* __restrict__ conf_out, int32_t* __restrict__ argmax_out) {
+  __shared__ float conf_of[64];
+  const float threshold = rule.threshold;
+  const int fixed_k = rule.fixed_k;
   const int s = blockIdx.x, lane = threadIdx.x;
-  const uint64_t old = mask[s];
+  const uint64_t old = mask[s] & (block_len >= 64 ? ~0ull : ((1ull << block_len) - 1));
   const bool masked = lane < block_len && ((old >> lane) & 1ull);
   const int row = s * row_stride + row_off + lane;
   const float c = lane < block_len ? conf[row] : -1.f;
@@ -483,6 +486,34 @@ __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ co
     }
   } else {
     sel = __ballot(masked && c >= threshold);
+    if (rule.hier) {
+      // Runs of consecutive masked positions: lane's run is first .. last.  A run without a commit so far offers
+      // its positions at or above the lower boundary; the one closest to the run's centre wins (then the more
+      // confident, then the lower position).
+      conf_of[lane] = c;
+      __syncthreads();
+      const uint64_t gaps = ~old;                                        // decided positions and everything past the block
+      const uint64_t below = gaps & ((1ull << lane) - 1);
+      const uint64_t above = lane < 63 ? gaps & (~0ull << (lane + 1)) : 0ull;
+      const int first = below ? 64 - __clzll((long long)below) : 0;
+      const int last = above ? __ffsll((unsigned long long)above) - 2 : 63;
+      const uint64_t run = (last >= 63 ? ~0ull : ((2ull << last) - 1)) & ~((1ull << first) - 1);
+      const bool open = masked && (sel & run) == 0;
+      const uint64_t offers = __ballot(open && c >= rule.tau_low);
+      bool wins = open && c >= rule.tau_low;
+      if (wins) {
+        const int mine = abs(2 * lane - (first + last));
+        uint64_t rivals = offers & run & ~(1ull << lane);
+        while (rivals) {
+          const int j = __ffsll((unsigned long long)rivals) - 1;
+          rivals &= rivals - 1;
+          const int theirs = abs(2 * j - (first + last));
+          const float cj = conf_of[j];
+          if (theirs < mine || (theirs == mine && (cj > c || (cj == c && j < lane)))) wins = false;
+        }
+      }
+      sel |= __ballot(wins);
+    }
     if (sel == 0 && old != 0) {
       const float val = masked ? c : -1.f;
       const float best = wave_max(val);
@@ -497,10 +528,57 @@ __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ co
   }
 }
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
-                   int32_t* tokens, uint64_t* mask, float threshold, int fixed_k, int32_t* n_committed, float* conf_out,
+                   int32_t* tokens, uint64_t* mask, CommitRule rule, int32_t* n_committed, float* conf_out,
                    int32_t* argmax_out, hipStream_t st) {
-  commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, row_stride, row_off, tokens, mask, threshold, fixed_k,
-                                      n_committed, conf_out, argmax_out);
+  commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, row_stride, row_off, tokens, mask, rule, n_committed,
+                                      conf_out, argmax_out);
+}
+
+// ---------------------------------------------------------------- generation loop over blocks
+__global__ __launch_bounds__(64) void block_begin_kernel(int block_len, int mask_id, int eos_id,
+                                                          int32_t* __restrict__ finished, bool first,
+                                                          int32_t* __restrict__ block_tokens, uint64_t* __restrict__ mask) {
+  const int s = blockIdx.x, lane = threadIdx.x;
+  const bool fin = !first && finished[s] != 0;
+  if (first && lane == 0) finished[s] = 0;
+  if (lane < block_len) block_tokens[s * block_len + lane] = fin ? eos_id : mask_id;
+  if (lane == 0) mask[s] = fin ? 0ull : (block_len >= 64 ? ~0ull : ((1ull << block_len) - 1));
+}
+void launch_block_begin(int n_seq, int block_len, int mask_id, int eos_id, int32_t* finished, bool first,
+                        int32_t* block_tokens, uint64_t* mask, hipStream_t st) {
+  block_begin_kernel<<<n_seq, 64, 0, st>>>(block_len, mask_id, eos_id, finished, first, block_tokens, mask);
+}
+// One wave walks the sequences, so that the count of finished sequences needs no atomics.
+__global__ __launch_bounds__(64) void block_end_kernel(int n_seq, int block_len, int n_blocks, int block_index, int eos_id,
+                                                        const int32_t* __restrict__ block_tokens, int32_t* __restrict__ out,
+                                                        int32_t* __restrict__ finished, int32_t* __restrict__ n_finished) {
+  const int lane = threadIdx.x;
+  int count = 0;
+  for (int s = 0; s < n_seq; ++s) {
+    const int tok = lane < block_len ? block_tokens[s * block_len + lane] : -1;
+    if (lane < block_len) out[((int64_t)s * n_blocks + block_index) * block_len + lane] = tok;
+    const bool fin = finished[s] != 0 || (eos_id >= 0 && __ballot(lane < block_len && tok == eos_id) != 0);
+    if (fin) {
+      ++count;
+      if (lane == 0) finished[s] = 1;
+    }
+  }
+  if (lane == 0) n_finished[0] = count;
+}
+void launch_block_end(int n_seq, int block_len, int n_blocks, int block_index, int eos_id, const int32_t* block_tokens,
+                      int32_t* out, int32_t* finished, int32_t* n_finished, hipStream_t st) {
+  block_end_kernel<<<1, 64, 0, st>>>(n_seq, block_len, n_blocks, block_index, eos_id, block_tokens, out, finished,
+                                     n_finished);
+}
+__global__ void fill_blocks_kernel(int block_len, int n_blocks, int first_block, int eos_id, int32_t* __restrict__ out) {
+  const int s = blockIdx.x;
+  for (int i = first_block * block_len + threadIdx.x; i < n_blocks * block_len; i += blockDim.x)
+    out[(int64_t)s * n_blocks * block_len + i] = eos_id;
+}
+void launch_fill_blocks(int n_seq, int block_len, int n_blocks, int first_block, int eos_id, int32_t* out,
+                        hipStream_t st) {
+  if (first_block >= n_blocks) return;
+  fill_blocks_kernel<<<n_seq, 256, 0, st>>>(block_len, n_blocks, first_block, eos_id, out);
 }
 
 // Token run of a vicinity-refresh forward: per sequence the look_back neighbour ids, then the block's ids; the run

@@ -1,0 +1,209 @@
+"""GPU parity of hierarchical decoding and of the generation loop with early termination, through the C-ABI.
+
+The decoder is integer work on float32 confidences: dinfer_commit is compared bit for bit with the oracle's rule on
+the same float32 values.  Inside a step the confidences of the two sides differ by rounding, so the step test checks
+the confidences against the oracle's within the usual bars and the selection bit for bit against the oracle's rule
+applied to the step's own confidences; with thresholds placed in gaps of the confidence distribution it must also
+equal the oracle's step."""
+import numpy as np
+import pytest
+
+import dinfer_inputs as di
+import oracle
+from harness import GpuRun, OracleRun, bars_for, compare_logits, make_case
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_binding():
+    import torch
+    from paper_2510_08666_amd import binding
+    return torch, binding
+
+
+def _commit_case(torch, binding, conf, am, masks, S, decode, ora):
+    dev = torch.device("cuda:0")
+    ns = conf.shape[0]
+    d_conf = torch.from_numpy(conf).to(dev)
+    d_am = torch.from_numpy(am).to(dev)
+    tokens0 = np.full((ns, S), -5, dtype=np.int32)
+    d_tok = torch.from_numpy(tokens0.copy()).to(dev)
+    d_mask = torch.from_numpy(masks.view(np.int64).copy()).to(dev)
+    d_n = torch.zeros(ns, dtype=torch.int32, device=dev)
+    binding.commit(d_conf, d_am, d_tok, d_mask, decode, d_n)
+    torch.cuda.synchronize()
+    got_tok, got_mask, got_n = d_tok.cpu().numpy(), d_mask.cpu().numpy().view(np.uint64), d_n.cpu().numpy()
+    for s in range(ns):
+        n, m, t = ora(conf[s].astype(np.float64), am[s], int(masks[s]), tokens0[s])
+        assert (int(got_n[s]), int(got_mask[s])) == (n, m), (s, bin(int(masks[s])), bin(int(got_mask[s])), bin(m))
+        assert np.array_equal(got_tok[s], t)
+
+
+@pytest.mark.parametrize("S", [1, 7, 31, 32, 33, 63, 64])
+def test_decoder_alone_is_bit_exact(torch_binding, S):
+    torch, binding = torch_binding
+    rng = np.random.default_rng(100 + S)
+    ns = 64
+    hi, lo = float(np.float32(0.92)), float(np.float32(0.62))
+    levels = np.array([0.05, 0.3, 0.62, 0.7, 0.8, 0.92, 0.99], dtype=np.float32)
+    for style in ("levels", "uniform", "all_low", "all_mid"):
+        if style == "levels":
+            conf = levels[rng.integers(0, len(levels), (ns, S))]
+        elif style == "uniform":
+            conf = rng.random((ns, S)).astype(np.float32)
+        elif style == "all_low":
+            conf = (0.5 * rng.random((ns, S))).astype(np.float32)
+        else:
+            conf = np.full((ns, S), 0.75, dtype=np.float32)
+        am = rng.integers(0, 100000, (ns, S)).astype(np.int32)
+        full = (1 << S) - 1
+        masks = np.array([int(rng.integers(0, 1 << 62)) << 2 | int(rng.integers(0, 4)) for _ in range(ns)],
+                         dtype=np.uint64) & np.uint64(full)
+        masks[0], masks[1] = np.uint64(full), np.uint64(0)
+        _commit_case(torch, binding, conf, am, masks, S, binding.hierarchical(hi, lo),
+                     lambda c, a, m, t: oracle.commit_hier(c, a, m, t, hi, lo))
+        _commit_case(torch, binding, conf, am, masks, S, binding.Decode(hi, 0, 0, 0.0),
+                     lambda c, a, m, t: oracle.commit(c, a, m, t, hi))
+        if style != "all_mid":             # fixed-k leaves the order of exactly equal confidences to the lower position
+            _commit_case(torch, binding, conf, am, masks, S, binding.Decode(0.0, 3, 0, 0.0),
+                         lambda c, a, m, t: oracle.commit(c, a, m, t, 0.0, 3))
+
+
+def test_log_n_passes_on_the_gpu(torch_binding):
+    """63 masked positions, every confidence between the thresholds: 1, 2, 4, 8, 16, 32 commits."""
+    torch, binding = torch_binding
+    dev = torch.device("cuda:0")
+    S = 63
+    d_conf = torch.full((1, S), 0.75, dtype=torch.float32, device=dev)
+    d_am = torch.arange(S, dtype=torch.int32, device=dev).reshape(1, S)
+    d_tok = torch.full((1, S), -1, dtype=torch.int32, device=dev)
+    d_mask = torch.tensor([(1 << S) - 1], dtype=torch.int64, device=dev)
+    d_n = torch.zeros(1, dtype=torch.int32, device=dev)
+    for t in range(6):
+        binding.commit(d_conf, d_am, d_tok, d_mask, binding.hierarchical(0.92, 0.62), d_n)
+        assert int(d_n.cpu()[0]) == 1 << t
+    assert int(d_mask.cpu()[0]) == 0 and np.array_equal(d_tok.cpu().numpy()[0], np.arange(S))
+
+
+def test_bad_decoder_settings(torch_binding):
+    torch, binding = torch_binding
+    dev = torch.device("cuda:0")
+    z = torch.zeros((1, 8), dtype=torch.float32, device=dev)
+    zi = torch.zeros((1, 8), dtype=torch.int32, device=dev)
+    m = torch.zeros(1, dtype=torch.int64, device=dev)
+    n = torch.zeros(1, dtype=torch.int32, device=dev)
+    with pytest.raises(binding.DinferError):
+        binding.commit(z, zi, zi.clone(), m, binding.hierarchical(0.5, 0.6), n)      # lower boundary above the threshold
+    with pytest.raises(binding.DinferError):
+        binding.commit(z, zi, zi.clone(), m, binding.Decode(0.9, 2, 1, 0.5), n)      # hierarchical with fixed k
+
+
+def _variant(name):
+    tiny = di.model_preset("tiny")
+    W = di.Workload
+    return {
+        "c1": W("c1", tiny, 1, 32, 64, 64, seed_index=1),
+        "c1_bf16": W("c1_bf16", di.configs.scaled(tiny, dtype="bf16"), 1, 32, 64, 64, seed_index=1),
+        "trio": W("trio", tiny, 3, 64, 20, 70, seed_index=4),
+    }[name]
+
+
+@pytest.mark.parametrize("name", ["c1", "c1_bf16", "trio"])
+def test_hierarchical_steps_match_oracle(name):
+    wl = _variant(name)
+    cfg, w, inp = make_case(wl)
+    ns, S = inp.block_tokens.shape
+    cap = int(inp.prefix_len.max()) + S + 16
+    ora = OracleRun(cfg, w, inp, cap)
+    g = GpuRun(cfg, w, inp, ns * S, cap)
+    bars = bars_for(cfg)
+    from paper_2510_08666_amd import binding
+    g.inject_prefix(ora.caches)
+    tokens, masks = inp.block_tokens.copy(), inp.mask_bits.copy()
+    same, steps = 0, 0
+    while masks.any() and steps < 64:
+        # thresholds inside the two widest gaps of the oracle's confidences of sequence 0 (upper and lower half)
+        s0 = next(s for s in range(ns) if masks[s])
+        kc, vc = ora.caches[s0]
+        probe = ora.o.step(tokens[s0], int(masks[s0]), int(inp.prefix_len[s0]), kc.copy(), vc.copy(), 2.0)["conf"]
+        q = np.sort(probe[[i for i in range(S) if (int(masks[s0]) >> i) & 1]])
+        if len(q) >= 4:
+            mid = len(q) // 2
+            gaps_hi, gaps_lo = np.diff(q[mid:]), np.diff(q[:mid + 1])
+            hi = float(np.float32(q[mid + int(gaps_hi.argmax())] + gaps_hi.max() / 2))
+            lo = float(np.float32(q[int(gaps_lo.argmax())] + gaps_lo.max() / 2))
+        else:
+            hi, lo = float(np.float32(q[-1] * 1.5)), float(np.float32(q[0] * 0.5))
+        g.set_state(tokens, masks, inp.prefix_len)
+        got = g.step(binding.hierarchical(hi, lo))
+        logits = g.logits(ns * S).reshape(ns, S, -1)
+        for s in range(ns):
+            kc, vc = ora.caches[s]
+            keep = kc.copy(), vc.copy()
+            ref = ora.o.step_hier(tokens[s], int(masks[s]), int(inp.prefix_len[s]), kc, vc, hi, lo, want_logits=True)
+            kc[...], vc[...] = keep
+            compare_logits(ref["logits"], logits[s], bars)
+            ctol = np.minimum(bars.conf_abs, bars.conf_rel * np.maximum(ref["conf"], 1e-30))
+            assert np.all(np.abs(got["conf"][s] - ref["conf"]) <= ctol)
+            # the rule, bit for bit, on the step's own float32 confidences
+            n, m, t = oracle.commit_hier(got["conf"][s].astype(np.float64), got["argmax"][s], int(masks[s]), tokens[s],
+                                         hi, lo)
+            assert (int(got["n_committed"][s]), int(got["mask"][s])) == (n, m), (steps, s)
+            assert np.array_equal(got["tokens"][s], t)
+            if int(masks[s]):
+                assert n >= 1
+            # and the oracle's own step, where no confidence sits at a threshold within the error bars
+            clear = all(abs(ref["conf"][i] - th) > 2 * ctol[i] for i in range(S) if (int(masks[s]) >> i) & 1
+                        for th in (hi, lo))
+            if clear and int(got["mask"][s]) == ref["mask"]:
+                same += 1
+            elif clear:
+                # only the order of two nearly equal confidences at equal distance from a centre may differ
+                diff = int(got["mask"][s]) ^ ref["mask"]
+                idx = [i for i in range(S) if (diff >> i) & 1]
+                assert len(idx) % 2 == 0 and all(
+                    abs(ref["conf"][a] - ref["conf"][b]) <= 2 * max(ctol[a], ctol[b]) for a, b in zip(idx[::2], idx[1::2]))
+        tokens, masks = got["tokens"].copy(), got["mask"].copy()
+        steps += 1
+    assert not masks.any()
+    if cfg.dtype == "f32":          # bf16 error bars are wider than most gaps between 32 confidences
+        assert same >= steps        # at least one sequence per step in full agreement with the oracle's own step
+    g.close()
+
+
+def test_generation_stops_at_eos():
+    """Two sequences, four blocks of 16, four commits per step, float32 tiny model.  The end-of-sequence id is an id
+    the oracle's free run produces in a middle block of sequence 0."""
+    tiny = di.model_preset("tiny")
+    S, nb = 16, 4
+    wl = di.Workload("gen", tiny, 2, S, 40, 64, fixed_k=4, gen_len=S * nb, seed_index=1)
+    cfg, w, inp = make_case(wl)
+    cap = int(inp.prefix_len.max()) + S * nb + 16
+    ora = OracleRun(cfg, w, inp, cap)
+    g = GpuRun(cfg, w, inp, 2 * S, cap)
+    torch = g.torch
+    g.inject_prefix(ora.caches)
+    free = [ora.o.generate(S, nb, int(inp.prefix_len[s]), ora.caches[s][0].copy(), ora.caches[s][1].copy(), 0.9, 4)
+            for s in range(2)]
+    toks0 = free[0]["tokens"].reshape(nb, S)
+    found = [(b, int(t)) for b in range(1, nb - 1) for t in toks0[b] if t not in toks0[:b]]
+    assert found, "the free run of sequence 0 never produces a new id in a middle block"
+    out = torch.zeros((2, nb * S), dtype=torch.int32, device=g.dev)
+    fin = torch.zeros(2, dtype=torch.int32, device=g.dev)
+    for eos in (-1, found[0][1]):
+        ref = [ora.o.generate(S, nb, int(inp.prefix_len[s]), ora.caches[s][0].copy(), ora.caches[s][1].copy(), 0.9, 4,
+                              eos_id=eos) for s in range(2)]
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        out.fill_(-3)
+        run = g.ctx.generate(out, g.tokens, g.mask, g.prefix_len, g.page_table, 0.9, 4, eos, fin, g.conf, g.argmax,
+                             g.n_committed)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want_run = max(r["blocks"] for r in ref)
+        assert run == want_run, (eos, run, want_run)
+        for s in range(2):
+            assert np.array_equal(got[s], ref[s]["tokens"]), (eos, s)
+            assert int(fin.cpu()[s]) == (1 if eos >= 0 and eos in ref[s]["tokens"] else 0)
+        assert np.array_equal(g.prefix_len.cpu().numpy(), inp.prefix_len + run * S)
+    g.close()
