@@ -18,9 +18,30 @@ constexpr int WKC = 4;     // k-steps per staged chunk
 // (Measured at 512 tokens: four waves with the whole register file behind a six-chunk weight prefetch are slower
 // for the expert GEMMs, 173 against 141 microseconds.)
 constexpr int EXPERT_WW = 8, EXPERT_PRE = 2;
-constexpr int LM_WW = 8, LM_PRE = 2;
+#ifndef LM_WW_N
+#define LM_WW_N 8
+#endif
+#ifndef LM_PRE_N
+#define LM_PRE_N 2
+#endif
+constexpr int LM_WW = LM_WW_N, LM_PRE = LM_PRE_N;
+#ifndef LM_BF16_PLANES
+#define LM_BF16_PLANES 1
+#endif
+#ifndef LM_WIDE_NT
+#define LM_WIDE_NT 1          // LM-head weights with non-temporal loads
+#endif
+constexpr int XCDS = 8;      // accelerator dies, each with its own L2; workgroup i of a launch runs on die i % 8
 
-template <typename E> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * Planes<E>::N * WAVE * 16; }
+// Planes of the activations a kernel (by its trace id) feeds to the matrix cores.  The LM head with hundreds of
+// token rows is bound by the matrix cores, and its rounding error is not carried into later layers: it takes the
+// high bf16 plane only, that is activations rounded to bf16 as in the paper's arithmetic (bf16 inputs, float32
+// accumulation); the low plane would double its matrix work.  The expert GEMMs stay bound by their weight streams
+// and keep both planes (one plane: 7 % faster, but the error carried through 16 layers reaches the test bars).
+template <typename E, int KID> struct WidePlanes { static constexpr int N = Planes<E>::N; };
+template <> struct WidePlanes<bf16_t, 9> { static constexpr int N = LM_BF16_PLANES; };
+
+template <typename E, int KID> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * WidePlanes<E, KID>::N * WAVE * 16; }
 
 // Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow: the k-major
 // activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
@@ -35,8 +56,9 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
                                       int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
                                       f32x16 (&acc1)[WT]) {
   typedef typename ET<E>::vec vec;
-  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = WidePlanes<E, KID>::N;   // planes used; the rows hold Planes<E>::N
   constexpr int64_t STEP = 2 * WAVE * G;
+  auto wload = [](const E* p) { return (KID == 9 && LM_WIDE_NT == 0) ? load16<E>(p) : load16_stream<E>(p); };
   static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int last = n_chunks - 1;
@@ -51,8 +73,8 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
   // iteration never includes waiting for weights requested after them.
 #pragma unroll
   for (int ks = 0; ks < WKC; ++ks) {
-    wa0[0][ks] = load16_stream<E>(wp + (int64_t)ks * STEP);
-    wa1[0][ks] = load16_stream<E>(wp + (int64_t)ks * STEP + WAVE * G);
+    wa0[0][ks] = wload(wp + (int64_t)ks * STEP);
+    wa1[0][ks] = wload(wp + (int64_t)ks * STEP + WAVE * G);
   }
   {
     vec b0[SKS][NP];
@@ -73,8 +95,8 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
       const int c = min(i, last);
 #pragma unroll
       for (int ks = 0; ks < WKC; ++ks) {
-        wa0[i][ks] = load16_stream<E>(wp + (int64_t)(c * WKC + ks) * STEP);
-        wa1[i][ks] = load16_stream<E>(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
+        wa0[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP);
+        wa1[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
       }
     }
 #pragma unroll
@@ -117,8 +139,8 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
         const int cw = min(c + WPRE, last);
 #pragma unroll
         for (int ks = 0; ks < WKC; ++ks) {
-          wa0[i][ks] = load16_stream<E>(wp + (int64_t)(cw * WKC + ks) * STEP);
-          wa1[i][ks] = load16_stream<E>(wp + (int64_t)(cw * WKC + ks) * STEP + WAVE * G);
+          wa0[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP);
+          wa1[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP + WAVE * G);
         }
       }
     }
@@ -246,13 +268,13 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.I / TILE;
   expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
+                                EXPERT_WW * WAVE, wide_lds<E, 10>(), st>>>(
       (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.H / (2 * TILE);
   expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E>(), st>>>(
+                                EXPERT_WW * WAVE, wide_lds<E, 11>(), st>>>(
       (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.work, a.T * a.top_k, a.H, a.I);
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
@@ -265,9 +287,14 @@ void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// LM head fused with the confidence reduction, many-token form.  Grid (task quads, groups of 128 tokens); a
-// wave turns its accumulators (64 vocabulary ids x 128 tokens) into one (max, sum-exp, lowest arg max) partial
-// per token: part[(quad * 4 + wave)][token].  Logits are never stored (unless the debug pointer is set).
+// LM head fused with the confidence reduction, many-token form.  A workgroup takes one task group (8 tasks = 512
+// vocabulary ids) and one group of 128 tokens; a wave turns its accumulators (64 vocabulary ids x 128 tokens) into
+// one (max, sum-exp, lowest arg max) partial per token: part[task group * 8 + wave][token].  Logits are never
+// stored (unless the debug pointer is set).
+// The token groups of one task group stream the same weights.  Workgroups go to the dies in turn, so the launch is
+// one-dimensional and workgroup i = die (i % 8), turn (i / 8): consecutive turns of ONE die take the token groups
+// of one task group, which then run side by side behind the same L2 (measured at 512 tokens: 0.88 GB fetched from
+// HBM per launch for 0.64 GB of weights, where four separate passes would fetch 2.6 GB).
 // ------------------------------------------------------------------------------------------------
 template <typename E>
 __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
@@ -279,10 +306,14 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int tok0 = blockIdx.y * WT * TILE;
-  const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
+  const int groups = (T + WT * TILE - 1) / (WT * TILE);
+  const int turn = blockIdx.x / XCDS;
+  const int tgroup = (turn / groups) * XCDS + blockIdx.x % XCDS;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
-  const int slot = blockIdx.x * LM_WW + wave, task = min(slot, n_tasks - 1);
+  if (tgroup * LM_WW >= n_tasks) return;   // uniform over the workgroup
+  const int tok0 = (turn % groups) * WT * TILE;
+  const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
+  const int slot = tgroup * LM_WW + wave, task = min(slot, n_tasks - 1);
   const int ksteps = H / KS;
   float zs[WT];
 #pragma unroll
@@ -342,7 +373,8 @@ int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_
 
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
-  lm_head_wide_kernel<E><<<dim3(lm_head_wide_parts(a.V) / LM_WW, groups), LM_WW * WAVE, wide_lds<E>(), st>>>(
+  const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
+  lm_head_wide_kernel<E><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9>(), st>>>(
       (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {

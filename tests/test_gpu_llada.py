@@ -12,7 +12,7 @@ import pytest
 
 import dinfer_inputs as di
 import oracle
-from harness import kv_close, GpuRun, bars_for, compare_logits, compare_step, check_routing, max_abs_err
+from harness import kv_close, kv_err_ratio, GpuRun, bars_for, compare_logits, compare_step, check_routing, max_abs_err
 
 pytestmark = pytest.mark.gpu
 
@@ -91,8 +91,8 @@ class BigCase:
             kc, vc = self.caches[s]
             for l in (0, self.cfg.n_layers - 1):
                 k, v = self.gpu.read_kv(s, l, P, self.S)
-                assert kv_close(k, kc[l, P:P + self.S], self.bars)
-                assert kv_close(v, vc[l, P:P + self.S], self.bars)
+                rk, rv = kv_err_ratio(k, kc[l, P:P + self.S], self.bars), kv_err_ratio(v, vc[l, P:P + self.S], self.bars)
+                assert rk <= 1.0 and rv <= 1.0, "layer %d K,V error %.2f / %.2f of the bar" % (l, rk, rv)
             flagged += len(rep["flagged"])
             near_total += near
             log("%s seq %d: oracle step %.0f s, logits err %.2f of bar, conf rel err %.1e, flagged %s, "
