@@ -229,9 +229,10 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
     if (col < nvalid) {
       const float inv = 1.f / L;
 #pragma unroll
-      for (int i = 0; i < RPW; ++i) {
-        const int g = wave * RPW + i;
-        store_actk<E>(out, T_out, tok0 + col, head * HD + (g / 16) * TILE + acc_row(g % 16, half), r[i] * inv);
+      for (int i4 = 0; i4 < RPW / 4; ++i4) {   // four accumulator registers = four consecutive features
+        const int g = wave * RPW + 4 * i4;
+        const f32x4 o = {r[4 * i4] * inv, r[4 * i4 + 1] * inv, r[4 * i4 + 2] * inv, r[4 * i4 + 3] * inv};
+        store_actk4<E>(out, T_out, tok0 + col, head * HD + (g / 16) * TILE + acc_row(g % 16, half), o);
       }
     }
     TRACE_MARK(7, 4);

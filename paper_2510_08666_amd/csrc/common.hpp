@@ -87,6 +87,17 @@ template <typename E> __device__ inline void store_actk4(E* base, int64_t n_rows
   store_act4<E>(base, act_index<E>(n_rows, row, col), ET<E>::KS, v);   // col a multiple of 4
 }
 
+// Four consecutive stored elements at once (dst 8- or 16-byte aligned): one store instruction instead of four,
+// which matters where every lane addresses a row of its own and the address unit takes the lanes one by one.
+template <typename E> __device__ inline void store_elems4(E* dst, const f32x4& v);
+template <> __device__ inline void store_elems4<float>(float* dst, const f32x4& v) { *reinterpret_cast<f32x4*>(dst) = v; }
+template <> __device__ inline void store_elems4<bf16_t>(bf16_t* dst, const f32x4& v) {
+  bf16x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (bf16_t)v[i];
+  *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
 // acc[32 x 32] += A[32 x KS] * B[KS x 32].  Lane l supplies row (A) / column (B) l%32 and the G consecutive
 // k values that start at (l/32)*G; result: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4.
 __device__ inline void mfma32(f32x16& acc, const bf16x8& a, const bf16x8& b) {

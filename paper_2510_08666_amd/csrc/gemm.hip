@@ -7,6 +7,7 @@
 // feed those planes to the matrix cores and scale their accumulators by the row's 1/rms in the epilogue.
 #include "gemm.hpp"
 #include "kernels.hpp"
+#include "wide_stream.hpp"
 
 namespace dinfer {
 
@@ -59,10 +60,20 @@ template <typename E> struct QkvEpi {
     p.page = page_table[(int64_t)p.seq * pt_stride + p.pos / PAGE];
     const int j0 = (task % (hd / 64)) * TILE + acc_row(v0, half);
     const bool rot = task < 2 * geom.n_heads * (hd / 64);
+    if constexpr (PER == 4) {   // j0 is a multiple of 4: one 16-byte load per table
+      const f32x4 c4 = *reinterpret_cast<const f32x4*>(cos_tab + (int64_t)p.pos * (hd / 2) + (rot ? j0 : 0));
+      const f32x4 s4 = *reinterpret_cast<const f32x4*>(sin_tab + (int64_t)p.pos * (hd / 2) + (rot ? j0 : 0));
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      p.c[i] = rot ? cos_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 1.f;
-      p.s[i] = rot ? sin_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 0.f;
+      for (int i = 0; i < 4; ++i) {
+        p.c[i] = rot ? c4[i] : 1.f;
+        p.s[i] = rot ? s4[i] : 0.f;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        p.c[i] = rot ? cos_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 1.f;
+        p.s[i] = rot ? sin_tab[(int64_t)p.pos * (hd / 2) + j0 + i] : 0.f;
+      }
     }
   }
 
@@ -92,17 +103,27 @@ template <typename E> struct QkvEpi {
       }
       if (is_k) {
         E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
+        if constexpr (PER == 4) {
+          store_elems4<E>(dst, f32x4{lo[0], lo[1], lo[2], lo[3]});
+          store_elems4<E>(dst + hd / 2, f32x4{hi[0], hi[1], hi[2], hi[3]});
+        } else {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          dst[i] = from_f32<E>(lo[i]);
-          dst[hd / 2 + i] = from_f32<E>(hi[i]);
+          for (int i = 0; i < PER; ++i) {
+            dst[i] = from_f32<E>(lo[i]);
+            dst[hd / 2 + i] = from_f32<E>(hi[i]);
+          }
         }
       } else {
         const int64_t dst = (int64_t)tok * D + head * hd + j0;
+        if constexpr (PER == 4) {
+          store_act4<E>(q, dst, q_plane, f32x4{lo[0], lo[1], lo[2], lo[3]});
+          store_act4<E>(q, dst + hd / 2, q_plane, f32x4{hi[0], hi[1], hi[2], hi[3]});
+        } else {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          store_act<E>(q, dst + i, q_plane, lo[i]);
-          store_act<E>(q, dst + hd / 2 + i, q_plane, hi[i]);
+          for (int i = 0; i < PER; ++i) {
+            store_act<E>(q, dst + i, q_plane, lo[i]);
+            store_act<E>(q, dst + hd / 2 + i, q_plane, hi[i]);
+          }
         }
       }
     } else {
@@ -138,6 +159,18 @@ template <typename E> struct ResidualEpi {
     Pre<PER> p;
     const int col = (2 * task) * TILE + acc_row(v0, half);
     const float* p0 = x + (int64_t)(valid ? tok : 0) * H + col;
+    if constexpr (PER == 4) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(p0), b = *reinterpret_cast<const f32x4*>(p0 + TILE);
+      const f32x4 c = *reinterpret_cast<const f32x4*>(gain + col), d = *reinterpret_cast<const f32x4*>(gain + col + TILE);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p.x0[i] = a[i];
+        p.x1[i] = b[i];
+        p.g0[i] = c[i];
+        p.g1[i] = d[i];
+      }
+      return p;
+    }
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       p.x0[i] = p0[i];
@@ -156,6 +189,22 @@ template <typename E> struct ResidualEpi {
     const int col = (2 * task) * TILE + acc_row(v0, half);
     float* p0 = x + (int64_t)tok * H + col;
     float ss = 0.f;
+    if constexpr (PER == 4) {
+      f32x4 n0, n1, m0, m1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        n0[i] = pre.x0[i] + a0[i];
+        n1[i] = pre.x1[i] + a1[i];
+        m0[i] = n0[i] * pre.g0[i];
+        m1[i] = n1[i] * pre.g1[i];
+        ss += n0[i] * n0[i] + n1[i] * n1[i];
+      }
+      *reinterpret_cast<f32x4*>(p0) = n0;
+      *reinterpret_cast<f32x4*>(p0 + TILE) = n1;
+      store_actk4<E>(xn, T, tok, col, m0);
+      store_actk4<E>(xn, T, tok, col + TILE, m1);
+      return ss;
+    }
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const float n0 = pre.x0[i] + a0[i], n1 = pre.x1[i] + a1[i];
@@ -380,12 +429,154 @@ template <typename E, class Epi> static bool configure_ksplit() {
          opt_in_lds((const void*)gemm_ksplit_kernel<E, 4, 4, Epi>);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Dense projections over many token rows (more than 64).  A workgroup takes four tasks and WT token tiles; its
+// 4 * KH waves are KH teams of four, each team with its own share of the K range, its own LDS staging area for the
+// activation fragments (wide_stream.hpp) and one wave per task, which streams that task's weights once and keeps
+// the accumulators of 64 features x WT*32 rows.  The teams' sums are folded through LDS at the end and team 0
+// runs the epilogue (those of the split-K kernel, called for four accumulator registers at a time).  KH > 1 puts
+// several waves on every SIMD, so that one multiplies while another waits for LDS or memory, without asking the
+// launch for more workgroups than there are (task, token) tiles.
+// Grid (task groups, token groups): with a multiple of eight task groups the workgroups of one die always take the
+// same tasks, so the weights (a few MB per die) are read from HBM once and then served by that die's L2.
+// ------------------------------------------------------------------------------------------------
+#ifndef DENSE_KH_N
+#define DENSE_KH_N 2
+#endif
+#ifndef DENSE_WT_BIG
+#define DENSE_WT_BIG 2
+#endif
+#ifndef DENSE_FILL
+#define DENSE_FILL 160
+#endif
+constexpr int DENSE_TASKS = 4, DENSE_PRE = 2, DENSE_KH = DENSE_KH_N, DENSE_WT = DENSE_WT_BIG;
+
+template <typename E, int KID, int WT> constexpr size_t dense_lds() {
+  const size_t stage = DENSE_KH * wide_lds<E, KID, WT>();
+  const size_t fold = (size_t)(DENSE_KH - 1) * DENSE_TASKS * 2 * WT * 16 * WAVE * 4;
+  return stage > fold ? stage : fold;
+}
+
+template <typename E, int WT, class Epi>
+__global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kernel(const E* __restrict__ W, int ksteps,
+                                                                                  const E* __restrict__ B, int T,
+                                                                                  int n_tasks, Epi epi) {
+  typedef typename ET<E>::vec vec;
+  extern __shared__ char lds_raw[];
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N, PER = 4;
+  constexpr int KID = Epi::ROWSUM ? 13 : 12;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int team = wave / DENSE_TASKS, rank = wave % DENSE_TASKS;
+  const int slot = blockIdx.x * DENSE_TASKS + rank, task = min(slot, n_tasks - 1);
+  const int tok0 = blockIdx.y * WT * TILE;
+  const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
+  const int chunks = ksteps / WKC / DENSE_KH;          // per team
+  const int ks0 = team * chunks * WKC;
+  vec* sb = reinterpret_cast<vec*>(lds_raw + team * wide_lds<E, KID, WT>());
+  const E* brow = B + (int64_t)ks0 * T * (NP * KS) + (int64_t)min(tok0 + (rank % WT) * TILE + col, T - 1) * (NP * KS) + half * G;
+  f32x16 acc0[WT], acc1[WT];
+  zero_acc<WT>(acc0);
+  zero_acc<WT>(acc1);
+  wide_stream<E, WT, DENSE_TASKS, DENSE_PRE, KID>(
+      W + (int64_t)task * task_stride_elems<E>(ksteps) + (int64_t)ks0 * (2 * WAVE * G) + lane * G, chunks, brow,
+      (int64_t)T * (NP * KS), sb, nt, acc0, acc1, rank);
+  if (DENSE_KH > 1) {
+    // fold: team h > 0 leaves its sums at red[h-1][rank][t*32 + tile*16 + v][lane], team 0 adds them up
+    float* red = reinterpret_cast<float*>(lds_raw);
+    __syncthreads();   // the staging areas are done with
+    if (team > 0) {
+      float* r = red + ((int64_t)((team - 1) * DENSE_TASKS + rank) * (2 * WT * 16)) * WAVE + lane;
+#pragma unroll
+      for (int t = 0; t < WT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          r[(t * 32 + v) * WAVE] = acc0[t][v];
+          r[(t * 32 + 16 + v) * WAVE] = acc1[t][v];
+        }
+    }
+    __syncthreads();
+    if (team > 0) return;
+    for (int h = 1; h < DENSE_KH; ++h) {
+      const float* r = red + ((int64_t)((h - 1) * DENSE_TASKS + rank) * (2 * WT * 16)) * WAVE + lane;
+#pragma unroll
+      for (int t = 0; t < WT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          acc0[t][v] += r[(t * 32 + v) * WAVE];
+          acc1[t][v] += r[(t * 32 + 16 + v) * WAVE];
+        }
+    }
+  }
+  if (slot >= n_tasks) return;
+  // Epilogue in three sweeps over the (tile, register group) pairs, so that the loads of one sweep are all in flight
+  // together: what is addressed by the token, what is addressed by what those loads return, then the arithmetic.
+  constexpr int NG = 16 / PER;
+  typename Epi::template Pre<PER> pre[WT][NG];
+#pragma unroll
+  for (int t = 0; t < WT; ++t)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int tok = tok0 + t * TILE + col;
+      pre[t][g] = epi.template prefetch<PER>(task, tok, t < nt && tok < T, half, g * PER);
+    }
+#pragma unroll
+  for (int t = 0; t < WT; ++t)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) epi.template prefetch2<PER>(pre[t][g], task, half, g * PER);
+#pragma unroll
+  for (int t = 0; t < WT; ++t) {
+    const int tok = tok0 + t * TILE + col;
+    const bool valid = t < nt && tok < T;
+    float ss = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      float a0[PER], a1[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        a0[i] = acc0[t][g * PER + i];
+        a1[i] = acc1[t][g * PER + i];
+      }
+      ss += epi.template apply<PER>(pre[t][g], task, tok, valid, half, g * PER, a0, a1);
+    }
+    if (Epi::ROWSUM) {   // the wave holds the whole task: the row statistic is the sum over its two half-waves
+      ss += __shfl_xor(ss, 32, WAVE);
+      if (half == 0 && valid) epi.row_sum(task, tok, ss);
+    }
+  }
+  TRACE_MARK(KID, 7);
+}
+
+// True when the dense form takes the call (many rows, K a whole number of staged chunks per team).
+static bool dense_applies(int T, int ksteps) { return T > 2 * TILE && ksteps % (WKC * DENSE_KH) == 0; }
+
+template <typename E, class Epi>
+static void launch_dense(const E* W, int ksteps, const E* B, int T, int n_tasks, const Epi& epi, hipStream_t st) {
+  constexpr int KID = Epi::ROWSUM ? 13 : 12;
+  constexpr int THREADS = DENSE_TASKS * DENSE_KH * WAVE;
+  const int tgroups = (n_tasks + DENSE_TASKS - 1) / DENSE_TASKS;
+  // more token tiles per workgroup cut the weight traffic of the L2, but only if the launch still fills the chip
+  if (tgroups * ((T + DENSE_WT * TILE - 1) / (DENSE_WT * TILE)) >= DENSE_FILL) {
+    gemm_dense_kernel<E, DENSE_WT, Epi><<<dim3(tgroups, (T + DENSE_WT * TILE - 1) / (DENSE_WT * TILE)), THREADS, dense_lds<E, KID, DENSE_WT>(), st>>>(
+        W, ksteps, B, T, n_tasks, epi);
+  } else {
+    gemm_dense_kernel<E, 1, Epi><<<dim3(tgroups, (T + TILE - 1) / TILE), THREADS, dense_lds<E, KID, 1>(), st>>>(
+        W, ksteps, B, T, n_tasks, epi);
+  }
+}
+
+template <typename E, class Epi> static bool configure_dense() {
+  return opt_in_lds((const void*)gemm_dense_kernel<E, DENSE_WT, Epi>) && opt_in_lds((const void*)gemm_dense_kernel<E, 1, Epi>);
+}
+
 template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipStream_t st) {
   const int D = a.geom.n_heads * a.geom.head_dim;
   QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
                 a.pt_stride, a.cos_tab, a.sin_tab, a.rinv, D};
-  launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, a.H, 3 * D / 64, a.part,
-                   a.tickets, epi, st);
+  if (dense_applies(a.T, a.H / ET<E>::KS))
+    launch_dense<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, 3 * D / 64, epi, st);
+  else
+    launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, a.H, 3 * D / 64, a.part,
+                     a.tickets, epi, st);
 }
 void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
   if (bf16) launch_qkv_t<bf16_t>(true, a, st);
@@ -394,8 +585,11 @@ void launch_qkv(bool bf16, const QkvArgs& a, hipStream_t st) {
 
 template <typename E> static void launch_oproj_t(bool bf16, const OprojArgs& a, hipStream_t st) {
   ResidualEpi<E> epi{a.x, a.H, a.gain, (E*)a.xn, a.ssq, a.T};
-  launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.T, a.D, a.H / 64, a.part, a.tickets,
-                   epi, st);
+  if (dense_applies(a.T, a.D / ET<E>::KS))
+    launch_dense<E>((const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.T, a.H / 64, epi, st);
+  else
+    launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.T, a.D, a.H / 64, a.part, a.tickets,
+                     epi, st);
 }
 void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
   if (bf16) launch_oproj_t<bf16_t>(true, a, st);
@@ -790,10 +984,17 @@ __global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __res
       }
     }
     if (row[t] < n_rows) {
+      if constexpr (PER == 4) {   // four consecutive features: one store per plane
+        f32x4 y;
 #pragma unroll
-      for (int i = 0; i < PER; ++i)
-        store_actk<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0 + i, half),
-                      silu_f(g[i] * r[t]) * (u[i] * r[t]));
+        for (int i = 0; i < 4; ++i) y[i] = silu_f(g[i] * r[t]) * (u[i] * r[t]);
+        store_actk4<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0, half), y);
+      } else {
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+          store_actk<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0 + i, half),
+                        silu_f(g[i] * r[t]) * (u[i] * r[t]));
+      }
     }
   }
   TRACE_MARK(4, 4);
@@ -1039,6 +1240,8 @@ bool configure_kernels() {
   bool ok = configure_ksplit<bf16_t, QkvEpi<bf16_t>>() && configure_ksplit<float, QkvEpi<float>>() &&
             configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>() &&
             configure_ksplit<bf16_t, SmoothEpi>() && configure_ksplit<float, SmoothEpi>();
+  ok = ok && configure_dense<bf16_t, QkvEpi<bf16_t>>() && configure_dense<float, QkvEpi<float>>() &&
+       configure_dense<bf16_t, ResidualEpi<bf16_t>>() && configure_dense<float, ResidualEpi<float>>();
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
   ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&

@@ -1,18 +1,15 @@
 // Many-token forms (more than 64 tokens in a forward) of the weight-streaming contractions: routed-expert
 // grouped GEMMs and the LM head.  With hundreds of token rows a wave that fetched its own activation operands
 // would pull several times more bytes through the L2 than it streams weights from HBM, so here a workgroup of
-// four waves shares them: the workgroup covers 128 token rows (four 32-row tiles) and four tasks (256 output
-// features), each wave streams the weights of one task for the whole K range, and the activation fragments of the
-// four token tiles go through LDS, staged chunk by chunk (wave w stages tile w) and double buffered, so that
-// every fragment is fetched once per workgroup.  The accumulators of a wave (64 features x 128 rows) stay in
-// registers for the whole K range: there is no split of K and no fold.
-#include "gemm.hpp"
+// eight waves shares them (wide_stream.hpp): the workgroup covers 128 token rows (four 32-row tiles) and eight
+// tasks (512 output features).  The accumulators of a wave (64 features x 128 rows) stay in registers for the
+// whole K range: there is no split of K and no fold.
 #include "kernels.hpp"
+#include "wide_stream.hpp"
 
 namespace dinfer {
 
 constexpr int WT = 4;      // token tiles per workgroup
-constexpr int WKC = 4;     // k-steps per staged chunk
 // Waves (= tasks) per workgroup and weight chunks in flight per wave.  Eight waves put two on every SIMD, so one
 // computes while the other waits for LDS or memory, and the activation fragments are shared by eight tasks.
 // (Measured at 512 tokens: four waves with the whole register file behind a six-chunk weight prefetch are slower
@@ -25,139 +22,7 @@ constexpr int EXPERT_WW = 8, EXPERT_PRE = 2;
 #define LM_PRE_N 2
 #endif
 constexpr int LM_WW = LM_WW_N, LM_PRE = LM_PRE_N;
-#ifndef LM_BF16_PLANES
-#define LM_BF16_PLANES 1
-#endif
-#ifndef LM_WIDE_NT
-#define LM_WIDE_NT 1          // LM-head weights with non-temporal loads
-#endif
 constexpr int XCDS = 8;      // accelerator dies, each with its own L2; workgroup i of a launch runs on die i % 8
-
-// Planes of the activations a kernel (by its trace id) feeds to the matrix cores.  The LM head with hundreds of
-// token rows is bound by the matrix cores, and its rounding error is not carried into later layers: it takes the
-// high bf16 plane only, that is activations rounded to bf16 as in the paper's arithmetic (bf16 inputs, float32
-// accumulation); the low plane would double its matrix work.  The expert GEMMs stay bound by their weight streams
-// and keep both planes (one plane: 7 % faster, but the error carried through 16 layers reaches the test bars).
-template <typename E, int KID> struct WidePlanes { static constexpr int N = Planes<E>::N; };
-template <> struct WidePlanes<bf16_t, 9> { static constexpr int N = LM_BF16_PLANES; };
-
-template <typename E, int KID> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * WidePlanes<E, KID>::N * WAVE * 16; }
-
-// Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow: the k-major
-// activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
-// sb: LDS [2][WKC][WT][planes][64] operand vectors.  NT: token tiles that hold rows.
-// Pipeline per chunk c: barrier; the fragments of chunk c+1 go from registers to LDS buffer (c+1)&1 and the
-// loads of chunk c+3 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
-// requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
-// around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
-// computes while the other waits at its barrier.
-template <typename E, int NT, int WW, int WPRE, int KID>
-__device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
-                                      int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
-                                      f32x16 (&acc1)[WT]) {
-  typedef typename ET<E>::vec vec;
-  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = WidePlanes<E, KID>::N;   // planes used; the rows hold Planes<E>::N
-  constexpr int64_t STEP = 2 * WAVE * G;
-  auto wload = [](const E* p) { return (KID == 9 && LM_WIDE_NT == 0) ? load16<E>(p) : load16_stream<E>(p); };
-  static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int last = n_chunks - 1;
-  TRACE_MARK(KID, 0);
-  constexpr int SKS = WKC * WT / WW;               // k-steps of a chunk this wave stages (of token tile wave % WT)
-  const int st = wave % WT, sk0 = (wave / WT) * SKS;
-  vec wa0[WPRE][WKC], wa1[WPRE][WKC];
-  vec bset[2][SKS][NP];                            // fragments of the next two chunks, on their way to LDS
-  auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
-  // Prologue, in the order the loop keeps: weights of chunk 0, fragments of chunk 0 (to LDS) and chunk 1 (to
-  // registers), then the weights of the following chunks -- so that waiting for the fragments at the top of an
-  // iteration never includes waiting for weights requested after them.
-#pragma unroll
-  for (int ks = 0; ks < WKC; ++ks) {
-    wa0[0][ks] = wload(wp + (int64_t)ks * STEP);
-    wa1[0][ks] = wload(wp + (int64_t)ks * STEP + WAVE * G);
-  }
-  {
-    vec b0[SKS][NP];
-    const int c1 = min(1, last), c2 = min(2, last);
-#pragma unroll
-    for (int ks = 0; ks < SKS; ++ks)
-#pragma unroll
-      for (int q = 0; q < NP; ++q) b0[ks][q] = load16<E>(brow + (int64_t)(sk0 + ks) * bkstride + q * KS);
-#pragma unroll
-    for (int ks = 0; ks < SKS; ++ks)
-#pragma unroll
-      for (int q = 0; q < NP; ++q) {
-        bset[1][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
-        bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
-      }
-#pragma unroll
-    for (int i = 1; i < WPRE; ++i) {
-      const int c = min(i, last);
-#pragma unroll
-      for (int ks = 0; ks < WKC; ++ks) {
-        wa0[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP);
-        wa1[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < SKS; ++ks)
-#pragma unroll
-      for (int q = 0; q < NP; ++q) sb_at(0, sk0 + ks, st, q) = b0[ks][q];
-  }
-  for (int c0 = 0; c0 < n_chunks; c0 += WPRE) {
-#pragma unroll
-    for (int i = 0; i < WPRE; ++i) {
-      const int c = c0 + i;
-      if (c < n_chunks) {   // uniform over the workgroup
-        __syncthreads();
-        if (c == 0) TRACE_MARK(KID, 1);
-        if (c == 1) TRACE_MARK(KID, 2);
-        if (c == 2) TRACE_MARK(KID, 3);
-        if (c == 16) TRACE_MARK(KID, 4);
-        if (c == 17) TRACE_MARK(KID, 5);
-        const int nb = (i + 1) & 1, cb = i & 1;   // c0 is even: parities of c+1 and c
-#pragma unroll
-        for (int ks = 0; ks < SKS; ++ks)
-#pragma unroll
-          for (int q = 0; q < NP; ++q) sb_at(nb, sk0 + ks, st, q) = bset[nb][ks][q];
-        const int cn = min(c + 3, last);
-#pragma unroll
-        for (int ks = 0; ks < SKS; ++ks)
-#pragma unroll
-          for (int q = 0; q < NP; ++q)
-            bset[nb][ks][q] = load16<E>(brow + (int64_t)(cn * WKC + sk0 + ks) * bkstride + q * KS);
-#pragma unroll
-        for (int ks = 0; ks < WKC; ++ks)
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int q = 0; q < NP; ++q) {
-              const vec b = sb_at(cb, ks, t, q);
-              mfma32(acc0[t], wa0[i][ks], b);
-              mfma32(acc1[t], wa1[i][ks], b);
-            }
-        const int cw = min(c + WPRE, last);
-#pragma unroll
-        for (int ks = 0; ks < WKC; ++ks) {
-          wa0[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP);
-          wa1[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP + WAVE * G);
-        }
-      }
-    }
-  }
-  TRACE_MARK(KID, 6);
-}
-
-// nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
-template <typename E, int WW, int WPRE, int KID>
-__device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
-                                   int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
-                                   f32x16 (&acc1)[WT]) {
-  if (nt >= 4) wide_stream_nt<E, 4, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 3) wide_stream_nt<E, 3, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else if (nt == 2) wide_stream_nt<E, 2, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-  else wide_stream_nt<E, 1, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1);
-}
 
 __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
 
@@ -202,7 +67,7 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(con
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, EXPERT_WW, EXPERT_PRE, 10>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, WT, EXPERT_WW, EXPERT_PRE, 10>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
   if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
@@ -210,9 +75,12 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(con
     const int row = row0 + t * TILE + col;
     if (t < nt && row < n_rows) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        store_actk<E>(Y, (int64_t)T * top_k, base + row, task * TILE + acc_row(v, half),
-                      silu_w(acc0[t][v] * r[t]) * (acc1[t][v] * r[t]));
+      for (int g = 0; g < 4; ++g) {   // accumulator registers 4g .. 4g+3 are four consecutive features
+        f32x4 y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[i] = silu_w(acc0[t][4 * g + i] * r[t]) * (acc1[t][4 * g + i] * r[t]);
+        store_actk4<E>(Y, (int64_t)T * top_k, base + row, task * TILE + acc_row(4 * g, half), y);
+      }
     }
   }
 }
@@ -243,7 +111,7 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, EXPERT_WW, EXPERT_PRE, 11>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
+  wide_stream<E, WT, EXPERT_WW, EXPERT_PRE, 11>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
                  (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
   if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
 #pragma unroll
@@ -268,13 +136,13 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.I / TILE;
   expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E, 10>(), st>>>(
+                                EXPERT_WW * WAVE, wide_lds<E, 10, WT>(), st>>>(
       (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.H / (2 * TILE);
   expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E, 11>(), st>>>(
+                                EXPERT_WW * WAVE, wide_lds<E, 11, WT>(), st>>>(
       (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.work, a.T * a.top_k, a.H, a.I);
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
@@ -322,7 +190,7 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, LM_WW, LM_PRE, 9>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+  wide_stream<E, WT, LM_WW, LM_PRE, 9>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
@@ -374,7 +242,7 @@ int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
-  lm_head_wide_kernel<E><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9>(), st>>>(
+  lm_head_wide_kernel<E><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
       (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {

@@ -1,0 +1,178 @@
+// Shared-operand weight streaming for forwards with many token rows: a workgroup of WW waves covers WW tasks
+// (64 output features each) and WT tiles of 32 token rows.  Each wave streams the weights of its task from memory
+// into registers for the whole K range; the activation fragments of the WT token tiles go through LDS, staged
+// chunk by chunk (WKC k-steps) and double buffered, so that every fragment is fetched once per workgroup.
+#pragma once
+#include <type_traits>
+
+#include "gemm.hpp"
+
+namespace dinfer {
+
+constexpr int WKC = 4;     // k-steps per staged chunk
+
+#ifndef LM_BF16_PLANES
+#define LM_BF16_PLANES 1
+#endif
+#ifndef LM_WIDE_NT
+#define LM_WIDE_NT 1          // LM-head weights with non-temporal loads
+#endif
+
+// Planes of the activations a kernel (by its trace id) feeds to the matrix cores.  The LM head with hundreds of
+// token rows is bound by the matrix cores, and its rounding error is not carried into later layers: it takes the
+// high bf16 plane only, that is activations rounded to bf16 as in the paper's arithmetic (bf16 inputs, float32
+// accumulation); the low plane would double its matrix work.  The expert GEMMs stay bound by their weight streams
+// and keep both planes (one plane: 7 % faster, but the error carried through 16 layers reaches the test bars).
+template <typename E, int KID> struct WidePlanes { static constexpr int N = Planes<E>::N; };
+template <> struct WidePlanes<bf16_t, 9> { static constexpr int N = LM_BF16_PLANES; };
+
+template <int N, class F, int I = 0> __device__ inline void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, F, I + 1>(static_cast<F&&>(f));
+  }
+}
+
+template <typename E, int KID, int WT> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * WidePlanes<E, KID>::N * WAVE * 16; }
+
+// Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow: the k-major
+// activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
+// sb: LDS [2][WKC][WT][planes][64] operand vectors.  NT: token tiles that hold rows.  wave: 0 .. WW-1, the
+// wave's rank among the WW waves that share sb (every wave of the workgroup must make the call: it holds the
+// workgroup's barriers).
+// Pipeline per chunk c: barrier; the fragments of chunk c+1 go from registers to LDS buffer (c+1)&1 and the
+// loads of chunk c+3 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
+// requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
+// around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
+// computes while the other waits at its barrier.
+template <typename E, int WT, int NT, int WW, int WPRE, int KID>
+__device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
+                                      int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
+                                      f32x16 (&acc1)[WT], int wave) {
+  typedef typename ET<E>::vec vec;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = WidePlanes<E, KID>::N;   // planes used; the rows hold Planes<E>::N
+  constexpr int64_t STEP = 2 * WAVE * G;
+  // Weights that are streamed once (experts, LM head) are loaded non-temporally; those of the dense projections
+  // (kernel ids 12, 13: a few MB that every token group reads again) must stay in the L2.
+  auto wload = [](const E* p) { return ((KID == 9 && LM_WIDE_NT == 0) || KID >= 12) ? load16<E>(p) : load16_stream<E>(p); };
+  static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
+  static_assert(WW % WT == 0 && (WKC * WT) % WW == 0, "every wave stages whole k-steps of one token tile");
+  const int lane = threadIdx.x & 63;
+  const int last = n_chunks - 1;
+  TRACE_MARK(KID, 0);
+  constexpr int SKS = WKC * WT / WW;               // k-steps of a chunk this wave stages (of token tile wave % WT)
+  const int st = wave % WT, sk0 = (wave / WT) * SKS;
+  vec wa0[WPRE][WKC], wa1[WPRE][WKC];
+  vec bset[2][SKS][NP];                            // fragments of the next two chunks, on their way to LDS
+  auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
+  // Prologue, in the order the loop keeps: weights of chunk 0, fragments of chunk 0 (to LDS) and chunk 1 (to
+  // registers), then the weights of the following chunks -- so that waiting for the fragments at the top of an
+  // iteration never includes waiting for weights requested after them.
+#pragma unroll
+  for (int ks = 0; ks < WKC; ++ks) {
+    wa0[0][ks] = wload(wp + (int64_t)ks * STEP);
+    wa1[0][ks] = wload(wp + (int64_t)ks * STEP + WAVE * G);
+  }
+  {
+    vec b0[SKS][NP];
+    const int c1 = min(1, last), c2 = min(2, last);
+#pragma unroll
+    for (int ks = 0; ks < SKS; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) b0[ks][q] = load16<E>(brow + (int64_t)(sk0 + ks) * bkstride + q * KS);
+#pragma unroll
+    for (int ks = 0; ks < SKS; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        bset[1][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
+        bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
+      }
+#pragma unroll
+    for (int i = 1; i < WPRE; ++i) {
+      const int c = min(i, last);
+#pragma unroll
+      for (int ks = 0; ks < WKC; ++ks) {
+        wa0[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP);
+        wa1[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < SKS; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) sb_at(0, sk0 + ks, st, q) = b0[ks][q];
+  }
+  // One chunk; i = c % WPRE picks the weight registers and the LDS buffer parities at compile time.
+  auto chunk = [&](auto I, int c) {
+    constexpr int i = decltype(I)::value;
+    __syncthreads();
+    if (c == 0) TRACE_MARK(KID, 1);
+    if (c == 1) TRACE_MARK(KID, 2);
+    if (c == 2) TRACE_MARK(KID, 3);
+    if (c == 16) TRACE_MARK(KID, 4);
+    if (c == 17) TRACE_MARK(KID, 5);
+    constexpr int nb = (i + 1) & 1, cb = i & 1;   // WPRE is even: parities of c+1 and c
+#pragma unroll
+    for (int ks = 0; ks < SKS; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) sb_at(nb, sk0 + ks, st, q) = bset[nb][ks][q];
+    const int cn = min(c + 3, last);
+#pragma unroll
+    for (int ks = 0; ks < SKS; ++ks)
+#pragma unroll
+      for (int q = 0; q < NP; ++q)
+        bset[nb][ks][q] = load16<E>(brow + (int64_t)(cn * WKC + sk0 + ks) * bkstride + q * KS);
+    // the fragments of k-step ks+1 are read from LDS before the matrix instructions of k-step ks are issued
+    vec bf[2][NT][NP];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) bf[0][t][q] = sb_at(cb, 0, t, q);
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks) {
+      if (ks + 1 < WKC) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int q = 0; q < NP; ++q) bf[(ks + 1) & 1][t][q] = sb_at(cb, ks + 1, t, q);
+      }
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int q = 0; q < NP; ++q) {
+          mfma32(acc0[t], wa0[i][ks], bf[ks & 1][t][q]);
+          mfma32(acc1[t], wa1[i][ks], bf[ks & 1][t][q]);
+        }
+    }
+    const int cw = min(c + WPRE, last);
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks) {
+      wa0[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP);
+      wa1[i][ks] = wload(wp + (int64_t)(cw * WKC + ks) * STEP + WAVE * G);
+    }
+  };
+  // Whole rounds of WPRE chunks run without a test between the chunks: a branch there gives the compiler a path from
+  // one chunk straight back to the loop top, for which it drains every load in flight at each iteration.
+  int c0 = 0;
+  for (; c0 + WPRE <= n_chunks; c0 += WPRE) static_for<WPRE>([&](auto I) { chunk(I, c0 + decltype(I)::value); });
+  static_for<WPRE - 1>([&](auto I) {
+    if (c0 + decltype(I)::value < n_chunks) chunk(I, c0 + decltype(I)::value);   // uniform over the workgroup
+  });
+  TRACE_MARK(KID, 6);
+}
+
+// nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
+template <typename E, int WT, int WW, int WPRE, int KID>
+__device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
+                                   int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
+                                   f32x16 (&acc1)[WT], int wave = threadIdx.x >> 6) {
+  if constexpr (WT >= 4) {
+    if (nt >= 4) return wide_stream_nt<E, WT, 4, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
+    if (nt == 3) return wide_stream_nt<E, WT, 3, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
+  }
+  if constexpr (WT >= 2) {
+    if (nt >= 2) return wide_stream_nt<E, WT, 2, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
+  }
+  wide_stream_nt<E, WT, 1, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
+}
+
+}  // namespace dinfer

@@ -36,13 +36,18 @@ def _variant(name):
         "deep": W("deep", sc(tiny, hidden=1024), 1, 32, 40, 40, threshold=0.9, seed_index=12),
         "deep_bf16": W("deep_bf16", sc(tiny, hidden=1024, dtype="bf16", logit_scale=1.0), 1, 64, 40, 40, threshold=0.9,
                        seed_index=13),
+        # 896 tokens and 48 QKV tasks: the many-token projections take two token tiles per workgroup
+        "dense2": W("dense2", sc(tiny, hidden=1024, n_heads=16, head_dim=64), 14, 64, 5, 40, threshold=0.9, seed_index=14),
+        "dense2_bf16": W("dense2_bf16", sc(tiny, hidden=1024, n_heads=16, head_dim=64, dtype="bf16", logit_scale=1.0), 14, 64,
+                         5, 40, threshold=0.9, seed_index=14),
         # no prefix at all: the block attends to itself only
         "noprefix": W("noprefix", tiny, 2, 32, 0, 0, threshold=0.9, seed_index=10),
     }
     return table[name]
 
 
-CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "noprefix"]
+CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "dense2", "dense2_bf16",
+         "noprefix"]
 
 
 class Case:
