@@ -1217,7 +1217,7 @@ static int lm_head_wgs(int V) {
 }
 // Partials per token row: upper bound (workspace sizing) and what a launch for T tokens writes.
 int lm_head_waves(int V) { return lm_head_wgs(V) * 4 > lm_head_wide_parts(V) ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
-int lm_head_parts(int V, int T) { return T <= 2 * TILE ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
+int lm_head_parts(int V, int T) { return T <= TILE ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
 
 template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
   const int wgs = lm_head_wgs(a.V);
@@ -1231,7 +1231,7 @@ template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
 }
 
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
-  if (a.T > 2 * TILE) return launch_lm_head_wide(bf16, a, st);
+  if (a.T > TILE) return launch_lm_head_wide(bf16, a, st);   // its 64-token form or its many-token form
   if (bf16) launch_lm_t<bf16_t>(a, st);
   else launch_lm_t<float>(a, st);
 }

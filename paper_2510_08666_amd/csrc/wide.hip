@@ -164,8 +164,8 @@ void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
 // of one task group, which then run side by side behind the same L2 (measured at 512 tokens: 0.88 GB fetched from
 // HBM per launch for 0.64 GB of weights, where four separate passes would fetch 2.6 GB).
 // ------------------------------------------------------------------------------------------------
-template <typename E>
-__global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+template <typename E, int WT, int KID, int WW>
+__global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                   const float* __restrict__ rinv, int T, int H, int V,
                                                                   float scale, float* __restrict__ part,
                                                                   float* __restrict__ logits_out) {
@@ -178,10 +178,10 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
   const int turn = blockIdx.x / XCDS;
   const int tgroup = (turn / groups) * XCDS + blockIdx.x % XCDS;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
-  if (tgroup * LM_WW >= n_tasks) return;   // uniform over the workgroup
+  if (tgroup * WW >= n_tasks) return;   // uniform over the workgroup
   const int tok0 = (turn % groups) * WT * TILE;
   const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
-  const int slot = tgroup * LM_WW + wave, task = min(slot, n_tasks - 1);
+  const int slot = tgroup * WW + wave, task = min(slot, n_tasks - 1);
   const int ksteps = H / KS;
   float zs[WT];
 #pragma unroll
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, WT, LM_WW, LM_PRE, 9>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+  wide_stream<E, WT, WW, LM_PRE, KID>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
@@ -239,10 +239,19 @@ __global__ __launch_bounds__(LM_WW * WAVE) void lm_head_wide_kernel(const E* __r
 
 int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_WW; }
 
+// Up to 64 tokens: two token tiles per workgroup and both activation planes (trace id 14): there the weight stream
+// is the bound, and sharing the activation fragments of eight tasks relieves the address unit, which would
+// otherwise take every lane's own activation row one by one.  More tokens: four tiles, high plane only (id 9).
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
-  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
+  if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
+    const int tgroups = lm_head_wide_parts(a.V) / 4;
+    lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
+        (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+    return;
+  }
   const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
-  lm_head_wide_kernel<E><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
+  const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
+  lm_head_wide_kernel<E, WT, 9, LM_WW><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
       (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
@@ -253,7 +262,7 @@ void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
 bool configure_wide() {
   const void* fns[6] = {(const void*)expert_gemm1_wide_kernel<bf16_t>, (const void*)expert_gemm1_wide_kernel<float>,
                         (const void*)expert_gemm2_wide_kernel<bf16_t>, (const void*)expert_gemm2_wide_kernel<float>,
-                        (const void*)lm_head_wide_kernel<bf16_t>,      (const void*)lm_head_wide_kernel<float>};
+                        (const void*)lm_head_wide_kernel<bf16_t, WT, 9, LM_WW>, (const void*)lm_head_wide_kernel<float, WT, 9, LM_WW>};
   for (const void* f : fns)
     if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) return false;
   return true;
