@@ -40,6 +40,9 @@ def _variant(name):
         "dense2": W("dense2", sc(tiny, hidden=1024, n_heads=16, head_dim=64), 14, 64, 5, 40, threshold=0.9, seed_index=14),
         "dense2_bf16": W("dense2_bf16", sc(tiny, hidden=1024, n_heads=16, head_dim=64, dtype="bf16", logit_scale=1.0), 14, 64,
                          5, 40, threshold=0.9, seed_index=14),
+        # the most sequences a call takes (64) with full blocks: 4096 tokens, experts with hundreds of rows (several row
+        # groups per expert in the many-token expert GEMMs), 32 token groups in the LM head
+        "max64": W("max64", tiny, 64, 64, 0, 70, precommit=True, threshold=0.9, seed_index=15),
         # no prefix at all: the block attends to itself only
         "noprefix": W("noprefix", tiny, 2, 32, 0, 0, threshold=0.9, seed_index=10),
     }
@@ -47,7 +50,7 @@ def _variant(name):
 
 
 CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "dense2", "dense2_bf16",
-         "noprefix"]
+         "max64", "noprefix"]
 
 
 class Case:
