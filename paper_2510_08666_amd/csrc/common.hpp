@@ -186,7 +186,8 @@ __device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int sl
 
 // Optional in-kernel phase timestamps (builds with -DDINFER_TRACE=<kernel id> only): thread 0 of every workgroup
 // of the chosen kernel stores the 100 MHz wall clock at each mark.  Kernel ids: 1 QKV, 2 O-proj, 3 router,
-// 4 expert GEMM 1, 5 expert GEMM 2, 6 LM head, 7 attention, 8 combine, 9 / 10 / 11 many-token LM head / expert GEMM 1 / expert GEMM 2.
+// 4 expert GEMM 1, 5 expert GEMM 2, 6 LM head, 7 attention, 8 combine, 9 / 10 / 11 many-token LM head / expert GEMM 1 /
+// expert GEMM 2, 12 / 13 many-token QKV / output projection, 14 LM head of 33 to 64 tokens.
 #ifdef DINFER_TRACE
 constexpr int TRACE_WGS = 8192, TRACE_SLOTS = 8;
 static __device__ unsigned long long g_trace[TRACE_WGS * TRACE_SLOTS];

@@ -440,16 +440,11 @@ template <typename E, class Epi> static bool configure_ksplit() {
 // Grid (task groups, token groups): with a multiple of eight task groups the workgroups of one die always take the
 // same tasks, so the weights (a few MB per die) are read from HBM once and then served by that die's L2.
 // ------------------------------------------------------------------------------------------------
-#ifndef DENSE_KH_N
-#define DENSE_KH_N 2
-#endif
-#ifndef DENSE_WT_BIG
-#define DENSE_WT_BIG 2
-#endif
-#ifndef DENSE_FILL
-#define DENSE_FILL 160
-#endif
-constexpr int DENSE_TASKS = 4, DENSE_PRE = 2, DENSE_KH = DENSE_KH_N, DENSE_WT = DENSE_WT_BIG;
+// Measured at 512 tokens (QKV / output projection, microseconds): one team 58 / 34, two teams 58 / 34 before and
+// 41 / 29 after the epilogue stores were widened, four teams of one token tile 94 / 37; four token tiles per
+// workgroup 102 / 95 (too few workgroups).
+constexpr int DENSE_TASKS = 4, DENSE_PRE = 2, DENSE_KH = 2, DENSE_WT = 2;
+constexpr int DENSE_FILL = 160;   // workgroups a launch with DENSE_WT token tiles must keep, else one tile each
 
 template <typename E, int KID, int WT> constexpr size_t dense_lds() {
   const size_t stage = DENSE_KH * wide_lds<E, KID, WT>();
@@ -478,7 +473,7 @@ __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kern
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
   wide_stream<E, WT, DENSE_TASKS, DENSE_PRE, KID>(
-      W + (int64_t)task * task_stride_elems<E>(ksteps) + (int64_t)ks0 * (2 * WAVE * G) + lane * G, chunks, brow,
+      W + (int64_t)task * task_stride_elems<E>(ksteps) + (int64_t)ks0 * (2 * WAVE * G) + lane * G, chunks, [&] { return brow; },
       (int64_t)T * (NP * KS), sb, nt, acc0, acc1, rank);
   if (DENSE_KH > 1) {
     // fold: team h > 0 leaves its sums at red[h-1][rank][t*32 + tile*16 + v][lane], team 0 adds them up
@@ -907,334 +902,12 @@ void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
   else launch_router_t<float>(false, a, st);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Routed experts.  Rows of expert e are the pairs perm[off[e] .. off[e]+cnt[e]) (pair = token*top_k + slot).
-// One workgroup of EKS waves per (expert, task, row group): the waves split K (a single wave walking a whole
-// 256 KiB task with 16 KiB in flight is latency bound at a few GB/s, which sets a floor of ~50 us under the
-// kernel however few experts are touched), partials are folded through LDS in wave order, and each wave
-// finishes a share of the accumulator registers.  Experts without rows sit at the end of the grid and exit.
-//   GEMM 1: task = 32 gate features + the same 32 up features; input = normalised-input planes of the token rows,
-//           scaled by the row's 1/rms in the epilogue;  y = silu(gate) * up   -> Y[sorted row][I] (hi / lo planes)
-//   GEMM 2: task = 64 adjacent output features of the down projection                  -> O[token*top_k + slot][H]
-// ------------------------------------------------------------------------------------------------
-__device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
-
-template <int TT> struct ExpertSplit { static constexpr int EKS = TT <= 2 ? 4 : 2; };
-template <int TT, int EKS> constexpr size_t expert_lds() { return (size_t)EKS * 2 * TT * 16 * WAVE * 4; }
-
-template <typename E, int TT, int EKS>
-__global__ __launch_bounds__(EKS * WAVE) void expert_gemm1_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                                   const float* __restrict__ rinv, E* __restrict__ Y,
-                                                                   const int32_t* __restrict__ cnt,
-                                                                   const int32_t* __restrict__ off,
-                                                                   const int32_t* __restrict__ perm, int T, int H, int I,
-                                                                   int top_k) {
-  extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
-  TRACE_MARK(4, 0);
-  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;   // uniform over the block
-  const int4 rec = *reinterpret_cast<const int4*>(off + ACTIVE_RECORDS + 4 * blockIdx.y);
-  const int e = rec.x, base = rec.y, n_rows = rec.z, group = blockIdx.z;
-  const int row0 = group * TT * TILE;
-  if (row0 >= n_rows) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int task = blockIdx.x;
-  const int n_tasks = I / TILE;
-  PlaneLoader<E, TT> ld;
-  int row[TT];
-  float r[TT];
-  // the token rows hang on the permutation: that chain is resolved while the first weights are in flight
-  auto prep = [&]() {
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-      row[t] = row0 + t * TILE + (lane & 31);
-      const int tok = perm[base + min(row[t], n_rows - 1)] / top_k;
-      ld.set(t, xn, T, tok, half);
-      r[t] = rinv[tok];
-    }
-  };
-  TRACE_MARK(4, 1);
-  f32x16 acc0[TT], acc1[TT];
-  zero_acc<TT>(acc0);
-  zero_acc<TT>(acc1);
-  const int ksteps = H / ET<E>::KS;
-  const int per = (ksteps + EKS - 1) / EKS;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
-                                        acc0, acc1, prep);
-  TRACE_MARK(4, 2);
-  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-  __syncthreads();
-  TRACE_MARK(4, 3);
-  const int v0 = wave * PER;
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    float g[PER], u[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      g[i] = 0.f;
-      u[i] = 0.f;
-    }
-    for (int w = 0; w < EKS; ++w) {
-      const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        g[i] += rp[i * WAVE];
-        u[i] += rp[(16 + i) * WAVE];
-      }
-    }
-    if (row[t] < n_rows) {
-      if constexpr (PER == 4) {   // four consecutive features: one store per plane
-        f32x4 y;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) y[i] = silu_f(g[i] * r[t]) * (u[i] * r[t]);
-        store_actk4<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0, half), y);
-      } else {
-#pragma unroll
-        for (int i = 0; i < PER; ++i)
-          store_actk<E>(Y, (int64_t)T * top_k, base + row[t], task * TILE + acc_row(v0 + i, half),
-                        silu_f(g[i] * r[t]) * (u[i] * r[t]));
-      }
-    }
-  }
-  TRACE_MARK(4, 4);
-}
-
-template <typename E, int TT, int EKS>
-__global__ __launch_bounds__(EKS * WAVE) void expert_gemm2_kernel(const E* __restrict__ W, const E* __restrict__ Y,
-                                                                   float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                                   const int32_t* __restrict__ off,
-                                                                   const int32_t* __restrict__ perm, int n_pairs, int H,
-                                                                   int I) {
-  extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
-  TRACE_MARK(5, 0);
-  if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return;
-  const int4 rec = *reinterpret_cast<const int4*>(off + ACTIVE_RECORDS + 4 * blockIdx.y);
-  const int e = rec.x, base = rec.y, n_rows = rec.z, group = blockIdx.z;
-  const int row0 = group * TT * TILE;
-  if (row0 >= n_rows) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int task = blockIdx.x;
-  const int n_tasks = H / (2 * TILE);
-  PlaneLoader<E, TT> ld;
-  int row[TT], pair[TT];   // pair = token * top_k + slot: the output row (token order, no indirection for the reader)
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    row[t] = row0 + t * TILE + (lane & 31);
-    pair[t] = perm[base + min(row[t], n_rows - 1)];
-    ld.set(t, Y, n_pairs, base + min(row[t], n_rows - 1), half);
-  }
-  f32x16 acc0[TT], acc1[TT];
-  zero_acc<TT>(acc0);
-  zero_acc<TT>(acc1);
-  const int ksteps = I / ET<E>::KS;
-  const int per = (ksteps + EKS - 1) / EKS;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps), ks0, ks1, ld,
-                                        acc0, acc1);
-  TRACE_MARK(5, 2);
-  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-  __syncthreads();
-  TRACE_MARK(5, 3);
-  const int v0 = wave * PER;
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    float a0[PER], a1[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      a0[i] = 0.f;
-      a1[i] = 0.f;
-    }
-    for (int w = 0; w < EKS; ++w) {
-      const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        a0[i] += rp[i * WAVE];
-        a1[i] += rp[(16 + i) * WAVE];
-      }
-    }
-    if (row[t] < n_rows) {
-      float* orow = O + (int64_t)pair[t] * H + (2 * task) * TILE;
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        orow[acc_row(v0 + i, half)] = a0[i];
-        orow[TILE + acc_row(v0 + i, half)] = a1[i];
-      }
-    }
-  }
-}
-
-template <typename E, int TT> static void launch_gate_up_t(const ExpertArgs& a, int groups, hipStream_t st) {
-  constexpr int EKS = ExpertSplit<TT>::EKS;
-  expert_gemm1_kernel<E, TT, EKS><<<dim3(a.I / TILE, a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.T, a.H, a.I, a.top_k);
-}
-template <typename E, int TT> static void launch_down_t(const ExpertArgs& a, int groups, hipStream_t st) {
-  constexpr int EKS = ExpertSplit<TT>::EKS;
-  expert_gemm2_kernel<E, TT, EKS><<<dim3(a.H / (2 * TILE), a.E, groups), EKS * WAVE, expert_lds<TT, EKS>(), st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.T * a.top_k, a.H, a.I);
-}
-template <typename E, int TT> static bool configure_experts() {
-  constexpr int EKS = ExpertSplit<TT>::EKS;
-  return opt_in_lds((const void*)expert_gemm1_kernel<E, TT, EKS>) && opt_in_lds((const void*)expert_gemm2_kernel<E, TT, EKS>);
-}
-
-// An expert can receive at most T rows (a token selects an expert at most once): T fixes the row tiling.  Past
-// 64 tokens the many-token forms take over.
-void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) {
-  if (a.T > 2 * TILE) return launch_expert_gate_up_wide(bf16, a, st);
-  if (a.T <= TILE) {
-    if (bf16) launch_gate_up_t<bf16_t, 1>(a, 1, st); else launch_gate_up_t<float, 1>(a, 1, st);
-  } else {
-    if (bf16) launch_gate_up_t<bf16_t, 2>(a, 1, st); else launch_gate_up_t<float, 2>(a, 1, st);
-  }
-}
-void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) {
-  if (a.T > 2 * TILE) return launch_expert_down_wide(bf16, a, st);
-  if (a.T <= TILE) {
-    if (bf16) launch_down_t<bf16_t, 1>(a, 1, st); else launch_down_t<float, 1>(a, 1, st);
-  } else {
-    if (bf16) launch_down_t<bf16_t, 2>(a, 1, st); else launch_down_t<float, 2>(a, 1, st);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// LM head fused with the confidence reduction.  Workgroups of EKS waves walk the tasks (64 vocabulary ids each):
-// K is split over the waves as in the expert GEMMs; after the fold each wave owns 16/EKS accumulator registers of
-// both tiles, i.e. a fixed subset of every task's ids for each token, over which it keeps the running maximum
-// logit, its lowest id and sum exp(z - max).  One (max, sum-exp, id) partial per (workgroup, wave, token) is
-// written at the end; logits are never stored (unless the debug pointer is set).
-// Input: normalised-input planes (final gain); logit = acc * (1/rms of the row) * logit_scale.
-// ------------------------------------------------------------------------------------------------
-template <typename E, int TT, int EKS>
-__global__ __launch_bounds__(EKS * WAVE) void lm_head_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                              const float* __restrict__ rinv, int T, int H, int V,
-                                                              float scale, float* __restrict__ part,
-                                                              float* __restrict__ logits_out) {
-  extern __shared__ float red[];   // [EKS][2*TT*16][64]
-  constexpr int ROWS = 2 * TT * 16, PER = 16 / EKS;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
-  const int group = blockIdx.y;
-  const int tok0 = group * TT * TILE;
-  const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
-  const int ksteps = H / ET<E>::KS;
-  PlaneLoader<E, TT> ld;
-  float m[TT], sum[TT], zs[TT];
-  int best[TT];
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    const int tok = min(tok0 + t * TILE + (lane & 31), T - 1);
-    ld.set(t, xn, T, tok, half);
-    zs[t] = rinv[tok] * scale;
-    m[t] = -INFINITY;
-    sum[t] = 0.f;
-    best[t] = 0x7fffffff;
-  }
-  const int per = (ksteps + EKS - 1) / EKS;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  const int v0 = wave * PER;
-  for (int task = blockIdx.x; task < n_tasks; task += gridDim.x) {
-    f32x16 acc0[TT], acc1[TT];
-    zero_acc<TT>(acc0);
-    zero_acc<TT>(acc1);
-    stream_task<E, TT, (TT == 1 ? 8 : 4)>(W + (int64_t)task * task_stride_elems<E>(ksteps), ks0, ks1, ld, acc0, acc1);
-    spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-      const int tok = tok0 + t * TILE + (lane & 31);
-      // this lane's 2*PER logits of the task, ids ascending
-      float z[2 * PER];
-      int id[2 * PER];
-#pragma unroll
-      for (int i = 0; i < 2 * PER; ++i) z[i] = 0.f;
-      for (int w = 0; w < EKS; ++w) {
-        const float* rp = red + ((int64_t)w * ROWS + t * 32 + v0) * WAVE + lane;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          z[i] += rp[i * WAVE];
-          z[PER + i] += rp[(16 + i) * WAVE];
-        }
-      }
-      float tm = -INFINITY;
-      int ti = 0x7fffffff;
-#pragma unroll
-      for (int i = 0; i < 2 * PER; ++i) {
-        id[i] = (2 * task + (i >= PER)) * TILE + acc_row(v0 + (i % PER), half);
-        z[i] = id[i] < V ? z[i] * zs[t] : -INFINITY;
-        if (z[i] > tm) {          // ids ascend with i, so strict '>' keeps the lowest id
-          tm = z[i];
-          ti = id[i];
-        }
-      }
-      if (logits_out && tok < T) {
-#pragma unroll
-        for (int i = 0; i < 2 * PER; ++i)
-          if (id[i] < V) logits_out[(int64_t)tok * V + id[i]] = z[i];
-      }
-      if (tm > m[t] || (tm == m[t] && ti < best[t])) {
-        sum[t] *= __expf(m[t] - tm);      // exp(-inf) = 0 on the first task
-        m[t] = tm;
-        best[t] = ti;
-      }
-      if (m[t] > -INFINITY) {
-#pragma unroll
-        for (int i = 0; i < 2 * PER; ++i) sum[t] += __expf(z[i] - m[t]);
-      }
-    }
-    __syncthreads();   // the partials are consumed: the next task may overwrite them
-  }
-#pragma unroll
-  for (int t = 0; t < TT; ++t) {
-    // fold the two half-waves (same token, other rows)
-    const float om = __shfl_xor(m[t], 32, WAVE), os = __shfl_xor(sum[t], 32, WAVE);
-    const int ob = __shfl_xor(best[t], 32, WAVE);
-    float M = m[t], S = sum[t];
-    int B = best[t];
-    if (om > M || (om == M && ob < B)) {
-      S = (M > -INFINITY ? S * __expf(M - om) : 0.f) + os;
-      M = om;
-      B = ob;
-    } else if (om > -INFINITY) {
-      S += os * __expf(om - M);
-    }
-    const int tok = tok0 + t * TILE + (lane & 31);
-    if (half == 0 && tok < T) {
-      float* p = part + ((int64_t)(blockIdx.x * EKS + wave) * T + tok) * 4;
-      p[0] = M;
-      p[1] = S;
-      p[2] = __int_as_float(B);
-      p[3] = 0.f;
-    }
-  }
-}
-
-// Workgroups along the vocabulary: about three per compute unit, never more than tasks.
-static int lm_head_wgs(int V) {
-  const int n_tasks = (V + 63) / 64;
-  return n_tasks < 768 ? n_tasks : 768;
-}
-// Partials per token row: upper bound (workspace sizing) and what a launch for T tokens writes.
-int lm_head_waves(int V) { return lm_head_wgs(V) * 4 > lm_head_wide_parts(V) ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
-int lm_head_parts(int V, int T) { return T <= TILE ? lm_head_wgs(V) * 4 : lm_head_wide_parts(V); }
-
-template <typename E> static void launch_lm_t(const LmArgs& a, hipStream_t st) {
-  const int wgs = lm_head_wgs(a.V);
-  if (a.T <= 32) {
-    lm_head_kernel<E, 1, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<1, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
-                                                                              a.scale, a.part, a.logits_out);
-  } else {
-    lm_head_kernel<E, 2, 4><<<dim3(wgs, 1), 4 * WAVE, expert_lds<2, 4>(), st>>>((const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V,
-                                                                              a.scale, a.part, a.logits_out);
-  }
-}
-
-void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) {
-  if (a.T > TILE) return launch_lm_head_wide(bf16, a, st);   // its 64-token form or its many-token form
-  if (bf16) launch_lm_t<bf16_t>(a, st);
-  else launch_lm_t<float>(a, st);
-}
+// The routed-expert GEMMs and the LM head live in wide.hip (shared-operand forms for every token count).
+void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) { launch_expert_gate_up_wide(bf16, a, st); }
+void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { launch_expert_down_wide(bf16, a, st); }
+int lm_head_waves(int V) { return lm_head_wide_parts(V); }
+int lm_head_parts(int V, int) { return lm_head_wide_parts(V); }
+void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st) { launch_lm_head_wide(bf16, a, st); }
 
 bool configure_kernels() {
   bool ok = configure_ksplit<bf16_t, QkvEpi<bf16_t>>() && configure_ksplit<float, QkvEpi<float>>() &&
@@ -1244,10 +917,6 @@ bool configure_kernels() {
        configure_dense<bf16_t, ResidualEpi<bf16_t>>() && configure_dense<float, ResidualEpi<float>>();
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
-  ok = ok && opt_in_lds((const void*)lm_head_kernel<bf16_t, 1, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 1, 4>) &&
-       opt_in_lds((const void*)lm_head_kernel<bf16_t, 2, 4>) && opt_in_lds((const void*)lm_head_kernel<float, 2, 4>);
-  ok = ok && configure_experts<bf16_t, 1>() && configure_experts<bf16_t, 2>() && configure_experts<float, 1>() &&
-       configure_experts<float, 2>();
   (void)hipGetLastError();
   return ok;
 }

@@ -49,16 +49,10 @@ template <typename E, int TT> struct PlaneLoader {
 
 // Software-pipelined core: PF k-steps of loads are always in flight.  The loop body is straight-line (no
 // predicated loads), so the compiler can count outstanding loads exactly and every MFMA waits only for its own
-// operands; n must be a positive multiple of PF.  `prep` runs after the first PF k-steps of WEIGHT loads have been
-// issued and before the first activation load: a caller whose activation addresses hang on a chain of dependent
-// loads (expert -> row range -> permutation -> token) finishes that chain there, with the weight stream already
-// under way.
-struct NoPrep {
-  __device__ void operator()() const {}
-};
-template <typename E, int TT, int PF, class Loader, class Prep>
+// operands; n must be a positive multiple of PF.
+template <typename E, int TT, int PF, class Loader>
 __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks0, int n, f32x16 (&acc0)[TT],
-                                    f32x16 (&acc1)[TT], Prep& prep) {
+                                    f32x16 (&acc1)[TT]) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, NP = Planes<E>::N;
   constexpr int64_t STEP = 2 * WAVE * G;   // elements of packed weights per k-step
@@ -69,7 +63,6 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
     a0[i] = load16<E>(wp + i * STEP);
     a1[i] = load16<E>(wp + i * STEP + WAVE * G);
   }
-  prep();
 #pragma unroll
   for (int i = 0; i < PF; ++i)
 #pragma unroll
@@ -110,26 +103,17 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
 
 // Accumulate k-steps [ks0, ks1) of one task for TT token tiles; wtask = packed weights of the task (k-step 0).
 // The prefetch depth follows the step count (a wave-uniform choice): PFMAX when it divides, else 4, else 1.
-template <typename E, int TT, int PFMAX, class Loader, class Prep>
+template <typename E, int TT, int PFMAX, class Loader>
 __device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, Loader& ld, f32x16 (&acc0)[TT],
-                                   f32x16 (&acc1)[TT], Prep& prep) {
+                                   f32x16 (&acc1)[TT]) {
   constexpr int G = ET<E>::G;
   const int lane = threadIdx.x & (WAVE - 1);
   const E* wp = wtask + (int64_t)ks0 * (2 * WAVE * G) + lane * G;
   const int n = ks1 - ks0;
-  if (n <= 0) {
-    prep();
-    return;
-  }
-  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, ld, ks0, n, acc0, acc1, prep);
-  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, ld, ks0, n, acc0, acc1, prep);
-  else stream_steps<E, TT, 1>(wp, ld, ks0, n, acc0, acc1, prep);
-}
-template <typename E, int TT, int PFMAX, class Loader>
-__device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, Loader& ld, f32x16 (&acc0)[TT],
-                                   f32x16 (&acc1)[TT]) {
-  NoPrep none;
-  stream_task<E, TT, PFMAX>(wtask, ks0, ks1, ld, acc0, acc1, none);
+  if (n <= 0) return;
+  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, ld, ks0, n, acc0, acc1);
+  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, ld, ks0, n, acc0, acc1);
+  else stream_steps<E, TT, 1>(wp, ld, ks0, n, acc0, acc1);
 }
 
 template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {

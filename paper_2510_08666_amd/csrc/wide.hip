@@ -1,27 +1,22 @@
-// Many-token forms (more than 64 tokens in a forward) of the weight-streaming contractions: routed-expert
-// grouped GEMMs and the LM head.  With hundreds of token rows a wave that fetched its own activation operands
-// would pull several times more bytes through the L2 than it streams weights from HBM, so here a workgroup of
-// eight waves shares them (wide_stream.hpp): the workgroup covers 128 token rows (four 32-row tiles) and eight
-// tasks (512 output features).  The accumulators of a wave (64 features x 128 rows) stay in registers for the
-// whole K range: there is no split of K and no fold.
+// The weight-streaming contractions with the most bytes: routed-expert grouped GEMMs and the LM head, in the
+// shared-operand form of wide_stream.hpp for every token count.  A workgroup takes a few tasks (64 output features
+// each) and 1, 2 or 4 tiles of 32 token rows; each wave streams the whole K range of one task and keeps its
+// accumulators in registers (no split of K, no fold), and the activation fragments go through LDS once per
+// workgroup.  With hundreds of token rows a wave that fetched its own activation operands would pull several
+// times more bytes through the L2 than it streams weights from HBM; with few rows it still keeps the compute
+// unit's address path busy with 64 separate rows per load.  Above 64 tokens: 8 tasks x 128 rows per workgroup.
 #include "kernels.hpp"
 #include "wide_stream.hpp"
 
 namespace dinfer {
 
-constexpr int WT = 4;      // token tiles per workgroup
+constexpr int WT = 4;      // token tiles per workgroup above 64 tokens
 // Waves (= tasks) per workgroup and weight chunks in flight per wave.  Eight waves put two on every SIMD, so one
 // computes while the other waits for LDS or memory, and the activation fragments are shared by eight tasks.
-// (Measured at 512 tokens: four waves with the whole register file behind a six-chunk weight prefetch are slower
-// for the expert GEMMs, 173 against 141 microseconds.)
+// (Measured at 512 tokens: four waves with two, four or six weight chunks in flight are slower for the expert
+// GEMMs, 131 to 134 against 120 microseconds; four waves in the LM head, 450 against 352.)
 constexpr int EXPERT_WW = 8, EXPERT_PRE = 2;
-#ifndef LM_WW_N
-#define LM_WW_N 8
-#endif
-#ifndef LM_PRE_N
-#define LM_PRE_N 2
-#endif
-constexpr int LM_WW = LM_WW_N, LM_PRE = LM_PRE_N;
+constexpr int LM_WW = 8, LM_PRE = 2;
 constexpr int XCDS = 8;      // accelerator dies, each with its own L2; workgroup i of a launch runs on die i % 8
 
 __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
@@ -32,44 +27,66 @@ __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
 //   GEMM 1: task = 32 gate features + the same 32 up features;  y = silu(gate) * up  -> Y[sorted row][I]
 //   GEMM 2: task = 64 adjacent output features of the down projection                -> O[token*top_k + slot][H]
 // ------------------------------------------------------------------------------------------------
-template <typename E>
-__global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                                       const float* __restrict__ rinv,
-                                                                       E* __restrict__ Y, const int32_t* __restrict__ cnt,
-                                                                       const int32_t* __restrict__ off,
-                                                                       const int32_t* __restrict__ perm,
-                                                                       const int32_t* __restrict__ work, int T, int H,
-                                                                       int I, int top_k) {
+// What a workgroup of the expert GEMMs works on.  RECORDS: the y-th expert with rows, from the records the router's
+// fused permutation leaves (at most 64 tokens, one row group per expert); otherwise the y-th item of the work list.
+struct ExpertItem {
+  int e, base, n_rows, row0;
+};
+template <int WT, bool RECORDS>
+__device__ inline bool expert_item(const int32_t* __restrict__ cnt, const int32_t* __restrict__ off,
+                                   const int32_t* __restrict__ work, ExpertItem& it) {
+  if constexpr (RECORDS) {
+    if ((int)blockIdx.y >= off[ACTIVE_LIST + MAX_EXPERTS]) return false;   // uniform over the block
+    const int4 rec = *reinterpret_cast<const int4*>(off + ACTIVE_RECORDS + 4 * blockIdx.y);
+    it = ExpertItem{rec.x, rec.y, rec.z, 0};
+  } else {
+    if ((int)blockIdx.y >= work[0]) return false;
+    const int item = work[1 + blockIdx.y], e = item >> 16;
+    it = ExpertItem{e, off[e], cnt[e], (item & 0xffff) * WT * TILE};
+  }
+  return true;
+}
+
+template <typename E, int WT, int WW, int KID, bool RECORDS>
+__global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+                                                                      const float* __restrict__ rinv, E* __restrict__ Y,
+                                                                      const int32_t* __restrict__ cnt,
+                                                                      const int32_t* __restrict__ off,
+                                                                      const int32_t* __restrict__ perm,
+                                                                      const int32_t* __restrict__ work, int T, int H, int I,
+                                                                      int top_k) {
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
-  if ((int)blockIdx.y >= work[0]) return;   // uniform over the block
-  const int item = work[1 + blockIdx.y], e = item >> 16;
-  const int n_rows = cnt[e], row0 = (item & 0xffff) * WT * TILE;
+  ExpertItem it;
+  if (!expert_item<WT, RECORDS>(cnt, off, work, it)) return;
+  const int e = it.e, base = it.base, n_rows = it.n_rows, row0 = it.row0;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int n_tasks = I / TILE, task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
-  const int base = off[e];
+  const int n_tasks = I / TILE, task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
   const int ksteps = H / KS;
-  int tok[WT];
   float r[WT];
+  // the token rows hang on the permutation: that chain is resolved while the first weights are in flight
+  auto brow = [&]() {
+    int tok[WT];
 #pragma unroll
-  for (int t = 0; t < WT; ++t) {
-    tok[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)] / top_k;
-    r[t] = rinv[tok[t]];
-  }
-  int stage_tok = tok[0];
+    for (int t = 0; t < WT; ++t) {
+      tok[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)] / top_k;
+      r[t] = rinv[tok[t]];
+    }
+    int stage_tok = tok[0];
 #pragma unroll
-  for (int t = 1; t < WT; ++t)
-    if (wave % WT == t) stage_tok = tok[t];
-  const E* brow = xn + (int64_t)stage_tok * (NP * KS) + half * G;
+    for (int t = 1; t < WT; ++t)
+      if (wave % WT == t) stage_tok = tok[t];
+    return xn + (int64_t)stage_tok * (NP * KS) + half * G;
+  };
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, WT, EXPERT_WW, EXPERT_PRE, 10>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
-                 (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
-  if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
+  wide_stream<E, WT, WW, EXPERT_PRE, KID>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G,
+                                          ksteps / WKC, brow, (int64_t)T * (NP * KS), sb, nt, acc0, acc1);
+  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
     const int row = row0 + t * TILE + col;
@@ -85,35 +102,34 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm1_wide_kernel(con
   }
 }
 
-template <typename E>
-__global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
-                                                                       float* __restrict__ O, const int32_t* __restrict__ cnt,
-                                                                       const int32_t* __restrict__ off,
-                                                                       const int32_t* __restrict__ perm,
-                                                                       const int32_t* __restrict__ work, int n_pairs,
-                                                                       int H, int I) {
+template <typename E, int WT, int WW, int KID, bool RECORDS>
+__global__ __launch_bounds__(WW * WAVE) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+                                                                      float* __restrict__ O, const int32_t* __restrict__ cnt,
+                                                                      const int32_t* __restrict__ off,
+                                                                      const int32_t* __restrict__ perm,
+                                                                      const int32_t* __restrict__ work, int n_pairs, int H,
+                                                                      int I) {
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
-  if ((int)blockIdx.y >= work[0]) return;
-  const int item = work[1 + blockIdx.y], e = item >> 16;
-  const int n_rows = cnt[e], row0 = (item & 0xffff) * WT * TILE;
+  ExpertItem it;
+  if (!expert_item<WT, RECORDS>(cnt, off, work, it)) return;
+  const int e = it.e, base = it.base, n_rows = it.n_rows, row0 = it.row0;
   const int nt = min(WT, (n_rows - row0 + TILE - 1) / TILE);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * EXPERT_WW + wave, n_tasks - 1);
-  const int base = off[e];
+  const int n_tasks = H / (2 * TILE), task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
   const int ksteps = I / KS;
   int pair[WT];
 #pragma unroll
-  for (int t = 0; t < WT; ++t) pair[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)];
-  const E* brow = Y + (int64_t)(base + min(row0 + (wave % WT) * TILE + col, n_rows - 1)) * (NP * KS) + half * G;
+  for (int t = 0; t < WT; ++t) pair[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)];   // for the epilogue
+  auto brow = [&]() { return Y + (int64_t)(base + min(row0 + (wave % WT) * TILE + col, n_rows - 1)) * (NP * KS) + half * G; };
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, WT, EXPERT_WW, EXPERT_PRE, 11>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow,
-                 (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
-  if ((int)blockIdx.x * EXPERT_WW + wave >= n_tasks) return;
+  wide_stream<E, WT, WW, EXPERT_PRE, KID>(W + ((int64_t)e * n_tasks + task) * task_stride_elems<E>(ksteps) + lane * G,
+                                          ksteps / WKC, brow, (int64_t)n_pairs * (NP * KS), sb, nt, acc0, acc1);
+  if ((int)blockIdx.x * WW + wave >= n_tasks) return;
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
     if (t < nt && row0 + t * TILE + col < n_rows) {
@@ -133,17 +149,46 @@ __global__ __launch_bounds__(EXPERT_WW * WAVE) void expert_gemm2_wide_kernel(con
   }
 }
 
+// Up to 32 / 64 tokens: one / two token tiles and SMALL_WW tasks per workgroup, experts from the router's records
+// (trace ids 16 .. 19); more: four tiles, eight tasks, the work list of the permutation kernel (ids 10, 11).
+// (Measured, gate/up + down in microseconds: two tasks 69.8 + 37.6 at 32 tokens and 86.6 + 49.2 at 64; four tasks
+// 68.9 + 38.9 and 88.1 + 50.7; the earlier per-wave-operand kernels, whose four waves split K, 72.9 + 38.6 and
+// 100.5 + 55.2.)
+constexpr int SMALL_WW = 2;
+
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.I / TILE;
-  expert_gemm1_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E, 10, WT>(), st>>>(
-      (const E*)a.w_gate_up, (const E*)a.xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+  const E *w = (const E*)a.w_gate_up, *xn = (const E*)a.xn;
+  if (a.T <= TILE) {
+    expert_gemm1_wide_kernel<E, 1, SMALL_WW, 16, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
+                                                         wide_lds<E, 16, 1>(), st>>>(
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+  } else if (a.T <= 2 * TILE) {
+    expert_gemm1_wide_kernel<E, 2, SMALL_WW, 17, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
+                                                         wide_lds<E, 17, 2>(), st>>>(
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+  } else {
+    expert_gemm1_wide_kernel<E, WT, EXPERT_WW, 10, false>
+        <<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)), EXPERT_WW * WAVE,
+           wide_lds<E, 10, WT>(), st>>>(w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+  }
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
-  const int n_tasks = a.H / (2 * TILE);
-  expert_gemm2_wide_kernel<E><<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)),
-                                EXPERT_WW * WAVE, wide_lds<E, 11, WT>(), st>>>(
-      (const E*)a.w_down, (const E*)a.y, a.o, a.cnt, a.off, a.perm, a.work, a.T * a.top_k, a.H, a.I);
+  const int n_tasks = a.H / (2 * TILE), n_pairs = a.T * a.top_k;
+  const E *w = (const E*)a.w_down, *y = (const E*)a.y;
+  if (a.T <= TILE) {
+    expert_gemm2_wide_kernel<E, 1, SMALL_WW, 18, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
+                                                         wide_lds<E, 18, 1>(), st>>>(
+        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+  } else if (a.T <= 2 * TILE) {
+    expert_gemm2_wide_kernel<E, 2, SMALL_WW, 19, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
+                                                         wide_lds<E, 19, 2>(), st>>>(
+        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+  } else {
+    expert_gemm2_wide_kernel<E, WT, EXPERT_WW, 11, false>
+        <<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, n_pairs)), EXPERT_WW * WAVE,
+           wide_lds<E, 11, WT>(), st>>>(w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+  }
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
   if (bf16) launch_gate_up_wide_t<bf16_t>(a, st);
@@ -190,7 +235,7 @@ __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __rest
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
-  wide_stream<E, WT, WW, LM_PRE, KID>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, brow, (int64_t)T * (NP * KS),
+  wide_stream<E, WT, WW, LM_PRE, KID>(W + (int64_t)task * task_stride_elems<E>(ksteps) + lane * G, ksteps / WKC, [&] { return brow; }, (int64_t)T * (NP * KS),
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
@@ -243,6 +288,12 @@ int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_
 // is the bound, and sharing the activation fragments of eight tasks relieves the address unit, which would
 // otherwise take every lane's own activation row one by one.  More tokens: four tiles, high plane only (id 9).
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
+  if (a.T <= TILE) {   // one token tile (trace id 15)
+    const int tgroups = lm_head_wide_parts(a.V) / 4;
+    lm_head_wide_kernel<E, 1, 15, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 15, 1>(), st>>>(
+        (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+    return;
+  }
   if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
@@ -260,8 +311,10 @@ void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
 }
 
 bool configure_wide() {
-  const void* fns[6] = {(const void*)expert_gemm1_wide_kernel<bf16_t>, (const void*)expert_gemm1_wide_kernel<float>,
-                        (const void*)expert_gemm2_wide_kernel<bf16_t>, (const void*)expert_gemm2_wide_kernel<float>,
+  const void* fns[6] = {(const void*)expert_gemm1_wide_kernel<bf16_t, WT, EXPERT_WW, 10, false>,
+                        (const void*)expert_gemm1_wide_kernel<float, WT, EXPERT_WW, 10, false>,
+                        (const void*)expert_gemm2_wide_kernel<bf16_t, WT, EXPERT_WW, 11, false>,
+                        (const void*)expert_gemm2_wide_kernel<float, WT, EXPERT_WW, 11, false>,
                         (const void*)lm_head_wide_kernel<bf16_t, WT, 9, LM_WW>, (const void*)lm_head_wide_kernel<float, WT, 9, LM_WW>};
   for (const void* f : fns)
     if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) return false;

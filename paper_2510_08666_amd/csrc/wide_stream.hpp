@@ -11,12 +11,6 @@ namespace dinfer {
 
 constexpr int WKC = 4;     // k-steps per staged chunk
 
-#ifndef LM_BF16_PLANES
-#define LM_BF16_PLANES 1
-#endif
-#ifndef LM_WIDE_NT
-#define LM_WIDE_NT 1          // LM-head weights with non-temporal loads
-#endif
 
 // Planes of the activations a kernel (by its trace id) feeds to the matrix cores.  The LM head with hundreds of
 // token rows is bound by the matrix cores, and its rounding error is not carried into later layers: it takes the
@@ -24,7 +18,7 @@ constexpr int WKC = 4;     // k-steps per staged chunk
 // accumulation); the low plane would double its matrix work.  The expert GEMMs stay bound by their weight streams
 // and keep both planes (one plane: 7 % faster, but the error carried through 16 layers reaches the test bars).
 template <typename E, int KID> struct WidePlanes { static constexpr int N = Planes<E>::N; };
-template <> struct WidePlanes<bf16_t, 9> { static constexpr int N = LM_BF16_PLANES; };
+template <> struct WidePlanes<bf16_t, 9> { static constexpr int N = 1; };
 
 template <int N, class F, int I = 0> __device__ inline void static_for(F&& f) {
   if constexpr (I < N) {
@@ -35,8 +29,8 @@ template <int N, class F, int I = 0> __device__ inline void static_for(F&& f) {
 
 template <typename E, int KID, int WT> constexpr size_t wide_lds() { return (size_t)2 * WKC * WT * WidePlanes<E, KID>::N * WAVE * 16; }
 
-// Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow: the k-major
-// activation row this lane stages (row of token tile `wave`) + (lane / 32) * G; bkstride: its k-step stride.
+// Accumulate all n_chunks * WKC k-steps.  wp: this wave's task (k-step 0) + lane * G.  brow_of(): the k-major
+// activation row this lane stages (row of token tile `wave % WT`) + (lane / 32) * G; bkstride: its k-step stride.
 // sb: LDS [2][WKC][WT][planes][64] operand vectors.  NT: token tiles that hold rows.  wave: 0 .. WW-1, the
 // wave's rank among the WW waves that share sb (every wave of the workgroup must make the call: it holds the
 // workgroup's barriers).
@@ -45,16 +39,15 @@ template <typename E, int KID, int WT> constexpr size_t wide_lds() { return (siz
 // requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
 // around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
 // computes while the other waits at its barrier.
-template <typename E, int WT, int NT, int WW, int WPRE, int KID>
-__device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
-                                      int64_t bkstride, typename ET<E>::vec* sb, f32x16 (&acc0)[WT],
-                                      f32x16 (&acc1)[WT], int wave) {
+template <typename E, int WT, int NT, int WW, int WPRE, int KID, class BRow>
+__device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BRow&& brow_of, int64_t bkstride,
+                                      typename ET<E>::vec* sb, f32x16 (&acc0)[WT], f32x16 (&acc1)[WT], int wave) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = WidePlanes<E, KID>::N;   // planes used; the rows hold Planes<E>::N
   constexpr int64_t STEP = 2 * WAVE * G;
   // Weights that are streamed once (experts, LM head) are loaded non-temporally; those of the dense projections
   // (kernel ids 12, 13: a few MB that every token group reads again) must stay in the L2.
-  auto wload = [](const E* p) { return ((KID == 9 && LM_WIDE_NT == 0) || KID >= 12) ? load16<E>(p) : load16_stream<E>(p); };
+  auto wload = [](const E* p) { return (KID == 12 || KID == 13) ? load16<E>(p) : load16_stream<E>(p); };
   static_assert(WPRE % 2 == 0, "buffer parities are taken from the unrolled index");
   static_assert(WW % WT == 0 && (WKC * WT) % WW == 0, "every wave stages whole k-steps of one token tile");
   const int lane = threadIdx.x & 63;
@@ -65,14 +58,19 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
   vec wa0[WPRE][WKC], wa1[WPRE][WKC];
   vec bset[2][SKS][NP];                            // fragments of the next two chunks, on their way to LDS
   auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
-  // Prologue, in the order the loop keeps: weights of chunk 0, fragments of chunk 0 (to LDS) and chunk 1 (to
-  // registers), then the weights of the following chunks -- so that waiting for the fragments at the top of an
-  // iteration never includes waiting for weights requested after them.
+  // Prologue: the weights of the first WPRE chunks are requested before anything else, since they hang on nothing;
+  // brow_of() then resolves the activation row this lane stages (for the experts a chain of dependent loads through
+  // the permutation), and the fragments of chunks 0 (to LDS), 1 and 2 (to registers) follow.
 #pragma unroll
-  for (int ks = 0; ks < WKC; ++ks) {
-    wa0[0][ks] = wload(wp + (int64_t)ks * STEP);
-    wa1[0][ks] = wload(wp + (int64_t)ks * STEP + WAVE * G);
+  for (int i = 0; i < WPRE; ++i) {
+    const int c = min(i, last);
+#pragma unroll
+    for (int ks = 0; ks < WKC; ++ks) {
+      wa0[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP);
+      wa1[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
+    }
   }
+  const E* __restrict__ brow = brow_of();
   {
     vec b0[SKS][NP];
     const int c1 = min(1, last), c2 = min(2, last);
@@ -87,15 +85,6 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
         bset[1][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
         bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
       }
-#pragma unroll
-    for (int i = 1; i < WPRE; ++i) {
-      const int c = min(i, last);
-#pragma unroll
-      for (int ks = 0; ks < WKC; ++ks) {
-        wa0[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP);
-        wa1[i][ks] = wload(wp + (int64_t)(c * WKC + ks) * STEP + WAVE * G);
-      }
-    }
 #pragma unroll
     for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
@@ -161,10 +150,11 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, co
 }
 
 // nt: token tiles that hold rows (the others are skipped); the tile count is a compile-time constant of the loop.
-template <typename E, int WT, int WW, int WPRE, int KID>
-__device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, const E* __restrict__ brow,
-                                   int64_t bkstride, typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT],
-                                   f32x16 (&acc1)[WT], int wave = threadIdx.x >> 6) {
+// brow: a callable that returns the activation row pointer the lane stages (see wide_stream_nt).
+template <typename E, int WT, int WW, int WPRE, int KID, class BRow>
+__device__ inline void wide_stream(const E* __restrict__ wp, int n_chunks, BRow&& brow, int64_t bkstride,
+                                   typename ET<E>::vec* sb, int nt, f32x16 (&acc0)[WT], f32x16 (&acc1)[WT],
+                                   int wave = threadIdx.x >> 6) {
   if constexpr (WT >= 4) {
     if (nt >= 4) return wide_stream_nt<E, WT, 4, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
     if (nt == 3) return wide_stream_nt<E, WT, 3, WW, WPRE, KID>(wp, n_chunks, brow, bkstride, sb, acc0, acc1, wave);
