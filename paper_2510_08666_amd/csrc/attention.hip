@@ -261,10 +261,12 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   const int head = blockIdx.x, qt = blockIdx.y;
   const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
   const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
-  // thread -> (query, 4 consecutive features); 32 * HD / 4 items over 256 threads
-  for (int item = threadIdx.x; item < TILE * HD / 4; item += 256) {
+  // thread -> (query, 4 consecutive features): 32 * HD / 4 items, one per thread over gridDim.z workgroups (every
+  // item is a chain of dependent loads over the parts, so the items are spread as widely as possible)
+  {
+    const int item = blockIdx.z * 256 + threadIdx.x;
     const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
-    if (q >= nvalid) continue;
+    if (q >= nvalid) return;
     float M = -INFINITY;
     for (int p = 0; p < n_parts; ++p) M = fmaxf(M, pb[(int64_t)p * TILE * (HD + 2) + TILE * HD + q]);
     float L = 0.f;
@@ -294,7 +296,7 @@ template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, 
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
       (E*)a.out, a.T);
   if (a.n_splits > 1)
-    attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
+    attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles, TILE * HD / 4 / 256), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
                                                                                   a.n_splits, (E*)a.out, a.T);
 }
 
