@@ -94,18 +94,14 @@ WeightMap map_weights(const dinfer_config& c) {
   return m;
 }
 
-// Key splits per (query tile, head).  A workgroup's eight waves walk their key tiles with the next tile's loads
-// in flight, every tile a dependent memory round trip; a split is worth its merge pass when a wave would
-// otherwise walk more than 4 tiles.  The count is capped where the grid already covers the chip (key_bound =
-// most keys a sequence can have).
+// Key splits the attention grid offers per (query tile, head): what the longest possible sequence (key_bound keys)
+// would use under the rule of attn_splits_for (common.hpp), but no more than it takes to give every compute unit
+// a workgroup, and at most 32; every sequence then uses its own count.
 int attn_splits(int n_qtiles, int n_heads, int key_bound) {
-  const int tiles = (key_bound + TILE - 1) / TILE;
-  int s = (tiles + 31) / 32;                               // <= 4 tiles per wave, 8 waves
-  const int cover = (1024 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
+  int s = attn_splits_for(key_bound);
+  const int cover = (256 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
   if (s > cover) s = cover;
-  if (s > 32) s = 32;
-  if (s < 1) s = 1;
-  return s;
+  return s > 32 ? 32 : s;
 }
 
 struct Workspace {

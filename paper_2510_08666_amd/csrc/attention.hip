@@ -1,8 +1,9 @@
 // Bidirectional (non-causal) attention of a tile of 32 query tokens over every key of its sequence: the
 // cached prefix pages plus the tokens of this forward, read through the page table.
 //
-// Work split: grid (split, head, query tile), ATTN_WAVES waves per workgroup; the key tiles (32 keys) are dealt
-// round-robin to the n_splits*ATTN_WAVES waves of a (head, query tile).  Each wave keeps its own online-softmax
+// Work split: grid (split, head, query tile), ATTN_WAVES waves per workgroup.  A sequence uses as many of the
+// grid's splits as its own key count asks for (attn_splits_for; the other workgroups exit at once), and its key
+// tiles (32 keys) are dealt round-robin to the waves of those splits.  Each wave keeps its own online-softmax
 // state; the waves of a workgroup are folded through LDS in wave order, each wave finishing its share of the
 // output rows.  With one split the workgroup writes the normalised output itself; otherwise it writes one
 // partial (unnormalised output, max, sum) and attn_merge_kernel folds the partials of a (query tile, head) in
@@ -82,6 +83,8 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int seq = meta.qtile[qt * 3 + 0], tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
   const int n_keys = meta.seq_nkeys[seq];
+  const int my_splits = min(attn_splits_for(n_keys), n_splits);   // splits this sequence uses of those the grid offers
+  if (split >= my_splits) return;                                  // uniform over the workgroup
   const int D = geom.n_heads * HD;
   const float scale = rsqrtf((float)HD);
   TRACE_MARK(7, 0);
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
   float m_run = -INFINITY, l_run = 0.f;
 
   const int n_ktiles = (n_keys + TILE - 1) / TILE;
-  const int stride = n_splits * ATTN_WAVES;              // key tiles are dealt round-robin to all waves
+  const int stride = my_splits * ATTN_WAVES;             // key tiles are dealt round-robin to all its waves
   const int kt0 = split * ATTN_WAVES + wave;
   // K rows and V^T rows of one key tile, loaded straight into MFMA operand registers
   struct TileRegs {
@@ -224,7 +227,7 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
 #pragma unroll
     for (int i = 0; i < RPW; ++i) r[i] += sw * pb[(wave * RPW + i) * WAVE];
   }
-  if (n_splits == 1) {
+  if (my_splits == 1) {
     // the whole key range was here: normalise and write the attention output
     if (col < nvalid) {
       const float inv = 1.f / L;
@@ -260,6 +263,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
                                                           int n_parts, E* __restrict__ out, int T_out) {
   const int head = blockIdx.x, qt = blockIdx.y;
   const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
+  const int my_parts = min(attn_splits_for(meta.seq_nkeys[meta.qtile[qt * 3]]), n_parts);
+  if (my_parts == 1) return;   // a single workgroup had the whole key range and wrote the output itself
   const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
   // thread -> (query, 4 consecutive features): 32 * HD / 4 items, one per thread over gridDim.z workgroups (every
   // item is a chain of dependent loads over the parts, so the items are spread as widely as possible)
@@ -268,10 +273,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
     const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
     if (q >= nvalid) return;
     float M = -INFINITY;
-    for (int p = 0; p < n_parts; ++p) M = fmaxf(M, pb[(int64_t)p * TILE * (HD + 2) + TILE * HD + q]);
+    for (int p = 0; p < my_parts; ++p) M = fmaxf(M, pb[(int64_t)p * TILE * (HD + 2) + TILE * HD + q]);
     float L = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int p = 0; p < n_parts; ++p) {
+    for (int p = 0; p < my_parts; ++p) {
       const float* pp = pb + (int64_t)p * TILE * (HD + 2);
       const float mp = pp[TILE * HD + q];
       if (mp == -INFINITY) continue;             // a wave that saw no key tile

@@ -184,6 +184,19 @@ __device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int sl
          ((int64_t)head * g.head_dim + d) * PAGE + slot;
 }
 
+// Attention: workgroups (splits) that share the keys of one (head, query tile) of a sequence with n_keys keys: one
+// per 4 key tiles and wave (8 waves).  Every workgroup pays for staging the page table and the queries, the fold
+// of its waves and, with more than one split, the merge pass, so splitting pays only while the launch would
+// otherwise leave compute units idle: the host offers at most ceil(256 / (heads x query tiles)) splits (measured at
+// 512 tokens in 16 sequences, 256 such pairs: 44 us without splits, 55 with up to 3, 69 with up to 5; at 64 tokens
+// over 4160 keys, 32 pairs: 29 us with 5 splits, 33 with 3, 35 with 9).  Host (largest possible key count, for the
+// grid and the workspace) and kernels (the sequence's own count) use the same rule.
+__host__ __device__ inline int attn_splits_for(int n_keys) {
+  const int tiles = (n_keys + 31) / 32;
+  const int s = (tiles + 31) / 32;
+  return s < 1 ? 1 : s;
+}
+
 // Optional in-kernel phase timestamps (builds with -DDINFER_TRACE=<kernel id> only): thread 0 of every workgroup
 // of the chosen kernel stores the 100 MHz wall clock at each mark.  Kernel ids: 1 QKV, 2 O-proj, 3 router,
 // 4 expert GEMM 1, 5 expert GEMM 2, 6 LM head, 7 attention, 8 combine, 9 / 10 / 11 many-token LM head / expert GEMM 1 /

@@ -43,6 +43,9 @@ def _variant(name):
         # the most sequences a call takes (64) with full blocks: 4096 tokens, experts with hundreds of rows (several row
         # groups per expert in the many-token expert GEMMs), 32 token groups in the LM head
         "max64": W("max64", tiny, 64, 64, 0, 70, precommit=True, threshold=0.9, seed_index=15),
+        # short and long cached prefixes in one call: sequences use different numbers of attention key splits
+        "longctx": W("longctx", tiny, 4, 32, 60, 1500, threshold=0.9, seed_index=22),
+        "longctx_bf16": W("longctx_bf16", sc(tiny, dtype="bf16", logit_scale=1.0), 4, 32, 60, 1500, threshold=0.9, seed_index=22),
         # no prefix at all: the block attends to itself only
         "noprefix": W("noprefix", tiny, 2, 32, 0, 0, threshold=0.9, seed_index=10),
     }
@@ -50,7 +53,7 @@ def _variant(name):
 
 
 CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "dense2", "dense2_bf16",
-         "max64", "noprefix"]
+         "max64", "longctx", "longctx_bf16", "noprefix"]
 
 
 class Case:
