@@ -430,8 +430,8 @@ template <typename E, class Epi> static bool configure_ksplit() {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Dense projections over many token rows (more than 64).  A workgroup takes four tasks and WT token tiles; its
-// 4 * KH waves are KH teams of four, each team with its own share of the K range, its own LDS staging area for the
+// Dense projections over many token rows (more than 64).  A workgroup takes TASKS (four or two) tasks and WT token
+// tiles; its TASKS * KH waves are KH teams, each team with its own share of the K range, its own LDS staging area for the
 // activation fragments (wide_stream.hpp) and one wave per task, which streams that task's weights once and keeps
 // the accumulators of 64 features x WT*32 rows.  The teams' sums are folded through LDS at the end and team 0
 // runs the epilogue (those of the split-K kernel, called for four accumulator registers at a time).  KH > 1 puts
@@ -442,17 +442,18 @@ template <typename E, class Epi> static bool configure_ksplit() {
 // ------------------------------------------------------------------------------------------------
 // Measured at 512 tokens (QKV / output projection, microseconds): one team 58 / 34, two teams 58 / 34 before and
 // 41 / 29 after the epilogue stores were widened, four teams of one token tile 94 / 37; four token tiles per
-// workgroup 102 / 95 (too few workgroups).
-constexpr int DENSE_TASKS = 4, DENSE_PRE = 2, DENSE_KH = 2, DENSE_WT = 2;
+// workgroup 102 / 95 (too few workgroups); two tasks per workgroup 57 / 19 (the output projection, with 32 tasks,
+// then fills the chip with 256 workgroups).
+constexpr int DENSE_PRE = 2, DENSE_KH = 2, DENSE_WT = 2;
 constexpr int DENSE_FILL = 160;   // workgroups a launch with DENSE_WT token tiles must keep, else one tile each
 
-template <typename E, int KID, int WT> constexpr size_t dense_lds() {
+template <typename E, int KID, int WT, int DENSE_TASKS> constexpr size_t dense_lds() {
   const size_t stage = DENSE_KH * wide_lds<E, KID, WT>();
   const size_t fold = (size_t)(DENSE_KH - 1) * DENSE_TASKS * 2 * WT * 16 * WAVE * 4;
   return stage > fold ? stage : fold;
 }
 
-template <typename E, int WT, class Epi>
+template <typename E, int WT, int DENSE_TASKS, class Epi>
 __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kernel(const E* __restrict__ W, int ksteps,
                                                                                   const E* __restrict__ B, int T,
                                                                                   int n_tasks, Epi epi) {
@@ -544,23 +545,25 @@ __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kern
 // True when the dense form takes the call (many rows, K a whole number of staged chunks per team).
 static bool dense_applies(int T, int ksteps) { return T > 2 * TILE && ksteps % (WKC * DENSE_KH) == 0; }
 
+template <typename E, int WT, int TASKS, class Epi>
+static void launch_dense_as(const E* W, int ksteps, const E* B, int T, int n_tasks, const Epi& epi, hipStream_t st) {
+  constexpr int KID = Epi::ROWSUM ? 13 : 12;
+  gemm_dense_kernel<E, WT, TASKS, Epi><<<dim3((n_tasks + TASKS - 1) / TASKS, (T + WT * TILE - 1) / (WT * TILE)),
+                                        TASKS * DENSE_KH * WAVE, dense_lds<E, KID, WT, TASKS>(), st>>>(W, ksteps, B, T,
+                                                                                                    n_tasks, epi);
+}
+// More tasks and token tiles per workgroup cut the operand traffic, but only while the launch still fills the chip.
 template <typename E, class Epi>
 static void launch_dense(const E* W, int ksteps, const E* B, int T, int n_tasks, const Epi& epi, hipStream_t st) {
-  constexpr int KID = Epi::ROWSUM ? 13 : 12;
-  constexpr int THREADS = DENSE_TASKS * DENSE_KH * WAVE;
-  const int tgroups = (n_tasks + DENSE_TASKS - 1) / DENSE_TASKS;
-  // more token tiles per workgroup cut the weight traffic of the L2, but only if the launch still fills the chip
-  if (tgroups * ((T + DENSE_WT * TILE - 1) / (DENSE_WT * TILE)) >= DENSE_FILL) {
-    gemm_dense_kernel<E, DENSE_WT, Epi><<<dim3(tgroups, (T + DENSE_WT * TILE - 1) / (DENSE_WT * TILE)), THREADS, dense_lds<E, KID, DENSE_WT>(), st>>>(
-        W, ksteps, B, T, n_tasks, epi);
-  } else {
-    gemm_dense_kernel<E, 1, Epi><<<dim3(tgroups, (T + TILE - 1) / TILE), THREADS, dense_lds<E, KID, 1>(), st>>>(
-        W, ksteps, B, T, n_tasks, epi);
-  }
+  auto wgs = [&](int tasks, int wt) { return ((n_tasks + tasks - 1) / tasks) * ((T + wt * TILE - 1) / (wt * TILE)); };
+  if (wgs(4, DENSE_WT) >= DENSE_FILL) launch_dense_as<E, DENSE_WT, 4, Epi>(W, ksteps, B, T, n_tasks, epi, st);
+  else if (wgs(4, 1) >= DENSE_FILL) launch_dense_as<E, 1, 4, Epi>(W, ksteps, B, T, n_tasks, epi, st);
+  else launch_dense_as<E, 1, 2, Epi>(W, ksteps, B, T, n_tasks, epi, st);
 }
 
 template <typename E, class Epi> static bool configure_dense() {
-  return opt_in_lds((const void*)gemm_dense_kernel<E, DENSE_WT, Epi>) && opt_in_lds((const void*)gemm_dense_kernel<E, 1, Epi>);
+  return opt_in_lds((const void*)gemm_dense_kernel<E, DENSE_WT, 4, Epi>) && opt_in_lds((const void*)gemm_dense_kernel<E, 1, 4, Epi>) &&
+         opt_in_lds((const void*)gemm_dense_kernel<E, 1, 2, Epi>);
 }
 
 template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipStream_t st) {
