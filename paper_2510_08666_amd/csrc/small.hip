@@ -619,7 +619,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const f32x4* __restric
     for (size_t i = 0; i < CHUNK; i += 64 * 16) {
       f32x4 v[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = q[i + u * 64];
+      for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(q + i + u * 64);   // as the weight streams do: measured 7.1 against 6.3 TB/s
 #pragma unroll
       for (int u = 0; u < 16; ++u) acc += v[u];
     }

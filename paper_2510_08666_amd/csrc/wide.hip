@@ -153,7 +153,8 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm2_wide_kernel(const E* _
 // (trace ids 16 .. 19); more: four tiles, eight tasks, the work list of the permutation kernel (ids 10, 11).
 // (Measured, gate/up + down in microseconds: two tasks 69.8 + 37.6 at 32 tokens and 86.6 + 49.2 at 64; four tasks
 // 68.9 + 38.9 and 88.1 + 50.7; the earlier per-wave-operand kernels, whose four waves split K, 72.9 + 38.6 and
-// 100.5 + 55.2.)
+// 100.5 + 55.2.  Four or six weight chunks in flight per wave instead of two: 71.9 + 39.4 at 32 tokens, 90.8 + 53.0
+// at 64.)
 constexpr int SMALL_WW = 2;
 
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
