@@ -60,8 +60,8 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
   typename Loader::Raw raw[PF][TT];
 #pragma unroll
   for (int i = 0; i < PF; ++i) {
-    a0[i] = load16<E>(wp + i * STEP);
-    a1[i] = load16<E>(wp + i * STEP + WAVE * G);
+    a0[i] = load16_stream<E>(wp + i * STEP);
+    a1[i] = load16_stream<E>(wp + i * STEP + WAVE * G);
   }
 #pragma unroll
   for (int i = 0; i < PF; ++i)
@@ -81,8 +81,8 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
         }
       }
       const int nx = s + i + PF;
-      a0[i] = load16<E>(wp + nx * STEP);
-      a1[i] = load16<E>(wp + nx * STEP + WAVE * G);
+      a0[i] = load16_stream<E>(wp + nx * STEP);
+      a1[i] = load16_stream<E>(wp + nx * STEP + WAVE * G);
 #pragma unroll
       for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + nx);
     }
