@@ -777,7 +777,7 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
   for (int t = 0; t < TT; ++t) ld.set(t, xn, T, min(tok0 + t * TILE + (lane & 31), T - 1), half);
   const int per = (ksteps + n_slices * KW - 1) / (n_slices * KW);
   const int ks0 = min(ksteps, (slice * KW + wave) * per), ks1 = min(ksteps, ks0 + per);
-  stream_task<E, TT, (TT == 1 ? 8 : 4)>(W, ks0, ks1, ld, acc0, acc1);
+  stream_task<E, TT, (TT == 1 ? 8 : 4), false>(W, ks0, ks1, ld, acc0, acc1);
   TRACE_MARK(3, 1);
   spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
   {

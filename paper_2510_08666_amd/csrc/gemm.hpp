@@ -50,18 +50,21 @@ template <typename E, int TT> struct PlaneLoader {
 // Software-pipelined core: PF k-steps of loads are always in flight.  The loop body is straight-line (no
 // predicated loads), so the compiler can count outstanding loads exactly and every MFMA waits only for its own
 // operands; n must be a positive multiple of PF.
-template <typename E, int TT, int PF, class Loader>
+// STREAM: the weights are read once per launch and loaded non-temporally (false where several token groups read the
+// same weights again, as in the router).
+template <typename E, int TT, int PF, bool STREAM, class Loader>
 __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks0, int n, f32x16 (&acc0)[TT],
                                     f32x16 (&acc1)[TT]) {
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, NP = Planes<E>::N;
   constexpr int64_t STEP = 2 * WAVE * G;   // elements of packed weights per k-step
+  auto wload = [](const E* p) { return STREAM ? load16_stream<E>(p) : load16<E>(p); };
   vec a0[PF], a1[PF];
   typename Loader::Raw raw[PF][TT];
 #pragma unroll
   for (int i = 0; i < PF; ++i) {
-    a0[i] = load16_stream<E>(wp + i * STEP);
-    a1[i] = load16_stream<E>(wp + i * STEP + WAVE * G);
+    a0[i] = wload(wp + i * STEP);
+    a1[i] = wload(wp + i * STEP + WAVE * G);
   }
 #pragma unroll
   for (int i = 0; i < PF; ++i)
@@ -81,8 +84,8 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
         }
       }
       const int nx = s + i + PF;
-      a0[i] = load16_stream<E>(wp + nx * STEP);
-      a1[i] = load16_stream<E>(wp + nx * STEP + WAVE * G);
+      a0[i] = wload(wp + nx * STEP);
+      a1[i] = wload(wp + nx * STEP + WAVE * G);
 #pragma unroll
       for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + nx);
     }
@@ -103,7 +106,7 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
 
 // Accumulate k-steps [ks0, ks1) of one task for TT token tiles; wtask = packed weights of the task (k-step 0).
 // The prefetch depth follows the step count (a wave-uniform choice): PFMAX when it divides, else 4, else 1.
-template <typename E, int TT, int PFMAX, class Loader>
+template <typename E, int TT, int PFMAX, bool STREAM = true, class Loader>
 __device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1, Loader& ld, f32x16 (&acc0)[TT],
                                    f32x16 (&acc1)[TT]) {
   constexpr int G = ET<E>::G;
@@ -111,9 +114,9 @@ __device__ inline void stream_task(const E* __restrict__ wtask, int ks0, int ks1
   const E* wp = wtask + (int64_t)ks0 * (2 * WAVE * G) + lane * G;
   const int n = ks1 - ks0;
   if (n <= 0) return;
-  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX>(wp, ld, ks0, n, acc0, acc1);
-  else if (n % 4 == 0) stream_steps<E, TT, 4>(wp, ld, ks0, n, acc0, acc1);
-  else stream_steps<E, TT, 1>(wp, ld, ks0, n, acc0, acc1);
+  if (PFMAX > 4 && n % PFMAX == 0) stream_steps<E, TT, PFMAX, STREAM>(wp, ld, ks0, n, acc0, acc1);
+  else if (n % 4 == 0) stream_steps<E, TT, 4, STREAM>(wp, ld, ks0, n, acc0, acc1);
+  else stream_steps<E, TT, 1, STREAM>(wp, ld, ks0, n, acc0, acc1);
 }
 
 template <int TT> __device__ inline void zero_acc(f32x16 (&a)[TT]) {
