@@ -893,8 +893,8 @@ template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
   } else {
-    const int groups = (a.T + 2 * TILE - 1) / (2 * TILE);
-    router_kernel<E, 2, 8><<<dim3(1, groups), 8 * WAVE, ksplit_lds<2, 8>(), st>>>(
+    const int groups = (a.T + TILE - 1) / TILE;   // 32 tokens per workgroup: one round of the top-k lanes, more workgroups
+    router_kernel<E, 1, 8><<<dim3(1, groups), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
         a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
     launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, a.work, st);
