@@ -207,3 +207,53 @@ def test_generation_stops_at_eos():
             assert int(fin.cpu()[s]) == (1 if eos >= 0 and eos in ref[s]["tokens"] else 0)
         assert np.array_equal(g.prefix_len.cpu().numpy(), inp.prefix_len + run * S)
     g.close()
+
+
+def test_hierarchical_rule_inside_the_other_step_variants():
+    """The decoder settings travel through every step variant.  Each variant is run twice from the same state, with
+    threshold decoding and with the hierarchical rule: the forward is the same, so confidences and candidates must
+    agree bit for bit, and the hierarchical commit must be the oracle's rule applied to those confidences."""
+    from paper_2510_08666_amd import binding
+    tiny = di.model_preset("tiny")
+    wl = di.Workload("variants", tiny, 2, 32, 40, 64, seed_index=5)
+    cfg, w, inp = make_case(wl)
+    ns, S = inp.block_tokens.shape
+    cap = int(inp.prefix_len.max()) + S + 16
+    ora = OracleRun(cfg, w, inp, cap)
+    g = GpuRun(cfg, w, inp, ns * (S + 16), cap)
+    g.inject_prefix(ora.caches)
+    torch = g.torch
+    vic = torch.from_numpy(np.stack([inp.prefix_tokens[s][int(inp.prefix_len[s]) - 16:] for s in range(ns)]).astype(np.int32)).to(g.dev)
+    credit = g.credit_state()
+    sm = g.smooth_state()
+    ctx = g.ctx
+
+    def run(kind, dec):
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        args = (g.tokens, g.mask, g.prefix_len, g.page_table)
+        out = (g.conf, g.argmax, g.n_committed)
+        if kind == "vicinity":
+            ctx.step_vicinity(g.tokens, vic, g.mask, g.prefix_len, g.page_table, dec, 0, *out)
+        elif kind == "credit":
+            for k in credit.values():
+                k.zero_()
+            ctx.step_credit(*args, dec, 0, 0.65, 0.7, 0.5, credit["ids"], credit["val"], credit["n"], *out)
+        else:
+            sm["delta"].zero_()
+            ctx.step_smooth(*args, dec, 0, 0.0, sm["delta"], sm["scratch"], *out)
+        torch.cuda.synchronize()
+        return g.state()
+
+    for kind in ("vicinity", "credit", "smooth"):
+        plain = run(kind, 2.0)                                   # nothing reaches 2.0: one commit per sequence
+        q = np.sort(plain["conf"].reshape(-1))
+        hi, lo = float(q[-4]), float(q[len(q) // 2])
+        got = run(kind, binding.hierarchical(hi, lo))
+        assert np.array_equal(got["conf"], plain["conf"]) and np.array_equal(got["argmax"], plain["argmax"]), kind
+        for s in range(ns):
+            n, m, t = oracle.commit_hier(got["conf"][s].astype(np.float64), got["argmax"][s], int(inp.mask_bits[s]),
+                                         inp.block_tokens[s], hi, lo)
+            assert (int(got["n_committed"][s]), int(got["mask"][s])) == (n, m), (kind, s)
+            assert np.array_equal(got["tokens"][s], t), (kind, s)
+        assert int(got["n_committed"].sum()) > ns, kind           # more than the fallback's one per sequence
+    g.close()
