@@ -146,10 +146,21 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+    {
+      // the query fragments are read from LDS QD ahead of the matrix instructions that use them; the scheduling
+      // barrier keeps the compiler from moving the reads back next to their use
+      constexpr int QF = DSTEPS * NP, QD = 3;
+      vec ring[QD];
 #pragma unroll
-    for (int s = 0; s < DSTEPS; ++s)
+      for (int f = 0; f < QD; ++f) ring[f] = qs[f * WAVE + lane];
 #pragma unroll
-      for (int pl = 0; pl < NP; ++pl) mfma32(sacc, cur.k[s], qs[(s * NP + pl) * WAVE + lane]);
+      for (int f = 0; f < QF; ++f) {
+        const vec b = ring[f % QD];
+        if (f + QD < QF) ring[f % QD] = qs[(f + QD) * WAVE + lane];
+        __builtin_amdgcn_sched_barrier(0);
+        mfma32(sacc, cur.k[f / NP], b);
+      }
+    }
     float p[16];
     float mx = -INFINITY;
 #pragma unroll
