@@ -10,12 +10,12 @@
 namespace dinfer {
 
 constexpr int WKC = 4;     // k-steps per staged chunk
-// LDS fragments read ahead of the matrix instructions that use them, and the kernels (by trace id) whose read-ahead
-// is pinned by scheduling barriers: all but the many-token expert GEMMs (ids 10, 11), whose 128 accumulator
-// registers and two activation planes leave no room for it (pinned, they spill and run at half speed).
+// LDS fragments read ahead of the matrix instructions that use them (pinned by scheduling barriers, see the chunk
+// body), and the chunks of activation fragments a wave holds in registers on their way to LDS: two everywhere
+// except in the many-token expert GEMMs (trace ids 10, 11), whose 128 accumulator registers and two activation
+// planes leave room for one only (with two, the pinned read-ahead spills and they run at half speed).
 constexpr int WIDE_FD = 4;
-template <int KID> constexpr bool wide_pinned() { return KID != 10 && KID != 11; }
-
+template <int KID> constexpr int wide_bdepth() { return (KID == 10 || KID == 11) ? 1 : 2; }
 
 // Planes of the activations a kernel (by its trace id) feeds to the matrix cores.  The LM head with hundreds of
 // token rows is bound by the matrix cores, and its rounding error is not carried into later layers: it takes the
@@ -61,7 +61,8 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BR
   constexpr int SKS = WKC * WT / WW;               // k-steps of a chunk this wave stages (of token tile wave % WT)
   const int st = wave % WT, sk0 = (wave / WT) * SKS;
   vec wa0[WPRE][WKC], wa1[WPRE][WKC];
-  vec bset[2][SKS][NP];                            // fragments of the next two chunks, on their way to LDS
+  constexpr int BD = wide_bdepth<KID>();
+  vec bset[BD][SKS][NP];                           // fragments of the next BD chunks, on their way to LDS
   auto sb_at = [&](int buf, int ks, int t, int q) -> vec& { return sb[((((buf * WKC + ks) * WT + t) * NP + q) * WAVE) + lane]; };
   // Prologue: the weights of the first WPRE chunks are requested before anything else, since they hang on nothing;
   // brow_of() then resolves the activation row this lane stages (for the experts a chain of dependent loads through
@@ -87,8 +88,8 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BR
     for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        bset[1][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
-        bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
+        bset[1 % BD][ks][q] = load16<E>(brow + (int64_t)(c1 * WKC + sk0 + ks) * bkstride + q * KS);
+        if constexpr (BD == 2) bset[0][ks][q] = load16<E>(brow + (int64_t)(c2 * WKC + sk0 + ks) * bkstride + q * KS);
       }
 #pragma unroll
     for (int ks = 0; ks < SKS; ++ks)
@@ -108,17 +109,17 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BR
 #pragma unroll
     for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
-      for (int q = 0; q < NP; ++q) sb_at(nb, sk0 + ks, st, q) = bset[nb][ks][q];
-    const int cn = min(c + 3, last);
+      for (int q = 0; q < NP; ++q) sb_at(nb, sk0 + ks, st, q) = bset[nb % BD][ks][q];
+    const int cn = min(c + 1 + BD, last);
 #pragma unroll
     for (int ks = 0; ks < SKS; ++ks)
 #pragma unroll
       for (int q = 0; q < NP; ++q)
-        bset[nb][ks][q] = load16<E>(brow + (int64_t)(cn * WKC + sk0 + ks) * bkstride + q * KS);
+        bset[nb % BD][ks][q] = load16<E>(brow + (int64_t)(cn * WKC + sk0 + ks) * bkstride + q * KS);
     // Fragment pipeline: the LDS read of fragment f + FD is issued before the matrix instructions of fragment f, and
     // a scheduling barrier keeps the compiler from sinking it back next to its use (left alone it keeps only two
     // reads in flight and the matrix pipe waits for LDS after every four instructions; measured at 512 tokens: LM
-    // head 362 -> 322 us, QKV 41.7 -> 38.7 us).  Fragments in the order (k-step, token tile, plane).
+    // head 362 -> 322 us, QKV 41.7 -> 38.7 us, expert gate/up 118 -> 113 us).  Fragments in the order (k-step, token tile, plane).
     constexpr int F = WKC * NT * NP;
     constexpr int FD = WIDE_FD < F ? WIDE_FD : F;
     vec ring[FD];
@@ -128,7 +129,7 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BR
       constexpr int f = decltype(Fi)::value, ks = f / (NT * NP), t = (f / NP) % NT;
       const vec b = ring[f % FD];
       if constexpr (f + FD < F) ring[f % FD] = frag(f + FD);
-      if constexpr (wide_pinned<KID>()) __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);
       mfma32(acc0[t], wa0[i][ks], b);
       mfma32(acc1[t], wa1[i][ks], b);
     });
