@@ -42,8 +42,7 @@ template <typename E, int KID, int WT> constexpr size_t wide_lds() { return (siz
 // Pipeline per chunk c: barrier; the fragments of chunk c+1 go from registers to LDS buffer (c+1)&1 and the
 // loads of chunk c+3 take their place; chunk c is multiplied out of buffer c&1; the weights of chunk c+WPRE are
 // requested.  Loads past the end are clamped to the last chunk (never used), so the loop body has no branch
-// around a load.  Registers are kept under half the file so that two workgroups share a compute unit and one
-// computes while the other waits at its barrier.
+// around a load.  A wave stays within 256 registers, so that the eight waves of a workgroup fit on a compute unit.
 template <typename E, int WT, int NT, int WW, int WPRE, int KID, class BRow>
 __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BRow&& brow_of, int64_t bkstride,
                                       typename ET<E>::vec* sb, f32x16 (&acc0)[WT], f32x16 (&acc1)[WT], int wave) {
