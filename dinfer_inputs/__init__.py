@@ -23,6 +23,7 @@ from .configs import (  # noqa: F401
     make_weights,
     make_workload_inputs,
     synthetic_prefix_kv,
+    peaked_positions,
     bf16_to_f32,
     f32_to_bf16,
 )

@@ -195,13 +195,34 @@ def make_workload_inputs(wl, seed=None, room=None):
 KV_STD = 0.9   # std of a key / value element of the random-init LLaDA-MoE-shaped model (0.02 * sqrt(2048))
 
 
-def synthetic_prefix_kv(cfg, seed, s, length, std=KV_STD):
+def synthetic_prefix_kv(cfg, seed, s, length, std=KV_STD, peaked=0):
     """Seeded stand-in for the cached prefix of sequence s: K,V rows ~ N(0, std^2), every value representable
-    in bfloat16 (so that a bf16 and a float64 consumer see the same numbers).  Returns float32 [L][length][D]."""
+    in bfloat16 (so that a bf16 and a float64 consumer see the same numbers).  Returns float32 [L][length][D].
+
+    peaked > 0: in every layer that many seeded positions (peaked_positions) carry key rows 16 times and value rows
+    4 times as large (powers of two: still exact in bfloat16).  Their attention scores dominate, so every query's
+    softmax is sharply peaked on a few cached keys that sit in different key tiles, instead of nearly flat."""
     D = cfg.qkv_dim
-    k = g.normal(g.stream_key(seed, 200, s), (cfg.n_layers, length, D), std, "bf16")
-    v = g.normal(g.stream_key(seed, 201, s), (cfg.n_layers, length, D), std, "bf16")
-    return bf16_to_f32(k), bf16_to_f32(v)
+    k = bf16_to_f32(g.normal(g.stream_key(seed, 200, s), (cfg.n_layers, length, D), std, "bf16"))
+    v = bf16_to_f32(g.normal(g.stream_key(seed, 201, s), (cfg.n_layers, length, D), std, "bf16"))
+    if peaked:
+        for layer in range(cfg.n_layers):
+            pos = peaked_positions(seed, s, layer, length, peaked)
+            k[layer, pos] *= 16.0
+            v[layer, pos] *= 4.0
+    return k, v
+
+
+def peaked_positions(seed, s, layer, length, n):
+    """The n distinct cached positions of (sequence s, layer) that synthetic_prefix_kv(peaked=n) enlarges."""
+    draws = g.uniform_ids(g.stream_key(seed, 202 + layer, s), 4 * n, length)
+    pos = []
+    for p in draws:
+        if int(p) not in pos:
+            pos.append(int(p))
+        if len(pos) == n:
+            break
+    return np.array(sorted(pos), dtype=np.int64)
 
 
 def scaled(cfg, **kw):

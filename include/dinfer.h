@@ -192,7 +192,8 @@ int dinfer_step_credit(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_
  * commit concern the block only; every other argument is as in dinfer_step.  There is no look-ahead part: the
  * block attends to its prefix and itself, positions after it do not exist here.
  * 0 <= look_back <= 64; the caller guarantees d_prefix_len[s] >= look_back for every sequence (a shorter prefix
- * keeps all accesses in bounds but misplaces the block); n_seq * (look_back + block_len) <= max_tokens.
+ * keeps all accesses in bounds but misplaces the block); n_seq * (look_back + block_len) <= max_tokens, and
+ * look_back + block_len positions must fit max_pos and the page-table row (DINFER_ENOSPACE otherwise).
  * look_back = 0 is dinfer_step. */
 int dinfer_step_vicinity(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t look_back,
                          int32_t* d_block_tokens, const int32_t* d_vicinity_tokens, uint64_t* d_mask,
@@ -242,8 +243,8 @@ int dinfer_kv_write(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, i
 int dinfer_kv_read(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, int32_t first_pos, int32_t n_pos,
                    float* d_k, float* d_v, void* stream);
 
-/* Test hooks.  dinfer_debug_logits recomputes the logits of the last forward's n_rows first rows through
- * the LM-head kernel's arithmetic and stores them: d_out [n_rows][vocab] float32.  dinfer_debug_get copies
+/* Test hooks.  dinfer_debug_logits recomputes the logits of the last forward's rows (n_rows must equal their
+ * number) through the LM-head kernel's arithmetic and stores them: d_out [n_rows][vocab] float32.  dinfer_debug_get copies
  * an intermediate of the last forward: what = 0 residual stream leaving the last layer [T][hidden] f32;
  * 1 router expert ids of every layer [n_layers][T][top_k] i32; 2 their mixture weights, same shape, f32;
  * and of the last layer: 3 expert row counts [n_experts] i32; 4 expert offsets [n_experts+1] i32;

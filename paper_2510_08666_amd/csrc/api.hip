@@ -628,6 +628,10 @@ int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_
   const int run = look_back + block_len;
   if ((int64_t)n_seq * run > c->max_tokens)
     return fail(DINFER_ENOSPACE, "n_seq*(look_back+block_len) %d exceeds max_tokens %d", n_seq * run, c->max_tokens);
+  // the run of look_back + block_len positions must fit the rotary table and the page-table row like a block does
+  if (run > c->cfg.max_pos || (int64_t)pt_stride * PAGE < run)
+    return fail(DINFER_ENOSPACE, "look_back+block_len %d exceeds max_pos %d or the page-table row (%d positions)", run,
+                c->cfg.max_pos, pt_stride * PAGE);
   hipStream_t st = (hipStream_t)stream;
   const dinfer_config& f = c->cfg;
   int32_t* run_tokens = at<int32_t>(c->ws, c->wsm.run_tokens);
@@ -809,7 +813,8 @@ int dinfer_profile_stop(dinfer_ctx* c, int32_t* n_launches, float* total_ms) {
 
 int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* stream) {
   if (!c || !d_out) return fail(DINFER_EINVAL, "null argument");
-  if (n_rows < 1 || n_rows > c->last_T) return fail(DINFER_EINVAL, "n_rows %d outside [1, %d]", n_rows, c->last_T);
+  // the normalised-input planes are laid out for last_T rows: the kernel must be run over exactly those
+  if (n_rows != c->last_T) return fail(DINFER_EINVAL, "n_rows %d is not the last forward's %d rows", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
             at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,

@@ -148,7 +148,9 @@ __device__ inline float coherent_load(const float* p) {
 // thread waits for its own stores to complete, then one thread counts the arrival.  Nothing spins, so the order
 // in which workgroups are scheduled does not matter.  Every thread of the workgroup must call.
 __device__ inline bool last_arrival(int32_t* c, int n, int32_t* s_flag) {
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's global stores have been performed
+  // vmcnt(0): this thread's write-through stores have been acknowledged.  As inline assembly with a memory clobber,
+  // so that the compiler can neither sink a store below the wait nor hoist a later load above it.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
     const int last = atomicAdd(c, 1) == n - 1;
@@ -156,7 +158,9 @@ __device__ inline bool last_arrival(int32_t* c, int n, int32_t* s_flag) {
     *s_flag = last;
   }
   __syncthreads();
-  return *s_flag != 0;
+  const bool last = *s_flag != 0;
+  asm volatile("" ::: "memory");   // the partials are read only after the ticket has been seen
+  return last;
 }
 
 // Which sequence a forward's packed tokens belong to: sequence s owns tokens [off[s], off[s+1]).

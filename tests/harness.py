@@ -5,6 +5,8 @@ Bars (block-denoising benchmark statement): committed ids and positions bit-exac
 flagged as within `tau_margin` of the threshold or at an arg-max / most-confident near-tie; logits within
 relative `logit_rel` of the row's largest |logit|; confidences within absolute `conf_abs`.
 """
+import json
+import os
 from dataclasses import dataclass
 
 import numpy as np
@@ -23,12 +25,48 @@ class Bars:
     router_rel: float    # two router probabilities closer than this (relative) count as a near-tie
 
 
+# Worst margins seen, per test: every routing / K,V / logits / confidence comparison records how much of its bar it
+# used, keyed by the running test.  conftest.py prints the table at the end of the session and writes it to
+# gpurun_out/parity_stats.json, so that the head-room under every bar is visible and not only "passed".
+STATS = {}
+
+
+def _record(key, value, where=None):
+    test = os.environ.get("PYTEST_CURRENT_TEST", "(no test)").split(" ")[0]
+    slot = STATS.setdefault(test, {})
+    if value > slot.get(key, -1.0):
+        slot[key] = float(value)
+        if where is not None:
+            slot[key + "_at"] = [int(x) for x in where]
+
+
+def dump_stats(path=None):
+    """Worst value per key over all tests, and the per-test table as JSON (if a path is given)."""
+    worst = {}
+    for test, slot in STATS.items():
+        for k, v in slot.items():
+            if not k.endswith("_at") and v > worst.get(k, (-1.0, ""))[0]:
+                worst[k] = (v, test)
+    if path:
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+        with open(path, "w") as f:
+            json.dump({"worst": {k: {"value": v, "test": t} for k, (v, t) in worst.items()}, "per_test": STATS}, f,
+                      indent=1)
+    return worst
+
+
 def bars_for(cfg):
     if cfg.dtype == "f32":
         # float32 kernels against the float64 oracle: rounding only
         return Bars(logit_rel=2e-4, conf_abs=2e-5, conf_rel=2e-3, tau_margin=1e-4, kv_abs=1e-4, router_rel=1e-4)
-    # bf16 inputs, float32 accumulation
-    return Bars(logit_rel=2e-2, conf_abs=1e-3, conf_rel=8e-2, tau_margin=1e-3, kv_abs=3e-2, router_rel=5e-2)
+    # bf16 inputs, float32 accumulation.
+    # router_rel: two experts' probabilities differ by the factor exp(h . (w_a - w_b)); an error dh of the normalised
+    # row h moves that exponent by dh . (w_a - w_b), whose spread is sqrt(2) times that of a logit error dh . w_v
+    # (router and LM-head weights have the same scale).  The logit errors measured at the full shapes have a standard
+    # deviation of about 7e-3 (largest 0.037 over 5e6 logits), so the exponent moves by about 1e-2 (one sigma) and a
+    # choice between experts can flip up to about 3.5 sigma = 3.5e-2 over the ~2000 routings of a step.  The
+    # largest gap of a flipped choice seen over all full-shape cases is 1.26e-2; the bar is twice that.
+    return Bars(logit_rel=2e-2, conf_abs=1e-3, conf_rel=8e-2, tau_margin=1e-3, kv_abs=3e-2, router_rel=2.5e-2)
 
 
 class OracleRun:
@@ -221,6 +259,8 @@ def check_routing(trace, gpu_routing, top_k, bars, stats=None):
     if stats is not None:
         stats["router_worst_gap"] = worst
         stats["router_worst_at"] = where
+    _record("router_gap", worst, where)
+    _record("router_gap_of_bar", worst / bars.router_rel)
     assert worst <= bars.router_rel, "routing differs beyond a near-tie (relative gap %.3g) at layer/token/expert %s" % (
         worst, where)
     return flagged
@@ -244,7 +284,9 @@ def kv_err_ratio(got, ref, bars):
         return 0.0
     err = np.abs(np.asarray(got, dtype=np.float64) - ref).max(axis=-1)
     allowed = np.maximum(bars.kv_abs, bars.logit_rel * np.abs(ref).max(axis=-1))
-    return float((err / allowed).max())
+    ratio = float((err / allowed).max())
+    _record("kv_err_of_bar", ratio)
+    return ratio
 
 
 def compare_logits(ref, got, bars):
@@ -254,34 +296,45 @@ def compare_logits(ref, got, bars):
         allowed = bars.logit_rel * max(np.abs(ref[i]).max(), 1e-3)
         err = np.abs(got[i].astype(np.float64) - ref[i]).max()
         worst = max(worst, err / allowed)
+    _record("logits_err_of_bar", worst)
     assert worst <= 1.0, "logits off by %.3g x the allowed error" % worst
     return worst
 
 
 def compare_step(ref, got_tokens, got_mask, got_conf, got_argmax, got_n, old_tokens, old_mask, threshold, fixed_k,
-                 bars, ref_logits=None):
+                 bars, ref_logits=None, got_logits=None):
     """One sequence, one step.  ref: the oracle's step result.  Returns dict(flagged=..., conf_err=...).
 
     Positions are flagged (and excused from bit-exactness) when the oracle's own numbers leave the decision
-    within the error bars: confidence within tau_margin of the threshold; the position GPU chose as most
-    confident within 2*conf tolerance of the oracle's best; an arg max whose oracle logit is within the logit
-    bar of the oracle's top logit."""
+    within the stated bars: a confidence within tau_margin of the threshold; a most-confident / k-th most confident
+    choice between positions whose oracle confidences are closer than the two confidence tolerances; an arg max
+    whose oracle logit is below the oracle's top logit by no more than the logit errors of the two ids (with the
+    HIP path's logits at hand, got_logits: their actual errors; otherwise the logits' bar, twice).  With
+    got_logits the reported arg max must also be the first maximum of the HIP path's own logits, exactly."""
     S = len(ref["conf"])
     old_mask, got_mask = int(old_mask), int(got_mask)
     masked = [i for i in range(S) if (old_mask >> i) & 1]
     conf_o, conf_g = ref["conf"], got_conf.astype(np.float64)
     ctol = np.minimum(bars.conf_abs, bars.conf_rel * np.maximum(conf_o, 1e-30))
     cerr = np.abs(conf_g - conf_o)
+    _record("conf_err_of_bar", float((cerr / ctol).max()))
     assert np.all(cerr <= ctol), "confidence error %.3g (allowed %.3g) at %d" % (
         cerr.max(), ctol[int(np.argmax(cerr / ctol))], int(np.argmax(cerr / ctol)))
     flagged = set()
     # candidate ids
     for i in range(S):
+        if got_logits is not None:
+            assert got_argmax[i] == int(np.argmax(got_logits[i])), "arg max at %d is not the first maximum of the logits" % i
         if got_argmax[i] != ref["argmax"][i]:
             assert ref_logits is not None, "arg max differs at %d and no logits to judge a tie" % i
-            gap = ref_logits[i, ref["argmax"][i]] - ref_logits[i, got_argmax[i]]
-            allowed = 2 * bars.logit_rel * max(np.abs(ref_logits[i]).max(), 1e-3)
-            assert gap <= allowed, "arg max differs at %d beyond a near-tie (gap %.3g)" % (i, gap)
+            a, b = int(ref["argmax"][i]), int(got_argmax[i])
+            gap = ref_logits[i, a] - ref_logits[i, b]
+            if got_logits is not None:
+                allowed = abs(float(got_logits[i, a]) - ref_logits[i, a]) + abs(float(got_logits[i, b]) - ref_logits[i, b])
+            else:
+                allowed = 2 * bars.logit_rel * max(np.abs(ref_logits[i]).max(), 1e-3)
+            _record("argmax_tie_gap_of_logit_bar", gap / (bars.logit_rel * max(np.abs(ref_logits[i]).max(), 1e-3)))
+            assert gap <= allowed, "arg max differs at %d beyond a near-tie (gap %.3g, allowed %.3g)" % (i, gap, allowed)
             flagged.add(i)
     # structural invariants that hold whatever the numbers are
     assert got_mask & ~old_mask == 0, "a decided position returned to the mask"
@@ -301,9 +354,10 @@ def compare_step(ref, got_tokens, got_mask, got_conf, got_argmax, got_n, old_tok
             kth = sorted((conf_o[i] for i in masked), reverse=True)[min(fixed_k, len(masked)) - 1]
             near = {i for i in masked if abs(conf_o[i] - kth) <= 2 * ctol[i]}
         else:
-            margin = min(bars.tau_margin, bars.conf_rel * threshold)
-            near = {i for i in masked if abs(conf_o[i] - threshold) <= margin + ctol[i]}
-            if not any(conf_o[i] >= threshold + margin for i in masked):
+            # a confidence can only end on the other side of the threshold if the oracle's lies within the
+            # confidence tolerance of it, which is never more than the stated margin
+            near = {i for i in masked if abs(conf_o[i] - threshold) <= min(bars.tau_margin, ctol[i])}
+            if not any(conf_o[i] >= threshold + ctol[i] for i in masked):
                 best = max(conf_o[i] for i in masked)
                 near |= {i for i in masked if best - conf_o[i] <= 2 * ctol[i]}
         diff = {i for i in range(S) if ((sel_g ^ sel_o) >> i) & 1}

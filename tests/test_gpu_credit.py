@@ -72,25 +72,31 @@ def test_credit_steps_match_oracle(case):
                                     want_logits=True, trace=tr)
             rep = compare_step(ref, got["tokens"][s], got["mask"][s], got["conf"][s], got["argmax"][s],
                                got["n_committed"][s], tokens[s], masks[s], tau, fixed_k, bars, ref["logits"])
-            # the credit lists against the dense credits
+            # the credit lists against the dense credits.  The oracle keeps its own credits from step to step; only
+            # where the two sides rewarded different top-1 candidates - which the plain logits must show to be a
+            # near-tie - does it continue from the GPU's list (teacher forcing of that one decision).
             mine = dense(credit, s, V)
             tol = 1e-4 if cfg.dtype == "f32" else 5e-2
             masked = [i for i in range(S) if (int(masks[s]) >> i) & 1]
+            kc[...], vc[...] = keep
+            plain_ref = ora.o.step(tokens[s], int(masks[s]), P, kc, vc, 2.0, want_logits=True,
+                                   trace=oracle.Trace(cfg, S, forced_idx=routing[:, s]))
+            kc[...], vc[...] = keep
+            plain, zp = plain_ref["conf"], plain_ref["logits"]
             for i in masked:
-                if set(np.nonzero(mine[i])[0]) != set(np.nonzero(ora_credit[s][i])[0]):
-                    # the two sides rewarded different top-1 candidates: only a near-tie of the plain logits allows it
-                    assert i in rep["flagged"] or got["argmax"][s][i] == ref["argmax"][i], (step, s, i)
+                ids_g, ids_o = set(np.nonzero(mine[i])[0]), set(np.nonzero(ora_credit[s][i])[0])
+                if ids_g != ids_o:
+                    allowed = 2 * bars.logit_rel * np.abs(zp[i]).max()
+                    for v in ids_g ^ ids_o:
+                        assert zp[i].max() - zp[i, v] <= allowed, (step, s, i, int(v))
+                    ora_credit[s][i] = mine[i]
                     continue
                 nz = np.nonzero(mine[i])[0]
                 assert np.allclose(mine[i, nz], ora_credit[s][i, nz], rtol=tol), (step, s, i)
             assert not mine[[i for i in range(S) if i not in masked]].any() or step > 0
             # the fusion is really at work: from the second step on the enhanced confidences sit well above the plain ones
-            kc[...], vc[...] = keep
-            plain = ora.o.step(tokens[s], int(masks[s]), P, kc, vc, 2.0)["conf"]
-            kc[...], vc[...] = keep
             if step > 0 and masked and np.all(ref["conf"][masked] > plain[masked] * 1.05):
                 enhanced_differs = True
-            ora_credit[s] = mine                              # teacher forcing
         tokens, masks = got["tokens"].copy(), got["mask"].copy()
     assert enhanced_differs, "the credits never changed a confidence: the test does not exercise the fusion"
 

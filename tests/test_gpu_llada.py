@@ -48,7 +48,7 @@ def gpu_run(model, inp, max_tokens, max_pos):
 class BigCase:
     """One workload on both sides, prefix K,V synthetic.  Oracle caches hold [L][cap][D] per sequence."""
 
-    def __init__(self, model, wl, max_tokens=None):
+    def __init__(self, model, wl, max_tokens=None, peaked=0):
         self.cfg, self.w, self.o = model
         self.wl = wl
         self.inp = di.make_workload_inputs(wl)
@@ -62,7 +62,7 @@ class BigCase:
             P = int(self.inp.prefix_len[s])
             kc, vc = self.o.new_cache(P + max(self.S, wl.gen_len))
             if P:
-                k, v = di.synthetic_prefix_kv(self.cfg, self.inp.seed, s, P)
+                k, v = di.synthetic_prefix_kv(self.cfg, self.inp.seed, s, P, peaked=peaked)
                 kc[:, :P], vc[:, :P] = k, v
                 for l in range(self.cfg.n_layers):
                     self.gpu.ctx.kv_write(l, self.gpu.page_table[s], 0, torch.from_numpy(k[l]).to(self.gpu.dev),
@@ -74,7 +74,8 @@ class BigCase:
         kc, vc = self.caches[s]
         tr = oracle.Trace(self.cfg, len(tokens), forced_idx=routing)
         ref = self.o.step(tokens, mask, prefix_len, kc, vc, threshold, fixed_k, want_logits=True, trace=tr)
-        return ref, check_routing(tr, routing, self.cfg.top_k, self.bars)
+        self.router_stats = {}
+        return ref, check_routing(tr, routing, self.cfg.top_k, self.bars, self.router_stats)
 
     def check_step(self, got, logits, routing, tokens, masks, prefix_len, threshold, fixed_k, seqs=None):
         """Compare the sequences in `seqs` (default all) of a GPU step against the oracle."""
@@ -86,18 +87,21 @@ class BigCase:
             worst = compare_logits(ref["logits"], logits[s], self.bars)
             rep = compare_step(ref, got["tokens"][s], got["mask"][s], got["conf"][s], got["argmax"][s],
                                got["n_committed"][s], tokens[s], masks[s], threshold, fixed_k, self.bars,
-                               ref["logits"])
+                               ref["logits"], logits[s])
             P = int(prefix_len[s])
             kc, vc = self.caches[s]
-            for l in (0, self.cfg.n_layers - 1):
+            kv_worst = 0.0
+            for l in range(self.cfg.n_layers):
                 k, v = self.gpu.read_kv(s, l, P, self.S)
                 rk, rv = kv_err_ratio(k, kc[l, P:P + self.S], self.bars), kv_err_ratio(v, vc[l, P:P + self.S], self.bars)
                 assert rk <= 1.0 and rv <= 1.0, "layer %d K,V error %.2f / %.2f of the bar" % (l, rk, rv)
+                kv_worst = max(kv_worst, rk, rv)
             flagged += len(rep["flagged"])
             near_total += near
-            log("%s seq %d: oracle step %.0f s, logits err %.2f of bar, conf rel err %.1e, flagged %s, "
-                "router near-ties %d, committed %d" % (self.wl.name, s, time.time() - t, worst, rep["conf_rel_err"],
-                                                       rep["flagged"], near, got["n_committed"][s]))
+            log("%s seq %d: oracle step %.0f s, logits err %.2f of bar, K,V err %.2f of bar, conf rel err %.1e, "
+                "flagged %s, router near-ties %d (worst gap %.2e), committed %d" % (
+                    self.wl.name, s, time.time() - t, worst, kv_worst, rep["conf_rel_err"], rep["flagged"], near,
+                    self.router_stats.get("router_worst_gap", 0.0), got["n_committed"][s]))
         return flagged, near_total
 
     def gpu_step(self, tokens, masks, prefix_len, threshold, fixed_k=0):
@@ -133,6 +137,36 @@ def test_c3_long_prefix_half_committed(model):
     got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold)
     c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, c.wl.threshold, 0)
     c.gpu.close()
+
+
+def test_c3_peaked_attention(model):
+    """Configuration 3's shapes with a sharply peaked softmax: in every layer 12 of the 4096 cached positions carry
+    key rows 16 times as large as the rest (same values on both sides), spread over the key tiles of different
+    waves and key splits.  A query's scores on them are ~N(0, 13^2) against ~N(0, 0.8^2) elsewhere, so its softmax
+    sits on one or two of them: the running-maximum rescale across key tiles, the fold across waves and the merge
+    across splits all see weights that differ by many orders of magnitude, which the flat synthetic prefix never
+    produces.  Attention errors would show in the K,V rows of the following layers (compared in every layer) and in
+    the logits."""
+    wl = di.workload_preset(3)
+    c = BigCase(model, wl, peaked=12)
+    inp = c.inp
+    P = int(inp.prefix_len[0])
+    cells = set()
+    for l in range(c.cfg.n_layers):
+        for p in di.peaked_positions(inp.seed, 0, l, P, 12):
+            cells.add((p // 32) % 40)          # (key split, wave) that owns the position's key tile: 5 splits x 8 waves
+    assert len(cells) >= 30, "the enlarged keys do not cover the waves and splits"
+    # the oracle's own attention is peaked: the largest softmax weight of a query is far above 1/4160
+    got, logits, routing = c.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, wl.threshold)
+    c.check_step(got, logits, routing, inp.block_tokens, inp.mask_bits, inp.prefix_len, wl.threshold, 0)
+    # and the result differs from the flat-prefix case by far more than the bars (the enlarged rows matter)
+    flat = BigCase(model, wl)
+    got_f, logits_f, _ = flat.gpu_step(inp.block_tokens, inp.mask_bits, inp.prefix_len, wl.threshold)
+    moved = np.abs(logits_f - logits).max() / np.abs(logits).max()
+    log("C3 peaked: logits moved by %.2f of their range against the flat prefix" % moved)
+    assert moved > 10 * c.bars.logit_rel
+    c.gpu.close()
+    flat.gpu.close()
 
 
 def test_c4_batch16_paged(model):
@@ -255,19 +289,39 @@ def test_c2_credit_decoding_steps(model):
         ids, val, n = (credit[k][0].cpu().numpy() for k in ("ids", "val", "n"))
         mine = np.zeros((S, V))
         for i in range(S):
+            assert len(set(ids[i, :n[i]].tolist())) == n[i], "a token is listed twice"
             mine[i, ids[i, :n[i]]] = val[i, :n[i]]
-        for i in range(S):
-            if (int(masks[0]) >> i) & 1 and set(np.nonzero(mine[i])[0]) == set(np.nonzero(ora_credit[i])[0]):
-                nz = np.nonzero(mine[i])[0]
-                assert np.allclose(mine[i, nz], ora_credit[i, nz], rtol=5e-2), (step, i)
-        plain = o.step(tokens[0], int(masks[0]), P, kc, vc, 2.0)["conf"]
+        # the plain logits of the same forward (same expert sets): they decide which candidate a side may reward
+        plain_ref = o.step(tokens[0], int(masks[0]), P, kc, vc, 2.0, want_logits=True,
+                           trace=oracle.Trace(cfg, S, forced_idx=routing))
+        plain, zp = plain_ref["conf"], plain_ref["logits"]
         masked = [i for i in range(S) if (int(masks[0]) >> i) & 1]
+        tie_positions = []
+        for i in masked:
+            ids_g, ids_o = set(np.nonzero(mine[i])[0]), set(np.nonzero(ora_credit[i])[0])
+            if ids_g != ids_o:
+                # the two sides rewarded different top-1 candidates: only a near-tie of the plain logits allows that
+                # (each logit within the logits' bar).  The oracle continues from the GPU's list at this position.
+                allowed = 2 * c.bars.logit_rel * np.abs(zp[i]).max()
+                for v in ids_g ^ ids_o:
+                    assert zp[i].max() - zp[i, v] <= allowed, (step, i, int(v), float(zp[i].max() - zp[i, v]), allowed)
+                tie_positions.append(i)
+                ora_credit[i] = mine[i]
+            else:
+                nz = np.nonzero(mine[i])[0]
+                assert 1 <= len(nz) <= step + 1, (step, i, len(nz))
+                assert np.allclose(mine[i, nz], ora_credit[i, nz], rtol=5e-2), (step, i)
+        assert len(tie_positions) <= max(2, len(masked) // 8), tie_positions
+        for i in range(S):
+            if i not in masked and step == 0:
+                assert not mine[i].any()
         if step > 0 and np.median(ref["conf"][masked] / plain[masked]) > 1.005:
             boosted = True
-        log("C2 credit step %d: conf rel err %.1e, flagged %s, near-ties %d, median enhanced/plain conf %.3f, "
-            "max list length %d" % (step, rep["conf_rel_err"], rep["flagged"], near,
-                                    float(np.median(ref["conf"][masked] / plain[masked])), int(n.max())))
-        ora_credit = mine
+        log("C2 credit step %d: conf rel err %.1e, flagged %s, near-ties %d, rewarded-candidate ties at %s, median "
+            "enhanced/plain conf %.3f, max list length %d" % (step, rep["conf_rel_err"], rep["flagged"], near,
+                                                              tie_positions,
+                                                              float(np.median(ref["conf"][masked] / plain[masked])),
+                                                              int(n.max())))
         tokens, masks = got["tokens"].copy(), got["mask"].copy()
     assert boosted
     c.gpu.close()

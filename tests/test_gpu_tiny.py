@@ -134,7 +134,8 @@ def _run_step(case, threshold, fixed_k=0, tokens=None, masks=None):
         assert near <= max(1, case.cfg.n_layers * case.S // 4), "too many router near-ties: %d" % near
         compare_logits(ref["logits"], logits[s], case.bars)
         rep = compare_step(ref, got["tokens"][s], got["mask"][s], got["conf"][s], got["argmax"][s],
-                           got["n_committed"][s], tokens[s], masks[s], threshold, fixed_k, case.bars, ref["logits"])
+                           got["n_committed"][s], tokens[s], masks[s], threshold, fixed_k, case.bars, ref["logits"],
+                           logits[s])
         # K,V of the block positions as the step wrote them; prefix rows untouched
         for l in range(case.cfg.n_layers):
             k, v = g.read_kv(s, l, 0, P + case.S)
