@@ -160,6 +160,24 @@ int dinfer_step_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_
                        const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch,
                        size_t scratch_bytes, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream);
 
+/* dinfer_step_smooth for callers that cannot allocate device memory or hand over a scratch buffer (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): the logits and probability planes live in a
+ * device array that is part of the library image, DINFER_STATIC_SCRATCH_BYTES per GPU, held from the moment the
+ * library is loaded until the process ends.  The call allocates nothing and frees nothing; everything else is
+ * dinfer_step_smooth (same kernels, same results bit for bit).
+ *  - n_seq * block_len tokens are accepted while dinfer_smooth_scratch_bytes(cfg, n_seq * block_len) fits the array
+ *    (e.g. 37 block tokens at a vocabulary of 157184 in bf16); more is refused with DINFER_ENOSPACE.
+ *  - The array's address is looked up once per GPU, at dinfer_create; the context must be used with the GPU that was
+ *    current then (DINFER_EINVAL otherwise).
+ *  - All calls on one GPU share the array, whatever their context: calls that overlap on one GPU (different streams
+ *    or threads) race.  Nothing in it has to start at zero: every call overwrites all the rows it reads, so the
+ *    previous call's contents, of any size, do no harm. */
+#define DINFER_STATIC_SCRATCH_BYTES (48u << 20)
+int dinfer_step_smooth_static(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens,
+                              uint64_t* d_mask, const int32_t* d_prefix_len, const int32_t* d_page_table,
+                              int32_t pt_stride, const dinfer_decode* decode, float alpha, float* d_delta,
+                              float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream);
+
 /* The step with credit decoding (Appendix "Credit decoding").  Every undecided position keeps a credit per token,
  * C_t[v] = beta * C_{t-1}[v] + (v == top-1 candidate of step t ? p_t(v)^gamma : 0)          (equation 1)
  * and the decoder sees softmax(logits + alpha * log(1 + C_t)) instead of softmax(logits)     (equation 2):

@@ -22,7 +22,7 @@ TENSOR_IDS = {"emb": T_EMB, "lm_head": T_LM_HEAD, "final_gain": T_FINAL_GAIN, "a
               "w_up": T_UP, "w_down": T_DOWN}
 
 EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", "dinfer_create", "dinfer_destroy",
-           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit", "dinfer_step_smooth", "dinfer_smooth_scratch_bytes",
+           "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit", "dinfer_step_smooth", "dinfer_step_smooth_static", "dinfer_smooth_scratch_bytes",
            "dinfer_refresh_block", "dinfer_commit", "dinfer_generate",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
            "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
@@ -101,6 +101,9 @@ def _load():
     L.dinfer_step_smooth.restype = c_i32
     L.dinfer_step_smooth.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_f32, c_vp, c_vp, c_sz,
                                      c_vp, c_vp, c_vp, c_vp]
+    L.dinfer_step_smooth_static.restype = c_i32
+    L.dinfer_step_smooth_static.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_f32, c_vp,
+                                            c_vp, c_vp, c_vp, c_vp]
     L.dinfer_step_credit.restype = c_i32
     L.dinfer_step_credit.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), P(Credit), c_vp, c_vp,
                                      c_vp, c_vp, c_vp, c_vp, c_vp]
@@ -260,6 +263,16 @@ class Context:
                                       _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec), float(alpha),
                                       _ptr(d_delta), _ptr(d_scratch), d_scratch.numel(), _ptr(d_conf), _ptr(d_argmax),
                                       _ptr(d_n_committed), _stream()))
+
+    def step_smooth_static(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, alpha, d_delta,
+                           d_conf, d_argmax, d_n_committed):
+        """step_smooth with the library's own static scratch: the call allocates nothing."""
+        n_seq, block_len = d_block_tokens.shape
+        dec = _decode(threshold, fixed_k)
+        _check(lib.dinfer_step_smooth_static(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask),
+                                             _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1],
+                                             ctypes.byref(dec), float(alpha), _ptr(d_delta), _ptr(d_conf),
+                                             _ptr(d_argmax), _ptr(d_n_committed), _stream()))
 
     def step_credit(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, alpha, beta, gamma,
                     d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, d_n_committed):

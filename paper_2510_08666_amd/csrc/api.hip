@@ -13,7 +13,15 @@
 
 using namespace dinfer;
 
+// Scratch of dinfer_step_smooth_static: device memory that exists from the moment the library is loaded until the
+// process ends, one copy per GPU.  In host code this name is only a handle for hipGetSymbolAddress; kernels and
+// copies get the device address kept in g_static_scratch.
+static __device__ __align__(256) unsigned char scratch[DINFER_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void* g_static_scratch[MAX_DEVICES];   // device address of `scratch` on each GPU, resolved with that GPU current
 
 thread_local char g_err[512] = "";
 
@@ -32,6 +40,22 @@ int fail(int code, const char* fmt, ...) {
   } while (0)
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Address of the static scratch array on the current device (*dev_out).  Resolved once per device.
+int static_scratch_of_current_device(void** out, int* dev_out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(DINFER_EUNSUPPORTED, "device ordinal %d", dev);
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(DINFER_EHIP, "hipGetSymbolAddress returned a null address");
+    g_static_scratch[dev] = p;
+  }
+  *out = g_static_scratch[dev];
+  if (dev_out) *dev_out = dev;
+  return DINFER_OK;
+}
 
 struct LayerW {
   size_t attn_gain, wqkv, wo, ffn_gain, router, gate_up, down;   // byte offsets into d_weights
@@ -189,6 +213,7 @@ struct dinfer_ctx {
   KvGeom geom;
   size_t kv_layer_bytes;
   int last_T;   // tokens of the last forward (debug hooks)
+  int device;   // GPU that was current at dinfer_create: owner of the three buffers
   uint64_t* h_mask_pinned;
   // optional per-launch timing of one stage (dinfer_profile_start / _stop)
   int prof_stage;
@@ -404,6 +429,16 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   c->geom.layer_stride = c->geom.page_stride * n_pages;
   c->kv_layer_bytes = (size_t)c->geom.layer_stride * es;
   c->last_T = 0;
+  {
+    // set-up is the place for everything that may allocate: the static scratch of this GPU is resolved here, so
+    // that dinfer_step_smooth_static finds its address ready
+    void* unused = nullptr;
+    rc = static_scratch_of_current_device(&unused, &c->device);
+    if (rc != DINFER_OK) {
+      delete c;
+      return rc;
+    }
+  }
   c->prof_stage = -1;
   c->prof_n = 0;
   c->h_mask_pinned = nullptr;
@@ -579,6 +614,27 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
+}
+
+int dinfer_step_smooth_static(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                              const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                              const dinfer_decode* decode, float alpha, float* d_delta, float* d_conf, int32_t* d_argmax,
+                              int32_t* d_n_committed, void* stream) {
+  int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
+  if (rc != DINFER_OK) return rc;
+  const size_t need = dinfer_smooth_scratch_bytes(&c->cfg, n_seq * block_len);
+  if (need == 0) return fail(DINFER_EUNSUPPORTED, "iteration smoothing handles at most %d block tokens per call", 2 * TILE);
+  if (need > (size_t)DINFER_STATIC_SCRATCH_BYTES)
+    return fail(DINFER_ENOSPACE, "%d block tokens of a %d-id vocabulary need %zu bytes of scratch; the static scratch holds %zu",
+                n_seq * block_len, c->cfg.vocab, need, (size_t)DINFER_STATIC_SCRATCH_BYTES);
+  void* p = nullptr;
+  int dev = -1;
+  if ((rc = static_scratch_of_current_device(&p, &dev)) != DINFER_OK) return rc;   // a look-up: resolved at dinfer_create
+  if (dev != c->device)
+    return fail(DINFER_EINVAL, "the context was created on device %d, the current device is %d", c->device, dev);
+  return dinfer_step_smooth(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
+                            alpha, d_delta, p, (size_t)DINFER_STATIC_SCRATCH_BYTES, d_conf, d_argmax, d_n_committed,
+                            stream);
 }
 
 int dinfer_step_credit(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
