@@ -129,7 +129,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 }
 
 struct Workspace {
-  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, tk_part, tickets, tickets_bytes, rinv_a, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
+  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, ssq_a, tk_part, tickets, tickets_bytes, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
       perm, pos_of_pair, work, run_tokens, run_base, n_finished, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
@@ -147,11 +147,11 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.seq_nkeys = cv.take((size_t)max_seqs * 4);
   w.qtile = cv.take((size_t)max_qtiles * 3 * 4);
   w.x = cv.take(T * H * 4);
-  w.rinv_a = cv.take(T * 4);   // 1/rms of the residual rows entering the attention half / the LM head
-  w.rinv_f = cv.take(T * 4);   // ... entering the expert half
+  w.rinv_f = cv.take(T * 4);   // 1/rms of the residual rows entering the expert half
   const size_t planes = c.dtype == DINFER_BF16 ? 2 : 1;   // stored bf16 activations are hi + lo planes
   w.xn = cv.take(planes * T * H * es);   // normalised-input planes of the residual rows
-  w.ssq = cv.take((size_t)(H / 64) * T * 4);
+  w.ssq = cv.take((size_t)(H / 64) * T * 4);     // sums of squares of the rows entering the expert half, per task
+  w.ssq_a = cv.take((size_t)(H / 64) * T * 4);   // ... of the rows entering the attention half / the LM head
   {
     // cross-workgroup split-K scratch: units (tasks) x slices x [2 * token tiles * 16][64] floats, for one and
     // two token tiles, over the QKV projection (K = H), the output projection (K = D) and the router
@@ -162,6 +162,8 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
       const size_t qkv = (size_t)(3 * D / 64) * gemm_slices(bf, H, tt * TILE) * tile;
       const size_t opr = (size_t)(H / 64) * gemm_slices(bf, D, tt * TILE) * tile;
       const size_t smooth = (size_t)(H / 64) * SMOOTH_SLICES * tile;   // expected-embedding contraction
+      const size_t down = (size_t)(H / 64) * down_fused_slices() * tile;   // fused down projection
+      most = down > most ? down : most;
       most = qkv > most ? qkv : most;
       most = opr > most ? opr : most;
       most = smooth > most ? smooth : most;
@@ -213,6 +215,7 @@ struct dinfer_ctx {
   KvGeom geom;
   size_t kv_layer_bytes;
   int last_T;   // tokens of the last forward (debug hooks)
+  int last_n_ssq;   // shares the last forward left per row in ssq_a (statistics of the rows the LM head reads)
   int device;   // GPU that was current at dinfer_create: owner of the three buffers
   uint64_t* h_mask_pinned;
   // optional per-launch timing of one stage (dinfer_profile_start / _stop)
@@ -278,8 +281,14 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   launch_meta(span, d_base, limit, at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
               at<int32_t>(ws, w.qtile), st);
   float* x = at<float>(ws, w.x);
-  float* rinv_a = at<float>(ws, w.rinv_a);
+  float* ssq_a = at<float>(ws, w.ssq_a);
   float* rinv_f = at<float>(ws, w.rinv_f);
+  // Up to 32 tokens the down projection sums a token's experts itself and leaves the residual row, its planes for
+  // the next norm and one share of its sum of squares per task; larger forwards run the combine kernel.  (With two
+  // token tiles every wave of the fused form fetches twice the activation operands per weight byte, and the
+  // separate kernels are faster: measured at 64 tokens, 251 against 259 steps/s.)
+  const bool fused_down = T <= TILE;
+  int n_ssq_a = 1;
   const int64_t q_plane = (int64_t)c->max_tokens * D;
   for (int l = 0; l < f.n_layers; ++l) {
     const LayerW& lw = c->wm.layers[l];
@@ -290,13 +299,13 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     float* tk_part = at<float>(ws, w.tk_part);
     int32_t* tickets = at<int32_t>(ws, w.tickets);
     if (l == 0)
-      launch_embed(bf, d_tokens, c->weights + c->wm.emb, f.rms_eps, T, H, f.vocab, x, rinv_a,
-                   at<float>(c->weights, lw.attn_gain), xn, smooth, st);
-    else
-      launch_combine(bf, x, at<float>(ws, w.o), topk_w - (size_t)T * f.top_k, f.top_k,
-                     f.rms_eps, T, H, rinv_a, at<float>(c->weights, lw.attn_gain), xn, st);
-    QkvArgs qa{c->weights + lw.wqkv, xn, rinv_a, ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table,
-               pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H, tk_part, tickets};
+      launch_embed(bf, d_tokens, c->weights + c->wm.emb, T, H, f.vocab, x, ssq_a, at<float>(c->weights, lw.attn_gain),
+                   xn, smooth, st);
+    else if (!fused_down)
+      launch_combine(bf, x, at<float>(ws, w.o), topk_w - (size_t)T * f.top_k, f.top_k, T, H, ssq_a,
+                     at<float>(c->weights, lw.attn_gain), xn, st);
+    QkvArgs qa{c->weights + lw.wqkv, xn, RowNorm{ssq_a, n_ssq_a, f.rms_eps}, ws + w.q, q_plane, kv_layer, c->geom, meta,
+               d_page_table, pt_stride, at<float>(ws, w.cos_tab), at<float>(ws, w.sin_tab), T, H, tk_part, tickets};
     {
       StageTimer tm(c, DINFER_STAGE_QKV, st);
       launch_qkv(bf, qa, st);
@@ -325,20 +334,31 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     }
     ExpertArgs ea{c->weights + lw.gate_up, c->weights + lw.down, xn, rinv_f,
                   ws + w.y, at<float>(ws, w.o), at<int32_t>(ws, w.cnt), at<int32_t>(ws, w.off),
-                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.work), T, H, f.moe_inter, f.n_experts, f.top_k};
+                  at<int32_t>(ws, w.perm), at<int32_t>(ws, w.work), T, H, f.moe_inter, f.n_experts, f.top_k,
+                  fused_down ? topk_w : nullptr, topk_idx, at<int32_t>(ws, w.pos_of_pair)};
     {
       StageTimer tm(c, DINFER_STAGE_EXPERT_GATE_UP, st);
       launch_expert_gate_up(bf, ea, st);
     }
     {
       StageTimer tm(c, DINFER_STAGE_EXPERT_DOWN, st);
-      launch_expert_down(bf, ea, st);
+      if (fused_down) {
+        // the gain of the norm that reads the new rows: the next layer's attention norm, or the final norm
+        const float* next_gain = l + 1 < f.n_layers ? at<float>(c->weights, c->wm.layers[l + 1].attn_gain)
+                                                    : at<float>(c->weights, c->wm.final_gain);
+        OprojArgs res{nullptr, nullptr, x, next_gain, xn, ssq_a, T, 0, H, tk_part, tickets};
+        launch_expert_down_fused(bf, ea, res, st);
+        n_ssq_a = H / 64;
+      } else {
+        launch_expert_down(bf, ea, st);
+      }
     }
   }
-  // the last layer's expert outputs are folded into the residual here; rinv_a then belongs to the final norm
-  launch_combine(bf, x, at<float>(ws, w.o),
-                 at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k, f.rms_eps, T, H, rinv_a,
-                 at<float>(c->weights, c->wm.final_gain), ws + w.xn, st);
+  // many tokens: the last layer's expert outputs are folded into the residual here, with the final norm's gain
+  if (!fused_down)
+    launch_combine(bf, x, at<float>(ws, w.o), at<float>(ws, w.topk_w) + (size_t)(f.n_layers - 1) * T * f.top_k, f.top_k,
+                   T, H, ssq_a, at<float>(c->weights, c->wm.final_gain), ws + w.xn, st);
+  c->last_n_ssq = n_ssq_a;
   (void)with_head;
   c->last_T = T;
   HIP_TRY(hipGetLastError());
@@ -429,6 +449,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   c->geom.layer_stride = c->geom.page_stride * n_pages;
   c->kv_layer_bytes = (size_t)c->geom.layer_stride * es;
   c->last_T = 0;
+  c->last_n_ssq = 1;
   {
     // set-up is the place for everything that may allocate: the static scratch of this GPU is resolved here, so
     // that dinfer_step_smooth_static finds its address ready
@@ -555,7 +576,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
-            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
@@ -601,7 +622,7 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   // this variant keeps the logits of the block (T x vocab float32): the second contraction over the vocabulary
   // needs the normalised probabilities, which exist only once the row's maximum and sum are known
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
-            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), logits};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
@@ -657,14 +678,14 @@ int dinfer_step_credit(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   const int T = n_seq * block_len;
   float* stats = at<float>(c->ws, c->wsm.lm_stats);
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
-            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, stats, st);
-  launch_credit(c->bf16, la.w, la.xn, la.rinv, T, f.hidden, f.vocab, f.logit_scale, stats, d_mask, block_len,
+  launch_credit(c->bf16, la.w, la.xn, la.norm, T, f.hidden, f.vocab, f.logit_scale, stats, d_mask, block_len,
                 credit->alpha, credit->beta, credit->gamma, d_credit_ids, d_credit_val, d_credit_n, d_conf, d_argmax, st);
   launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
   HIP_TRY(hipGetLastError());
@@ -700,7 +721,7 @@ int dinfer_step_vicinity(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_
   float* conf_rows = at<float>(c->ws, c->wsm.conf);
   int32_t* argmax_rows = at<int32_t>(c->ws, c->wsm.argmax);
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
-            at<float>(c->ws, c->wsm.rinv_a), T, f.hidden, f.vocab, f.logit_scale,
+            RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
@@ -873,7 +894,7 @@ int dinfer_debug_logits(dinfer_ctx* c, int32_t n_rows, float* d_out, void* strea
   if (n_rows != c->last_T) return fail(DINFER_EINVAL, "n_rows %d is not the last forward's %d rows", n_rows, c->last_T);
   const dinfer_config& f = c->cfg;
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
-            at<float>(c->ws, c->wsm.rinv_a), n_rows, f.hidden, f.vocab, f.logit_scale,
+            RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, n_rows, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), d_out};
   launch_lm_head(c->bf16, la, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());

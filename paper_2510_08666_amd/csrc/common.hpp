@@ -133,6 +133,22 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
+// 1/rms of residual row `tok` from the shares of its sum of squares that the row's producer left: ssq[n_ssq][T]
+// (one share per 64-feature task of a projection epilogue, or a single share holding the whole sum).  The shares
+// are added in index order, so every consumer of a row derives the same bits.
+__device__ inline float row_rinv(const float* __restrict__ ssq, int n_ssq, int T, int tok, int H, float eps) {
+  if (n_ssq == 1) return rsqrtf(ssq[tok] / H + eps);
+  float s = 0.f;
+  for (int j0 = 0; j0 < n_ssq; j0 += 32) {   // 32 independent loads at a time
+    float v[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = ssq[(int64_t)min(j0 + i, n_ssq - 1) * T + tok];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) s += j0 + i < n_ssq ? v[i] : 0.f;
+  }
+  return rsqrtf(s / H + eps);
+}
+
 // Data handed from one workgroup to another INSIDE a kernel goes through device-coherent accesses (they bypass
 // the per-XCD L2, which is not coherent across the chip): no cache-wide write-back or invalidate is needed then.
 __device__ inline void coherent_store(float* p, float v) {
@@ -140,6 +156,39 @@ __device__ inline void coherent_store(float* p, float v) {
 }
 __device__ inline float coherent_load(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The same device-coherent accesses for N = 1, 2 or 4 consecutive floats at once, through a buffer descriptor
+// (cache policy sc1, what the compiler emits for the agent-scope accesses above).  off: byte offset from the
+// descriptor's base, a multiple of 4 * N.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc;
+__device__ inline buf_rsrc coherent_buffer(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+constexpr int COHERENT_AUX = 0x10;   // sc1
+template <int N> __device__ inline void coherent_store_n(buf_rsrc r, uint32_t off, const float (&v)[N]) {
+  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 floats");
+  if constexpr (N == 4)
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])},
+                                           r, off, 0, COHERENT_AUX);
+  else if constexpr (N == 2)
+    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(v[0]), __float_as_uint(v[1])}, r, off, 0, COHERENT_AUX);
+  else
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[0]), r, off, 0, COHERENT_AUX);
+}
+template <int N> __device__ inline void coherent_load_n(buf_rsrc r, uint32_t off, float (&v)[N]) {
+  static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 floats");
+  if constexpr (N == 4) {
+    const u32x4 b = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, COHERENT_AUX);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(b[i]);
+  } else if constexpr (N == 2) {
+    const u32x2 b = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, COHERENT_AUX);
+    v[0] = __uint_as_float(b[0]);
+    v[1] = __uint_as_float(b[1]);
+  } else {
+    v[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, COHERENT_AUX));
+  }
 }
 
 // Completion ticket over the n workgroups that share the counter *c (zero before the first arrives): true in every
@@ -215,6 +264,14 @@ static __device__ unsigned long long g_trace[TRACE_WGS * TRACE_SLOTS];
       if (wg_ < (unsigned)TRACE_WGS) g_trace[wg_ * TRACE_SLOTS + (slot)] = wall_clock64();             \
     }                                                                                                  \
   } while (0)
+// Per-wave variant: lane 0 of every wave marks, record index = workgroup * waves + wave.
+#define TRACE_MARK_WAVE(kid, slot, n_waves)                                                            \
+  do {                                                                                                 \
+    if ((kid) == DINFER_TRACE && (threadIdx.x & 63) == 0) {                                            \
+      const unsigned wg_ = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (n_waves) + (threadIdx.x >> 6); \
+      if (wg_ < (unsigned)TRACE_WGS) g_trace[wg_ * TRACE_SLOTS + (slot)] = wall_clock64();             \
+    }                                                                                                  \
+  } while (0)
 #define TRACE_READER(name)                                                                             \
   int name(void* h_out, size_t bytes) {                                                                \
     if (bytes > sizeof(unsigned long long) * TRACE_WGS * TRACE_SLOTS) return -1;                       \
@@ -222,6 +279,7 @@ static __device__ unsigned long long g_trace[TRACE_WGS * TRACE_SLOTS];
   }
 #else
 #define TRACE_MARK(kid, slot) do {} while (0)
+#define TRACE_MARK_WAVE(kid, slot, n_waves) do {} while (0)
 #define TRACE_READER(name) int name(void*, size_t) { return -1; }
 #endif
 

@@ -36,7 +36,8 @@ template <typename E> struct QkvEpi {
   int pt_stride;
   const float* cos_tab;
   const float* sin_tab;
-  const float* rinv;   // [T] 1/rms of the token's residual row
+  RowNorm norm;        // statistics of the tokens' residual rows
+  int T, H;
   int D;               // n_heads * head_dim
 
   // What the epilogue needs from memory besides the accumulators.  prefetch() runs before the weight stream
@@ -52,7 +53,7 @@ template <typename E> struct QkvEpi {
     const int t = valid ? tok : 0;
     p.pos = tok_pos[t];
     p.seq = tok_seq[t];
-    p.r = rinv[t];
+    p.r = row_rinv(norm.ssq, norm.n_ssq, T, t, H, norm.eps);
     return p;
   }
   template <int PER> __device__ void prefetch2(Pre<PER>& p, int task, int half, int v0) const {
@@ -286,22 +287,29 @@ __device__ inline void fold_partials(const float* red, int lane, int v0, float (
   }
 }
 
-// The workgroup's sums leave for / come back from the cross-workgroup buffer: part[unit][slice][row][lane].
+// The workgroup's sums leave for / come back from the cross-workgroup buffer.  A thread holds PER consecutive
+// accumulator registers (v0 .. v0+PER-1) of each tile; they travel as one PER-float piece:
+//   part[unit][slice][token tile][weight tile][v0 / PER][lane][PER]
+// Writer and reader are the same (wave, lane) of their workgroups, so each reads what its counterpart wrote.
+template <int TT, int PER> __device__ inline uint32_t slice_piece(int64_t unit_slice, int t, int tile, int v0, int lane) {
+  return (uint32_t)(((((unit_slice * TT + t) * 2 + tile) * (16 / PER) + v0 / PER) * WAVE + lane) * PER * sizeof(float));
+}
 template <int TT, int PER>
 __device__ inline void put_slice(float* part, int64_t unit_slice, int lane, int v0, const float (&a0)[TT][PER],
                                  const float (&a1)[TT][PER]) {
-  float* p = part + unit_slice * (2 * TT * 16) * WAVE + lane;
+  const buf_rsrc r = coherent_buffer(part);
 #pragma unroll
-  for (int t = 0; t < TT; ++t)
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      coherent_store(p + (t * 32 + v0 + i) * WAVE, a0[t][i]);
-      coherent_store(p + (t * 32 + 16 + v0 + i) * WAVE, a1[t][i]);
-    }
+  for (int t = 0; t < TT; ++t) {
+    coherent_store_n<PER>(r, slice_piece<TT, PER>(unit_slice, t, 0, v0, lane), a0[t]);
+    coherent_store_n<PER>(r, slice_piece<TT, PER>(unit_slice, t, 1, v0, lane), a1[t]);
+  }
 }
-template <int TT, int PER>
+// The loads of CH slices are issued together before any of them is added (a loop that loads and adds slice by
+// slice pays one memory round trip per slice); the sum still runs in slice order.
+template <int TT, int PER, int CH = 4>
 __device__ inline void sum_slices(const float* part, int64_t unit, int n_slices, int lane, int v0, float (&a0)[TT][PER],
                                   float (&a1)[TT][PER]) {
+  const buf_rsrc r = coherent_buffer(part);
 #pragma unroll
   for (int t = 0; t < TT; ++t)
 #pragma unroll
@@ -309,15 +317,28 @@ __device__ inline void sum_slices(const float* part, int64_t unit, int n_slices,
       a0[t][i] = 0.f;
       a1[t][i] = 0.f;
     }
-  for (int s = 0; s < n_slices; ++s) {
-    const float* p = part + (unit * n_slices + s) * (2 * TT * 16) * WAVE + lane;
+  for (int s0 = 0; s0 < n_slices; s0 += CH) {
+    float b0[CH][TT][PER], b1[CH][TT][PER];
 #pragma unroll
-    for (int t = 0; t < TT; ++t)
+    for (int c = 0; c < CH; ++c) {
+      const int64_t us = unit * n_slices + min(s0 + c, n_slices - 1);
 #pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        a0[t][i] += coherent_load(p + (t * 32 + v0 + i) * WAVE);
-        a1[t][i] += coherent_load(p + (t * 32 + 16 + v0 + i) * WAVE);
+      for (int t = 0; t < TT; ++t) {
+        coherent_load_n<PER>(r, slice_piece<TT, PER>(us, t, 0, v0, lane), b0[c][t]);
+        coherent_load_n<PER>(r, slice_piece<TT, PER>(us, t, 1, v0, lane), b1[c][t]);
       }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const bool on = s0 + c < n_slices;
+#pragma unroll
+      for (int t = 0; t < TT; ++t)
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          a0[t][i] += on ? b0[c][t][i] : 0.f;
+          a1[t][i] += on ? b1[c][t][i] : 0.f;
+        }
+    }
   }
 }
 
@@ -427,6 +448,193 @@ template <typename E, class Epi> static bool configure_ksplit() {
   return opt_in_lds((const void*)gemm_ksplit_kernel<E, 1, 4, Epi>) &&
          opt_in_lds((const void*)gemm_ksplit_kernel<E, 2, 4, Epi>) &&
          opt_in_lds((const void*)gemm_ksplit_kernel<E, 4, 4, Epi>);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Down projection of the routed experts fused with the weighted combine, the residual add and the statistics of
+// the norm that follows, for at most 32 tokens.  The sum over a token's k experts is a contraction like any other:
+//   x[t][f] += sum_e sum_i  y[e][t][i] * Wd[e][f][i]      (y already carries the routing weight; y[e][t] = 0
+//                                                           for tokens that were not routed to expert e)
+// so a task (64 output features) runs over the "long K" of all experts that received rows, 64 k-steps each, with
+// the token tile as the MFMA columns: a lane whose token is not among an expert's rows feeds zeros.  The long K is
+// cut into pieces for n_slices x KW waves; wave sums are folded through LDS, workgroup sums through the
+// cross-workgroup hand-off of the split-K kernel, in fixed order, and the last workgroup of a task runs the
+// residual epilogue.  No per-(token, expert) output rows are stored and no separate combine pass runs; and because
+// the work is cut by weight bytes, a layer that touches 8 experts fills the chip as well as one that touches 60.
+// ------------------------------------------------------------------------------------------------
+template <typename E, int TT, int KW, int PF>
+__global__ __launch_bounds__(KW * WAVE) void expert_down_fused_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+                                                                       int64_t y_rows, const int32_t* __restrict__ off,
+                                                                       const int32_t* __restrict__ topk_idx,
+                                                                       const int32_t* __restrict__ pos_of_pair, int T,
+                                                                       int I, int top_k, int n_tasks,
+                                                                       float* __restrict__ part,
+                                                                       int32_t* __restrict__ tickets, ResidualEpi<E> epi) {
+  typedef typename ET<E>::vec vec;
+  extern __shared__ float red[];   // [KW][2*TT*16][64]
+  __shared__ int32_t s_flag;
+  constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N, ROWS = 2 * TT * 16;
+  constexpr int EW = 4, PER = 16 / EW;   // the first EW waves run the epilogue, four accumulator registers each
+  static_assert(KW >= EW && MAX_EXPERTS <= WAVE, "epilogue waves; one lane per listed expert");
+  constexpr int64_t STEP = 2 * WAVE * G;
+  const int slice = blockIdx.x, n_slices = gridDim.x, task = blockIdx.y;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  TRACE_MARK(5, 0);
+  TRACE_MARK_WAVE(55, 0, KW);
+  // Everything the first loads hang on is requested at once, so that a workgroup is two memory round trips away
+  // from its first weights however busy the memory system already is: the list of experts with rows (one per
+  // lane) and their number, and this lane's tokens -- which experts they were routed to, where those rows sit in Y.
+  const int listed = off[ACTIVE_LIST + lane];
+  const int n_act = __builtin_amdgcn_readfirstlane(off[ACTIVE_LIST + MAX_EXPERTS]);
+  int my_e[TT][MAX_TOPK], my_row[TT][MAX_TOPK];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int tok = min(t * TILE + col, T - 1);
+#pragma unroll
+    for (int j = 0; j < MAX_TOPK; ++j) {
+      const int jj = min(j, top_k - 1);
+      my_e[t][j] = topk_idx[tok * top_k + jj];
+      my_row[t][j] = pos_of_pair[tok * top_k + jj];
+    }
+  }
+  // The long K: experts with rows in list order, ksteps_e k-steps each, in groups of PF k-steps; this wave's
+  // contiguous share [g0, g1).  A share is never longer than one expert's groups, so it meets at most two experts.
+  const int ksteps_e = I / KS, groups_e = ksteps_e / PF, total = n_act * groups_e;
+  const int units = n_slices * KW, per = (total + units - 1) / units;
+  const int g0 = min(total, (slice * KW + wave) * per), g1 = min(total, g0 + per);
+  const int i0 = g0 / groups_e;
+  const int e_first = __builtin_amdgcn_readlane(listed, min(i0, MAX_EXPERTS - 1));
+  const int e_second = __builtin_amdgcn_readlane(listed, min(i0 + 1, MAX_EXPERTS - 1));
+  const E* wbase = W + (int64_t)task * task_stride_elems<E>(ksteps_e) + lane * G;
+  const int64_t wexpert = (int64_t)n_tasks * task_stride_elems<E>(ksteps_e);
+  auto weights_of = [&](int g) { return wbase + (g / groups_e == i0 ? e_first : e_second) * wexpert + (g % groups_e) * PF * STEP; };
+  // Which Y row this lane reads for group g (byte offset of its first k-step) and how far it moves per k-step.
+  // Y is read through a buffer descriptor with hardware range checking: a lane whose token was not routed to the
+  // group's expert is given an offset past the end, for which the load returns zeros without touching memory --
+  // exactly the operand such a token contributes.
+  const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<E*>(Y), 0, (uint32_t)(y_rows * I * NP * sizeof(E)), 0x00020000);
+  constexpr uint32_t ROW_BYTES = NP * KS * sizeof(E), PAST_END = 0x80000000u;
+  const uint32_t ykstride = (uint32_t)y_rows * ROW_BYTES;
+  auto rows_of = [&](int g, uint32_t (&yoff)[TT], uint32_t (&ystep)[TT]) {
+    const int e = g / groups_e == i0 ? e_first : e_second, kk = (g % groups_e) * PF;
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      int row = -1;
+#pragma unroll
+      for (int j = 0; j < MAX_TOPK; ++j) row = (j < top_k && my_e[t][j] == e) ? my_row[t][j] : row;
+      yoff[t] = row >= 0 ? ((uint32_t)kk * (uint32_t)y_rows + row) * ROW_BYTES + half * 16 : PAST_END;
+      ystep[t] = row >= 0 ? ykstride : 0;
+    }
+  };
+  f32x16 acc0[TT], acc1[TT];
+  zero_acc<TT>(acc0);
+  zero_acc<TT>(acc1);
+  vec a0[PF], a1[PF], yr[PF][TT][NP];
+  auto issue_w = [&](int i, const E* wp) {
+    a0[i] = load16_stream<E>(wp + i * STEP);
+    a1[i] = load16_stream<E>(wp + i * STEP + WAVE * G);
+  };
+  auto issue_y = [&](int i, const uint32_t (&yoff)[TT], const uint32_t (&ystep)[TT]) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int q = 0; q < NP; ++q)
+        yr[i][t][q] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  ybuf, yoff[t] + i * ystep[t] + q * (uint32_t)(KS * sizeof(E)), 0, 0));
+  };
+  auto use = [&](int i) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t)
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        mfma32(acc0[t], a0[i], yr[i][t][q]);
+        mfma32(acc1[t], a1[i], yr[i][t][q]);
+      }
+  };
+  if (g0 < g1) {
+    {
+      const E* wp = weights_of(g0);
+      TRACE_MARK_WAVE(55, 1, KW);
+#pragma unroll
+      for (int i = 0; i < PF; ++i) issue_w(i, wp);
+      uint32_t yoff[TT], ystep[TT];
+      rows_of(g0, yoff, ystep);
+#pragma unroll
+      for (int i = 0; i < PF; ++i) issue_y(i, yoff, ystep);
+    }
+    for (int g = g0; g + 1 < g1; ++g) {
+      if (g == g0 + 1) TRACE_MARK(5, 5);
+      if (g == g0 + 2) TRACE_MARK(5, 6);
+      if (g == g0 + 4) TRACE_MARK(5, 7);
+      if (g == g0) TRACE_MARK_WAVE(55, 2, KW);
+      if (g == g0 + 1) TRACE_MARK_WAVE(55, 3, KW);
+      if (g == g0 + 3) TRACE_MARK_WAVE(55, 4, KW);
+      const E* wn = weights_of(g + 1);
+      uint32_t yn[TT], ynstep[TT];
+      rows_of(g + 1, yn, ynstep);
+      // k-step by k-step: multiply, then request the same slot of the next group.  The scheduling barriers keep
+      // the compiler from collecting the requests at the end of the iteration (it then waits for all of them at
+      // the top of the next one and the memory pipe idles while the group is multiplied).
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        use(i);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_w(i, wn);
+        issue_y(i, yn, ynstep);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < PF; ++i) use(i);
+  }
+  // Epilogue by the first EW waves (the others only keep the workgroup's barriers company).
+  const bool worker = wave < EW;
+  const int v0 = (worker ? wave : 0) * PER;
+  typename ResidualEpi<E>::template Pre<PER> pre[TT];
+  if (worker) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      const int tok = t * TILE + col;
+      pre[t] = epi.template prefetch<PER>(task, tok, tok < T, half, v0);
+    }
+  }
+  TRACE_MARK(5, 1);
+  TRACE_MARK_WAVE(55, 5, KW);
+  spill_partials<TT, ROWS>(red, wave, lane, acc0, acc1);
+  __syncthreads();
+  TRACE_MARK(5, 2);
+  float s0[TT][PER], s1[TT][PER];
+  if (worker) fold_partials<TT, KW, PER>(red, lane, v0, s0, s1);
+  if (n_slices > 1) {
+    if (worker) put_slice<TT, PER>(part, (int64_t)task * n_slices + slice, lane, v0, s0, s1);
+    if (!last_arrival(tickets + task, n_slices, &s_flag)) return;
+    TRACE_MARK(5, 3);
+    if (worker) sum_slices<TT, PER, 8>(part, task, n_slices, lane, v0, s0, s1);
+  }
+  float ss[TT];
+  if (worker) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      const int tok = t * TILE + col;
+      ss[t] = epi.template apply<PER>(pre[t], task, tok, tok < T, half, v0, s0[t], s1[t]);
+    }
+  }
+  __syncthreads();   // the partials in `red` are consumed
+  if (worker) {
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+      const float s2 = ss[t] + __shfl_xor(ss[t], 32, WAVE);
+      if (half == 0) red[(wave * TT + t) * TILE + lane] = s2;
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < TT * TILE; i += KW * WAVE) {
+    float s = 0.f;
+    for (int w = 0; w < EW; ++w) s += red[w * TT * TILE + i];
+    if (i < T) epi.row_sum(task, i, s);
+  }
+  TRACE_MARK(5, 4);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -569,7 +777,7 @@ template <typename E, class Epi> static bool configure_dense() {
 template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipStream_t st) {
   const int D = a.geom.n_heads * a.geom.head_dim;
   QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
-                a.pt_stride, a.cos_tab, a.sin_tab, a.rinv, D};
+                a.pt_stride, a.cos_tab, a.sin_tab, a.norm, a.T, a.H, D};
   if (dense_applies(a.T, a.H / ET<E>::KS))
     launch_dense<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, 3 * D / 64, epi, st);
   else
@@ -905,6 +1113,27 @@ void launch_router(bool bf16, const RouterArgs& a, hipStream_t st) {
   else launch_router_t<float>(false, a, st);
 }
 
+// Fused down projection: DOWN_SLICES workgroups of DOWN_KW waves share a task's long K.
+constexpr int DOWN_SLICES = 8, DOWN_KW = 8;
+int down_fused_slices() { return DOWN_SLICES; }
+template <typename E> static void launch_down_fused_t(const ExpertArgs& a, const OprojArgs& r, hipStream_t st) {
+  ResidualEpi<E> epi{r.x, r.H, r.gain, (E*)r.xn, r.ssq, r.T};
+  const int n_tasks = a.H / 64, ksteps_e = a.I / ET<E>::KS;
+  const dim3 grid(DOWN_SLICES, n_tasks);
+  const E *w = (const E*)a.w_down, *y = (const E*)a.y;
+  const int64_t y_rows = (int64_t)a.T * a.top_k;
+  if (ksteps_e % 8 == 0)
+    expert_down_fused_kernel<E, 1, DOWN_KW, 8><<<grid, DOWN_KW * WAVE, ksplit_lds<1, DOWN_KW>(), st>>>(
+        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi);
+  else
+    expert_down_fused_kernel<E, 1, DOWN_KW, 4><<<grid, DOWN_KW * WAVE, ksplit_lds<1, DOWN_KW>(), st>>>(
+        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi);
+}
+void launch_expert_down_fused(bool bf16, const ExpertArgs& a, const OprojArgs& res, hipStream_t st) {
+  if (bf16) launch_down_fused_t<bf16_t>(a, res, st);
+  else launch_down_fused_t<float>(a, res, st);
+}
+
 // The routed-expert GEMMs and the LM head live in wide.hip (shared-operand forms for every token count).
 void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st) { launch_expert_gate_up_wide(bf16, a, st); }
 void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st) { launch_expert_down_wide(bf16, a, st); }
@@ -918,6 +1147,10 @@ bool configure_kernels() {
             configure_ksplit<bf16_t, SmoothEpi>() && configure_ksplit<float, SmoothEpi>();
   ok = ok && configure_dense<bf16_t, QkvEpi<bf16_t>>() && configure_dense<float, QkvEpi<float>>() &&
        configure_dense<bf16_t, ResidualEpi<bf16_t>>() && configure_dense<float, ResidualEpi<float>>();
+  ok = ok && opt_in_lds((const void*)expert_down_fused_kernel<bf16_t, 1, DOWN_KW, 8>) &&
+       opt_in_lds((const void*)expert_down_fused_kernel<bf16_t, 1, DOWN_KW, 4>) &&
+       opt_in_lds((const void*)expert_down_fused_kernel<float, 1, DOWN_KW, 8>) &&
+       opt_in_lds((const void*)expert_down_fused_kernel<float, 1, DOWN_KW, 4>);
   ok = ok && opt_in_lds((const void*)router_kernel<bf16_t, 1, 8>) && opt_in_lds((const void*)router_kernel<float, 1, 8>) &&
        opt_in_lds((const void*)router_kernel<bf16_t, 2, 8>) && opt_in_lds((const void*)router_kernel<float, 2, 8>);
   (void)hipGetLastError();

@@ -31,7 +31,14 @@ void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_se
 // Normalised-input planes: whoever produces a residual row x[t] also stores x[t] * gain (gain of the RMSNorm
 // that follows; the row's 1/rms factor is NOT applied) as a k-major activation matrix [T][H] (act_index in
 // common.hpp).  The consumers feed it to the matrix cores and apply 1/rms in their epilogues.
-// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
+// Row statistics travel as shares of the row's sum of squares, ssq[n_ssq][T] (row_rinv in common.hpp): one share
+// per 64-feature task where a projection epilogue produced the row, a single share from the kernels below.
+struct RowNorm {
+  const float* ssq;
+  int n_ssq;
+  float eps;
+};
+// x[t] = emb[token[t]];  ssq[t] = sum(x[t]^2);  xn[t] = planes of x[t] * gain
 // Iteration smoothing: a position that is still masked (bit of its sequence's mask, uniform blocks of block_len
 // tokens) is embedded as emb[token] + alpha * delta[t].  Pass null for a plain embedding.
 struct SmoothIn {
@@ -40,11 +47,11 @@ struct SmoothIn {
   const uint64_t* mask;     // [n_seq]
   int block_len;
 };
-void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st);
-// x[t] += sum_j topk_w[t][j] * O[t*k+j];  rinv[t] and xn[t] as above, of the updated row
+void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int H, int V, float* x,
+                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st);
+// x[t] += sum_j topk_w[t][j] * O[t*k+j];  ssq[t] and xn[t] as above, of the updated row
 void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
-                    float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st);
+                    int T, int H, float* ssq, const float* gain, void* xn, hipStream_t st);
 
 // Cross-workgroup split-K scratch shared by the projections and the router (see gemm.hip): `part` holds the
 // workgroup sums, `tickets` one arrival counter per (task, token group), all zero between launches.
@@ -53,7 +60,7 @@ int gemm_slices(bool bf16, int K, int T);   // workgroups that share one task's 
 struct QkvArgs {
   const void* w;            // packed fused QKV
   const void* xn;           // [T][H] normalised-input planes (attention gain)
-  const float* rinv;        // [T] 1/rms of the residual rows
+  RowNorm norm;             // statistics of the residual rows
   void* q;                  // [T][D] (hi / lo planes)
   int64_t q_plane;
   void* kv_layer;           // pool base of this layer
@@ -156,22 +163,31 @@ struct ExpertArgs {
   const void* xn;           // [T][H] normalised-input planes (FFN gain)
   const float* rinv;        // [T]
   void* y;                  // [T*k][I] k-major
-  float* o;                 // [T*k][H], row = token*top_k + slot
+  float* o;                 // [T*k][H], row = token*top_k + slot (many-token form only)
   const int32_t* cnt;
   const int32_t* off;
   const int32_t* perm;
   const int32_t* work;      // see RouterArgs
   int T, H, I, E, top_k;
+  // at most 32 tokens: the down projection is fused with the combine (launch_expert_down_fused); the expert
+  // intermediate then carries the routing weight, taken from topk_w [T][top_k] (null: not applied)
+  const float* topk_w;
+  const int32_t* topk_idx;  // [T][top_k]
+  const int32_t* pos_of_pair;
 };
 void launch_expert_gate_up(bool bf16, const ExpertArgs& a, hipStream_t st);   // picks the form by a.T
 void launch_expert_down(bool bf16, const ExpertArgs& a, hipStream_t st);
+// x += sum over a token's experts of (weighted intermediate) . Wd^T, then as launch_oproj: normalised-input planes
+// with the gain of the norm that follows, sums of squares per task.  At most 32 tokens (one token tile).
+void launch_expert_down_fused(bool bf16, const ExpertArgs& a, const OprojArgs& res, hipStream_t st);
+int down_fused_slices();      // workgroups that share one task's sum (workspace sizing)
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st);   // many-token forms (wide.hip)
 void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st);
 
 struct LmArgs {
   const void* w;            // packed LM head
   const void* xn;           // [T][H] normalised-input planes (final gain)
-  const float* rinv;        // [T]
+  RowNorm norm;             // statistics of the residual rows
   int T, H, V;
   float scale;
   float* part;              // [lm_head_parts(V, T)][T][4]: max, sum-exp, argmax bits, unused
@@ -186,7 +202,7 @@ int lm_head_wide_parts(int V);
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
                      hipStream_t st);
 // Credit decoding of the masked rows: conf / argmax hold the plain values on entry and the enhanced ones on return.
-void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rinv, int T, int H, int V, float scale,
+void launch_credit(bool bf16, const void* w_lm, const void* xn, RowNorm norm, int T, int H, int V, float scale,
                    const float* stats, const uint64_t* mask, int block_len, float alpha, float beta, float gamma,
                    int32_t* cred_ids, float* cred_val, int32_t* cred_n, float* conf, int32_t* argmax, hipStream_t st);
 // conf / argmax: one row per forward token, position i of sequence s at row s*row_stride + row_off + i;

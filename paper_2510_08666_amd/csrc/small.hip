@@ -70,11 +70,11 @@ __device__ inline float block_sum_256(float v, float* sh) {
   return r;
 }
 
-// x[t] = emb[token[t]];  rinv[t] = 1 / sqrt(mean(x[t]^2) + eps);  xn[t] = planes of x[t] * gain
+// x[t] = emb[token[t]];  ssq[t] = sum(x[t]^2);  xn[t] = planes of x[t] * gain
 template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
-                                                             float eps, int H, int V, float* __restrict__ x,
-                                                             float* __restrict__ rinv, const float* __restrict__ gain,
+                                                             int H, int V, float* __restrict__ x,
+                                                             float* __restrict__ ssq, const float* __restrict__ gain,
                                                              E* __restrict__ xn, int T, SmoothIn sm) {
   __shared__ float sh[4];
   const int t = blockIdx.x;
@@ -90,17 +90,15 @@ __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __re
     ss += v * v;
   }
   ss = block_sum_256(ss, sh);
-  if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
+  if (threadIdx.x == 0) ssq[t] = ss;
 }
-void launch_embed(bool bf16, const int32_t* tokens, const void* emb, float eps, int T, int H, int V, float* x,
-                  float* rinv, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st) {
+void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int H, int V, float* x,
+                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st) {
   const SmoothIn sm = smooth ? *smooth : SmoothIn{nullptr, 0.f, nullptr, 1};
   if (bf16)
-    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, eps, H, V, x, rinv, gain, (bf16_t*)xn,
-                                                    T, sm);
+    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, H, V, x, ssq, gain, (bf16_t*)xn, T, sm);
   else
-    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, eps, H, V, x, rinv, gain, (float*)xn,
-                                                   T, sm);
+    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, H, V, x, ssq, gain, (float*)xn, T, sm);
 }
 
 // ---------------------------------------------------------------- iteration smoothing: probabilities
@@ -125,13 +123,14 @@ void launch_prob_planes(bool bf16, const float* logits, const float* stats, int 
   else prob_planes_kernel<float><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (float*)probs);
 }
 
-// x[t] += sum_j w[t][j] * O[t*k+j]  (j ascending: a fixed summation order);  rinv[t] and the normalised-input
-// planes of the new row.
+// x[t] += sum_j w[t][j] * O[t*k+j]  (j ascending: a fixed summation order);  ssq[t] = sum of squares and the
+// normalised-input planes of the new row.  (Forwards of more than 64 tokens; smaller ones fold this into the down
+// projection.)
 // Thread i owns columns 4*i + 1024*c .. +3 (hidden is a multiple of 64, so chunks are whole or absent).
 template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict__ x, const float* __restrict__ O,
-                                                               const float* __restrict__ topk_w, int top_k, float eps,
-                                                               int H, float* __restrict__ rinv,
+                                                               const float* __restrict__ topk_w, int top_k,
+                                                               int H, float* __restrict__ ssq,
                                                                const float* __restrict__ gain, E* __restrict__ xn,
                                                                int T) {
   __shared__ float sh[4];
@@ -168,14 +167,14 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
     }
   }
   ss = block_sum_256(ss, sh);
-  if (threadIdx.x == 0) rinv[t] = rsqrtf(ss / H + eps);
+  if (threadIdx.x == 0) ssq[t] = ss;
 }
 void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
-                    float eps, int T, int H, float* rinv, const float* gain, void* xn, hipStream_t st) {
+                    int T, int H, float* ssq, const float* gain, void* xn, hipStream_t st) {
   if (bf16)
-    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, eps, H, rinv, gain, (bf16_t*)xn, T);
+    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (bf16_t*)xn, T);
   else
-    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, eps, H, rinv, gain, (float*)xn, T);
+    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (float*)xn, T);
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
@@ -343,7 +342,7 @@ void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int3
 // of the row's normalised-input planes with the listed rows of the packed LM head.  One workgroup per position.
 template <typename E>
 __global__ __launch_bounds__(256) void credit_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                      const float* __restrict__ rinv, int T, int H, int V, float scale,
+                                                      RowNorm norm, int T, int H, int V, float scale,
                                                       const float* __restrict__ stats, const uint64_t* __restrict__ mask,
                                                       int block_len, float alpha, float beta, float gamma,
                                                       int32_t* __restrict__ cred_ids, float* __restrict__ cred_val,
@@ -398,7 +397,7 @@ __global__ __launch_bounds__(256) void credit_kernel(const E* __restrict__ W, co
   __syncthreads();
   const int n = s_n;
   const int ksteps = H / KS;
-  const float zs = rinv[row] * scale;
+  const float zs = row_rinv(norm.ssq, norm.n_ssq, T, row, H, norm.eps) * scale;
   for (int k = wave; k < n; k += 4) {
     const int v = s_ids[k];
     float z;
@@ -439,14 +438,14 @@ __global__ __launch_bounds__(256) void credit_kernel(const E* __restrict__ W, co
     argmax[row] = best;
   }
 }
-void launch_credit(bool bf16, const void* w_lm, const void* xn, const float* rinv, int T, int H, int V, float scale,
+void launch_credit(bool bf16, const void* w_lm, const void* xn, RowNorm norm, int T, int H, int V, float scale,
                    const float* stats, const uint64_t* mask, int block_len, float alpha, float beta, float gamma,
                    int32_t* cred_ids, float* cred_val, int32_t* cred_n, float* conf, int32_t* argmax, hipStream_t st) {
   if (bf16)
-    credit_kernel<bf16_t><<<T, 256, 0, st>>>((const bf16_t*)w_lm, (const bf16_t*)xn, rinv, T, H, V, scale, stats, mask,
+    credit_kernel<bf16_t><<<T, 256, 0, st>>>((const bf16_t*)w_lm, (const bf16_t*)xn, norm, T, H, V, scale, stats, mask,
                                              block_len, alpha, beta, gamma, cred_ids, cred_val, cred_n, conf, argmax);
   else
-    credit_kernel<float><<<T, 256, 0, st>>>((const float*)w_lm, (const float*)xn, rinv, T, H, V, scale, stats, mask,
+    credit_kernel<float><<<T, 256, 0, st>>>((const float*)w_lm, (const float*)xn, norm, T, H, V, scale, stats, mask,
                                             block_len, alpha, beta, gamma, cred_ids, cred_val, cred_n, conf, argmax);
 }
 

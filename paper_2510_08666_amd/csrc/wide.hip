@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* _
                                                                       const int32_t* __restrict__ off,
                                                                       const int32_t* __restrict__ perm,
                                                                       const int32_t* __restrict__ work, int T, int H, int I,
-                                                                      int top_k) {
+                                                                      int top_k, const float* __restrict__ topk_w) {
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
@@ -66,14 +66,16 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* _
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int n_tasks = I / TILE, task = min((int)blockIdx.x * WW + wave, n_tasks - 1);
   const int ksteps = H / KS;
-  float r[WT];
+  float r[WT], wgt[WT];
   // the token rows hang on the permutation: that chain is resolved while the first weights are in flight
   auto brow = [&]() {
     int tok[WT];
 #pragma unroll
     for (int t = 0; t < WT; ++t) {
-      tok[t] = perm[base + min(row0 + t * TILE + col, n_rows - 1)] / top_k;
+      const int pair = perm[base + min(row0 + t * TILE + col, n_rows - 1)];
+      tok[t] = pair / top_k;
       r[t] = rinv[tok[t]];
+      wgt[t] = topk_w ? topk_w[pair] : 1.f;   // the routing weight, when the down projection sums the experts itself
     }
     int stage_tok = tok[0];
 #pragma unroll
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* _
       for (int g = 0; g < 4; ++g) {   // accumulator registers 4g .. 4g+3 are four consecutive features
         f32x4 y;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) y[i] = silu_w(acc0[t][4 * g + i] * r[t]) * (acc1[t][4 * g + i] * r[t]);
+        for (int i = 0; i < 4; ++i) y[i] = silu_w(acc0[t][4 * g + i] * r[t]) * (acc1[t][4 * g + i] * r[t]) * wgt[t];
         store_actk4<E>(Y, (int64_t)T * top_k, base + row, task * TILE + acc_row(4 * g, half), y);
       }
     }
@@ -163,15 +165,16 @@ template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hip
   if (a.T <= TILE) {
     expert_gemm1_wide_kernel<E, 1, SMALL_WW, 16, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 16, 1>(), st>>>(
-        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w);
   } else if (a.T <= 2 * TILE) {
     expert_gemm1_wide_kernel<E, 2, SMALL_WW, 17, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 17, 2>(), st>>>(
-        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w);
   } else {
     expert_gemm1_wide_kernel<E, WT, EXPERT_WW, 10, false>
         <<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)), EXPERT_WW * WAVE,
-           wide_lds<E, 10, WT>(), st>>>(w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k);
+           wide_lds<E, 10, WT>(), st>>>(w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k,
+                                        a.topk_w);
   }
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
@@ -212,7 +215,7 @@ void launch_expert_down_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
 // ------------------------------------------------------------------------------------------------
 template <typename E, int WT, int KID, int WW>
 __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
-                                                                  const float* __restrict__ rinv, int T, int H, int V,
+                                                                  RowNorm norm, int T, int H, int V,
                                                                   float scale, float* __restrict__ part,
                                                                   float* __restrict__ logits_out) {
   typedef typename ET<E>::vec vec;
@@ -231,7 +234,7 @@ __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __rest
   const int ksteps = H / KS;
   float zs[WT];
 #pragma unroll
-  for (int t = 0; t < WT; ++t) zs[t] = rinv[min(tok0 + t * TILE + col, T - 1)] * scale;
+  for (int t = 0; t < WT; ++t) zs[t] = row_rinv(norm.ssq, norm.n_ssq, T, min(tok0 + t * TILE + col, T - 1), H, norm.eps) * scale;
   const E* brow = xn + (int64_t)min(tok0 + (wave % WT) * TILE + col, T - 1) * (NP * KS) + half * G;
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
@@ -292,19 +295,19 @@ template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t 
   if (a.T <= TILE) {   // one token tile (trace id 15)
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 1, 15, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 15, 1>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
     return;
   }
   if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
     return;
   }
   const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   lm_head_wide_kernel<E, WT, 9, LM_WW><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
-      (const E*)a.w, (const E*)a.xn, a.rinv, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+      (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
   if (bf16) launch_lm_wide_t<bf16_t>(a, st);
