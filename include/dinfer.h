@@ -12,7 +12,7 @@
  *  - All `d_` pointers are DEVICE pointers, `h_` pointers are HOST pointers.  The caller owns every buffer;
  *    the library allocates no device memory and keeps only the pointers given to dinfer_create.
  *  - `stream` is a hipStream_t passed as void*; work is enqueued on it and the call returns without waiting
- *    (dinfer_generate_block in threshold mode waits between steps to read the mask).  Outputs are valid
+ *    (dinfer_generate_block in threshold mode waits once per batch of steps, see there).  Outputs are valid
  *    after the caller synchronises the stream.
  *  - Return value: 0 on success, a negative DINFER_E* code otherwise.  Nothing is launched when an argument
  *    is rejected.  dinfer_last_error() returns a thread-local description of the last failure.
@@ -230,7 +230,8 @@ int dinfer_refresh_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, cons
  * ceil(block_len / fixed_k) steps are enqueued without waiting) and is then run through dinfer_refresh_block.
  * Once a decoded block of a sequence contains eos_id (negative: never) the sequence is finished: its remaining
  * blocks are filled with eos_id and commit nothing; when every sequence is finished the loop stops.  The host
- * waits once per block to read the count of finished sequences.
+ * waits once per block to read the count of finished sequences (and, with threshold decoding, once per
+ * steps_per_wait steps inside a block: see dinfer_generate_block).
  *   d_out          [n_seq][n_blocks * block_len] out: the generated ids.
  *   d_block_tokens [n_seq][block_len], d_mask [n_seq], d_conf, d_argmax, d_n_committed: working buffers as in
  *                  dinfer_step (contents on return: those of the last step).
@@ -240,17 +241,26 @@ int dinfer_refresh_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, cons
  *   *h_blocks_run  (host, may be NULL): blocks that were run before the loop stopped. */
 int dinfer_generate(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t n_blocks, int32_t* d_out,
                     int32_t* d_block_tokens, uint64_t* d_mask, int32_t* d_prefix_len, const int32_t* d_page_table,
-                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t* d_finished,
-                    float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run, void* stream);
+                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t steps_per_wait,
+                    int32_t* d_finished, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run,
+                    void* stream);
 
-/* The inner loop of Algorithm 1: steps until every mask is empty or max_steps were taken.  With
- * fixed_k > 0 and h_masked_hint > 0 (the caller's count of undecided positions per sequence, the same for
- * all) exactly ceil(h_masked_hint / fixed_k) steps are enqueued without waiting; otherwise the masks are
- * read back after each step.  *h_steps_taken (host, may be NULL) receives the number of steps. */
+/* The inner loop of Algorithm 1: steps until every mask is empty or max_steps (at most 256) were taken.
+ *  - fixed_k > 0 and h_masked_hint > 0 (the caller's count of undecided positions per sequence, the same for
+ *    all): exactly ceil(h_masked_hint / fixed_k) steps are enqueued without waiting.
+ *  - otherwise the number of steps depends on the data.  Steps are enqueued steps_per_wait at a time (0 or 1: one
+ *    at a time) without waiting for their outcome, and the host waits once per such batch (Section 3, "Diffusion
+ *    iterations": iterations are launched back to back; "Parallel decoding": the decoder runs on the device and
+ *    nothing is copied to the host between iterations).  The device itself knows whether a step is still needed:
+ *    the decoder of every step records whether a masked position remains, and the kernels of a step that finds
+ *    nothing masked return at once -- such a step changes nothing, writes no output and is not counted.  A batch
+ *    can therefore run up to steps_per_wait - 1 such empty steps behind the last real one (about a tenth of a
+ *    real step each); the results are the same for every steps_per_wait.
+ * *h_steps_taken (host, may be NULL) receives the number of steps that ran. */
 int dinfer_generate_block(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens,
                           uint64_t* d_mask, const int32_t* d_prefix_len, const int32_t* d_page_table,
                           int32_t pt_stride, const dinfer_decode* decode, float* d_conf, int32_t* d_argmax,
-                          int32_t* d_n_committed, int32_t max_steps, int32_t h_masked_hint,
+                          int32_t* d_n_committed, int32_t max_steps, int32_t h_masked_hint, int32_t steps_per_wait,
                           int32_t* h_steps_taken, void* stream);
 
 /* Moves K,V rows of one layer and one sequence between the pool and plain float32 arrays

@@ -114,12 +114,12 @@ def _load():
     L.dinfer_refresh_block.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp]
     L.dinfer_generate_block.restype = c_i32
     L.dinfer_generate_block.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_vp, c_vp, c_vp,
-                                        c_i32, c_i32, P(c_i32), c_vp]
+                                        c_i32, c_i32, c_i32, P(c_i32), c_vp]
     L.dinfer_commit.restype = c_i32
     L.dinfer_commit.argtypes = [c_vp, c_vp, c_i32, c_i32, c_vp, c_vp, P(Decode), c_vp, c_vp]
     L.dinfer_generate.restype = c_i32
-    L.dinfer_generate.argtypes = [c_vp, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_i32, c_vp,
-                                  c_vp, c_vp, c_vp, P(c_i32), c_vp]
+    L.dinfer_generate.argtypes = [c_vp, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_i32, c_i32,
+                                  c_vp, c_vp, c_vp, c_vp, P(c_i32), c_vp]
     L.dinfer_kv_write.restype = c_i32
     L.dinfer_kv_write.argtypes = [c_vp, c_i32, c_vp, c_i32, c_i32, c_vp, c_vp, c_vp]
     L.dinfer_kv_read.restype = c_i32
@@ -300,18 +300,21 @@ class Context:
                                         _ptr(d_page_table), d_page_table.shape[1], _stream()))
 
     def generate_block(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, d_conf, d_argmax,
-                       d_n_committed, max_steps, masked_hint=0):
+                       d_n_committed, max_steps, masked_hint=0, steps_per_wait=1):
+        """The inner loop over the steps of a block; returns the number of steps that ran.  steps_per_wait: steps
+        enqueued between two host waits when the step count depends on the data."""
         n_seq, block_len = d_block_tokens.shape
         dec = _decode(threshold, fixed_k)
         steps = c_i32(0)
         _check(lib.dinfer_generate_block(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask),
                                          _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1],
                                          ctypes.byref(dec), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
-                                         int(max_steps), int(masked_hint), ctypes.byref(steps), _stream()))
+                                         int(max_steps), int(masked_hint), int(steps_per_wait), ctypes.byref(steps),
+                                         _stream()))
         return steps.value
 
     def generate(self, d_out, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, eos_id,
-                 d_finished, d_conf, d_argmax, d_n_committed):
+                 d_finished, d_conf, d_argmax, d_n_committed, steps_per_wait=1):
         """Outer loop over the blocks of d_out [n_seq][n_blocks * block_len]; returns the blocks that were run."""
         n_seq, block_len = d_block_tokens.shape
         n_blocks = d_out.shape[1] // block_len
@@ -320,8 +323,8 @@ class Context:
         run = c_i32(0)
         _check(lib.dinfer_generate(self.h, n_seq, block_len, n_blocks, _ptr(d_out), _ptr(d_block_tokens), _ptr(d_mask),
                                    _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1], ctypes.byref(dec),
-                                   int(eos_id), _ptr(d_finished), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
-                                   ctypes.byref(run), _stream()))
+                                   int(eos_id), int(steps_per_wait), _ptr(d_finished), _ptr(d_conf), _ptr(d_argmax),
+                                   _ptr(d_n_committed), ctypes.byref(run), _stream()))
         return run.value
 
     # ---- KV rows in and out, test hooks

@@ -41,6 +41,14 @@ int fail(int code, const char* fmt, ...) {
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+constexpr int MAX_LOOP_STEPS = 256;   // steps one dinfer_generate_block call can take (a block has at most 64 positions)
+
+// Every kernel enqueued while a LiveScope exists is handed `word` (see step_is_dead in common.hpp).
+struct LiveScope {
+  explicit LiveScope(const int32_t* word) { set_live_word(word); }
+  ~LiveScope() { set_live_word(nullptr); }
+};
+
 // Address of the static scratch array on the current device (*dev_out).  Resolved once per device.
 int static_scratch_of_current_device(void** out, int* dev_out) {
   int dev = -1;
@@ -130,7 +138,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, ssq_a, tk_part, tickets, tickets_bytes, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, work, run_tokens, run_base, n_finished, y, o, lm_part, lm_stats, conf, argmax, total;
+      perm, pos_of_pair, work, run_tokens, run_base, n_finished, loop_flags, loop_steps, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -190,6 +198,8 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.run_tokens = cv.take(T * 4);                 // token run and start positions of a vicinity-refresh forward
   w.run_base = cv.take((size_t)max_seqs * 4);
   w.n_finished = cv.take(4);                     // generation loop: sequences that have produced the end-of-sequence id
+  w.loop_flags = cv.take((size_t)(MAX_LOOP_STEPS + 1) * 4);   // inner loop: "step i is still needed" words
+  w.loop_steps = cv.take(4);                     // inner loop: steps that ran
   w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
@@ -563,14 +573,17 @@ int dinfer_prefill(dinfer_ctx* c, int32_t n_seq, const int32_t* d_tokens, const 
   return forward(c, span, d_tokens, nullptr, d_page_table, pt_stride, false, (hipStream_t)stream);
 }
 
-int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
-                const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, const dinfer_decode* decode,
-                float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+// One plain step.  live / next_live / steps: the words of a loop of steps enqueued ahead of the host (null for a
+// single step).
+static int step_impl(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                     const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                     const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
+                     hipStream_t st, const int32_t* live, int32_t* next_live, int32_t* steps) {
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
   if ((rc = check_decode(decode)) != DINFER_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
+  LiveScope scope(live);
   rc = forward(c, uniform_span(n_seq, block_len), d_block_tokens, d_prefix_len, d_page_table, pt_stride, true, st);
   if (rc != DINFER_OK) return rc;
   const dinfer_config& f = c->cfg;
@@ -583,9 +596,17 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
     launch_lm_head(c->bf16, la, st);
   }
   launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed,
+                nullptr, nullptr, st, next_live, steps);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
+}
+
+int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride, const dinfer_decode* decode,
+                float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+  return step_impl(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode, d_conf,
+                   d_argmax, d_n_committed, (hipStream_t)stream, nullptr, nullptr, nullptr);
 }
 
 size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens) {
@@ -748,9 +769,11 @@ int dinfer_refresh_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, const 
 int dinfer_generate_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
                           const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
                           const dinfer_decode* decode, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed,
-                          int32_t max_steps, int32_t h_masked_hint, int32_t* h_steps_taken, void* stream) {
-  if (max_steps < 1) return fail(DINFER_EINVAL, "max_steps < 1");
+                          int32_t max_steps, int32_t h_masked_hint, int32_t steps_per_wait, int32_t* h_steps_taken,
+                          void* stream) {
+  if (max_steps < 1 || max_steps > MAX_LOOP_STEPS) return fail(DINFER_EINVAL, "max_steps %d outside [1, %d]", max_steps, MAX_LOOP_STEPS);
   if (!decode) return fail(DINFER_EINVAL, "decode is null");
+  if (steps_per_wait < 0) return fail(DINFER_EINVAL, "steps_per_wait %d", steps_per_wait);
   hipStream_t st = (hipStream_t)stream;
   int steps = 0;
   if (decode->fixed_k > 0 && h_masked_hint > 0) {
@@ -762,17 +785,30 @@ int dinfer_generate_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32
       if (rc != DINFER_OK) return rc;
     }
   } else {
-    while (steps < max_steps) {
-      if (!c || !d_mask || n_seq < 1 || n_seq > MAX_SEQS) return fail(DINFER_EINVAL, "bad argument");
-      HIP_TRY(hipMemcpyAsync(c->h_mask_pinned, d_mask, (size_t)n_seq * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    // The number of steps depends on the data.  Steps are enqueued steps_per_wait at a time without waiting; the
+    // device keeps one "still needed" word per step, raised by the decoder of the step before it, and a step whose
+    // word is zero costs only the launches of its kernels.  The host waits once per batch to read the word of the
+    // next step and the number of steps that ran.
+    if (!c || !d_mask || n_seq < 1 || n_seq > c->max_seqs) return fail(DINFER_EINVAL, "bad argument");
+    const int batch = steps_per_wait > 0 ? steps_per_wait : 1;
+    int32_t* flags = at<int32_t>(c->ws, c->wsm.loop_flags);
+    int32_t* d_steps = at<int32_t>(c->ws, c->wsm.loop_steps);
+    int32_t* h_words = reinterpret_cast<int32_t*>(c->h_mask_pinned);
+    launch_loop_begin(d_mask, n_seq, flags, max_steps + 1, d_steps, st);
+    int enq = 0;
+    while (enq < max_steps) {
+      const int n = batch < max_steps - enq ? batch : max_steps - enq;
+      for (int i = 0; i < n; ++i) {
+        int rc = step_impl(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
+                           d_conf, d_argmax, d_n_committed, st, flags + enq + i, flags + enq + i + 1, d_steps);
+        if (rc != DINFER_OK) return rc;
+      }
+      enq += n;
+      HIP_TRY(hipMemcpyAsync(h_words, flags + enq, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipMemcpyAsync(h_words + 1, d_steps, sizeof(int32_t), hipMemcpyDeviceToHost, st));
       HIP_TRY(hipStreamSynchronize(st));
-      uint64_t any = 0;
-      for (int s = 0; s < n_seq; ++s) any |= c->h_mask_pinned[s];
-      if (!any) break;
-      int rc = dinfer_step(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
-                           d_conf, d_argmax, d_n_committed, stream);
-      if (rc != DINFER_OK) return rc;
-      ++steps;
+      steps = h_words[1];
+      if (h_words[0] == 0) break;
     }
   }
   if (h_steps_taken) *h_steps_taken = steps;
@@ -794,8 +830,9 @@ int dinfer_commit(const float* d_conf, const int32_t* d_argmax, int32_t n_seq, i
 
 int dinfer_generate(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t n_blocks, int32_t* d_out,
                     int32_t* d_block_tokens, uint64_t* d_mask, int32_t* d_prefix_len, const int32_t* d_page_table,
-                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t* d_finished, float* d_conf,
-                    int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run, void* stream) {
+                    int32_t pt_stride, const dinfer_decode* decode, int32_t eos_id, int32_t steps_per_wait,
+                    int32_t* d_finished, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, int32_t* h_blocks_run,
+                    void* stream) {
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   if (!d_out || !d_mask || !d_finished || !d_conf || !d_argmax || !d_n_committed) return fail(DINFER_EINVAL, "null pointer");
@@ -809,7 +846,7 @@ int dinfer_generate(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t n_b
   for (; b < n_blocks; ++b) {
     launch_block_begin(n_seq, block_len, c->cfg.mask_id, eos_id, d_finished, b == 0, d_block_tokens, d_mask, st);
     rc = dinfer_generate_block(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode,
-                               d_conf, d_argmax, d_n_committed, block_len, block_len, nullptr, stream);
+                               d_conf, d_argmax, d_n_committed, block_len, block_len, steps_per_wait, nullptr, stream);
     if (rc != DINFER_OK) return rc;
     rc = dinfer_refresh_block(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride, stream);
     if (rc != DINFER_OK) return rc;

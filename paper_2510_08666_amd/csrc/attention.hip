@@ -76,7 +76,8 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
                                                          const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
                                                          int n_splits, float* __restrict__ part, E* __restrict__ out,
-                                                         int T_out) {
+                                                         int T_out, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE, NP = Planes<E>::N;
   const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
@@ -271,7 +272,8 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
 
 template <typename E, int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, FwdMeta meta, int n_heads,
-                                                          int n_parts, E* __restrict__ out, int T_out) {
+                                                          int n_parts, E* __restrict__ out, int T_out, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   const int head = blockIdx.x, qt = blockIdx.y;
   const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
   const int my_parts = min(attn_splits_for(meta.seq_nkeys[meta.qtile[qt * 3]]), n_parts);
@@ -310,10 +312,10 @@ template <int HD> constexpr size_t attn_lds() { return (size_t)ATTN_WAVES * ((HD
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
   attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), ATTN_WAVES * WAVE, attn_lds<HD>(), st>>>(
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
-      (E*)a.out, a.T);
+      (E*)a.out, a.T, live_word());
   if (a.n_splits > 1)
     attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles, TILE * HD / 4 / 256), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
-                                                                                  a.n_splits, (E*)a.out, a.T);
+                                                                                  a.n_splits, (E*)a.out, a.T, live_word());
 }
 
 bool configure_attention() {

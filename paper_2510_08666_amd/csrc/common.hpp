@@ -212,6 +212,11 @@ __device__ inline bool last_arrival(int32_t* c, int n, int32_t* s_flag) {
   return last;
 }
 
+// Steps that are enqueued before the host knows whether they are still needed (the inner loop of blockwise
+// decoding without a host round trip per step) carry the address of a word that is zero once every mask was
+// already empty when the step began: every kernel of such a step returns at once.  Null: an ordinary step.
+__device__ inline bool step_is_dead(const int32_t* live) { return live != nullptr && *live == 0; }
+
 // Which sequence a forward's packed tokens belong to: sequence s owns tokens [off[s], off[s+1]).
 struct SeqSpan {
   int32_t n_seq;

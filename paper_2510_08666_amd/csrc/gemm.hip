@@ -44,7 +44,7 @@ template <typename E> struct QkvEpi {
   // starts and issues only loads whose addresses are known then; prefetch2() runs behind the stream and issues
   // the loads that depend on the first ones, so that they are under way while the partial sums are folded.
   template <int PER> struct Pre {
-    int pos, seq, page;
+    int pos, seq, page, tok;
     float r;
     float c[PER], s[PER];
   };
@@ -53,11 +53,12 @@ template <typename E> struct QkvEpi {
     const int t = valid ? tok : 0;
     p.pos = tok_pos[t];
     p.seq = tok_seq[t];
-    p.r = row_rinv(norm.ssq, norm.n_ssq, T, t, H, norm.eps);
+    p.tok = t;
     return p;
   }
   template <int PER> __device__ void prefetch2(Pre<PER>& p, int task, int half, int v0) const {
     const int hd = geom.head_dim;
+    p.r = row_rinv(norm.ssq, norm.n_ssq, T, p.tok, H, norm.eps);   // up to 32 loads: kept behind the weight stream
     p.page = page_table[(int64_t)p.seq * pt_stride + p.pos / PAGE];
     const int j0 = (task % (hd / 64)) * TILE + acc_row(v0, half);
     const bool rot = task < 2 * geom.n_heads * (hd / 64);
@@ -346,7 +347,8 @@ template <typename E, int TT, int KW, class Epi>
 __global__ __launch_bounds__(KW * WAVE) void gemm_ksplit_kernel(const E* __restrict__ W, int ksteps,
                                                                  const E* __restrict__ B, int T, int K,
                                                                  float* __restrict__ part, int32_t* __restrict__ tickets,
-                                                                 Epi epi) {
+                                                                 Epi epi, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   extern __shared__ float red[];   // [KW][2*TT*16][64]
   __shared__ int32_t s_flag;
   constexpr int ROWS = 2 * TT * 16, PER = 16 / KW;
@@ -427,12 +429,12 @@ static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int T, 
                           float* part, int32_t* tickets, const Epi& epi, hipStream_t st, int forced_slices = 0) {
   const int slices = forced_slices ? forced_slices : gemm_slices(bf16, K, T);
   if (T <= 32) {
-    gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi, live_word());
   } else if (T <= 64) {
-    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 2, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<2, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi, live_word());
   } else {
     const int groups = (T + 4 * TILE - 1) / (4 * TILE);
-    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(forced_slices ? forced_slices : 1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi);
+    gemm_ksplit_kernel<E, 4, 4, Epi><<<dim3(forced_slices ? forced_slices : 1, n_tasks, groups), 4 * WAVE, ksplit_lds<4, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi, live_word());
   }
 }
 
@@ -469,7 +471,8 @@ __global__ __launch_bounds__(KW * WAVE) void expert_down_fused_kernel(const E* _
                                                                        const int32_t* __restrict__ pos_of_pair, int T,
                                                                        int I, int top_k, int n_tasks,
                                                                        float* __restrict__ part,
-                                                                       int32_t* __restrict__ tickets, ResidualEpi<E> epi) {
+                                                                       int32_t* __restrict__ tickets, ResidualEpi<E> epi, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ float red[];   // [KW][2*TT*16][64]
   __shared__ int32_t s_flag;
@@ -664,7 +667,8 @@ template <typename E, int KID, int WT, int DENSE_TASKS> constexpr size_t dense_l
 template <typename E, int WT, int DENSE_TASKS, class Epi>
 __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kernel(const E* __restrict__ W, int ksteps,
                                                                                   const E* __restrict__ B, int T,
-                                                                                  int n_tasks, Epi epi) {
+                                                                                  int n_tasks, Epi epi, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N, PER = 4;
@@ -758,7 +762,7 @@ static void launch_dense_as(const E* W, int ksteps, const E* B, int T, int n_tas
   constexpr int KID = Epi::ROWSUM ? 13 : 12;
   gemm_dense_kernel<E, WT, TASKS, Epi><<<dim3((n_tasks + TASKS - 1) / TASKS, (T + WT * TILE - 1) / (WT * TILE)),
                                         TASKS * DENSE_KH * WAVE, dense_lds<E, KID, WT, TASKS>(), st>>>(W, ksteps, B, T,
-                                                                                                    n_tasks, epi);
+                                                                                                    n_tasks, epi, live_word());
 }
 // More tasks and token tiles per workgroup cut the operand traffic, but only while the launch still fills the chip.
 template <typename E, class Epi>
@@ -949,7 +953,8 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
                                                             int32_t* __restrict__ cnt, int32_t* __restrict__ off,
                                                             int32_t* __restrict__ perm,
                                                             int32_t* __restrict__ pos_of_pair, float* __restrict__ part,
-                                                            int32_t* __restrict__ tickets) {
+                                                            int32_t* __restrict__ tickets, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   extern __shared__ float red[];   // [KW][2*TT*16][64] partials
   constexpr int ROWS = 2 * TT * 16, NTOK = TT * TILE, NTHREADS = KW * WAVE, PER = 16 / KW;
   constexpr int SS_PARTS = NTHREADS / NTOK;                       // threads per token for the sums of squares
@@ -1095,16 +1100,16 @@ template <typename E> static void launch_router_t(bool bf16, const RouterArgs& a
   if (a.T <= 32) {
     router_kernel<E, 1, 8><<<dim3(slices, 1), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
-        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
+        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets, live_word());
   } else if (a.T <= 64) {
     router_kernel<E, 2, 8><<<dim3(slices, 1), 8 * WAVE, ksplit_lds<2, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
-        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
+        a.topk_w, 1, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets, live_word());
   } else {
     const int groups = (a.T + TILE - 1) / TILE;   // 32 tokens per workgroup: one round of the top-k lanes, more workgroups
     router_kernel<E, 1, 8><<<dim3(1, groups), 8 * WAVE, ksplit_lds<1, 8>(), st>>>(
         W, (const E*)a.xn, a.ssq, a.H / 64, a.eps, a.T, a.H, a.E, a.top_k, a.norm_topk, a.rinv, a.topk_idx,
-        a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets);
+        a.topk_w, 0, a.cnt, a.off, a.perm, a.pos_of_pair, a.part, a.tickets, live_word());
     launch_permute(a.topk_idx, a.T * a.top_k, a.E, a.cnt, a.off, a.perm, a.pos_of_pair, a.work, st);
   }
 }
@@ -1124,10 +1129,10 @@ template <typename E> static void launch_down_fused_t(const ExpertArgs& a, const
   const int64_t y_rows = (int64_t)a.T * a.top_k;
   if (ksteps_e % 8 == 0)
     expert_down_fused_kernel<E, 1, DOWN_KW, 8><<<grid, DOWN_KW * WAVE, ksplit_lds<1, DOWN_KW>(), st>>>(
-        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi);
+        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi, live_word());
   else
     expert_down_fused_kernel<E, 1, DOWN_KW, 4><<<grid, DOWN_KW * WAVE, ksplit_lds<1, DOWN_KW>(), st>>>(
-        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi);
+        w, y, y_rows, a.off, a.topk_idx, a.pos_of_pair, a.T, a.I, a.top_k, n_tasks, r.part, r.tickets, epi, live_word());
 }
 void launch_expert_down_fused(bool bf16, const ExpertArgs& a, const OprojArgs& res, hipStream_t st) {
   if (bf16) launch_down_fused_t<bf16_t>(a, res, st);

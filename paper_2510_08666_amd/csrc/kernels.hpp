@@ -8,6 +8,11 @@
 
 namespace dinfer {
 
+// The "is this step still needed" word of the forward being enqueued on this host thread (see step_is_dead in
+// common.hpp): set by the step entry points around a forward, handed to every kernel by its launcher.
+void set_live_word(const int32_t* d_live);
+const int32_t* live_word();
+
 // ---- weight packing (pack.hip) ----
 enum PackMode { PACK_ADJACENT = 0, PACK_ROPE_PAIR = 1, PACK_HALF0 = 2, PACK_HALF1 = 3 };
 // src: [batch][N][K] row-major; dst: [batch][n_tasks][K/KS][2][64][16 B]
@@ -215,9 +220,13 @@ struct CommitRule {
   int hier;
   float tau_low;
 };
+// next_live / steps (may be null): see launch_loop_begin.
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
                    int32_t* tokens, uint64_t* mask, CommitRule rule, int32_t* n_committed, float* conf_out,
-                   int32_t* argmax_out, hipStream_t st);
+                   int32_t* argmax_out, hipStream_t st, int32_t* next_live = nullptr, int32_t* steps = nullptr);
+// Loop of steps enqueued without waiting for the masks: step i runs only if flags[i] != 0 (set_live_word), its
+// decoder raises flags[i + 1] if a masked position remains and adds one to steps[0].
+void launch_loop_begin(const uint64_t* mask, int n_seq, int32_t* flags, int n_flags, int32_t* steps, hipStream_t st);
 // Generation loop over blocks: start of a block (ids = mask_id and a full mask, or eos_id and an empty mask for a
 // finished sequence; `first` clears the finished flags instead of reading them); end of a block (copy into out[s][block_index], mark sequences whose block holds eos_id,
 // count the finished ones into n_finished[0]); fill of the blocks from first_block on with eos_id.

@@ -6,6 +6,10 @@
 
 namespace dinfer {
 
+static thread_local const int32_t* t_live_word = nullptr;
+void set_live_word(const int32_t* d_live) { t_live_word = d_live; }
+const int32_t* live_word() { return t_live_word; }
+
 // ---------------------------------------------------------------- rotary table
 // cos / sin of pos * theta^(-2j/hd), computed in double on the device and stored as float.
 __global__ void rope_table_kernel(float* __restrict__ cos_tab, float* __restrict__ sin_tab, int max_pos, int head_dim,
@@ -28,7 +32,8 @@ void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim
 // leave it is pulled back so that no later kernel indexes outside its buffers.
 __global__ void meta_kernel(SeqSpan span, const int32_t* __restrict__ d_base, int limit, int32_t* __restrict__ tok_seq,
                             int32_t* __restrict__ tok_pos, int32_t* __restrict__ seq_nkeys,
-                            int32_t* __restrict__ qtile) {
+                            int32_t* __restrict__ qtile, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   for (int s = 0; s < span.n_seq; ++s) {
     const int o = span.off[s], len = span.off[s + 1] - o;
     const int base = d_base ? max(0, min(d_base[s], limit - len)) : 0;
@@ -53,7 +58,7 @@ __global__ void meta_kernel(SeqSpan span, const int32_t* __restrict__ d_base, in
 }
 void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
                  int32_t* seq_nkeys, int32_t* qtile, hipStream_t st) {
-  meta_kernel<<<1, 256, 0, st>>>(span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile);
+  meta_kernel<<<1, 256, 0, st>>>(span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile, live_word());
 }
 
 // ---------------------------------------------------------------- RMSNorm helpers
@@ -75,7 +80,8 @@ template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
                                                              int H, int V, float* __restrict__ x,
                                                              float* __restrict__ ssq, const float* __restrict__ gain,
-                                                             E* __restrict__ xn, int T, SmoothIn sm) {
+                                                             E* __restrict__ xn, int T, SmoothIn sm, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   __shared__ float sh[4];
   const int t = blockIdx.x;
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
@@ -96,9 +102,9 @@ void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int 
                   float* ssq, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st) {
   const SmoothIn sm = smooth ? *smooth : SmoothIn{nullptr, 0.f, nullptr, 1};
   if (bf16)
-    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, H, V, x, ssq, gain, (bf16_t*)xn, T, sm);
+    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, H, V, x, ssq, gain, (bf16_t*)xn, T, sm, live_word());
   else
-    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, H, V, x, ssq, gain, (float*)xn, T, sm);
+    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, H, V, x, ssq, gain, (float*)xn, T, sm, live_word());
 }
 
 // ---------------------------------------------------------------- iteration smoothing: probabilities
@@ -132,7 +138,8 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
                                                                const float* __restrict__ topk_w, int top_k,
                                                                int H, float* __restrict__ ssq,
                                                                const float* __restrict__ gain, E* __restrict__ xn,
-                                                               int T) {
+                                                               int T, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   __shared__ float sh[4];
   constexpr int CH = NORM_MAX_PER_THREAD / 4;
   const int t = blockIdx.x;
@@ -172,9 +179,9 @@ __global__ __launch_bounds__(NORM_THREADS) void combine_kernel(float* __restrict
 void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
                     int T, int H, float* ssq, const float* gain, void* xn, hipStream_t st) {
   if (bf16)
-    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (bf16_t*)xn, T);
+    combine_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (bf16_t*)xn, T, live_word());
   else
-    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (float*)xn, T);
+    combine_kernel<float><<<T, NORM_THREADS, 0, st>>>(x, O, topk_w, top_k, H, ssq, gain, (float*)xn, T, live_word());
 }
 
 // ---------------------------------------------------------------- token -> expert permutation
@@ -194,7 +201,8 @@ __device__ inline uint64_t chunk_ballots(unsigned long long* mine, int lane, int
 __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict__ expert_of_pair, int n_pairs,
                                                         int n_exp, int32_t* __restrict__ cnt, int32_t* __restrict__ off,
                                                         int32_t* __restrict__ perm, int32_t* __restrict__ pos_of_pair,
-                                                        int32_t* __restrict__ work) {
+                                                        int32_t* __restrict__ work, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   extern __shared__ uint16_t s_pre[];                       // [n_chunks][MAX_EXPERTS]
   __shared__ unsigned long long s_ballot[16 * MAX_EXPERTS];
   __shared__ int32_t s_off[MAX_EXPERTS + 1];
@@ -283,7 +291,7 @@ void launch_permute(const int32_t* topk_idx, int n_pairs, int E, int32_t* cnt, i
                     int32_t* pos_of_pair, int32_t* work, hipStream_t st) {
   const int n_chunks = (n_pairs + WAVE - 1) / WAVE;
   permute_kernel<<<1, 1024, (size_t)n_chunks * MAX_EXPERTS * sizeof(uint16_t), st>>>(topk_idx, n_pairs, E, cnt, off, perm,
-                                                                                     pos_of_pair, work);
+                                                                                     pos_of_pair, work, live_word());
 }
 
 // ---------------------------------------------------------------- LM-head partial merge
@@ -304,7 +312,8 @@ __device__ inline LmStat lm_combine(LmStat a, LmStat b) {
 }
 __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__ part, int n_waves, int T,
                                                         float* __restrict__ conf, int32_t* __restrict__ argmax,
-                                                        float* __restrict__ stats) {
+                                                        float* __restrict__ stats, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   __shared__ LmStat sh[4];
   const int t = blockIdx.x;
   LmStat a{-INFINITY, 0.f, 0x7fffffff};
@@ -331,7 +340,7 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__
 }
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
                      hipStream_t st) {
-  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax, stats);
+  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax, stats, live_word());
 }
 
 // ---------------------------------------------------------------- decoder: credit decoding
@@ -458,7 +467,10 @@ __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ co
                                                      int block_len, int row_stride, int row_off,
                                                      int32_t* __restrict__ tokens, uint64_t* __restrict__ mask,
                                                      CommitRule rule, int32_t* __restrict__ n_committed,
-                                                     float* __restrict__ conf_out, int32_t* __restrict__ argmax_out) {
+                                                     float* __restrict__ conf_out, int32_t* __restrict__ argmax_out,
+                                                     int32_t* __restrict__ next_live, int32_t* __restrict__ steps,
+                                                     const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   __shared__ float conf_of[64];
   const float threshold = rule.threshold;
   const int fixed_k = rule.fixed_k;
@@ -524,13 +536,33 @@ __global__ __launch_bounds__(64) void commit_kernel(const float* __restrict__ co
   if (lane == 0) {
     mask[s] = old & ~sel;
     n_committed[s] = __popcll(sel);
+    // a loop of steps enqueued ahead of the host: the next step is needed if any sequence still has a masked
+    // position (an OR over the sequences: integer, so the order of arrival does not matter), and this one counted
+    if (next_live && (old & ~sel)) atomicOr(next_live, 1);
+    if (steps && s == 0) atomicAdd(steps, 1);
   }
 }
 void launch_commit(const float* conf, const int32_t* argmax, int n_seq, int block_len, int row_stride, int row_off,
                    int32_t* tokens, uint64_t* mask, CommitRule rule, int32_t* n_committed, float* conf_out,
-                   int32_t* argmax_out, hipStream_t st) {
+                   int32_t* argmax_out, hipStream_t st, int32_t* next_live, int32_t* steps) {
   commit_kernel<<<n_seq, 64, 0, st>>>(conf, argmax, block_len, row_stride, row_off, tokens, mask, rule, n_committed,
-                                      conf_out, argmax_out);
+                                      conf_out, argmax_out, next_live, steps, live_word());
+}
+
+// Start of a loop of steps enqueued ahead of the host: flags[0] = does any sequence have a masked position;
+// flags[1 .. n_flags) = 0 (each step's decoder raises the flag of the step after it); steps[0] = 0.
+__global__ void loop_begin_kernel(const uint64_t* __restrict__ mask, int n_seq, int32_t* __restrict__ flags, int n_flags,
+                                  int32_t* __restrict__ steps) {
+  for (int i = 1 + threadIdx.x; i < n_flags; i += blockDim.x) flags[i] = 0;
+  if (threadIdx.x == 0) {
+    uint64_t any = 0;
+    for (int s = 0; s < n_seq; ++s) any |= mask[s];
+    flags[0] = any != 0;
+    steps[0] = 0;
+  }
+}
+void launch_loop_begin(const uint64_t* mask, int n_seq, int32_t* flags, int n_flags, int32_t* steps, hipStream_t st) {
+  loop_begin_kernel<<<1, 256, 0, st>>>(mask, n_seq, flags, n_flags, steps);
 }
 
 // ---------------------------------------------------------------- generation loop over blocks

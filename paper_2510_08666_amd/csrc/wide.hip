@@ -54,7 +54,8 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* _
                                                                       const int32_t* __restrict__ off,
                                                                       const int32_t* __restrict__ perm,
                                                                       const int32_t* __restrict__ work, int T, int H, int I,
-                                                                      int top_k, const float* __restrict__ topk_w) {
+                                                                      int top_k, const float* __restrict__ topk_w, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
@@ -110,7 +111,8 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm2_wide_kernel(const E* _
                                                                       const int32_t* __restrict__ off,
                                                                       const int32_t* __restrict__ perm,
                                                                       const int32_t* __restrict__ work, int n_pairs, int H,
-                                                                      int I) {
+                                                                      int I, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
@@ -165,16 +167,16 @@ template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hip
   if (a.T <= TILE) {
     expert_gemm1_wide_kernel<E, 1, SMALL_WW, 16, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 16, 1>(), st>>>(
-        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w);
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w, live_word());
   } else if (a.T <= 2 * TILE) {
     expert_gemm1_wide_kernel<E, 2, SMALL_WW, 17, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 17, 2>(), st>>>(
-        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w);
+        w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w, live_word());
   } else {
     expert_gemm1_wide_kernel<E, WT, EXPERT_WW, 10, false>
         <<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, a.T * a.top_k)), EXPERT_WW * WAVE,
            wide_lds<E, 10, WT>(), st>>>(w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k,
-                                        a.topk_w);
+                                        a.topk_w, live_word());
   }
 }
 template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStream_t st) {
@@ -183,15 +185,15 @@ template <typename E> static void launch_down_wide_t(const ExpertArgs& a, hipStr
   if (a.T <= TILE) {
     expert_gemm2_wide_kernel<E, 1, SMALL_WW, 18, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 18, 1>(), st>>>(
-        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I, live_word());
   } else if (a.T <= 2 * TILE) {
     expert_gemm2_wide_kernel<E, 2, SMALL_WW, 19, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
                                                          wide_lds<E, 19, 2>(), st>>>(
-        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+        w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I, live_word());
   } else {
     expert_gemm2_wide_kernel<E, WT, EXPERT_WW, 11, false>
         <<<dim3((n_tasks + EXPERT_WW - 1) / EXPERT_WW, expert_work_items(a.E, n_pairs)), EXPERT_WW * WAVE,
-           wide_lds<E, 11, WT>(), st>>>(w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I);
+           wide_lds<E, 11, WT>(), st>>>(w, y, a.o, a.cnt, a.off, a.perm, a.work, n_pairs, a.H, a.I, live_word());
   }
 }
 void launch_expert_gate_up_wide(bool bf16, const ExpertArgs& a, hipStream_t st) {
@@ -217,7 +219,8 @@ template <typename E, int WT, int KID, int WW>
 __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                   RowNorm norm, int T, int H, int V,
                                                                   float scale, float* __restrict__ part,
-                                                                  float* __restrict__ logits_out) {
+                                                                  float* __restrict__ logits_out, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
@@ -295,19 +298,19 @@ template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t 
   if (a.T <= TILE) {   // one token tile (trace id 15)
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 1, 15, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 15, 1>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
     return;
   }
   if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
     return;
   }
   const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   lm_head_wide_kernel<E, WT, 9, LM_WW><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
-      (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out);
+      (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
   if (bf16) launch_lm_wide_t<bf16_t>(a, st);

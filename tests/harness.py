@@ -227,9 +227,9 @@ class GpuRun:
         self.ctx.refresh_block(self.tokens, self.prefix_len, self.page_table)
         self.torch.cuda.synchronize()
 
-    def generate_block(self, threshold, fixed_k, max_steps, masked_hint=0):
+    def generate_block(self, threshold, fixed_k, max_steps, masked_hint=0, steps_per_wait=1):
         steps = self.ctx.generate_block(self.tokens, self.mask, self.prefix_len, self.page_table, threshold, fixed_k,
-                                        self.conf, self.argmax, self.n_committed, max_steps, masked_hint)
+                                        self.conf, self.argmax, self.n_committed, max_steps, masked_hint, steps_per_wait)
         self.torch.cuda.synchronize()
         return steps
 

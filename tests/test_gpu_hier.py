@@ -209,6 +209,43 @@ def test_generation_stops_at_eos():
     g.close()
 
 
+def test_threshold_generation_without_a_wait_per_step():
+    """The outer loop with threshold decoding (a data-dependent number of steps per block), float32 tiny model: the
+    library enqueues 1, 4 or 64 steps between two looks at the masks, the device skipping the steps that find
+    nothing masked.  All three runs give the same tokens bit for bit, and they are the tokens of the oracle's free
+    run (float32 against double: a confidence would have to sit within rounding of the threshold to differ)."""
+    tiny = di.model_preset("tiny")
+    S, nb = 16, 3
+    wl = di.Workload("gen_thr", tiny, 2, S, 40, 64, gen_len=S * nb, seed_index=3)
+    cfg, w, inp = make_case(wl)
+    cap = int(inp.prefix_len.max()) + S * nb + 16
+    ora = OracleRun(cfg, w, inp, cap)
+    g = GpuRun(cfg, w, inp, 2 * S, cap)
+    torch = g.torch
+    probe = ora.step(0, inp.block_tokens[0], int(inp.mask_bits[0]), int(inp.prefix_len[0]), 2.0)
+    c_sorted = np.sort(probe["conf"])
+    tau = float(0.5 * (c_sorted[9] + c_sorted[10]))      # halfway between two of the first step's confidences
+    ref = [ora.o.generate(S, nb, int(inp.prefix_len[s]), ora.caches[s][0].copy(), ora.caches[s][1].copy(), tau, 0)
+           for s in range(2)]
+    assert max(int(r["steps"].max()) for r in ref) > 2, "the blocks decode too quickly to exercise the loop"
+    out = torch.zeros((2, nb * S), dtype=torch.int32, device=g.dev)
+    fin = torch.zeros(2, dtype=torch.int32, device=g.dev)
+    runs = []
+    for per_wait in (1, 4, 64):
+        g.inject_prefix(ora.caches)
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        out.fill_(-3)
+        run = g.ctx.generate(out, g.tokens, g.mask, g.prefix_len, g.page_table, tau, 0, -1, fin, g.conf, g.argmax,
+                             g.n_committed, steps_per_wait=per_wait)
+        torch.cuda.synchronize()
+        assert run == nb
+        runs.append(out.cpu().numpy().copy())
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+    for s in range(2):
+        assert np.array_equal(runs[0][s], ref[s]["tokens"]), s
+    g.close()
+
+
 def test_hierarchical_rule_inside_the_other_step_variants():
     """The decoder settings travel through every step variant.  Each variant is run twice from the same state, with
     threshold decoding and with the hierarchical rule: the forward is the same, so confidences and candidates must

@@ -269,6 +269,23 @@ def test_generate_block_teacher_forced(case):
     n = g.generate_block(tau, 0, max_steps=case.S)
     st = g.state()
     assert n == steps and not st["mask"].any() and np.array_equal(st["tokens"], tokens)
+    # ... also when it enqueues several steps between two looks at the masks (the device skips the steps that find
+    # nothing masked): same tokens, same confidences of the last real step, same count
+    for per_wait in (3, 64):
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        n2 = g.generate_block(tau, 0, max_steps=case.S, steps_per_wait=per_wait)
+        st2 = g.state()
+        assert n2 == steps and not st2["mask"].any() and np.array_equal(st2["tokens"], tokens)
+        for key in ("conf", "argmax", "n_committed"):
+            assert np.array_equal(st2[key], st[key]), key
+    # max_steps cuts the loop short at the same point either way
+    if steps > 2:
+        for per_wait in (1, 4):
+            g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+            assert g.generate_block(tau, 0, max_steps=2, steps_per_wait=per_wait) == 2
+            assert g.state()["mask"].any()
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        assert g.generate_block(tau, 0, max_steps=case.S, steps_per_wait=8) == steps      # back to the decoded block
     # refresh: block K,V equal a forward over the final tokens, prefix length advances
     g.refresh()
     routing = g.routing().reshape(case.cfg.n_layers, case.ns, case.S, case.cfg.top_k)
