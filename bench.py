@@ -59,6 +59,43 @@ def measured_traffic(kernel, workload):
     return None
 
 
+STAGE_ROWS = {"expert_gate_up": "expert gate/up", "expert_down": "expert down", "lm_head": "LM head + confidence",
+              "qkv": "QKV + RoPE + KV write", "oproj": "output projection + residual"}
+
+
+def rocprof_kernel_us(kernel, workload):
+    """Average duration (us) of `kernel` in the committed rocprofv3 --kernel-trace --stats summary of this workload
+    (profiles/step_<workload>_kernel_trace.md, column 'avg us'); None if there is no such row."""
+    path = os.path.join(ROOT, "profiles", "step_%s_kernel_trace.md" % workload.split("-")[0])
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 4 and cells[1] == STAGE_ROWS.get(kernel):
+                return float(cells[4])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def roofline_entry(name, bytes_per_launch, launches, stage_ms, workload, ceilings=None):
+    """The dominant kernel's roofline object: algorithmic bytes per launch over its average launch duration (HIP
+    events around every launch on the launch stream; the bracket holds the dispatch gap, so it reads a few
+    microseconds more than the kernel itself: kernel_us_rocprof is the kernel's own duration from the committed trace)."""
+    avg_ms = stage_ms / launches
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    r = {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(name, workload),
+         "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches}
+    us = rocprof_kernel_us(name, workload)
+    if us:
+        r["kernel_us_rocprof"] = us
+        r["frac_rocprof"] = round(bytes_per_launch / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+    if ceilings:
+        r["measured_read_ceiling_GBs"] = {k: round(v, 1) for k, v in ceilings.items()}
+        r["frac_of_measured_ceiling"] = round(achieved / ceilings["400MB_launch"], 4)
+    return r
+
+
 def generation_loop(args):
     """Workload 5: prompt prefill, then blocks of (fixed number of denoising steps + cache refresh)."""
     import torch
@@ -110,10 +147,40 @@ def generation_loop(args):
         generate()
     n_gen = max(1, args.steps // (n_blocks * steps_per_block)) if args.steps >= n_blocks * steps_per_block else 1
     t_pre = t_loop = 0.0
+    ctx.profile_start(binding.STAGE_EXPERT_GATE_UP)
     for _ in range(n_gen):
         a, b = generate()
         t_pre += a
         t_loop += b
+    launches, stage_ms = ctx.profile_stop()
+    # experts that received rows, averaged over every layer of every forward of the timed loop (counted on the device)
+    tot = ctx.debug_get(6, (2,), torch.int32).cpu().numpy()
+    touched = float(tot[0]) / max(1, int(tot[1]))
+    gate_up_bytes = touched * 2 * cfg.moe_inter * cfg.hidden * 2
+    roofline = roofline_entry("expert_gate_up", gate_up_bytes, launches, stage_ms, wl.name) if launches else None
+    if roofline:
+        roofline["note"] = ("all gate/up launches of the loop (prefill, steps and refreshes); bytes per launch from the "
+                            "experts that received rows, mean over all %d launches: %.2f (a random-init model repeats "
+                            "few ids, so most rows of a block are identical and share their experts)" % (int(tot[1]), touched))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.Oracle(cfg, weights)
+        kc, vc = o.new_cache(P0 + S)
+        k, v = di.synthetic_prefix_kv(cfg, seed, 0, P0)     # the cached prompt: its values do not change the work
+        kc[:, :P0], vc[:, :P0] = k, v
+        tc = time.perf_counter()
+        toks, m = inp.block_tokens[0].copy(), int(inp.mask_bits[0])
+        for _ in range(steps_per_block):
+            r = o.step(toks, m, P0, kc, vc, wl.threshold, wl.fixed_k)
+            toks, m = r["tokens"], int(r["mask"])
+        o.forward(toks, P0, kc, vc)
+        cdt = time.perf_counter() - tc
+        cpu = {"value": round(S / cdt, 3), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "the first block only (%d oracle steps of %d commits + the refresh forward, %.1f s), prompt K,V "
+                         "synthetic; extrapolated x%d: the later blocks do the same work over longer prefixes" % (
+                             steps_per_block, wl.fixed_k, cdt, n_blocks)}
     assert int(mask.item()) == 0 and int(prefix_len.item()) == P0 + wl.gen_len
     n_steps = n_gen * n_blocks * steps_per_block
     n_tok = n_gen * wl.gen_len
@@ -124,6 +191,8 @@ def generation_loop(args):
     fwd = L * ((3 * D * H + H * D + E * H) * es + E * 3 * I * H * es)
     kv = sum(L * (P0 + b * S + S) * 2 * D * es * (steps_per_block + 1) for b in range(n_blocks))
     total_bytes = n_blocks * ((steps_per_block + 1) * fwd + steps_per_block * V * H * es) + kv
+    fwd_touched = L * ((3 * D * H + H * D + E * H) * es + touched * 3 * I * H * es)
+    touched_bytes = n_blocks * ((steps_per_block + 1) * fwd_touched + steps_per_block * V * H * es) + kv
     out = {
         "metric": "end-to-end committed tokens/s, block-diffusion generation loop, batch 1",
         "value": round(n_tok / t_loop, 2), "unit": "tokens/s", "n_gpus": 1, "steps": n_steps, "warmup": args.warmup,
@@ -137,8 +206,60 @@ def generation_loop(args):
         "prefill_ms": round(t_pre / n_gen * 1e3, 3), "generations_timed": n_gen,
         "forwards_per_generation": n_blocks * (steps_per_block + 1),
         "loop_GB_if_all_experts_touched": round(total_bytes / 1e9, 2),
-        "roofline": None, "cpu_baseline": None,
+        "loop_algorithmic_GB": round(touched_bytes / 1e9, 2), "experts_touched_per_layer": round(touched, 2),
+        "loop_hbm_frac": round(touched_bytes / (t_loop / n_gen) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "cpu_baseline": cpu,
         "note": "ms_per_step spreads the refresh forwards over the denoising steps",
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+def block_loop(args, ctx, wl, cfg, inp, tokens0, mask0, tokens, mask, prefix_len, page_table, conf, argmax, n_committed):
+    """The inner loop of blockwise decoding over one block (Section 3, "Diffusion iterations"): block completion time
+    with a host wait after every step and with --block-loop steps enqueued per wait."""
+    import torch
+    ns, S = tokens0.shape
+    # a threshold inside the first step's confidence distribution: its 70 % quantile
+    tokens.copy_(tokens0)
+    mask.copy_(mask0)
+    ctx.step(tokens, mask, prefix_len, page_table, 2.0, 0, conf, argmax, n_committed)
+    torch.cuda.synchronize()
+    tau = float(np.quantile(conf.cpu().numpy(), 0.7))
+
+    def run(per_wait):
+        tokens.copy_(tokens0)
+        mask.copy_(mask0)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        n = ctx.generate_block(tokens, mask, prefix_len, page_table, tau, 0, conf, argmax, n_committed, S,
+                               steps_per_wait=per_wait)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t, n
+
+    res = {}
+    for per_wait in (1, args.block_loop):
+        for _ in range(max(1, args.warmup // 2)):
+            run(per_wait)
+        times, steps = [], 0
+        for _ in range(max(3, args.steps // 10)):
+            dt, steps = run(per_wait)
+            times.append(dt)
+        times.sort()
+        res[per_wait] = (times[len(times) // 2], times[0], steps, len(times))
+    assert int(mask.cpu().numpy().view(np.uint64).max()) == 0
+    a, b = res[1], res[args.block_loop]
+    out = {
+        "metric": "block completion time, threshold decoding, batch %d" % ns, "value": round(b[0] * 1e3, 4), "unit": "ms",
+        "n_gpus": 1, "steps": b[2], "warmup": args.warmup, "ms_per_step": round(b[0] * 1e3 / b[2], 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": wl.name + "-block-loop", "n_seq": ns, "block_len": S, "threshold": tau,
+                   "steps_per_wait": args.block_loop},
+        "steps_per_block": b[2], "tokens_per_step": round(ns * S / b[2], 2), "blocks_timed": b[3],
+        "ms_block_median": round(b[0] * 1e3, 4), "ms_block_min": round(b[1] * 1e3, 4),
+        "ms_block_median_wait_every_step": round(a[0] * 1e3, 4), "ms_block_min_wait_every_step": round(a[1] * 1e3, 4),
+        "gain_over_wait_every_step": round(a[0] / b[0], 4),
+        "roofline": None, "cpu_baseline": None,
     }
     print(json.dumps(out))
     ctx.close()
@@ -164,6 +285,10 @@ def main():
                     help="time the step with vicinity KV-cache refresh over this many cached positions before the "
                          "block (the paper's experiments use 16); 0 = the plain step")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
+    ap.add_argument("--block-loop", type=int, default=0,
+                    help="time dinfer_generate_block over the workload's block with threshold decoding at a threshold "
+                         "inside the confidence distribution (several commits per step, a data-dependent number of steps): "
+                         "once with a host wait after every step, once with this many steps enqueued per wait")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device-to-device copy kernel (known traffic: "
                          "1 GiB read + 1 GiB written) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -244,6 +369,10 @@ def main():
         else:
             ctx.step(tokens, mask, prefix_len, page_table, thr, wl.fixed_k, conf, argmax, n_committed)
 
+    if args.block_loop:
+        return block_loop(args, ctx, wl, cfg, inp, tokens0, mask0, tokens, mask, prefix_len, page_table, conf, argmax,
+                          n_committed)
+
     # practical HBM read ceiling: the streaming-read probe over the weight buffer, and over one launch's worth
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -267,12 +396,16 @@ def main():
         one_step()
     torch.cuda.synchronize()
     ctx.profile_start(args.profile_stage)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()            # on the launch stream, between two steps: each step's own duration
         one_step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
     launches, stage_ms = ctx.profile_stop()
+    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -295,16 +428,8 @@ def main():
     if launches > 0 and args.profile_stage in stage_names:
         name = stage_names[args.profile_stage]
         per_launch_calls = cfg.n_layers if name != "lm_head" else 1
-        bytes_per_launch = stages[name] / per_launch_calls
-        avg_ms = stage_ms / launches
-        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        roofline = {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": measured_traffic(name, wl.name),
-                    "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2),
-                    "launches_timed": launches,
-                    "measured_read_ceiling_GBs": {"8GB_sweep": round(ceiling_big, 1), "400MB_launch": round(ceiling_launch, 1)},
-                    "frac_of_measured_ceiling": round(achieved / ceiling_launch, 4)}
+        roofline = roofline_entry(name, stages[name] / per_launch_calls, launches, stage_ms, wl.name,
+                                  {"8GB_sweep": ceiling_big, "400MB_launch": ceiling_launch})
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -331,7 +456,8 @@ def main():
     out = {
         "metric": "block denoising steps/s (committed tokens/s alongside), batch %d" % ns,
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "ms_median": round(per_step_ms[len(per_step_ms) // 2], 4),
+        "ms_min": round(per_step_ms[0], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else "")
                    + ("-smooth" if args.smooth else "") + ("-hier" if args.hier else ""),

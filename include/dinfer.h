@@ -276,7 +276,8 @@ int dinfer_kv_read(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, in
  * an intermediate of the last forward: what = 0 residual stream leaving the last layer [T][hidden] f32;
  * 1 router expert ids of every layer [n_layers][T][top_k] i32; 2 their mixture weights, same shape, f32;
  * and of the last layer: 3 expert row counts [n_experts] i32; 4 expert offsets [n_experts+1] i32;
- * 5 permutation [T*top_k] i32. */
+ * 5 permutation [T*top_k] i32; 6 two running totals since the last dinfer_profile_start [2] i32: experts that
+ * received rows, summed over every layer of every forward, and the number of such (layer, forward) pairs. */
 int dinfer_debug_logits(dinfer_ctx* ctx, int32_t n_rows, float* d_out, void* stream);
 int dinfer_debug_get(dinfer_ctx* ctx, int32_t what, void* d_out, size_t bytes, void* stream);
 

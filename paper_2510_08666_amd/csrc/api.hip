@@ -128,16 +128,16 @@ WeightMap map_weights(const dinfer_config& c) {
 
 // Key splits the attention grid offers per (query tile, head): what the longest possible sequence (key_bound keys)
 // would use under the rule of attn_splits_for (common.hpp), but no more than it takes to give every compute unit
-// a workgroup, and at most 32; every sequence then uses its own count.
+// one workgroup (a workgroup fills a compute unit's LDS, so more of them only queue up: measured at 16 sequences
+// with up to 5 splits each, 85 us against 43 without splits); every sequence then uses its own count.
 int attn_splits(int n_qtiles, int n_heads, int key_bound) {
   int s = attn_splits_for(key_bound);
   const int cover = (256 + n_qtiles * n_heads - 1) / (n_qtiles * n_heads);
-  if (s > cover) s = cover;
-  return s > 32 ? 32 : s;
+  return s > cover ? cover : s;
 }
 
 struct Workspace {
-  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, ssq_a, tk_part, tickets, tickets_bytes, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
+  size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, ssq_a, tk_part, tickets, tickets_bytes, attn_tickets, attn_tickets_bytes, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
       perm, pos_of_pair, work, run_tokens, run_base, n_finished, loop_flags, loop_steps, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
@@ -189,6 +189,8 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
     if (p > part) part = p;
   }
   w.attn_part = cv.take(part * 4);
+  w.attn_tickets_bytes = (size_t)max_qtiles * c.n_heads * 4;   // one arrival counter per (query tile, head)
+  w.attn_tickets = cv.take(w.attn_tickets_bytes);
   w.topk_idx = cv.take((size_t)c.n_layers * T * K * 4);   // kept per layer (tests read the routing back)
   w.topk_w = cv.take((size_t)c.n_layers * T * K * 4);
   w.cnt = cv.take((size_t)MAX_EXPERTS * 4);
@@ -324,7 +326,8 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
 #endif
     }
     AttnArgs aa{ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
-                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), ws + w.a, T};
+                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), at<int32_t>(ws, w.attn_tickets),
+                ws + w.a, T};
     {
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
       launch_attention(bf, aa, st);
@@ -483,7 +486,9 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
     return fail(DINFER_EHIP, "the runtime refused the kernels' LDS sizes");
   }
   // the arrival counters start at zero and every kernel that uses them leaves them at zero
-  if (hipMemsetAsync(c->ws + c->wsm.tickets, 0, c->wsm.tickets_bytes, (hipStream_t)stream) != hipSuccess) {
+  if (hipMemsetAsync(c->ws + c->wsm.tickets, 0, c->wsm.tickets_bytes, (hipStream_t)stream) != hipSuccess ||
+      hipMemsetAsync(c->ws + c->wsm.attn_tickets, 0, c->wsm.attn_tickets_bytes, (hipStream_t)stream) != hipSuccess ||
+      hipMemsetAsync(c->ws + c->wsm.off, 0, (size_t)OFF_INTS * 4, (hipStream_t)stream) != hipSuccess) {
     (void)hipHostFree(c->h_mask_pinned);
     delete c;
     return fail(DINFER_EHIP, "clearing the workspace failed");
@@ -905,6 +910,8 @@ int dinfer_profile_start(dinfer_ctx* c, int32_t stage) {
   }
   c->prof_stage = stage;
   c->prof_n = 0;
+  // the running totals of experts with rows (dinfer_debug_get 6) start over with the profile
+  HIP_TRY(hipMemset(at<int32_t>(c->ws, c->wsm.off) + STAT_ACTIVE_SUM, 0, 2 * sizeof(int32_t)));
   return DINFER_OK;
 }
 
@@ -950,6 +957,7 @@ int dinfer_debug_get(dinfer_ctx* c, int32_t what, void* d_out, size_t bytes, voi
     case 3: off = c->wsm.cnt; want = (size_t)f.n_experts * 4; break;
     case 4: off = c->wsm.off; want = (size_t)(f.n_experts + 1) * 4; break;
     case 5: off = c->wsm.perm; want = T * f.top_k * 4; break;
+    case 6: off = c->wsm.off + (size_t)STAT_ACTIVE_SUM * 4; want = 8; break;
     default: return fail(DINFER_EINVAL, "what %d", what);
   }
   if (bytes != want || want == 0) return fail(DINFER_EINVAL, "%zu bytes given, %zu expected", bytes, want);

@@ -5,9 +5,9 @@
 // grid's splits as its own key count asks for (attn_splits_for; the other workgroups exit at once), and its key
 // tiles (32 keys) are dealt round-robin to the waves of those splits.  Each wave keeps its own online-softmax
 // state; the waves of a workgroup are folded through LDS in wave order, each wave finishing its share of the
-// output rows.  With one split the workgroup writes the normalised output itself; otherwise it writes one
-// partial (unnormalised output, max, sum) and attn_merge_kernel folds the partials of a (query tile, head) in
-// split order.
+// output rows.  With one split the workgroup writes the normalised output itself; otherwise it leaves one
+// partial (unnormalised output, max, sum) and takes an arrival ticket of its (query tile, head); the workgroup
+// that arrives last folds the partials in split order and writes the output.
 //
 // MFMA mapping (32x32 tiles):  S^T[key][query] = K_tile . Q^T   (A = K rows, B = Q columns), so a lane owns
 // one query column and softmax statistics are per lane;  O^T[d][query] += V^T_tile . P^T  (A = V^T rows read
@@ -75,7 +75,8 @@ template <typename E, int HD>
 __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* __restrict__ Q, int64_t q_plane,
                                                          const E* __restrict__ kv_layer, KvGeom geom, FwdMeta meta,
                                                          const int32_t* __restrict__ page_table, int pt_stride,
-                                                         int n_splits, float* __restrict__ part, E* __restrict__ out,
+                                                         int n_splits, float* __restrict__ part,
+                                                         int32_t* __restrict__ tickets, E* __restrict__ out,
                                                          int T_out, const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
@@ -253,57 +254,60 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
     TRACE_MARK(7, 4);
     return;
   }
-  // partial of this split: O [32 q][HD] (unnormalised), m [32], l [32]
-  const int pidx = (qt * geom.n_heads + head) * n_splits + split;
-  float* pbase = part + (int64_t)pidx * TILE * (HD + 2);
-#pragma unroll
-  for (int i4 = 0; i4 < RPW / 4; ++i4) {
-    const int g = wave * RPW + 4 * i4;
-    f32x4 v4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v4[i] = r[4 * i4 + i];
-    *reinterpret_cast<f32x4*>(pbase + col * HD + (g / 16) * TILE + acc_row(g % 16, half)) = v4;
-  }
-  if (wave == 0 && half == 0) {
-    pbase[TILE * HD + col] = M;
-    pbase[TILE * HD + TILE + col] = L;
-  }
-}
-
-template <typename E, int HD>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, FwdMeta meta, int n_heads,
-                                                          int n_parts, E* __restrict__ out, int T_out, const int32_t* __restrict__ live) {
-  if (step_is_dead(live)) return;
-  const int head = blockIdx.x, qt = blockIdx.y;
-  const int tok0 = meta.qtile[qt * 3 + 1], nvalid = meta.qtile[qt * 3 + 2];
-  const int my_parts = min(attn_splits_for(meta.seq_nkeys[meta.qtile[qt * 3]]), n_parts);
-  if (my_parts == 1) return;   // a single workgroup had the whole key range and wrote the output itself
-  const float* pb = part + (int64_t)(qt * n_heads + head) * n_parts * TILE * (HD + 2);
-  // thread -> (query, 4 consecutive features): 32 * HD / 4 items, one per thread over gridDim.z workgroups (every
-  // item is a chain of dependent loads over the parts, so the items are spread as widely as possible)
+  // partial of this split: O [32 q][HD] (unnormalised), m [32], l [32], handed over with device-coherent stores
+  const int pair = qt * geom.n_heads + head;
+  const buf_rsrc pr = coherent_buffer(part);
+  const uint32_t pair_bytes = (uint32_t)pair * n_splits * TILE * (HD + 2) * 4, part_bytes = TILE * (HD + 2) * 4;
   {
-    const int item = blockIdx.z * 256 + threadIdx.x;
-    const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
-    if (q >= nvalid) return;
-    float M = -INFINITY;
-    for (int p = 0; p < my_parts; ++p) M = fmaxf(M, pb[(int64_t)p * TILE * (HD + 2) + TILE * HD + q]);
-    float L = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int p = 0; p < my_parts; ++p) {
-      const float* pp = pb + (int64_t)p * TILE * (HD + 2);
-      const float mp = pp[TILE * HD + q];
-      if (mp == -INFINITY) continue;             // a wave that saw no key tile
-      const float w = __expf(mp - M);
-      L += w * pp[TILE * HD + TILE + q];
-      const f32x4 ov = *reinterpret_cast<const f32x4*>(pp + q * HD + d);
+    const uint32_t pb = pair_bytes + split * part_bytes;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] += w * ov[i];
+    for (int i4 = 0; i4 < RPW / 4; ++i4) {
+      const int g = wave * RPW + 4 * i4;
+      const float v4[4] = {r[4 * i4], r[4 * i4 + 1], r[4 * i4 + 2], r[4 * i4 + 3]};
+      coherent_store_n<4>(pr, pb + (col * HD + (g / 16) * TILE + acc_row(g % 16, half)) * 4, v4);
     }
-    const float inv = 1.f / L;
-    f32x4 r;
+    if (wave == 0 && half == 0) {
+      const float mv[1] = {M}, lv[1] = {L};
+      coherent_store_n<1>(pr, pb + (TILE * HD + col) * 4, mv);
+      coherent_store_n<1>(pr, pb + (TILE * HD + TILE + col) * 4, lv);
+    }
+  }
+  __shared__ int32_t s_flag;
+  if (!last_arrival(tickets + pair, my_splits, &s_flag)) return;
+  // Last to arrive: fold the partials in split order.  A thread takes a (query, 4 consecutive features) item.
+  for (int item = threadIdx.x; item < TILE * HD / 4; item += ATTN_WAVES * WAVE) {
+    const int q = item / (HD / 4), d = (item % (HD / 4)) * 4;
+    if (q >= nvalid) continue;
+    float mp[ATTN_MAX_SPLITS], lp[ATTN_MAX_SPLITS], op[ATTN_MAX_SPLITS][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = acc[i] * inv;
-    store_actk4<E>(out, T_out, tok0 + q, head * HD + d, r);
+    for (int p = 0; p < ATTN_MAX_SPLITS; ++p) {   // all loads first (clamped: the unused ones repeat the last part)
+      const uint32_t pb = pair_bytes + min(p, my_splits - 1) * part_bytes;
+      float t1[1], t2[1];
+      coherent_load_n<1>(pr, pb + (TILE * HD + q) * 4, t1);
+      coherent_load_n<1>(pr, pb + (TILE * HD + TILE + q) * 4, t2);
+      coherent_load_n<4>(pr, pb + (q * HD + d) * 4, op[p]);
+      mp[p] = t1[0];
+      lp[p] = t2[0];
+    }
+    float Mx = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < ATTN_MAX_SPLITS; ++p) Mx = p < my_splits ? fmaxf(Mx, mp[p]) : Mx;
+    float Ls = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < ATTN_MAX_SPLITS; ++p) {
+      if (p < my_splits && mp[p] > -INFINITY) {   // (a split whose waves saw no key tile contributes nothing)
+        const float w = __expf(mp[p] - Mx);
+        Ls += w * lp[p];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] += w * op[p][i];
+      }
+    }
+    const float inv = 1.f / Ls;
+    f32x4 res;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) res[i] = acc[i] * inv;
+    store_actk4<E>(out, T_out, tok0 + q, head * HD + d, res);
   }
 }
 
@@ -312,10 +316,7 @@ template <int HD> constexpr size_t attn_lds() { return (size_t)ATTN_WAVES * ((HD
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
   attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), ATTN_WAVES * WAVE, attn_lds<HD>(), st>>>(
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
-      (E*)a.out, a.T, live_word());
-  if (a.n_splits > 1)
-    attn_merge_kernel<E, HD><<<dim3(a.geom.n_heads, a.n_qtiles, TILE * HD / 4 / 256), 256, 0, st>>>(a.part, a.meta, a.geom.n_heads,
-                                                                                  a.n_splits, (E*)a.out, a.T, live_word());
+      a.tickets, (E*)a.out, a.T, live_word());
 }
 
 bool configure_attention() {

@@ -242,17 +242,21 @@ __device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int sl
          ((int64_t)head * g.head_dim + d) * PAGE + slot;
 }
 
-// Attention: workgroups (splits) that share the keys of one (head, query tile) of a sequence with n_keys keys: one
-// per 4 key tiles and wave (8 waves).  Every workgroup pays for staging the page table and the queries, the fold
-// of its waves and, with more than one split, the merge pass, so splitting pays only while the launch would
-// otherwise leave compute units idle: the host offers at most ceil(256 / (heads x query tiles)) splits (measured at
-// 512 tokens in 16 sequences, 256 such pairs: 44 us without splits, 55 with up to 3, 69 with up to 5; at 64 tokens
-// over 4160 keys, 32 pairs: 29 us with 5 splits, 33 with 3, 35 with 9).  Host (largest possible key count, for the
-// grid and the workspace) and kernels (the sequence's own count) use the same rule.
+// Attention: workgroups (splits) that share the keys of one (head, query tile) of a sequence with n_keys keys.  The
+// key tiles (32 keys) of a pair are dealt round-robin to the 8 waves of its splits, and a wave holds the loads of two
+// tiles at a time; its third tile costs another memory round trip (about 3 us at batch 1, where nothing else hides
+// it).  Up to 24 tiles one workgroup takes the pair (at most three tiles per wave, no hand-off between workgroups);
+// beyond, one split per 16 tiles, so that every wave has its whole share in flight at once.  The splits of a pair
+// hand their partial results to whichever of them finishes last (arrival ticket), which merges them: no second
+// kernel.  The host offers at most ATTN_MAX_SPLITS splits per pair; a sequence uses what its own key count asks for
+// and the other workgroups exit at once.  Host (largest possible key count, for the grid and the workspace) and
+// kernels (the sequence's own count) use the same rule.
+constexpr int ATTN_MAX_SPLITS = 16;
 __host__ __device__ inline int attn_splits_for(int n_keys) {
   const int tiles = (n_keys + 31) / 32;
-  const int s = (tiles + 31) / 32;
-  return s < 1 ? 1 : s;
+  if (tiles <= 24) return 1;
+  const int s = (tiles + 15) / 16;
+  return s > ATTN_MAX_SPLITS ? ATTN_MAX_SPLITS : s;
 }
 
 // Optional in-kernel phase timestamps (builds with -DDINFER_TRACE=<kernel id> only): thread 0 of every workgroup

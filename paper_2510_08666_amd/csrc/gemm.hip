@@ -923,7 +923,11 @@ __device__ inline void ballot_permute_small(const int32_t* s_idx, int n_pairs, i
       off[ACTIVE_LIST + at] = lane;
       *reinterpret_cast<int4*>(off + ACTIVE_RECORDS + 4 * at) = make_int4(lane, start, tot, 0);
     }
-    if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+    if (lane == 0) {
+      off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+      off[STAT_ACTIVE_SUM] += __popcll(has_rows);
+      off[STAT_PERMUTATIONS] += 1;
+    }
     int run = start;                                      // chunk c of expert `lane` starts at run
     for (int c = 0; c < n_chunks; ++c) {
       const int n = s_cc[c * MAX_EXPERTS + lane];

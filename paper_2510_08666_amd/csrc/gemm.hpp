@@ -134,6 +134,10 @@ constexpr int ACTIVE_LIST = MAX_EXPERTS + 1;
 // ... and by one 16-byte record per listed expert, {expert, first sorted row, rows, 0}, at off[ACTIVE_RECORDS + 4*i]:
 // everything a grouped-GEMM workgroup needs to know about its expert in a single load.
 constexpr int ACTIVE_RECORDS = 2 * MAX_EXPERTS + 4;
-constexpr int OFF_INTS = ACTIVE_RECORDS + 4 * MAX_EXPERTS;   // size of the offset array with both lists
+// ... and by two running totals for benchmarks: experts with rows summed over the permutations built so far, and the
+// number of permutations (one per layer and forward); dinfer_profile_start clears them.
+constexpr int STAT_ACTIVE_SUM = ACTIVE_RECORDS + 4 * MAX_EXPERTS;
+constexpr int STAT_PERMUTATIONS = STAT_ACTIVE_SUM + 1;
+constexpr int OFF_INTS = STAT_PERMUTATIONS + 1;   // size of the offset array with everything behind it
 
 }  // namespace dinfer

@@ -93,6 +93,7 @@ struct AttnArgs {
   int pt_stride;
   int n_qtiles, n_splits;
   float* part;              // partial results, see attention.hip
+  int32_t* tickets;         // [n_qtiles][n_heads] arrival counters, zero between launches
   void* out;                // [T][D] k-major
   int T;
 };

@@ -243,7 +243,11 @@ __global__ __launch_bounds__(1024) void permute_kernel(const int32_t* __restrict
       off[ACTIVE_LIST + at] = lane;
       *reinterpret_cast<int4*>(off + ACTIVE_RECORDS + 4 * at) = make_int4(lane, incl - tot, tot, 0);
     }
-    if (lane == 0) off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+    if (lane == 0) {
+      off[ACTIVE_LIST + MAX_EXPERTS] = __popcll(has_rows);
+      off[STAT_ACTIVE_SUM] += __popcll(has_rows);
+      off[STAT_PERMUTATIONS] += 1;
+    }
     // Work list of the many-token expert GEMMs: one item per (expert, group of up to 128 rows), the groups with
     // the most 32-row tiles first, so that the long workgroups start first and the short ones fill the tail.
     // work[0] = number of items, work[1 + i] = expert << 16 | group.
