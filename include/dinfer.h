@@ -160,6 +160,30 @@ int dinfer_step_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_
                        const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch,
                        size_t scratch_bytes, float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream);
 
+/* A block denoised with iteration smoothing under the two schedules of Appendix "IterSmooth": the inner loop of
+ * Algorithm 1 with dinfer_step_smooth as its step.  Step t = 0, 1, ... of the block uses
+ *   mixing weight  alpha = 0 for t = 0 (nothing is retained yet), else min(alpha_init + alpha_growth * (t-1),
+ *                  alpha_preset): the weight alpha_{t-1} that the appendix attaches to the expected embeddings
+ *                  which step t-1 left for step t;
+ *   threshold      max(threshold_start - threshold_decay * t, decode->threshold): decays from threshold_start
+ *                  (1.0 in the appendix) to the decoder's own threshold as its target.  The appendix names no
+ *                  curve; this is a linear one.  A hierarchical lower bound above the step's threshold is lowered
+ *                  to it.
+ * decode->fixed_k must be 0.  d_delta [n_seq][block_len][hidden] needs no initial contents.  Steps are enqueued
+ * steps_per_wait at a time and the host waits once per batch, as in dinfer_generate_block's threshold mode (the
+ * schedules are functions of the step index, which the host knows without waiting).  n_seq * block_len <= 64;
+ * max_steps <= 256; scratch as in dinfer_step_smooth. */
+typedef struct {
+  float alpha_init, alpha_growth, alpha_preset;
+  float threshold_start, threshold_decay;
+} dinfer_smooth_schedule;
+int dinfer_generate_block_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens,
+                                 uint64_t* d_mask, const int32_t* d_prefix_len, const int32_t* d_page_table,
+                                 int32_t pt_stride, const dinfer_decode* decode, const dinfer_smooth_schedule* sched,
+                                 float* d_delta, void* d_scratch, size_t scratch_bytes, float* d_conf, int32_t* d_argmax,
+                                 int32_t* d_n_committed, int32_t max_steps, int32_t steps_per_wait,
+                                 int32_t* h_steps_taken, void* stream);
+
 /* dinfer_step_smooth for callers that cannot allocate device memory or hand over a scratch buffer (code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation): the logits and probability planes live in a
  * device array that is part of the library image, DINFER_STATIC_SCRATCH_BYTES per GPU, held from the moment the
@@ -280,11 +304,16 @@ int dinfer_kv_read(dinfer_ctx* ctx, int32_t layer, const int32_t* d_page_row, in
  * received rows, summed over every layer of every forward, and the number of such (layer, forward) pairs. */
 int dinfer_debug_logits(dinfer_ctx* ctx, int32_t n_rows, float* d_out, void* stream);
 int dinfer_debug_get(dinfer_ctx* ctx, int32_t what, void* d_out, size_t bytes, void* stream);
+/* Process-wide test switch.  While on (on != 0), no contraction shares a task's sum among workgroups: the
+ * projections, the router and attention run with a single K slice / key split and the expert down projection takes
+ * its unfused route (per-pair outputs, then the weighted combine), so no partial sum crosses workgroups.  Results then differ from the default path by float32 summation order only; the
+ * tests compare the two to check that the cross-workgroup hand-off delivers every partial.  Not for concurrent use. */
+int dinfer_debug_single_slice(int32_t on);
 
 /* Per-launch timing of one stage of the forward, for benchmarks: between dinfer_profile_start and
  * dinfer_profile_stop every launch of that stage is bracketed by a HIP event pair on the caller's stream
  * (at most 8192 launches are recorded).  _stop waits for the recorded events and returns their count and
- * the summed elapsed milliseconds.  The attention stage covers its two kernels (partials + merge). */
+ * the summed elapsed milliseconds. */
 enum {
   DINFER_STAGE_QKV = 0,
   DINFER_STAGE_ATTENTION = 1,

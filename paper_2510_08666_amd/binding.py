@@ -25,7 +25,8 @@ EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", 
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit", "dinfer_step_smooth", "dinfer_step_smooth_static", "dinfer_smooth_scratch_bytes",
            "dinfer_refresh_block", "dinfer_commit", "dinfer_generate",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
-           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace"]
+           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace",
+           "dinfer_debug_single_slice", "dinfer_generate_block_smooth"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
  STAGE_ROUTER) = range(7)
 
@@ -54,6 +55,11 @@ def hierarchical(threshold, lower_bound):
 
 class Credit(ctypes.Structure):
     _fields_ = [("alpha", c_f32), ("beta", c_f32), ("gamma", c_f32)]
+
+
+class SmoothSchedule(ctypes.Structure):
+    _fields_ = [("alpha_init", c_f32), ("alpha_growth", c_f32), ("alpha_preset", c_f32), ("threshold_start", c_f32),
+                ("threshold_decay", c_f32)]
 
 
 CREDIT_CAP = 64
@@ -101,6 +107,10 @@ def _load():
     L.dinfer_step_smooth.restype = c_i32
     L.dinfer_step_smooth.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_f32, c_vp, c_vp, c_sz,
                                      c_vp, c_vp, c_vp, c_vp]
+    L.dinfer_generate_block_smooth.restype = c_i32
+    L.dinfer_generate_block_smooth.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode),
+                                               P(SmoothSchedule), c_vp, c_vp, c_sz, c_vp, c_vp, c_vp, c_i32, c_i32,
+                                               P(c_i32), c_vp]
     L.dinfer_step_smooth_static.restype = c_i32
     L.dinfer_step_smooth_static.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_i32, P(Decode), c_f32, c_vp,
                                             c_vp, c_vp, c_vp, c_vp]
@@ -126,6 +136,8 @@ def _load():
     L.dinfer_kv_read.argtypes = [c_vp, c_i32, c_vp, c_i32, c_i32, c_vp, c_vp, c_vp]
     L.dinfer_debug_logits.restype = c_i32
     L.dinfer_debug_logits.argtypes = [c_vp, c_i32, c_vp, c_vp]
+    L.dinfer_debug_single_slice.restype = c_i32
+    L.dinfer_debug_single_slice.argtypes = [c_i32]
     L.dinfer_debug_get.restype = c_i32
     L.dinfer_debug_get.argtypes = [c_vp, c_i32, c_vp, c_sz, c_vp]
     L.dinfer_profile_start.restype = c_i32
@@ -164,6 +176,11 @@ def _stream():
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def debug_single_slice(on):
+    """Test switch: while on, no contraction shares a task's sum among workgroups."""
+    _check(lib.dinfer_debug_single_slice(1 if on else 0))
 
 
 def debug_trace(unit, n_wgs):
@@ -311,6 +328,21 @@ class Context:
                                          ctypes.byref(dec), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
                                          int(max_steps), int(masked_hint), int(steps_per_wait), ctypes.byref(steps),
                                          _stream()))
+        return steps.value
+
+    def generate_block_smooth(self, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, schedule, d_delta,
+                              d_scratch, d_conf, d_argmax, d_n_committed, max_steps, steps_per_wait=1):
+        """A block denoised with iteration smoothing; schedule = (alpha_init, alpha_growth, alpha_preset,
+        threshold_start, threshold_decay).  Returns the number of steps that ran."""
+        n_seq, block_len = d_block_tokens.shape
+        dec = _decode(threshold, 0)
+        sch = SmoothSchedule(*[float(v) for v in schedule])
+        steps = c_i32(0)
+        _check(lib.dinfer_generate_block_smooth(self.h, n_seq, block_len, _ptr(d_block_tokens), _ptr(d_mask),
+                                                _ptr(d_prefix_len), _ptr(d_page_table), d_page_table.shape[1],
+                                                ctypes.byref(dec), ctypes.byref(sch), _ptr(d_delta), _ptr(d_scratch),
+                                                d_scratch.numel(), _ptr(d_conf), _ptr(d_argmax), _ptr(d_n_committed),
+                                                int(max_steps), int(steps_per_wait), ctypes.byref(steps), _stream()))
         return steps.value
 
     def generate(self, d_out, d_block_tokens, d_mask, d_prefix_len, d_page_table, threshold, fixed_k, eos_id,

@@ -299,7 +299,9 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   // the next norm and one share of its sum of squares per task; larger forwards run the combine kernel.  (With two
   // token tiles every wave of the fused form fetches twice the activation operands per weight byte, and the
   // separate kernels are faster: measured at 64 tokens, 251 against 259 steps/s.)
-  const bool fused_down = T <= TILE;
+  // (the fused kernel needs its 64 wave shares, each within two experts; under the single-slice test switch the
+  // down projection takes the unfused route, which has no sum across workgroups)
+  const bool fused_down = T <= TILE && !single_slice();
   int n_ssq_a = 1;
   const int64_t q_plane = (int64_t)c->max_tokens * D;
   for (int l = 0; l < f.n_layers; ++l) {
@@ -326,7 +328,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
 #endif
     }
     AttnArgs aa{ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
-                attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), at<int32_t>(ws, w.attn_tickets),
+                single_slice() ? 1 : attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), at<int32_t>(ws, w.attn_tickets),
                 ws + w.a, T};
     {
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
@@ -621,10 +623,12 @@ size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens)
   return align_up((size_t)max_tokens * cfg->vocab * 4) + align_up(planes * max_tokens * smooth_kpad(bf, cfg->vocab) * es);
 }
 
-int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+// live / next_live / steps: as in step_impl.
+static int smooth_impl(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
                        const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
                        const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch, size_t scratch_bytes,
-                       float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+                       float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, hipStream_t st, const int32_t* live,
+                       int32_t* next_live, int32_t* steps) {
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   if (!d_mask || !decode || !d_conf || !d_argmax || !d_n_committed || !d_delta || !d_scratch)
@@ -637,7 +641,7 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   if ((uintptr_t)d_scratch & 255) return fail(DINFER_EINVAL, "scratch must be 256-byte aligned");
   const size_t need = dinfer_smooth_scratch_bytes(&f, T);
   if (scratch_bytes < need) return fail(DINFER_ENOSPACE, "smoothing scratch %zu < %zu bytes", scratch_bytes, need);
-  hipStream_t st = (hipStream_t)stream;
+  LiveScope scope(live);
   float* logits = (float*)d_scratch;
   void* probs = (char*)d_scratch + align_up((size_t)T * f.vocab * 4);
   SmoothIn sin{d_delta, alpha, d_mask, block_len};
@@ -658,9 +662,19 @@ int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   SmoothArgs sa{c->weights + c->wm.emb_t, logits, stats, probs, d_mask, block_len, d_delta, T, f.hidden, f.vocab,
                 at<float>(c->ws, c->wsm.tk_part), at<int32_t>(c->ws, c->wsm.tickets)};
   launch_expected_embedding(c->bf16, sa, st);
-  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed, nullptr, nullptr, st);
+  launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed,
+                nullptr, nullptr, st, next_live, steps);
   HIP_TRY(hipGetLastError());
   return DINFER_OK;
+}
+
+int dinfer_step_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
+                       const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
+                       const dinfer_decode* decode, float alpha, float* d_delta, void* d_scratch, size_t scratch_bytes,
+                       float* d_conf, int32_t* d_argmax, int32_t* d_n_committed, void* stream) {
+  return smooth_impl(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, decode, alpha,
+                     d_delta, d_scratch, scratch_bytes, d_conf, d_argmax, d_n_committed, (hipStream_t)stream, nullptr,
+                     nullptr, nullptr);
 }
 
 int dinfer_step_smooth_static(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
@@ -820,6 +834,59 @@ int dinfer_generate_block(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32
   return DINFER_OK;
 }
 
+int dinfer_generate_block_smooth(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens,
+                                 uint64_t* d_mask, const int32_t* d_prefix_len, const int32_t* d_page_table,
+                                 int32_t pt_stride, const dinfer_decode* decode, const dinfer_smooth_schedule* sched,
+                                 float* d_delta, void* d_scratch, size_t scratch_bytes, float* d_conf, int32_t* d_argmax,
+                                 int32_t* d_n_committed, int32_t max_steps, int32_t steps_per_wait,
+                                 int32_t* h_steps_taken, void* stream) {
+  if (max_steps < 1 || max_steps > MAX_LOOP_STEPS) return fail(DINFER_EINVAL, "max_steps %d outside [1, %d]", max_steps, MAX_LOOP_STEPS);
+  if (!c || !decode || !sched || !d_mask) return fail(DINFER_EINVAL, "null argument");
+  if (n_seq < 1 || n_seq > c->max_seqs) return fail(DINFER_EINVAL, "n_seq %d outside [1, %d]", n_seq, c->max_seqs);
+  if (steps_per_wait < 0) return fail(DINFER_EINVAL, "steps_per_wait %d", steps_per_wait);
+  if (decode->fixed_k > 0) return fail(DINFER_EINVAL, "the threshold schedule needs a threshold decoder (fixed_k == 0)");
+  if (!(sched->alpha_init >= 0.f) || !(sched->alpha_growth >= 0.f) || !(sched->alpha_preset >= sched->alpha_init))
+    return fail(DINFER_EINVAL, "schedule: 0 <= alpha_init <= alpha_preset, alpha_growth >= 0");
+  if (!(sched->threshold_decay >= 0.f) || !(sched->threshold_start >= decode->threshold) || !(sched->threshold_start <= 1.f))
+    return fail(DINFER_EINVAL, "schedule: decode->threshold <= threshold_start <= 1, threshold_decay >= 0");
+  hipStream_t st = (hipStream_t)stream;
+  const int batch = steps_per_wait > 0 ? steps_per_wait : 1;
+  int32_t* flags = at<int32_t>(c->ws, c->wsm.loop_flags);
+  int32_t* d_steps = at<int32_t>(c->ws, c->wsm.loop_steps);
+  int32_t* h_words = reinterpret_cast<int32_t*>(c->h_mask_pinned);
+  launch_loop_begin(d_mask, n_seq, flags, max_steps + 1, d_steps, st);
+  int enq = 0, steps = 0;
+  while (enq < max_steps) {
+    const int n = batch < max_steps - enq ? batch : max_steps - enq;
+    for (int i = 0; i < n; ++i) {
+      // Step t of the block (t = 0 first).  Steps only ever get skipped once every mask is empty, so the index
+      // of an enqueued step is also the number of steps that ran before it.
+      const int t = enq + i;
+      dinfer_decode d = *decode;
+      const float tau = sched->threshold_start - sched->threshold_decay * (float)t;
+      d.threshold = tau > decode->threshold ? tau : decode->threshold;
+      if (d.hierarchical && d.lower_bound > d.threshold) d.lower_bound = d.threshold;
+      float alpha = 0.f;   // the first step has nothing retained
+      if (t > 0) {
+        alpha = sched->alpha_init + sched->alpha_growth * (float)(t - 1);
+        if (alpha > sched->alpha_preset) alpha = sched->alpha_preset;
+      }
+      int rc = smooth_impl(c, n_seq, block_len, d_block_tokens, d_mask, d_prefix_len, d_page_table, pt_stride, &d, alpha,
+                           d_delta, d_scratch, scratch_bytes, d_conf, d_argmax, d_n_committed, st, flags + t,
+                           flags + t + 1, d_steps);
+      if (rc != DINFER_OK) return rc;
+    }
+    enq += n;
+    HIP_TRY(hipMemcpyAsync(h_words, flags + enq, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(h_words + 1, d_steps, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    steps = h_words[1];
+    if (h_words[0] == 0) break;
+  }
+  if (h_steps_taken) *h_steps_taken = steps;
+  return DINFER_OK;
+}
+
 int dinfer_commit(const float* d_conf, const int32_t* d_argmax, int32_t n_seq, int32_t block_len,
                   int32_t* d_block_tokens, uint64_t* d_mask, const dinfer_decode* decode, int32_t* d_n_committed,
                   void* stream) {
@@ -962,6 +1029,11 @@ int dinfer_debug_get(dinfer_ctx* c, int32_t what, void* d_out, size_t bytes, voi
   }
   if (bytes != want || want == 0) return fail(DINFER_EINVAL, "%zu bytes given, %zu expected", bytes, want);
   HIP_TRY(hipMemcpyAsync(d_out, c->ws + off, want, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return DINFER_OK;
+}
+
+int dinfer_debug_single_slice(int32_t on) {
+  set_single_slice(on != 0);
   return DINFER_OK;
 }
 

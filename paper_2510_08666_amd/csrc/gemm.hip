@@ -427,7 +427,7 @@ int gemm_slices(bool bf16, int K, int T) {
 template <typename E, class Epi>
 static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int T, int K, int n_tasks,
                           float* part, int32_t* tickets, const Epi& epi, hipStream_t st, int forced_slices = 0) {
-  const int slices = forced_slices ? forced_slices : gemm_slices(bf16, K, T);
+  const int slices = forced_slices ? forced_slices : single_slice() ? 1 : gemm_slices(bf16, K, T);
   if (T <= 32) {
     gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi, live_word());
   } else if (T <= 64) {
@@ -1092,7 +1092,7 @@ __global__ __launch_bounds__(KW * WAVE) void router_kernel(const E* __restrict__
 
 // Workgroups that share the router's K range: as for the projections, with 8 waves per workgroup.
 static int router_slices(bool bf16, int K, int T) {
-  if (T > 2 * TILE) return 1;
+  if (T > 2 * TILE || single_slice()) return 1;
   const int ksteps = K / (bf16 ? 16 : 8);
   const int burst = 8 * (T <= TILE ? 8 : 4);
   return ksteps % burst == 0 ? ksteps / burst : 1;

@@ -12,6 +12,10 @@ namespace dinfer {
 // common.hpp): set by the step entry points around a forward, handed to every kernel by its launcher.
 void set_live_word(const int32_t* d_live);
 const int32_t* live_word();
+// Test switch (process-wide): while on, no contraction shares a task's sum among workgroups -- projections, router
+// and attention run with one K slice / key split, the expert down projection unfused.
+void set_single_slice(bool on);
+bool single_slice();
 
 // ---- weight packing (pack.hip) ----
 enum PackMode { PACK_ADJACENT = 0, PACK_ROPE_PAIR = 1, PACK_HALF0 = 2, PACK_HALF1 = 3 };

@@ -9,6 +9,9 @@ namespace dinfer {
 static thread_local const int32_t* t_live_word = nullptr;
 void set_live_word(const int32_t* d_live) { t_live_word = d_live; }
 const int32_t* live_word() { return t_live_word; }
+static bool g_single_slice = false;
+void set_single_slice(bool on) { g_single_slice = on; }
+bool single_slice() { return g_single_slice; }
 
 // ---------------------------------------------------------------- rotary table
 // cos / sin of pos * theta^(-2j/hd), computed in double on the device and stored as float.
@@ -112,7 +115,9 @@ void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int 
 // the B operand of the expected-embedding contraction.
 template <typename E>
 __global__ __launch_bounds__(256) void prob_planes_kernel(const float* __restrict__ logits, const float* __restrict__ stats,
-                                                           int T, int V, int Kpad, E* __restrict__ probs) {
+                                                           int T, int V, int Kpad, E* __restrict__ probs,
+                                                           const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
   const int t = blockIdx.y;
   const float m = stats[2 * t], inv = 1.f / stats[2 * t + 1];
   for (int v0 = (blockIdx.x * 256 + threadIdx.x) * 4; v0 < Kpad; v0 += gridDim.x * 256 * 4) {
@@ -125,8 +130,8 @@ __global__ __launch_bounds__(256) void prob_planes_kernel(const float* __restric
 void launch_prob_planes(bool bf16, const float* logits, const float* stats, int T, int V, int Kpad, void* probs,
                         hipStream_t st) {
   dim3 grid(64, T);
-  if (bf16) prob_planes_kernel<bf16_t><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (bf16_t*)probs);
-  else prob_planes_kernel<float><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (float*)probs);
+  if (bf16) prob_planes_kernel<bf16_t><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (bf16_t*)probs, live_word());
+  else prob_planes_kernel<float><<<grid, 256, 0, st>>>(logits, stats, T, V, Kpad, (float*)probs, live_word());
 }
 
 // x[t] += sum_j w[t][j] * O[t*k+j]  (j ascending: a fixed summation order);  ssq[t] = sum of squares and the

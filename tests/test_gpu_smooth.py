@@ -107,3 +107,67 @@ def test_bad_arguments(case):
     small = dict(delta=sm["delta"], scratch=sm["scratch"][:4096])
     with pytest.raises(DinferError):
         g.step_smooth(small, 0.1, 0.5)
+
+
+def _schedules(t, sched, target):
+    """Appendix "IterSmooth", for step t of a block (0 first): the weight of what step t-1 retained, alpha_{t-1} =
+    min(alpha_init + alpha_growth * (t-1), alpha_preset) (nothing is retained before step 0), and the decode
+    threshold, which decays from its start value towards the target (linearly, floored at the target)."""
+    a_init, a_growth, a_preset, th_start, th_decay = sched
+    alpha = 0.0 if t == 0 else min(a_init + a_growth * (t - 1), a_preset)
+    return np.float32(alpha), max(np.float32(th_start) - np.float32(th_decay) * np.float32(t), np.float32(target))
+
+
+@pytest.mark.parametrize("steps_per_wait", [1, 5])
+def test_block_under_the_schedules_equals_its_steps_one_by_one(case, steps_per_wait):
+    """dinfer_generate_block_smooth against the same steps issued one at a time with the schedule values worked out
+    here from the appendix: same kernels, so the same bits, and the same number of steps."""
+    wl, cfg, inp, ora, g, bars = case
+    ns, S = inp.block_tokens.shape
+    sched, target = (0.1, 0.05, 0.3, 1.0, 0.2), 0.3
+    g.inject_prefix(ora.caches)
+    # one at a time
+    sm = g.smooth_state()
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    manual, t = [], 0
+    while True:
+        alpha, tau = _schedules(t, sched, target)
+        st = g.step_smooth(sm, float(alpha), float(tau))
+        manual.append(st)
+        t += 1
+        if not st["mask"].any():
+            break
+        assert t < 4 * S
+    delta_manual = sm["delta"].clone()
+    # the loop
+    sm2 = g.smooth_state()
+    sm2["delta"].fill_(123.0)                   # needs no initial contents
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    n = g.ctx.generate_block_smooth(g.tokens, g.mask, g.prefix_len, g.page_table, target, sched, sm2["delta"],
+                                    sm2["scratch"], g.conf, g.argmax, g.n_committed, 4 * S, steps_per_wait)
+    g.torch.cuda.synchronize()
+    got = g.state()
+    assert n == len(manual), "steps: %d in the loop, %d one by one" % (n, len(manual))
+    for key in ("tokens", "mask", "conf", "argmax", "n_committed"):
+        assert np.array_equal(got[key], manual[-1][key]), key
+    masked0 = np.array([[(int(inp.mask_bits[s]) >> i) & 1 for i in range(S)] for s in range(ns)], dtype=bool)
+    assert g.torch.equal(sm2["delta"][g.torch.from_numpy(masked0).to(g.dev)],
+                         delta_manual[g.torch.from_numpy(masked0).to(g.dev)])
+    # the thresholds did decay: the block took more than one step, and fewer than one per position
+    print("schedule block: %d steps for %d masked positions" % (n, int(masked0.sum())))
+    assert 1 < n
+
+
+def test_schedule_loop_bad_arguments(case):
+    wl, cfg, inp, ora, g, bars = case
+    from paper_2510_08666_amd.binding import DinferError
+    sm = g.smooth_state()
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    args = (g.tokens, g.mask, g.prefix_len, g.page_table)
+    tail = (sm["delta"], sm["scratch"], g.conf, g.argmax, g.n_committed)
+    with pytest.raises(DinferError):      # start below the target
+        g.ctx.generate_block_smooth(*args, 0.5, (0.1, 0.05, 0.3, 0.4, 0.1), *tail, 8)
+    with pytest.raises(DinferError):      # preset below init
+        g.ctx.generate_block_smooth(*args, 0.5, (0.3, 0.05, 0.1, 1.0, 0.1), *tail, 8)
+    with pytest.raises(DinferError):      # too many steps
+        g.ctx.generate_block_smooth(*args, 0.5, (0.1, 0.05, 0.3, 1.0, 0.1), *tail, 1000)

@@ -193,6 +193,37 @@ def test_step_twice_is_bit_identical(case):
     assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(la, lb)
 
 
+def test_split_sums_match_single_workgroup_sums(case):
+    """Projections, router, fused down projection and attention normally share a task's sum among workgroups and
+    hand the partials over through memory.  With the test switch on, one workgroup sums a task alone: the two
+    results may differ by float32 summation order only (carried through the layers, and in bf16 storage through
+    the re-rounding of activations to their two bf16 planes).  A partial that arrived late or stale would be off
+    by a share of the sum (an eighth or more), two orders of magnitude above this bar."""
+    from paper_2510_08666_amd import binding
+    g, inp = case.gpu, case.inp
+    T = case.ns * case.S
+    g.inject_prefix(case.ora.caches)
+    g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+    g.step(case.wl.threshold)
+    la = g.logits(T)
+    ids_a = g.ctx.debug_get(1, (case.cfg.n_layers, T, case.cfg.top_k), binding.torch.int32).cpu().numpy()
+    binding.debug_single_slice(True)
+    try:
+        g.set_state(inp.block_tokens, inp.mask_bits, inp.prefix_len)
+        g.step(case.wl.threshold)
+        lb = g.logits(T)
+        ids_b = g.ctx.debug_get(1, (case.cfg.n_layers, T, case.cfg.top_k), binding.torch.int32).cpu().numpy()
+    finally:
+        binding.debug_single_slice(False)
+    same_route = np.array_equal(np.sort(ids_a, axis=-1), np.sort(ids_b, axis=-1))
+    scale = float(np.abs(la).max())
+    err = float(np.abs(la - lb).max()) / scale
+    print("single-slice vs split: max |dz| / max |z| = %.2e, routing identical: %s" % (err, same_route))
+    if not same_route:
+        pytest.skip("a router near-tie fell differently under the other summation order; logits are not comparable")
+    assert err <= (1e-3 if case.cfg.dtype == "bf16" else 1e-4)
+
+
 def test_empty_mask_commits_nothing(case):
     g, inp = case.gpu, case.inp
     g.inject_prefix(case.ora.caches)
