@@ -153,7 +153,9 @@ int dinfer_commit(const float* d_conf, const int32_t* d_argmax, int32_t n_seq, i
  *   d_scratch device buffer of at least dinfer_smooth_scratch_bytes(cfg, n_seq * block_len) bytes, 256-byte
  *             aligned, contents irrelevant: this variant stores the block's logits there (the second contraction
  *             over the vocabulary needs normalised probabilities).
- * n_seq * block_len <= 64.  Everything else as in dinfer_step. */
+ * Any token count the context takes; above 64 tokens the contraction over the vocabulary runs in the many-token
+ * form, in which every group of 64 tokens streams the whole embedding matrix again.  Everything else as in
+ * dinfer_step. */
 size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens);
 int dinfer_step_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_t* d_block_tokens, uint64_t* d_mask,
                        const int32_t* d_prefix_len, const int32_t* d_page_table, int32_t pt_stride,
@@ -171,7 +173,7 @@ int dinfer_step_smooth(dinfer_ctx* ctx, int32_t n_seq, int32_t block_len, int32_
  *                  to it.
  * decode->fixed_k must be 0.  d_delta [n_seq][block_len][hidden] needs no initial contents.  Steps are enqueued
  * steps_per_wait at a time and the host waits once per batch, as in dinfer_generate_block's threshold mode (the
- * schedules are functions of the step index, which the host knows without waiting).  n_seq * block_len <= 64;
+ * schedules are functions of the step index, which the host knows without waiting);
  * max_steps <= 256; scratch as in dinfer_step_smooth. */
 typedef struct {
   float alpha_init, alpha_growth, alpha_preset;

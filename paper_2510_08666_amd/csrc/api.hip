@@ -617,7 +617,7 @@ int dinfer_step(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d_bloc
 }
 
 size_t dinfer_smooth_scratch_bytes(const dinfer_config* cfg, int32_t max_tokens) {
-  if (check_config(cfg) != DINFER_OK || max_tokens < 1 || max_tokens > 2 * TILE) return 0;
+  if (check_config(cfg) != DINFER_OK || max_tokens < 1) return 0;
   const bool bf = cfg->dtype == DINFER_BF16;
   const size_t planes = bf ? 2 : 1, es = bf ? 2 : 4;
   return align_up((size_t)max_tokens * cfg->vocab * 4) + align_up(planes * max_tokens * smooth_kpad(bf, cfg->vocab) * es);
@@ -637,7 +637,6 @@ static int smooth_impl(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t*
   if (!(alpha >= 0.f)) return fail(DINFER_EINVAL, "alpha must be >= 0");
   const dinfer_config& f = c->cfg;
   const int T = n_seq * block_len;
-  if (T > 2 * TILE) return fail(DINFER_EUNSUPPORTED, "iteration smoothing handles at most %d block tokens per call", 2 * TILE);
   if ((uintptr_t)d_scratch & 255) return fail(DINFER_EINVAL, "scratch must be 256-byte aligned");
   const size_t need = dinfer_smooth_scratch_bytes(&f, T);
   if (scratch_bytes < need) return fail(DINFER_ENOSPACE, "smoothing scratch %zu < %zu bytes", scratch_bytes, need);
@@ -684,7 +683,7 @@ int dinfer_step_smooth_static(dinfer_ctx* c, int32_t n_seq, int32_t block_len, i
   int rc = check_block_args(c, n_seq, block_len, d_block_tokens, d_prefix_len, d_page_table, pt_stride);
   if (rc != DINFER_OK) return rc;
   const size_t need = dinfer_smooth_scratch_bytes(&c->cfg, n_seq * block_len);
-  if (need == 0) return fail(DINFER_EUNSUPPORTED, "iteration smoothing handles at most %d block tokens per call", 2 * TILE);
+  if (need == 0) return fail(DINFER_EINVAL, "bad configuration");
   if (need > (size_t)DINFER_STATIC_SCRATCH_BYTES)
     return fail(DINFER_ENOSPACE, "%d block tokens of a %d-id vocabulary need %zu bytes of scratch; the static scratch holds %zu",
                 n_seq * block_len, c->cfg.vocab, need, (size_t)DINFER_STATIC_SCRATCH_BYTES);

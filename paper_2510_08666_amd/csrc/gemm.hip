@@ -813,8 +813,13 @@ int smooth_kpad(bool bf16, int V) {
 template <typename E> static void launch_smooth_t(bool bf16, const SmoothArgs& a, hipStream_t st) {
   const int Kpad = smooth_kpad(bf16, a.V);
   SmoothEpi epi{a.delta, a.H, a.mask, a.block_len};
-  launch_ksplit<E>(bf16, (const E*)a.w_emb_t, Kpad / ET<E>::KS, (const E*)a.probs, a.T, Kpad, a.H / 64, a.part, a.tickets,
-                   epi, st, SMOOTH_SLICES);
+  // More than 64 tokens: the shared-operand form, with the most token tiles per workgroup whatever the fill -- every
+  // token group streams the whole transposed embedding matrix, so fewer, larger groups move fewer bytes.
+  if (dense_applies(a.T, Kpad / ET<E>::KS))
+    launch_dense_as<E, DENSE_WT, 4, SmoothEpi>((const E*)a.w_emb_t, Kpad / ET<E>::KS, (const E*)a.probs, a.T, a.H / 64, epi, st);
+  else
+    launch_ksplit<E>(bf16, (const E*)a.w_emb_t, Kpad / ET<E>::KS, (const E*)a.probs, a.T, Kpad, a.H / 64, a.part,
+                     a.tickets, epi, st, SMOOTH_SLICES);
 }
 void launch_expected_embedding(bool bf16, const SmoothArgs& a, hipStream_t st) {
   launch_prob_planes(bf16, a.logits, a.stats, a.T, a.V, smooth_kpad(bf16, a.V), a.probs, st);
@@ -1155,7 +1160,8 @@ bool configure_kernels() {
             configure_ksplit<bf16_t, ResidualEpi<bf16_t>>() && configure_ksplit<float, ResidualEpi<float>>() &&
             configure_ksplit<bf16_t, SmoothEpi>() && configure_ksplit<float, SmoothEpi>();
   ok = ok && configure_dense<bf16_t, QkvEpi<bf16_t>>() && configure_dense<float, QkvEpi<float>>() &&
-       configure_dense<bf16_t, ResidualEpi<bf16_t>>() && configure_dense<float, ResidualEpi<float>>();
+       configure_dense<bf16_t, ResidualEpi<bf16_t>>() && configure_dense<float, ResidualEpi<float>>() &&
+       configure_dense<bf16_t, SmoothEpi>() && configure_dense<float, SmoothEpi>();
   ok = ok && opt_in_lds((const void*)expert_down_fused_kernel<bf16_t, 1, DOWN_KW, 8>) &&
        opt_in_lds((const void*)expert_down_fused_kernel<bf16_t, 1, DOWN_KW, 4>) &&
        opt_in_lds((const void*)expert_down_fused_kernel<float, 1, DOWN_KW, 8>) &&

@@ -22,10 +22,16 @@ def _variant(name):
         "pair": W("pair", tiny, 2, 20, 30, 50, threshold=0.9, seed_index=6),
         # a vocabulary that is not a multiple of anything (padding of the contraction)
         "odd_vocab": W("odd_vocab", sc(tiny, vocab=1000), 1, 32, 40, 40, threshold=0.9, seed_index=9),
+        # more than 64 tokens: the contraction over the vocabulary in its many-token form (5 x 32 tokens: three
+        # groups of 64, the last ragged), in both storage types.  (Above 64 tokens the LM head feeds the matrix cores
+        # activations rounded to one bf16 plane; at the tiny preset's logit scale of 8 that rounding alone moves a
+        # confidence by more than the bar, so the bf16 case runs at a scale of 2.)
+        "many": W("many", tiny, 5, 32, 20, 60, threshold=0.9, seed_index=31),
+        "many_bf16": W("many_bf16", sc(tiny, dtype="bf16", logit_scale=2.0), 5, 32, 20, 60, threshold=0.9, seed_index=31),
     }[name]
 
 
-@pytest.fixture(scope="module", params=["c1", "c1_bf16", "pair", "odd_vocab"])
+@pytest.fixture(scope="module", params=["c1", "c1_bf16", "pair", "odd_vocab", "many", "many_bf16"])
 def case(request):
     wl = _variant(request.param)
     cfg, w, inp = make_case(wl)
