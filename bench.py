@@ -116,6 +116,13 @@ def generation_loop(args):
     dev = ctx.device
     page_table = torch.from_numpy(inp.page_table).to(dev)
     prompt = torch.from_numpy(inp.prefix_tokens[0].astype(np.int32)).to(dev)
+    if args.half_decided:
+        keep = np.uint64(0x5555555555555555 & ((1 << S) - 1))
+        inp.mask_bits[:] = inp.mask_bits & keep
+        for s in range(ns):
+            for i in range(S):
+                if not (int(inp.mask_bits[s]) >> i) & 1 and inp.block_tokens[s, i] == cfg.mask_id:
+                    inp.block_tokens[s, i] = (7 * i + s) % (cfg.vocab - 1)
     tokens0 = torch.from_numpy(inp.block_tokens.copy()).to(dev)
     mask0 = torch.from_numpy(inp.mask_bits.view(np.int64).copy()).to(dev)
     tokens, mask = tokens0.clone(), mask0.clone()
@@ -280,10 +287,14 @@ def main():
                          "instead of the workload's threshold, in whichever step variant is timed")
     ap.add_argument("--smooth", action="store_true",
                     help="time the step with iteration smoothing (alpha 0.2); the expected embeddings carry over "
-                         "between the timed steps, as inside a block (single-block workloads with at most 64 tokens)")
+                         "between the timed steps, as inside a block")
     ap.add_argument("--vicinity", type=int, default=0,
                     help="time the step with vicinity KV-cache refresh over this many cached positions before the "
                          "block (the paper's experiments use 16); 0 = the plain step")
+    ap.add_argument("--half-decided", type=int, default=0, choices=[0, 1, 2],
+                    help="variant: every timed step starts with every other position of each block already decided "
+                         "(a block half way through its denoising); 1 = the plain step, 2 = with decode.skip_decided, "
+                         "which leaves the decided rows out of the LM head")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
     ap.add_argument("--block-loop", type=int, default=0,
                     help="time dinfer_generate_block over the workload's block with threshold decoding at a threshold "
@@ -329,6 +340,13 @@ def main():
     setup_s = time.time() - t0
 
     prefix_len = torch.from_numpy(inp.prefix_len.astype(np.int32)).to(dev)
+    if args.half_decided:
+        keep = np.uint64(0x5555555555555555 & ((1 << S) - 1))
+        inp.mask_bits[:] = inp.mask_bits & keep
+        for s in range(ns):
+            for i in range(S):
+                if not (int(inp.mask_bits[s]) >> i) & 1 and inp.block_tokens[s, i] == cfg.mask_id:
+                    inp.block_tokens[s, i] = (7 * i + s) % (cfg.vocab - 1)
     tokens0 = torch.from_numpy(inp.block_tokens.copy()).to(dev)
     mask0 = torch.from_numpy(inp.mask_bits.view(np.int64).copy()).to(dev)
     tokens, mask = tokens0.clone(), mask0.clone()
@@ -353,6 +371,8 @@ def main():
         smooth = (torch.zeros((ns, S, cfg.hidden), dtype=torch.float32, device=dev), ctx.smooth_scratch(ns * S))
 
     thr = binding.hierarchical(0.92, 0.62) if args.hier else wl.threshold
+    if args.half_decided == 2:
+        thr = binding.Decode(float(wl.threshold), int(wl.fixed_k), 0, 0.0, 1)
 
     def one_step():
         tokens.copy_(tokens0)
@@ -460,7 +480,8 @@ def main():
         "ms_min": round(per_step_ms[0], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ("-vicinity%d" % lb if lb else "") + ("-credit" if args.credit else "")
-                   + ("-smooth" if args.smooth else "") + ("-hier" if args.hier else ""),
+                   + ("-smooth" if args.smooth else "") + ("-hier" if args.hier else "")
+                   + (("-half-decided", "-half-decided-skip")[args.half_decided - 1] if args.half_decided else ""),
                    "n_seq": ns, "block_len": S,
                    "vicinity_look_back": lb, "prefix_len": [int(p) for p in inp.prefix_len][:4],
                    "threshold": wl.threshold, "weights": "random-init N(0,0.02) seed %d" % (di.BASE_SEED + 2),

@@ -87,6 +87,11 @@ typedef struct dinfer_decode {
   int32_t fixed_k;
   int32_t hierarchical;
   float lower_bound;
+  int32_t skip_decided;   /* dinfer_step, dinfer_generate_block, dinfer_generate: 1 = confidence and candidate id are
+                             worked out only for the positions that were undecided when the step began (the only
+                             ones the decoder reads); the d_conf / d_argmax entries of the others are left as they
+                             were.  With more than 64 tokens the LM head then skips the decided rows' matrix work.
+                             The other step variants ignore the field. */
 } dinfer_decode;
 
 typedef struct dinfer_ctx dinfer_ctx;

@@ -38,19 +38,20 @@ class Config(ctypes.Structure):
 
 
 class Decode(ctypes.Structure):
-    _fields_ = [("threshold", c_f32), ("fixed_k", c_i32), ("hierarchical", c_i32), ("lower_bound", c_f32)]
+    _fields_ = [("threshold", c_f32), ("fixed_k", c_i32), ("hierarchical", c_i32), ("lower_bound", c_f32),
+                ("skip_decided", c_i32)]
 
 
 def _decode(threshold, fixed_k):
     """A Decode passes through; otherwise threshold decoding (or fixed-k when fixed_k > 0)."""
     if isinstance(threshold, Decode):
         return threshold
-    return Decode(float(threshold), int(fixed_k), 0, 0.0)
+    return Decode(float(threshold), int(fixed_k), 0, 0.0, 0)
 
 
 def hierarchical(threshold, lower_bound):
     """Decoder settings of hierarchical decoding."""
-    return Decode(float(threshold), 0, 1, float(lower_bound))
+    return Decode(float(threshold), 0, 1, float(lower_bound), 0)
 
 
 class Credit(ctypes.Structure):

@@ -138,7 +138,7 @@ int attn_splits(int n_qtiles, int n_heads, int key_bound) {
 
 struct Workspace {
   size_t cos_tab, sin_tab, tok_seq, tok_pos, seq_nkeys, qtile, x, xn, ssq, ssq_a, tk_part, tickets, tickets_bytes, attn_tickets, attn_tickets_bytes, rinv_f, q, a, attn_part, topk_idx, topk_w, cnt, off,
-      perm, pos_of_pair, work, run_tokens, run_base, n_finished, loop_flags, loop_steps, y, o, lm_part, lm_stats, conf, argmax, total;
+      perm, pos_of_pair, work, run_tokens, run_base, n_finished, loop_flags, loop_steps, lm_rows, y, o, lm_part, lm_stats, conf, argmax, total;
 };
 
 Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
@@ -202,6 +202,7 @@ Workspace map_workspace(const dinfer_config& c, int max_seqs, int max_tokens) {
   w.n_finished = cv.take(4);                     // generation loop: sequences that have produced the end-of-sequence id
   w.loop_flags = cv.take((size_t)(MAX_LOOP_STEPS + 1) * 4);   // inner loop: "step i is still needed" words
   w.loop_steps = cv.take(4);                     // inner loop: steps that ran
+  w.lm_rows = cv.take((size_t)(1 + T) * 4);      // LM head: rows of the undecided positions
   w.work = cv.take((size_t)(1 + expert_work_items(MAX_EXPERTS, (int)(T * K))) * 4);
   w.y = cv.take(planes * T * K * I * es);
   w.o = cv.take(T * K * H * 4);
@@ -460,6 +461,7 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   c->geom.n_heads = cfg->n_heads;
   c->geom.head_dim = cfg->head_dim;
   c->geom.n_pages = n_pages;
+  c->geom.kblk = 32 / (int)es;
   c->geom.page_stride = (int64_t)2 * cfg->n_heads * PAGE * cfg->head_dim;
   c->geom.layer_stride = c->geom.page_stride * n_pages;
   c->kv_layer_bytes = (size_t)c->geom.layer_stride * es;
@@ -598,11 +600,17 @@ static int step_impl(dinfer_ctx* c, int32_t n_seq, int32_t block_len, int32_t* d
   LmArgs la{c->weights + c->wm.lm_head, c->ws + c->wsm.xn,
             RowNorm{at<float>(c->ws, c->wsm.ssq_a), c->last_n_ssq, f.rms_eps}, T, f.hidden, f.vocab, f.logit_scale,
             at<float>(c->ws, c->wsm.lm_part), nullptr};
+  const bool skip = decode->skip_decided != 0;
+  if (skip && T > 2 * TILE) {   // with few tokens the LM head is bound by its weight stream: rows cost nothing there
+    int32_t* rows = at<int32_t>(c->ws, c->wsm.lm_rows);
+    launch_lm_rows(d_mask, n_seq, block_len, rows, st);
+    la.rows = rows;
+  }
   {
     StageTimer tm(c, DINFER_STAGE_LM_HEAD, st);
     launch_lm_head(c->bf16, la, st);
   }
-  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st);
+  launch_lm_merge(la.part, lm_head_parts(f.vocab, T), T, d_conf, d_argmax, nullptr, st, skip ? d_mask : nullptr, block_len);
   launch_commit(d_conf, d_argmax, n_seq, block_len, block_len, 0, d_block_tokens, d_mask, commit_rule(decode), d_n_committed,
                 nullptr, nullptr, st, next_live, steps);
   HIP_TRY(hipGetLastError());

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
     const int key = min(kt * TILE + col, n_keys - 1);
     const E* krow = kv_layer + kv_k_index(geom, safe_page(geom, pt[key / PAGE]), head, key % PAGE, 0) + half * G;
 #pragma unroll
-    for (int s = 0; s < DSTEPS; ++s) r.k[s] = load16<E>(krow + s * KS);
+    for (int s = 0; s < DSTEPS; ++s) r.k[s] = load16<E>(krow + s * (PAGE * KS));   // k-step s of this slot
 #pragma unroll
     for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
       const int pkey = min(kt * TILE + PvStep<E>::page_of_step(s2) * PAGE, n_keys - 1);

@@ -224,18 +224,22 @@ struct SeqSpan {
 };
 
 // Where the KV pool keeps things.  Pool: [layer][page][K|V][head][PAGE*head_dim] elements.
-// K part of a (page, head): [slot][head_dim]; V part: [head_dim][slot] (transposed, so that the PV product
-// finds the keys of one page contiguous per feature).
+// K part of a (page, head): [head_dim / kblk][slot][kblk] with kblk elements = 32 bytes, one k-step of the
+// QK^T product: the 16 slots of a page lie next to each other for every k-step, so a wave's load of one k-step
+// for the 32 keys of a tile touches two runs of 512 contiguous bytes (8 cache lines) instead of 32 rows.
+// V part: [head_dim][slot] (transposed, so that the PV product finds the keys of one page contiguous per feature).
 struct KvGeom {
   int64_t layer_stride;   // elements
   int64_t page_stride;    // elements = 2 * n_heads * PAGE * head_dim
   int32_t n_heads, head_dim;
   int32_t n_pages;
+  int32_t kblk;           // elements in 32 bytes: 16 (bf16) or 8 (float)
 };
 // Page ids come from the caller's page table: keep every access inside the pool whatever they hold.
 __device__ inline int safe_page(const KvGeom& g, int id) { return min(max(id, 0), g.n_pages - 1); }
 __device__ inline int64_t kv_k_index(const KvGeom& g, int page, int head, int slot, int d) {
-  return (int64_t)page * g.page_stride + ((int64_t)head * PAGE + slot) * g.head_dim + d;
+  return (int64_t)page * g.page_stride + (int64_t)head * PAGE * g.head_dim +
+         ((int64_t)(d / g.kblk) * PAGE + slot) * g.kblk + d % g.kblk;
 }
 __device__ inline int64_t kv_v_index(const KvGeom& g, int page, int head, int slot, int d) {
   return (int64_t)page * g.page_stride + (int64_t)g.n_heads * PAGE * g.head_dim +

@@ -104,15 +104,17 @@ template <typename E> struct QkvEpi {
         hi[i] = b * pre.c[i] + a * pre.s[i];
       }
       if (is_k) {
+        // (PER consecutive features starting at a multiple of PER stay inside one 32-byte block of the K layout)
         E* dst = kv_layer + kv_k_index(geom, page, head, slot, j0);
+        E* dst_hi = kv_layer + kv_k_index(geom, page, head, slot, j0 + hd / 2);
         if constexpr (PER == 4) {
           store_elems4<E>(dst, f32x4{lo[0], lo[1], lo[2], lo[3]});
-          store_elems4<E>(dst + hd / 2, f32x4{hi[0], hi[1], hi[2], hi[3]});
+          store_elems4<E>(dst_hi, f32x4{hi[0], hi[1], hi[2], hi[3]});
         } else {
 #pragma unroll
           for (int i = 0; i < PER; ++i) {
             dst[i] = from_f32<E>(lo[i]);
-            dst[hd / 2 + i] = from_f32<E>(hi[i]);
+            dst_hi[i] = from_f32<E>(hi[i]);
           }
         }
       } else {

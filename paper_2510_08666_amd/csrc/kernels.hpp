@@ -202,15 +202,20 @@ struct LmArgs {
   float scale;
   float* part;              // [lm_head_parts(V, T)][T][4]: max, sum-exp, argmax bits, unused
   float* logits_out;        // debug: [T][V] or null
+  const int32_t* rows = nullptr;   // null: every row.  Else [1 + T]: rows[0] = n, rows[1 .. n] = the token rows to take,
+                                   // ascending (forwards of more than 64 tokens only; smaller ones take every row)
 };
+// rows[0] = number of undecided positions over all sequences, rows[1 ..] = their token rows n_seq-major, ascending.
+void launch_lm_rows(const uint64_t* mask, int n_seq, int block_len, int32_t* rows, hipStream_t st);
 int lm_head_waves(int V);          // upper bound of partials per token row (workspace sizing)
 int lm_head_parts(int V, int T);   // partials per token row launch_lm_head writes for T tokens
 void launch_lm_head(bool bf16, const LmArgs& a, hipStream_t st);        // picks the form by a.T
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st);
 int lm_head_wide_parts(int V);
 // stats (may be null): [T][2] = the row's largest logit and sum exp(z - max)
+// mask (may be null) with block_len: rows of decided positions are left alone.
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
-                     hipStream_t st);
+                     hipStream_t st, const uint64_t* mask = nullptr, int block_len = 0);
 // Credit decoding of the masked rows: conf / argmax hold the plain values on entry and the enhanced ones on return.
 void launch_credit(bool bf16, const void* w_lm, const void* xn, RowNorm norm, int T, int H, int V, float scale,
                    const float* stats, const uint64_t* mask, int block_len, float alpha, float beta, float gamma,

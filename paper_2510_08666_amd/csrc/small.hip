@@ -321,10 +321,12 @@ __device__ inline LmStat lm_combine(LmStat a, LmStat b) {
 }
 __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__ part, int n_waves, int T,
                                                         float* __restrict__ conf, int32_t* __restrict__ argmax,
-                                                        float* __restrict__ stats, const int32_t* __restrict__ live) {
+                                                        float* __restrict__ stats, const uint64_t* __restrict__ mask,
+                                                        int block_len, const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   __shared__ LmStat sh[4];
   const int t = blockIdx.x;
+  if (mask && !((mask[t / block_len] >> (t % block_len)) & 1ull)) return;   // a decided position: nothing was computed
   LmStat a{-INFINITY, 0.f, 0x7fffffff};
   for (int w = threadIdx.x; w < n_waves; w += 256) {
     const float* p = part + ((int64_t)w * T + t) * 4;
@@ -348,8 +350,35 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(const float* __restrict__
   }
 }
 void launch_lm_merge(const float* part, int n_lm_waves, int T, float* conf, int32_t* argmax, float* stats,
-                     hipStream_t st) {
-  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax, stats, live_word());
+                     hipStream_t st, const uint64_t* mask, int block_len) {
+  lm_merge_kernel<<<T, 256, 0, st>>>(part, n_lm_waves, T, conf, argmax, stats, mask, block_len, live_word());
+}
+
+// Row list of the LM head when only undecided positions are wanted: lane s counts the set bits of sequence s,
+// a scan over the lanes gives its offset, and it lists its positions in ascending order.
+__global__ __launch_bounds__(64) void lm_rows_kernel(const uint64_t* __restrict__ mask, int n_seq, int block_len,
+                                                      int32_t* __restrict__ rows, const int32_t* __restrict__ live) {
+  if (step_is_dead(live)) return;
+  const int lane = threadIdx.x;
+  const uint64_t keep = block_len >= 64 ? ~0ull : ((1ull << block_len) - 1);
+  uint64_t m = lane < n_seq ? mask[lane] & keep : 0ull;
+  const int n = __popcll(m);
+  int incl = n;
+#pragma unroll
+  for (int o = 1; o < WAVE; o <<= 1) {
+    const int up = __shfl_up(incl, o, WAVE);
+    if (lane >= o) incl += up;
+  }
+  int at = 1 + incl - n;
+  while (m) {
+    const int pos = __ffsll((unsigned long long)m) - 1;
+    rows[at++] = lane * block_len + pos;
+    m &= m - 1;
+  }
+  if (lane == WAVE - 1) rows[0] = incl;
+}
+void launch_lm_rows(const uint64_t* mask, int n_seq, int block_len, int32_t* rows, hipStream_t st) {
+  lm_rows_kernel<<<1, WAVE, 0, st>>>(mask, n_seq, block_len, rows, live_word());
 }
 
 // ---------------------------------------------------------------- decoder: credit decoding

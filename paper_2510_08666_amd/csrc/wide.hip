@@ -219,26 +219,37 @@ template <typename E, int WT, int KID, int WW>
 __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                   RowNorm norm, int T, int H, int V,
                                                                   float scale, float* __restrict__ part,
-                                                                  float* __restrict__ logits_out, const int32_t* __restrict__ live) {
+                                                                  float* __restrict__ logits_out,
+                                                                  const int32_t* __restrict__ rows,
+                                                                  const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
   extern __shared__ char lds_raw[];
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int groups = (T + WT * TILE - 1) / (WT * TILE);
+  // With a row list the workgroup's 128 "tokens" are entries of the list, and the token groups are counted from
+  // the list's length: the grid is sized for all T rows, and the workgroups left over at its end return at once.
+  const int n_rows = rows ? min(rows[0], T) : T;
+  if (n_rows == 0) return;              // uniform over the workgroup
+  const int groups = (n_rows + WT * TILE - 1) / (WT * TILE);
   const int turn = blockIdx.x / XCDS;
   const int tgroup = (turn / groups) * XCDS + blockIdx.x % XCDS;
   const int n_tasks = (V + 2 * TILE - 1) / (2 * TILE);
   if (tgroup * WW >= n_tasks) return;   // uniform over the workgroup
   const int tok0 = (turn % groups) * WT * TILE;
-  const int nt = min(WT, (T - tok0 + TILE - 1) / TILE);
+  const int nt = min(WT, (n_rows - tok0 + TILE - 1) / TILE);
   const int slot = tgroup * WW + wave, task = min(slot, n_tasks - 1);
   const int ksteps = H / KS;
+  auto row_of = [&](int i) { return rows ? min(max(rows[1 + min(i, n_rows - 1)], 0), T - 1) : min(i, T - 1); };
+  int tok_of[WT];
   float zs[WT];
 #pragma unroll
-  for (int t = 0; t < WT; ++t) zs[t] = row_rinv(norm.ssq, norm.n_ssq, T, min(tok0 + t * TILE + col, T - 1), H, norm.eps) * scale;
-  const E* brow = xn + (int64_t)min(tok0 + (wave % WT) * TILE + col, T - 1) * (NP * KS) + half * G;
+  for (int t = 0; t < WT; ++t) {
+    tok_of[t] = row_of(tok0 + t * TILE + col);
+    zs[t] = row_rinv(norm.ssq, norm.n_ssq, T, tok_of[t], H, norm.eps) * scale;
+  }
+  const E* brow = xn + (int64_t)row_of(tok0 + (wave % WT) * TILE + col) * (NP * KS) + half * G;
   f32x16 acc0[WT], acc1[WT];
   zero_acc<WT>(acc0);
   zero_acc<WT>(acc1);
@@ -246,7 +257,8 @@ __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __rest
                  sb, nt, acc0, acc1);
 #pragma unroll
   for (int t = 0; t < WT; ++t) {
-    const int tok = tok0 + t * TILE + col;
+    const bool listed = tok0 + t * TILE + col < n_rows;
+    const int tok = listed ? tok_of[t] : T;     // T: no row
     float m = -INFINITY, sum = 0.f;
     int best = 0x7fffffff;
     if (t < nt && slot < n_tasks) {
@@ -298,19 +310,19 @@ template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t 
   if (a.T <= TILE) {   // one token tile (trace id 15)
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 1, 15, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 15, 1>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, a.rows, live_word());
     return;
   }
   if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
-        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
+        (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, a.rows, live_word());
     return;
   }
   const int tgroups = lm_head_wide_parts(a.V) / LM_WW;
   const int groups = (a.T + WT * TILE - 1) / (WT * TILE);
   lm_head_wide_kernel<E, WT, 9, LM_WW><<<(tgroups + XCDS - 1) / XCDS * XCDS * groups, LM_WW * WAVE, wide_lds<E, 9, WT>(), st>>>(
-      (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, live_word());
+      (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, a.rows, live_word());
 }
 void launch_lm_head_wide(bool bf16, const LmArgs& a, hipStream_t st) {
   if (bf16) launch_lm_wide_t<bf16_t>(a, st);

@@ -224,6 +224,40 @@ def test_split_sums_match_single_workgroup_sums(case):
     assert err <= (1e-3 if case.cfg.dtype == "bf16" else 1e-4)
 
 
+def test_skip_decided_rows(case):
+    """decode.skip_decided: confidences and candidates of the undecided positions are the same bits as without it
+    (a token's column of the matrix product does not depend on which other tokens share its tile), the decided
+    positions' entries are left as they were, and the decoder commits the same."""
+    from paper_2510_08666_amd import binding
+    g, inp = case.gpu, case.inp
+    g.inject_prefix(case.ora.caches)
+    # every other position decided in every sequence (position 0 stays undecided), whatever the case's own mask
+    full = (1 << case.S) - 1
+    masks = np.array([((int(m) & 0x5555555555555555) | 1) & full for m in inp.mask_bits], dtype=np.uint64)
+    toks = inp.block_tokens.copy()
+    for s in range(case.ns):
+        for i in range(case.S):
+            if (int(masks[s]) >> i) & 1:
+                toks[s, i] = case.cfg.mask_id
+            elif toks[s, i] == case.cfg.mask_id:
+                toks[s, i] = (7 * i + s) % (case.cfg.vocab - 1)
+    g.set_state(toks, masks, inp.prefix_len)
+    a = g.step(case.wl.threshold)
+    g.set_state(toks, masks, inp.prefix_len)
+    g.conf.fill_(-7.0)
+    g.argmax.fill_(-7)
+    dec = binding.Decode(float(case.wl.threshold), 0, 0, 0.0, 1)
+    b = g.step(dec)
+    for s in range(case.ns):
+        for i in range(case.S):
+            if (int(masks[s]) >> i) & 1:
+                assert a["conf"][s, i] == b["conf"][s, i] and a["argmax"][s, i] == b["argmax"][s, i], (s, i)
+            else:
+                assert b["conf"][s, i] == -7.0 and b["argmax"][s, i] == -7, (s, i)
+    for key in ("tokens", "mask", "n_committed"):
+        assert np.array_equal(a[key], b[key]), key
+
+
 def test_empty_mask_commits_nothing(case):
     g, inp = case.gpu, case.inp
     g.inject_prefix(case.ora.caches)
