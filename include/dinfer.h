@@ -118,7 +118,8 @@ int dinfer_set_tensor(dinfer_ctx* ctx, int32_t tensor_id, int32_t layer, const v
                       void* stream);
 
 /* Prompt prefill: a bidirectional forward over each sequence's prompt alone, writing K,V of positions
- * 0..len-1 into the pages of its page-table row.  d_tokens: the prompts back to back (sum of lens);
+ * 0..len-1 into the pages of its page-table row.  (The paper does not describe prefill for a diffusion model; this
+ * is the reading taken here: the prompt attends to itself only, since the blocks after it do not exist yet.)  d_tokens: the prompts back to back (sum of lens);
  * h_lens: [n_seq] on the host; d_page_table: [n_seq][pt_stride] page ids. */
 int dinfer_prefill(dinfer_ctx* ctx, int32_t n_seq, const int32_t* d_tokens, const int32_t* h_lens,
                    const int32_t* d_page_table, int32_t pt_stride, void* stream);
