@@ -48,18 +48,46 @@ def _variant(name):
         "longctx_bf16": W("longctx_bf16", sc(tiny, dtype="bf16", logit_scale=1.0), 4, 32, 60, 1500, threshold=0.9, seed_index=22),
         # no prefix at all: the block attends to itself only
         "noprefix": W("noprefix", tiny, 2, 32, 0, 0, threshold=0.9, seed_index=10),
+        # a skewed router (see _skew_router): three hot experts take most rows, eight more take the rest by the tie
+        # rule, 53 stay empty.  32 tokens (records of the fused permutation, fused down projection over few experts),
+        # 64 tokens, and 288 tokens (work list: the hot experts have up to three row groups, most experts none)
+        "skew": W("skew", sc(tiny, n_heads=2, head_dim=128, n_experts=64, top_k=8, moe_inter=128, vocab=1000),
+                  1, 32, 5, 40, threshold=0.9, seed_index=41),
+        "skew_bf16": W("skew_bf16", sc(tiny, n_heads=2, head_dim=128, n_experts=64, top_k=8, moe_inter=128, vocab=1000,
+                                       dtype="bf16", logit_scale=1.0), 2, 32, 5, 40, threshold=0.9, seed_index=42),
+        "skew_many": W("skew_many", sc(tiny, n_heads=2, head_dim=128, n_experts=64, top_k=8, moe_inter=128, vocab=1000),
+                       9, 32, 5, 300, threshold=0.9, seed_index=43),
     }
     return table[name]
 
 
 CASES = ["c1", "c1_bf16", "ragged", "batch", "batch_bf16", "wide", "wide_bf16", "deep", "deep_bf16", "dense2", "dense2_bf16",
-         "max64", "longctx", "longctx_bf16", "noprefix"]
+         "max64", "longctx", "longctx_bf16", "noprefix", "skew", "skew_bf16", "skew_many"]
+
+HOT_EXPERTS = (5, 23, 40)
+
+
+def _skew_router(cfg, w):
+    """Router weights that send most rows to three experts: the rows of the hot experts are scaled by 16 (exact in
+    either storage type), every other row is zero.  A cold expert's logit is then exactly 0 on both sides, a hot
+    expert's is 16 times its usual value: a token takes the hot experts whose logits are positive and fills its
+    top-k with the lowest-numbered cold experts (ties go to the lower id), so experts 0..7 and the three hot ones
+    receive rows and the other 53 none."""
+    for layer in w["layers"]:
+        r = layer["w_router"]
+        f = di.configs.bf16_to_f32(r) if cfg.dtype == "bf16" else r.astype(np.float32)
+        g = np.zeros_like(f)
+        for e in HOT_EXPERTS:
+            g[e] = f[e] * 16.0
+        layer["w_router"] = di.configs.f32_to_bf16(g) if cfg.dtype == "bf16" else g
 
 
 class Case:
     def __init__(self, name):
         self.wl = _variant(name)
         self.cfg, self.w, self.inp = make_case(self.wl)
+        if name.startswith("skew"):
+            _skew_router(self.cfg, self.w)
         self.ns, self.S = self.inp.block_tokens.shape
         cap = int(self.inp.prefix_len.max()) + 2 * self.S + 16
         self.ora = OracleRun(self.cfg, self.w, self.inp, cap)
@@ -288,6 +316,9 @@ def test_router_and_permutation(case):
     perm = g.ctx.debug_get(5, (T * cfg.top_k,), torch.int32).cpu().numpy()
     c2, o2, p2 = oracle.permutation(idx.reshape(-1), cfg.n_experts)
     assert np.array_equal(cnt, c2) and np.array_equal(off, o2) and np.array_equal(perm, p2)
+    if case.wl.name.startswith("skew"):
+        print("skewed router: rows per expert with rows", {int(e): int(n) for e, n in enumerate(cnt) if n})
+        assert (cnt > 0).sum() <= 8 + len(HOT_EXPERTS) and cnt[list(HOT_EXPERTS)].sum() >= T
     mismatched = 0
     for s in range(case.ns):
         kc, vc = case.ora.caches[s]
