@@ -284,6 +284,13 @@ def test_skip_decided_rows(case):
                 assert b["conf"][s, i] == -7.0 and b["argmax"][s, i] == -7, (s, i)
     for key in ("tokens", "mask", "n_committed"):
         assert np.array_equal(a[key], b[key]), key
+    # nothing undecided at all: the row list is empty, nothing is computed, nothing is committed
+    done = np.where(toks == case.cfg.mask_id, 3, toks)
+    g.set_state(done, np.zeros(case.ns, dtype=np.uint64), inp.prefix_len)
+    g.conf.fill_(-7.0)
+    c = g.step(dec)
+    assert np.array_equal(c["tokens"], done) and not c["mask"].any() and not c["n_committed"].any()
+    assert (c["conf"] == -7.0).all()
 
 
 def test_empty_mask_commits_nothing(case):
