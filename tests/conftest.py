@@ -21,7 +21,8 @@ def pytest_sessionfinish(session, exitstatus):
         return
     if not harness.STATS:
         return
-    worst = harness.dump_stats(os.path.join(ROOT, "gpurun_out", "parity_stats.json"))
+    # DINFER_PARITY_STATS: where to leave the per-test table as JSON (nothing is written without it)
+    worst = harness.dump_stats(os.environ.get("DINFER_PARITY_STATS") or None)
     print("\nparity margins (worst over the session):")
     for k in sorted(worst):
         print("  %-32s %.4g   %s" % (k, worst[k][0], worst[k][1]))

@@ -27,7 +27,7 @@ class Bars:
 
 # Worst margins seen, per test: every routing / K,V / logits / confidence comparison records how much of its bar it
 # used, keyed by the running test.  conftest.py prints the table at the end of the session and writes it to
-# gpurun_out/parity_stats.json, so that the head-room under every bar is visible and not only "passed".
+# the file named by DINFER_PARITY_STATS, so that the head-room under every bar is visible and not only "passed".
 STATS = {}
 
 
@@ -48,7 +48,7 @@ def dump_stats(path=None):
             if not k.endswith("_at") and v > worst.get(k, (-1.0, ""))[0]:
                 worst[k] = (v, test)
     if path:
-        os.makedirs(os.path.dirname(path), exist_ok=True)
+        os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
         with open(path, "w") as f:
             json.dump({"worst": {k: {"value": v, "test": t} for k, (v, t) in worst.items()}, "per_test": STATS}, f,
                       indent=1)
