@@ -863,20 +863,18 @@ __device__ inline float group16_sum(float v) {
   v += dpp_f<DPP_HALF_MIRROR>(v);
   return v + dpp_f<DPP_MIRROR>(v);
 }
-// Largest value of the group and the lowest id that holds it.
-template <int CTRL> __device__ inline void argmax_step(float& bv, int& bi) {
-  const float ov = dpp_f<CTRL>(bv);
-  const int oi = dpp_i<CTRL>(bi);
-  if (ov > bv || (ov == bv && oi < bi)) {
-    bv = ov;
-    bi = oi;
-  }
+__device__ inline int group16_min(int v) {
+  v = min(v, dpp_i<DPP_SWAP1>(v));
+  v = min(v, dpp_i<DPP_SWAP2>(v));
+  v = min(v, dpp_i<DPP_HALF_MIRROR>(v));
+  return min(v, dpp_i<DPP_MIRROR>(v));
 }
+// Largest value of the group and the lowest id that holds it: the largest value first, then the lowest id among
+// the lanes whose own best equals it (two plain butterflies instead of one with a compound comparison).
 __device__ inline void group16_argmax(float& bv, int& bi) {
-  argmax_step<DPP_SWAP1>(bv, bi);
-  argmax_step<DPP_SWAP2>(bv, bi);
-  argmax_step<DPP_HALF_MIRROR>(bv, bi);
-  argmax_step<DPP_MIRROR>(bv, bi);
+  const float mx = group16_max(bv);
+  bi = group16_min(bv == mx ? bi : 0x7fffffff);
+  bv = mx;
 }
 
 // Token->expert permutation of at most 8*64 pairs whose expert ids sit in LDS (s_idx): a stable counting sort.
