@@ -77,15 +77,18 @@ def rocprof_kernel_us(kernel, workload):
     return None
 
 
-def roofline_entry(name, bytes_per_launch, launches, stage_ms, workload, ceilings=None):
+def roofline_entry(name, bytes_per_launch, launches, stage_ms, workload, ceilings=None, every=1):
     """The dominant kernel's roofline object: algorithmic bytes per launch over its average launch duration (HIP
-    events around every launch on the launch stream; the bracket holds the dispatch gap, so it reads a few
-    microseconds more than the kernel itself: kernel_us_rocprof is the kernel's own duration from the committed trace)."""
+    events around its launches on the launch stream, inside the timed region; the bracket holds the dispatch gap, so
+    it reads a few microseconds more than the kernel itself: kernel_us_rocprof is the kernel's own duration from the
+    committed trace).  An event pair also delays the stream by about 2.7 us (32 pairs a step cost the batch-1 step
+    3 %), so the launches of every `every`-th forward of the timed region are bracketed, not all of them."""
     avg_ms = stage_ms / launches
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     r = {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(name, workload),
-         "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches}
+         "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches,
+         "timed_forwards": "every %d%s of the timed region" % (every, {1: "st", 2: "nd", 3: "rd"}.get(every, "th"))}
     us = rocprof_kernel_us(name, workload)
     if us:
         r["kernel_us_rocprof"] = us
@@ -154,6 +157,7 @@ def generation_loop(args):
         generate()
     n_gen = max(1, args.steps // (n_blocks * steps_per_block)) if args.steps >= n_blocks * steps_per_block else 1
     t_pre = t_loop = 0.0
+    ctx.profile_every(args.profile_every)
     ctx.profile_start(binding.STAGE_EXPERT_GATE_UP)
     for _ in range(n_gen):
         a, b = generate()
@@ -164,9 +168,11 @@ def generation_loop(args):
     tot = ctx.debug_get(6, (2,), torch.int32).cpu().numpy()
     touched = float(tot[0]) / max(1, int(tot[1]))
     gate_up_bytes = touched * 2 * cfg.moe_inter * cfg.hidden * 2
-    roofline = roofline_entry("expert_gate_up", gate_up_bytes, launches, stage_ms, wl.name) if launches else None
+    roofline = (roofline_entry("expert_gate_up", gate_up_bytes, launches, stage_ms, wl.name, every=args.profile_every)
+                if launches else None)
     if roofline:
-        roofline["note"] = ("all gate/up launches of the loop (prefill, steps and refreshes); bytes per launch from the "
+        roofline["note"] = ("gate/up launches of the sampled forwards of the loop (prefill, steps and refreshes; 8 steps + 1 "
+                            "refresh per block, so a stride of 8 visits every phase); bytes per launch from the "
                             "experts that received rows, mean over all %d launches: %.2f (a random-init model repeats "
                             "few ids, so most rows of a block are identical and share their experts)" % (int(tot[1]), touched))
 
@@ -296,6 +302,9 @@ def main():
                          "(a block half way through its denoising); 1 = the plain step, 2 = with decode.skip_decided, "
                          "which leaves the decided rows out of the LM head")
     ap.add_argument("--profile-stage", type=int, default=3, help="stage timed with HIP events (3 = expert gate/up)")
+    ap.add_argument("--profile-every", type=int, default=8,
+                    help="the stage's launches are bracketed by events in every n-th forward of the timed region "
+                         "(a pair costs the stream about 2.7 us; 1 = every forward)")
     ap.add_argument("--block-loop", type=int, default=0,
                     help="time dinfer_generate_block over the workload's block with threshold decoding at a threshold "
                          "inside the confidence distribution (several commits per step, a data-dependent number of steps): "
@@ -415,6 +424,7 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    ctx.profile_every(args.profile_every)
     ctx.profile_start(args.profile_stage)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t1 = time.perf_counter()
@@ -449,7 +459,7 @@ def main():
         name = stage_names[args.profile_stage]
         per_launch_calls = cfg.n_layers if name != "lm_head" else 1
         roofline = roofline_entry(name, stages[name] / per_launch_calls, launches, stage_ms, wl.name,
-                                  {"8GB_sweep": ceiling_big, "400MB_launch": ceiling_launch})
+                                  {"8GB_sweep": ceiling_big, "400MB_launch": ceiling_launch}, every=args.profile_every)
 
     cpu = None
     if not args.no_cpu_baseline:

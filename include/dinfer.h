@@ -321,7 +321,10 @@ int dinfer_debug_single_slice(int32_t on);
 /* Per-launch timing of one stage of the forward, for benchmarks: between dinfer_profile_start and
  * dinfer_profile_stop every launch of that stage is bracketed by a HIP event pair on the caller's stream
  * (at most 8192 launches are recorded).  _stop waits for the recorded events and returns their count and
- * the summed elapsed milliseconds. */
+ * the summed elapsed milliseconds.  An event pair costs the stream a few microseconds around the launch it
+ * brackets, so a benchmark that times whole steps as well samples: dinfer_profile_every(ctx, n), called before
+ * _start, makes the profile bracket the launches of every n-th forward only (n >= 1; 1, the default, is every
+ * forward; the setting stays until it is changed). */
 enum {
   DINFER_STAGE_QKV = 0,
   DINFER_STAGE_ATTENTION = 1,
@@ -332,6 +335,7 @@ enum {
   DINFER_STAGE_ROUTER = 6,   /* RMSNorm statistics + router + top-k + permutation */
   DINFER_STAGE_COUNT = 7
 };
+int dinfer_profile_every(dinfer_ctx* ctx, int32_t n_forwards);
 int dinfer_profile_start(dinfer_ctx* ctx, int32_t stage);
 int dinfer_profile_stop(dinfer_ctx* ctx, int32_t* n_launches, float* total_ms);
 

@@ -25,7 +25,7 @@ EXPORTS = ["dinfer_weights_bytes", "dinfer_kv_bytes", "dinfer_workspace_bytes", 
            "dinfer_last_error", "dinfer_set_tensor", "dinfer_prefill", "dinfer_step", "dinfer_step_vicinity", "dinfer_step_credit", "dinfer_step_smooth", "dinfer_step_smooth_static", "dinfer_smooth_scratch_bytes",
            "dinfer_refresh_block", "dinfer_commit", "dinfer_generate",
            "dinfer_generate_block", "dinfer_kv_write", "dinfer_kv_read", "dinfer_debug_logits", "dinfer_debug_get",
-           "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace",
+           "dinfer_profile_every", "dinfer_profile_start", "dinfer_profile_stop", "dinfer_stream_read", "dinfer_debug_trace",
            "dinfer_debug_single_slice", "dinfer_generate_block_smooth"]
 (STAGE_QKV, STAGE_ATTENTION, STAGE_OPROJ, STAGE_EXPERT_GATE_UP, STAGE_EXPERT_DOWN, STAGE_LM_HEAD,
  STAGE_ROUTER) = range(7)
@@ -141,6 +141,8 @@ def _load():
     L.dinfer_debug_single_slice.argtypes = [c_i32]
     L.dinfer_debug_get.restype = c_i32
     L.dinfer_debug_get.argtypes = [c_vp, c_i32, c_vp, c_sz, c_vp]
+    L.dinfer_profile_every.restype = c_i32
+    L.dinfer_profile_every.argtypes = [c_vp, c_i32]
     L.dinfer_profile_start.restype = c_i32
     L.dinfer_profile_start.argtypes = [c_vp, c_i32]
     L.dinfer_profile_stop.restype = c_i32
@@ -376,6 +378,9 @@ class Context:
         out = torch.empty((n_rows, self.cfg.vocab), dtype=torch.float32, device=self.device)
         _check(lib.dinfer_debug_logits(self.h, n_rows, _ptr(out), _stream()))
         return out
+
+    def profile_every(self, n_forwards):
+        _check(lib.dinfer_profile_every(self.h, n_forwards))
 
     def profile_start(self, stage):
         _check(lib.dinfer_profile_start(self.h, stage))

@@ -234,6 +234,9 @@ struct dinfer_ctx {
   // optional per-launch timing of one stage (dinfer_profile_start / _stop)
   int prof_stage;
   size_t prof_n;
+  int prof_every;      // launches of every prof_every-th forward are bracketed
+  int64_t prof_fwd;    // forwards since dinfer_profile_start
+  bool prof_sampled;   // the current forward is one of them
   std::vector<hipEvent_t> prof_ev;   // start/stop pairs
 };
 
@@ -263,7 +266,7 @@ struct StageTimer {
   hipStream_t st;
   bool on;
   StageTimer(dinfer_ctx* c_, int stage, hipStream_t st_) : c(c_), st(st_), on(false) {
-    if (c->prof_stage == stage && c->prof_n < PROF_MAX_LAUNCHES) {
+    if (c->prof_stage == stage && c->prof_sampled && c->prof_n < PROF_MAX_LAUNCHES) {
       on = true;
       (void)hipEventRecord(c->prof_ev[2 * c->prof_n], st);
     }
@@ -286,6 +289,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   const int H = f.hidden, D = f.n_heads * f.head_dim;
   char* ws = c->ws;
   const Workspace& w = c->wsm;
+  if (c->prof_stage >= 0) c->prof_sampled = c->prof_fwd++ % c->prof_every == 0;
   int n_qtiles = 0;
   for (int s = 0; s < span.n_seq; ++s) n_qtiles += (span.off[s + 1] - span.off[s] + TILE - 1) / TILE;
   FwdMeta meta{at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
@@ -479,6 +483,9 @@ int dinfer_create(const dinfer_config* cfg, void* d_weights, size_t weights_byte
   }
   c->prof_stage = -1;
   c->prof_n = 0;
+  c->prof_every = 1;
+  c->prof_fwd = 0;
+  c->prof_sampled = true;
   c->h_mask_pinned = nullptr;
   if (hipHostMalloc((void**)&c->h_mask_pinned, MAX_SEQS * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
     delete c;
@@ -974,6 +981,13 @@ int dinfer_stream_read(const void* d_buf, size_t bytes, float* d_sink, void* str
   return DINFER_OK;
 }
 
+int dinfer_profile_every(dinfer_ctx* c, int32_t n_forwards) {
+  if (!c) return fail(DINFER_EINVAL, "context is null");
+  if (n_forwards < 1) return fail(DINFER_EINVAL, "profile every %d forwards", n_forwards);
+  c->prof_every = n_forwards;
+  return DINFER_OK;
+}
+
 int dinfer_profile_start(dinfer_ctx* c, int32_t stage) {
   if (!c) return fail(DINFER_EINVAL, "context is null");
   if (stage < 0 || stage >= DINFER_STAGE_COUNT) return fail(DINFER_EINVAL, "stage %d", stage);
@@ -984,6 +998,7 @@ int dinfer_profile_start(dinfer_ctx* c, int32_t stage) {
   }
   c->prof_stage = stage;
   c->prof_n = 0;
+  c->prof_fwd = 0;
   // the running totals of experts with rows (dinfer_debug_get 6) start over with the profile
   HIP_TRY(hipMemset(at<int32_t>(c->ws, c->wsm.off) + STAT_ACTIVE_SUM, 0, 2 * sizeof(int32_t)));
   return DINFER_OK;
