@@ -295,8 +295,6 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
   FwdMeta meta{at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
                at<int32_t>(ws, w.qtile)};
   const int limit = f.max_pos < pt_stride * PAGE ? f.max_pos : pt_stride * PAGE;
-  launch_meta(span, d_base, limit, at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos), at<int32_t>(ws, w.seq_nkeys),
-              at<int32_t>(ws, w.qtile), st);
   float* x = at<float>(ws, w.x);
   float* ssq_a = at<float>(ws, w.ssq_a);
   float* rinv_f = at<float>(ws, w.rinv_f);
@@ -319,7 +317,8 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     int32_t* tickets = at<int32_t>(ws, w.tickets);
     if (l == 0)
       launch_embed(bf, d_tokens, c->weights + c->wm.emb, T, H, f.vocab, x, ssq_a, at<float>(c->weights, lw.attn_gain),
-                   xn, smooth, st);
+                   xn, smooth, span, d_base, limit, at<int32_t>(ws, w.tok_seq), at<int32_t>(ws, w.tok_pos),
+                   at<int32_t>(ws, w.seq_nkeys), at<int32_t>(ws, w.qtile), st);
     else if (!fused_down)
       launch_combine(bf, x, at<float>(ws, w.o), topk_w - (size_t)T * f.top_k, f.top_k, T, H, ssq_a,
                      at<float>(c->weights, lw.attn_gain), xn, st);

@@ -35,8 +35,6 @@ struct FwdMeta {            // device arrays describing the tokens of one forwar
 };
 
 void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim, float theta, hipStream_t st);
-void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
-                 int32_t* seq_nkeys, int32_t* qtile, hipStream_t st);
 // Normalised-input planes: whoever produces a residual row x[t] also stores x[t] * gain (gain of the RMSNorm
 // that follows; the row's 1/rms factor is NOT applied) as a k-major activation matrix [T][H] (act_index in
 // common.hpp).  The consumers feed it to the matrix cores and apply 1/rms in their epilogues.
@@ -50,6 +48,9 @@ struct RowNorm {
 // x[t] = emb[token[t]];  ssq[t] = sum(x[t]^2);  xn[t] = planes of x[t] * gain
 // Iteration smoothing: a position that is still masked (bit of its sequence's mask, uniform blocks of block_len
 // tokens) is embedded as emb[token] + alpha * delta[t].  Pass null for a plain embedding.
+// The launch also writes the forward's token bookkeeping (FwdMeta's arrays) from `span` and the sequences' first
+// positions d_base (device, or null for 0): `limit` = positions a sequence may use (rotary table and page-table
+// row); a first position that would leave it is pulled back so that no later kernel indexes outside its buffers.
 struct SmoothIn {
   const float* delta;       // [T][H]
   float alpha;
@@ -57,7 +58,9 @@ struct SmoothIn {
   int block_len;
 };
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int H, int V, float* x,
-                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st);
+                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, const SeqSpan& span,
+                  const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos, int32_t* seq_nkeys,
+                  int32_t* qtile, hipStream_t st);
 // x[t] += sum_j topk_w[t][j] * O[t*k+j];  ssq[t] and xn[t] as above, of the updated row
 void launch_combine(bool bf16, float* x, const float* O, const float* topk_w, int top_k,
                     int T, int H, float* ssq, const float* gain, void* xn, hipStream_t st);

@@ -33,10 +33,10 @@ void launch_rope_table(float* cos_tab, float* sin_tab, int max_pos, int head_dim
 // ---------------------------------------------------------------- token bookkeeping
 // `limit` = positions a sequence may use (rotary table and page-table row); a prefix length that would
 // leave it is pulled back so that no later kernel indexes outside its buffers.
-__global__ void meta_kernel(SeqSpan span, const int32_t* __restrict__ d_base, int limit, int32_t* __restrict__ tok_seq,
-                            int32_t* __restrict__ tok_pos, int32_t* __restrict__ seq_nkeys,
-                            int32_t* __restrict__ qtile, const int32_t* __restrict__ live) {
-  if (step_is_dead(live)) return;
+// Runs in one workgroup (the extra one of the embedding launch).
+__device__ inline void token_meta(const SeqSpan& span, const int32_t* __restrict__ d_base, int limit,
+                                  int32_t* __restrict__ tok_seq, int32_t* __restrict__ tok_pos,
+                                  int32_t* __restrict__ seq_nkeys, int32_t* __restrict__ qtile) {
   for (int s = 0; s < span.n_seq; ++s) {
     const int o = span.off[s], len = span.off[s + 1] - o;
     const int base = d_base ? max(0, min(d_base[s], limit - len)) : 0;
@@ -59,10 +59,6 @@ __global__ void meta_kernel(SeqSpan span, const int32_t* __restrict__ d_base, in
     }
   }
 }
-void launch_meta(SeqSpan span, const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos,
-                 int32_t* seq_nkeys, int32_t* qtile, hipStream_t st) {
-  meta_kernel<<<1, 256, 0, st>>>(span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile, live_word());
-}
 
 // ---------------------------------------------------------------- RMSNorm helpers
 constexpr int NORM_THREADS = 256;
@@ -78,15 +74,24 @@ __device__ inline float block_sum_256(float v, float* sh) {
   return r;
 }
 
-// x[t] = emb[token[t]];  ssq[t] = sum(x[t]^2);  xn[t] = planes of x[t] * gain
+// x[t] = emb[token[t]];  ssq[t] = sum(x[t]^2);  xn[t] = planes of x[t] * gain.  Workgroup T, one past the tokens,
+// writes the token bookkeeping of the forward instead (nothing here reads it): one launch less per forward.
 template <typename E>
 __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __restrict__ tokens, const E* __restrict__ emb,
                                                              int H, int V, float* __restrict__ x,
                                                              float* __restrict__ ssq, const float* __restrict__ gain,
-                                                             E* __restrict__ xn, int T, SmoothIn sm, const int32_t* __restrict__ live) {
+                                                             E* __restrict__ xn, int T, SmoothIn sm, SeqSpan span,
+                                                             const int32_t* __restrict__ d_base, int limit,
+                                                             int32_t* __restrict__ tok_seq, int32_t* __restrict__ tok_pos,
+                                                             int32_t* __restrict__ seq_nkeys, int32_t* __restrict__ qtile,
+                                                             const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   __shared__ float sh[4];
   const int t = blockIdx.x;
+  if (t == T) {
+    token_meta(span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile);
+    return;
+  }
   const E* row = emb + (int64_t)min(max(tokens[t], 0), V - 1) * H;
   // iteration smoothing: a still-masked position adds alpha times what the previous iteration retained for it
   const bool smooth = sm.delta && ((sm.mask[t / sm.block_len] >> (t % sm.block_len)) & 1ull);
@@ -102,12 +107,16 @@ __global__ __launch_bounds__(NORM_THREADS) void embed_kernel(const int32_t* __re
   if (threadIdx.x == 0) ssq[t] = ss;
 }
 void launch_embed(bool bf16, const int32_t* tokens, const void* emb, int T, int H, int V, float* x,
-                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, hipStream_t st) {
+                  float* ssq, const float* gain, void* xn, const SmoothIn* smooth, const SeqSpan& span,
+                  const int32_t* d_base, int limit, int32_t* tok_seq, int32_t* tok_pos, int32_t* seq_nkeys,
+                  int32_t* qtile, hipStream_t st) {
   const SmoothIn sm = smooth ? *smooth : SmoothIn{nullptr, 0.f, nullptr, 1};
   if (bf16)
-    embed_kernel<bf16_t><<<T, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, H, V, x, ssq, gain, (bf16_t*)xn, T, sm, live_word());
+    embed_kernel<bf16_t><<<T + 1, NORM_THREADS, 0, st>>>(tokens, (const bf16_t*)emb, H, V, x, ssq, gain, (bf16_t*)xn, T, sm,
+                                                         span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile, live_word());
   else
-    embed_kernel<float><<<T, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, H, V, x, ssq, gain, (float*)xn, T, sm, live_word());
+    embed_kernel<float><<<T + 1, NORM_THREADS, 0, st>>>(tokens, (const float*)emb, H, V, x, ssq, gain, (float*)xn, T, sm,
+                                                        span, d_base, limit, tok_seq, tok_pos, seq_nkeys, qtile, live_word());
 }
 
 // ---------------------------------------------------------------- iteration smoothing: probabilities
