@@ -136,12 +136,14 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
         r.v[s2][t] = PvStep<E>::v_vec(kv_layer + kv_v_index(geom, page, head, 0, t * TILE + col), half, s2);
     }
   };
-  TileRegs cur, nxt;
-  if (kt0 < n_ktiles) load_tile(kt0, cur);
-  for (int kt = kt0; kt < n_ktiles; kt += stride) {
-    // the next tile's loads are issued before this tile is used (clamped, so the loop body has no branch
-    // around loads and the compiler can count them; the last iteration re-reads its own tile)
-    load_tile(min(kt + stride, n_ktiles - 1), nxt);
+  // Softmax statistics live in the log2 domain (scores times scale * log2(e), one fused multiply-add in front of
+  // the exponential).  A lane's reference maximum m_run moves only when a tile's maximum passes it by more than
+  // REF_SLACK: probabilities are then bounded by 2^REF_SLACK instead of 1, which float32 sums and the bf16
+  // hi + lo planes hold just as well, and the 64 output registers are rescaled only in the rare tile where some
+  // lane's reference moves (a wave-uniform branch), not in every tile.
+  constexpr float REF_SLACK = 6.f;
+  const float c2 = scale * 1.44269504088896341f;
+  auto use_tile = [&](TileRegs& cur, int kt) {
     // ---- S^T = K . Q^T  (the compiler barrier keeps the query reads inside the loop: hoisted, they would
     // occupy the 64 registers that staging them in LDS is meant to free)
     asm volatile("" ::: "memory");
@@ -163,49 +165,69 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
         mfma32(sacc, cur.k[f / NP], b);
       }
     }
-    float p[16];
-    float mx = -INFINITY;
+    if ((kt + 1) * TILE > n_keys) {
+      // the sequence's last, ragged tile (wave-uniform, at most once per wave; the empty asm keeps it a branch):
+      // scores of slots past the last key become -inf, and their V entries, which may hold anything (NaN * 0
+      // would poison the sum), become 0
+      asm volatile("" ::: "memory");
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const bool ok = kt * TILE + acc_row(v, half) < n_keys;
-      p[v] = ok ? sacc[v] * scale : -INFINITY;
-      mx = fmaxf(mx, p[v]);
+      for (int v = 0; v < 16; ++v)
+        if (kt * TILE + acc_row(v, half) >= n_keys) sacc[v] = -INFINITY;
+#pragma unroll
+      for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2)
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+          for (int i = 0; i < G; ++i)
+            if (kt * TILE + PvStep<E>::key_of(s2, half, i) >= n_keys) cur.v[s2][t][i] = (E)0.f;
     }
+    float mx = sacc[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));      // the other half-wave holds the column's other 16 keys
-    const float m_new = fmaxf(m_run, mx);           // finite: a key tile always holds at least one valid key
-    const float alpha = __expf(m_run - m_new);
+    const float mt = mx * c2;                       // finite: a key tile always holds at least one valid key
+    const bool moves = mt > m_run + REF_SLACK;      // (m_run = -inf before the wave's first tile)
+    if (__builtin_amdgcn_ballot_w64(moves)) {
+      const float m_new = moves ? mt : m_run;
+      const float alpha = moves ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] *= alpha;
+    }
+    float p[16];
     float psum = 0.f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      p[v] = __expf(p[v] - m_new);
+      p[v] = __builtin_amdgcn_exp2f(fmaf(sacc[v], c2, -m_run));
       psum += p[v];
     }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[t][v] *= alpha;
+    l_run += psum;
     // ---- O^T += V^T . P^T
-    const bool last = (kt + 1) * TILE > n_keys;
 #pragma unroll
     for (int s2 = 0; s2 < PvStep<E>::STEPS; ++s2) {
       vec pv[NP];
 #pragma unroll
       for (int pl = 0; pl < NP; ++pl) pv[pl] = PvStep<E>::p_vec(p, s2, pl);
 #pragma unroll
-      for (int t = 0; t < DT; ++t) {
-        vec vv = cur.v[s2][t];
-        if (last) {   // slots past the last key may hold anything (NaN * 0 would poison the sum)
+      for (int t = 0; t < DT; ++t)
 #pragma unroll
-          for (int i = 0; i < G; ++i)
-            if (kt * TILE + PvStep<E>::key_of(s2, half, i) >= n_keys) vv[i] = (E)0.f;
-        }
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl) mfma32(o[t], vv, pv[pl]);
-      }
+        for (int pl = 0; pl < NP; ++pl) mfma32(o[t], cur.v[s2][t], pv[pl]);
     }
-    cur = nxt;
+  };
+  // Two tile buffers that swap roles (the loop is unrolled by two, so no registers are copied): the next tile's
+  // loads are issued before this tile is used, clamped, so that no branch surrounds loads and the compiler can
+  // count them; a wave's last turn re-reads its own tile.
+  TileRegs ta, tb;
+  if (kt0 < n_ktiles) load_tile(kt0, ta);
+  for (int kt = kt0; kt < n_ktiles; kt += 2 * stride) {
+    load_tile(min(kt + stride, n_ktiles - 1), tb);
+    use_tile(ta, kt);
+    if (kt + stride >= n_ktiles) break;
+    load_tile(min(kt + 2 * stride, n_ktiles - 1), ta);
+    use_tile(tb, kt + stride);
   }
   TRACE_MARK(7, 2);
   // ---- fold the waves through LDS (lane-major, conflict free): every wave leaves its state, then wave w
@@ -235,7 +257,7 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
   for (int w = 0; w < ATTN_WAVES; ++w) {
     const float* pb = lds + w * PW + lane;
     const float mw = pb[(DT * 16) * WAVE];
-    const float sw = mw > -INFINITY ? __expf(mw - M) : 0.f;   // a wave that saw no key tile contributes nothing
+    const float sw = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - M) : 0.f;   // a wave that saw no key tile contributes nothing
     L += sw * pb[(DT * 16 + 1) * WAVE];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) r[i] += sw * pb[(wave * RPW + i) * WAVE];
@@ -297,7 +319,7 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
 #pragma unroll
     for (int p = 0; p < ATTN_MAX_SPLITS; ++p) {
       if (p < my_splits && mp[p] > -INFINITY) {   // (a split whose waves saw no key tile contributes nothing)
-        const float w = __expf(mp[p] - Mx);
+        const float w = __builtin_amdgcn_exp2f(mp[p] - Mx);
         Ls += w * lp[p];
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[i] += w * op[p][i];
