@@ -426,10 +426,22 @@ int gemm_slices(bool bf16, int K, int T) {
   return ksteps % burst == 0 ? ksteps / burst : 1;
 }
 
+// Slices a launch uses of those gemm_slices() allows (the workspace is sized for the latter): a hand-off among
+// fewer workgroups is cheaper, so a projection with many tasks takes only as many slices as bring the launch to
+// about half a workgroup per compute unit (measured at 32 tokens, K = 2048: the QKV projection, 96 tasks, 12.3 us
+// with 2 slices against 13.1 with 4 and 14.9 with 1; the output projection, 32 tasks, 8.1 us with 4 slices, 10.0
+// with 2, 13.4 with 1).
+static int ksplit_slices(bool bf16, int K, int T, int n_tasks) {
+  const int most = gemm_slices(bf16, K, T);
+  int s = 1;
+  while (s < most && s * n_tasks < 128) s *= 2;
+  return most % s == 0 ? s : most;
+}
+
 template <typename E, class Epi>
 static void launch_ksplit(bool bf16, const E* W, int ksteps, const E* B, int T, int K, int n_tasks,
                           float* part, int32_t* tickets, const Epi& epi, hipStream_t st, int forced_slices = 0) {
-  const int slices = forced_slices ? forced_slices : single_slice() ? 1 : gemm_slices(bf16, K, T);
+  const int slices = forced_slices ? forced_slices : single_slice() ? 1 : ksplit_slices(bf16, K, T, n_tasks);
   if (T <= 32) {
     gemm_ksplit_kernel<E, 1, 4, Epi><<<dim3(slices, n_tasks, 1), 4 * WAVE, ksplit_lds<1, 4>(), st>>>(W, ksteps, B, T, K, part, tickets, epi, live_word());
   } else if (T <= 64) {

@@ -48,7 +48,7 @@ __device__ inline bool expert_item(const int32_t* __restrict__ cnt, const int32_
 }
 
 template <typename E, int WT, int WW, int KID, bool RECORDS>
-__global__ __launch_bounds__(WW * WAVE) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
+__global__ __launch_bounds__(WW * WAVE) __attribute__((amdgpu_waves_per_eu(2))) void expert_gemm1_wide_kernel(const E* __restrict__ W, const E* __restrict__ xn,
                                                                       const float* __restrict__ rinv, E* __restrict__ Y,
                                                                       const int32_t* __restrict__ cnt,
                                                                       const int32_t* __restrict__ off,
