@@ -684,7 +684,7 @@ __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kern
                                                                                   int n_tasks, Epi epi, const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
-  extern __shared__ char lds_raw[];
+  extern __shared__ __align__(16) char lds_raw[];   // 16-byte aligned: staged fragments move as 128-bit LDS accesses
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N, PER = 4;
   constexpr int KID = Epi::ROWSUM ? 13 : 12;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(WW * WAVE) __attribute__((amdgpu_waves_per_eu(2))) 
                                                                       int top_k, const float* __restrict__ topk_w, const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
-  extern __shared__ char lds_raw[];
+  extern __shared__ __align__(16) char lds_raw[];   // 16-byte aligned: staged fragments move as 128-bit LDS accesses
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
   ExpertItem it;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(WW * WAVE) __attribute__((amdgpu_waves_per_eu(2))) 
 }
 
 template <typename E, int WT, int WW, int KID, bool RECORDS>
-__global__ __launch_bounds__(WW * WAVE) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
+__global__ __launch_bounds__(WW * WAVE) __attribute__((amdgpu_waves_per_eu(2))) void expert_gemm2_wide_kernel(const E* __restrict__ W, const E* __restrict__ Y,
                                                                       float* __restrict__ O, const int32_t* __restrict__ cnt,
                                                                       const int32_t* __restrict__ off,
                                                                       const int32_t* __restrict__ perm,
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(WW * WAVE) void expert_gemm2_wide_kernel(const E* _
                                                                       int I, const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
-  extern __shared__ char lds_raw[];
+  extern __shared__ __align__(16) char lds_raw[];   // 16-byte aligned: staged fragments move as 128-bit LDS accesses
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
   ExpertItem it;
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(WW * WAVE) void lm_head_wide_kernel(const E* __rest
                                                                   const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
   typedef typename ET<E>::vec vec;
-  extern __shared__ char lds_raw[];
+  extern __shared__ __align__(16) char lds_raw[];   // 16-byte aligned: staged fragments move as 128-bit LDS accesses
   vec* sb = reinterpret_cast<vec*>(lds_raw);
   constexpr int G = ET<E>::G, KS = ET<E>::KS, NP = Planes<E>::N;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
