@@ -141,8 +141,16 @@ __device__ inline void wide_stream_nt(const E* __restrict__ wp, int n_chunks, BR
   };
   // Whole rounds of WPRE chunks run without a test between the chunks: a branch there gives the compiler a path from
   // one chunk straight back to the loop top, for which it drains every load in flight at each iteration.
+  // The first round stands in front of the loop: the prologue leaves the loads in another order than a round does
+  // (all weights first, then the fragments), and the wait counts the compiler puts at the loop top are the smaller
+  // of what its two ways in allow -- entered straight from the prologue, every chunk waited until all but four of
+  // the loads in flight had returned, the weights requested one chunk earlier included, and a wave had one chunk
+  // of weights under way instead of WPRE.
   int c0 = 0;
-  for (; c0 + WPRE <= n_chunks; c0 += WPRE) static_for<WPRE>([&](auto I) { chunk(I, c0 + decltype(I)::value); });
+  if (n_chunks >= WPRE) {
+    static_for<WPRE>([&](auto I) { chunk(I, decltype(I)::value); });
+    for (c0 = WPRE; c0 + WPRE <= n_chunks; c0 += WPRE) static_for<WPRE>([&](auto I) { chunk(I, c0 + decltype(I)::value); });
+  }
   static_for<WPRE - 1>([&](auto I) {
     if (c0 + decltype(I)::value < n_chunks) chunk(I, c0 + decltype(I)::value);   // uniform over the workgroup
   });
