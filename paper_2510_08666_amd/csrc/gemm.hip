@@ -580,7 +580,7 @@ __global__ __launch_bounds__(KW * WAVE) void expert_down_fused_kernel(const E* _
 #pragma unroll
       for (int i = 0; i < PF; ++i) issue_y(i, yoff, ystep);
     }
-    for (int g = g0; g + 1 < g1; ++g) {
+    auto group = [&](int g) {
       if (g == g0 + 1) TRACE_MARK(5, 5);
       if (g == g0 + 2) TRACE_MARK(5, 6);
       if (g == g0 + 4) TRACE_MARK(5, 7);
@@ -601,6 +601,13 @@ __global__ __launch_bounds__(KW * WAVE) void expert_down_fused_kernel(const E* _
         issue_y(i, yn, ynstep);
         __builtin_amdgcn_sched_barrier(0);
       }
+    };
+    // The first group stands in front of the loop: it meets the loads in the prologue's order (all weights, then
+    // all rows), the later ones in the order the groups leave them (slot by slot), and wait counts at the top of a
+    // loop that is entered both ways are the smaller of the two: slot 0 then waited for half the group in flight.
+    if (g0 + 1 < g1) {
+      group(g0);
+      for (int g = g0 + 1; g + 1 < g1; ++g) group(g);
     }
 #pragma unroll
     for (int i = 0; i < PF; ++i) use(i);
