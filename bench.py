@@ -502,7 +502,7 @@ def main():
         "committed_per_step": committed,
         "step_algorithmic_GB": round(total_bytes / 1e9, 3),
         "step_hbm_frac": round(total_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
-        "experts_touched_per_layer": round(float(np.mean(touched)), 2),
+        "experts_touched_per_layer": round(float(np.mean(touched)), 2), "experts_touched_by_layer": touched,
         "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))

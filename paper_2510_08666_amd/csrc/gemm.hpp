@@ -70,7 +70,7 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
   for (int i = 0; i < PF; ++i)
 #pragma unroll
     for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + i);
-  for (int s = 0; s + PF < n; s += PF) {
+  auto burst = [&](int s) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
 #pragma unroll
@@ -89,6 +89,13 @@ __device__ inline void stream_steps(const E* __restrict__ wp, Loader& ld, int ks
 #pragma unroll
       for (int t = 0; t < TT; ++t) raw[i][t] = ld.issue(t, ks0 + nx);
     }
+  };
+  // The first burst stands in front of the loop: it meets the loads in the prologue's order (all weights, then all
+  // activation fragments), the later ones slot by slot, and the wait counts at the top of a loop entered both ways
+  // are the smaller of the two.
+  if (PF < n) {
+    burst(0);
+    for (int s = PF; s + PF < n; s += PF) burst(s);
   }
 #pragma unroll
   for (int i = 0; i < PF; ++i)
