@@ -17,6 +17,11 @@ constexpr int WT = 4;      // token tiles per workgroup above 64 tokens
 // GEMMs, 131 to 134 against 120 microseconds; four waves in the LM head, 450 against 352.)
 constexpr int EXPERT_WW = 8, EXPERT_PRE = 2;
 constexpr int LM_WW = 8, LM_PRE = 2;
+// Tasks per workgroup of the LM head up to 32 tokens.  All workgroups of these launches are resident at once and
+// the dispatcher deals them evenly, so a launch lasts as long as the compute units with one workgroup more than the
+// others: 614 workgroups of four tasks put 3 MB on some units and 2 MB on others (112 us), 1228 of two tasks 2.5 or
+// 2 MB (108 us).
+constexpr int LM_SMALL_WW = 2;
 constexpr int XCDS = 8;      // accelerator dies, each with its own L2; workgroup i of a launch runs on die i % 8
 
 __device__ inline float silu_w(float x) { return x / (1.f + __expf(-x)); }
@@ -160,12 +165,17 @@ __global__ __launch_bounds__(WW * WAVE) __attribute__((amdgpu_waves_per_eu(2))) 
 // 100.5 + 55.2.  Four or six weight chunks in flight per wave instead of two: 71.9 + 39.4 at 32 tokens, 90.8 + 53.0
 // at 64.)
 constexpr int SMALL_WW = 2;
+// The gate/up projection of up to 32 tokens takes one task per workgroup: with 49 to 56 experts touched, 16
+// two-task workgroups per expert are 3.1 to 3.5 per compute unit, so some units carry four (2 MB) and the launch
+// lasts as long as those; 32 one-task workgroups per expert put 1.75 MB on the fullest unit (78 -> 70 us for such
+// layers, 69.1 -> 65.7 us on average at batch 1, though every workgroup now stages the activation rows for itself).
+constexpr int GU1_WW = 1;
 
 template <typename E> static void launch_gate_up_wide_t(const ExpertArgs& a, hipStream_t st) {
   const int n_tasks = a.I / TILE;
   const E *w = (const E*)a.w_gate_up, *xn = (const E*)a.xn;
   if (a.T <= TILE) {
-    expert_gemm1_wide_kernel<E, 1, SMALL_WW, 16, true><<<dim3((n_tasks + SMALL_WW - 1) / SMALL_WW, a.E), SMALL_WW * WAVE,
+    expert_gemm1_wide_kernel<E, 1, GU1_WW, 16, true><<<dim3((n_tasks + GU1_WW - 1) / GU1_WW, a.E), GU1_WW * WAVE,
                                                          wide_lds<E, 16, 1>(), st>>>(
         w, xn, a.rinv, (E*)a.y, a.cnt, a.off, a.perm, a.work, a.T, a.H, a.I, a.top_k, a.topk_w, live_word());
   } else if (a.T <= 2 * TILE) {
@@ -308,12 +318,12 @@ int lm_head_wide_parts(int V) { return ((V + 63) / 64 + LM_WW - 1) / LM_WW * LM_
 // otherwise take every lane's own activation row one by one.  More tokens: four tiles, high plane only (id 9).
 template <typename E> static void launch_lm_wide_t(const LmArgs& a, hipStream_t st) {
   if (a.T <= TILE) {   // one token tile (trace id 15)
-    const int tgroups = lm_head_wide_parts(a.V) / 4;
-    lm_head_wide_kernel<E, 1, 15, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 15, 1>(), st>>>(
+    const int tgroups = lm_head_wide_parts(a.V) / LM_SMALL_WW;
+    lm_head_wide_kernel<E, 1, 15, LM_SMALL_WW><<<(tgroups + XCDS - 1) / XCDS * XCDS, LM_SMALL_WW * WAVE, wide_lds<E, 15, 1>(), st>>>(
         (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, a.rows, live_word());
     return;
   }
-  if (a.T <= 2 * TILE) {   // four tasks per workgroup: 614 work units spread more evenly over 256 compute units than 307
+  if (a.T <= 2 * TILE) {   // four tasks per workgroup (two: 144 against 119 us, the activation fragments of 64 rows are shared by too few)
     const int tgroups = lm_head_wide_parts(a.V) / 4;
     lm_head_wide_kernel<E, 2, 14, 4><<<(tgroups + XCDS - 1) / XCDS * XCDS, 4 * WAVE, wide_lds<E, 14, 2>(), st>>>(
         (const E*)a.w, (const E*)a.xn, a.norm, a.T, a.H, a.V, a.scale, a.part, a.logits_out, a.rows, live_word());
