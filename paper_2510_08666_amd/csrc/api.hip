@@ -333,7 +333,7 @@ int forward(dinfer_ctx* c, const SeqSpan& span, const int32_t* d_tokens, const i
     }
     AttnArgs aa{ws + w.q, q_plane, kv_layer, c->geom, meta, d_page_table, pt_stride, n_qtiles,
                 single_slice() ? 1 : attn_splits(n_qtiles, f.n_heads, limit), at<float>(ws, w.attn_part), at<int32_t>(ws, w.attn_tickets),
-                ws + w.a, T};
+                ws + w.a, T, oproj_prefetch_plan(bf, c->weights + lw.wo, D, H, T)};
     {
       StageTimer tm(c, DINFER_STAGE_ATTENTION, st);
       launch_attention(bf, aa, st);

@@ -18,6 +18,7 @@
 namespace dinfer {
 
 constexpr int ATTN_WAVES = 8;
+constexpr int ATTN_FETCH_MAX_OWN = 64;   // launches with at most this many workgroups of their own also fetch AttnArgs::pf
 
 size_t attn_part_floats(int n_qtiles, int n_heads, int n_splits, int head_dim) {
   return (size_t)n_qtiles * n_heads * n_splits * TILE * (head_dim + 2);
@@ -77,8 +78,16 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
                                                          const int32_t* __restrict__ page_table, int pt_stride,
                                                          int n_splits, float* __restrict__ part,
                                                          int32_t* __restrict__ tickets, E* __restrict__ out,
-                                                         int T_out, const int32_t* __restrict__ live) {
+                                                         int T_out, int n_qtiles, L2Prefetch pf,
+                                                         const int32_t* __restrict__ live) {
   if (step_is_dead(live)) return;
+  if ((int)blockIdx.z >= n_qtiles) {
+    // not an attention workgroup: one that fetches a region of a later launch's weights into this die's L2
+    const int index = (int)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
+    const int region = index - l2_prefetch_first(n_qtiles * gridDim.y * gridDim.x);
+    if (region >= 0 && region < pf.n_regions) l2_fetch(pf.base + (size_t)region * pf.region_bytes, pf.region_bytes);
+    return;
+  }
   typedef typename ET<E>::vec vec;
   constexpr int G = ET<E>::G, KS = ET<E>::KS, DSTEPS = HD / KS, DT = HD / TILE, NP = Planes<E>::N;
   const int split = blockIdx.x, head = blockIdx.y, qt = blockIdx.z;
@@ -336,9 +345,15 @@ __global__ __launch_bounds__(ATTN_WAVES * WAVE) void attention_kernel(const E* _
 template <int HD> constexpr size_t attn_lds() { return (size_t)ATTN_WAVES * ((HD / TILE) * 16 + 2) * WAVE * 4; }
 
 template <typename E, int HD> static void launch_attention_t(const AttnArgs& a, hipStream_t st) {
-  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, a.n_qtiles), ATTN_WAVES * WAVE, attn_lds<HD>(), st>>>(
+  // With few workgroups of its own the launch gets layers of the grid behind the query tiles that fetch a.pf (a
+  // workgroup fills a compute unit, so with many of its own the fetching ones would only queue up behind them).
+  const int per_layer = a.n_splits * a.geom.n_heads, real = per_layer * a.n_qtiles;
+  const bool fetch = a.pf.base != nullptr && real <= ATTN_FETCH_MAX_OWN;
+  const int last = fetch ? l2_prefetch_first(real) + a.pf.n_regions : real;   // one past the last index in use
+  attention_kernel<E, HD><<<dim3(a.n_splits, a.geom.n_heads, (last + per_layer - 1) / per_layer), ATTN_WAVES * WAVE,
+                            attn_lds<HD>(), st>>>(
       (const E*)a.q, a.q_plane, (const E*)a.kv_layer, a.geom, a.meta, a.page_table, a.pt_stride, a.n_splits, a.part,
-      a.tickets, (E*)a.out, a.T, live_word());
+      a.tickets, (E*)a.out, a.T, a.n_qtiles, fetch ? a.pf : L2Prefetch{nullptr, 0, 0}, live_word());
 }
 
 bool configure_attention() {

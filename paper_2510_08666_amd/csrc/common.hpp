@@ -212,6 +212,22 @@ __device__ inline bool last_arrival(int32_t* c, int n, int32_t* s_flag) {
   return last;
 }
 
+// Index of the first workgroup that fetches region 0 in a launch whose first n_real workgroups do other work: the
+// next multiple of 8, so that fetching workgroup first + i runs on the die of the later launch's workgroup i.
+__host__ __device__ inline int l2_prefetch_first(int n_real) { return (n_real + 7) / 8 * 8; }
+// Every thread of the workgroup reads its share of [p, p + bytes) with ordinary 16-byte loads and drops the data: the
+// lines are then in this die's L2 (bytes: a multiple of 16).
+__device__ inline void l2_fetch(const char* __restrict__ p, uint32_t bytes) {
+  const uint32_t step = blockDim.x * 16;
+  uint32_t acc = 0;
+#pragma unroll 8
+  for (uint32_t o = threadIdx.x * 16; o < bytes; o += step) {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(p + o);
+    acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+  }
+  asm volatile("" ::"v"(acc));   // the loads have a use, nothing is stored
+}
+
 // Steps that are enqueued before the host knows whether they are still needed (the inner loop of blockwise
 // decoding without a host round trip per step) carry the address of a word that is zero once every mask was
 // already empty when the step began: every kernel of such a step returns at once.  Null: an ordinary step.

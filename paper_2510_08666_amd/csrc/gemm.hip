@@ -825,6 +825,15 @@ template <typename E> static void launch_oproj_t(bool bf16, const OprojArgs& a, 
     launch_ksplit<E>(bf16, (const E*)a.w, a.D / ET<E>::KS, (const E*)a.a, a.T, a.D, a.H / 64, a.part, a.tickets,
                      epi, st);
 }
+// What the workgroups of the split-K launch stream: workgroup (slice, task) has index task * slices + slice and takes
+// the slice's share of the task's k-steps, 2 KB of packed weights each, so region i starts at i * region_bytes.
+L2Prefetch oproj_prefetch_plan(bool bf16, const void* w, int D, int H, int T) {
+  const int ksteps = D / (bf16 ? 16 : 8), n_tasks = H / 64;
+  if (T > 2 * TILE || single_slice()) return L2Prefetch{nullptr, 0, 0};   // more tokens: the dense form
+  const int slices = ksplit_slices(bf16, D, T, n_tasks);
+  if (ksteps % (slices * 4) != 0) return L2Prefetch{nullptr, 0, 0};       // slices of unequal length
+  return L2Prefetch{(const char*)w, (uint32_t)(ksteps / slices) * 2048u, n_tasks * slices};
+}
 void launch_oproj(bool bf16, const OprojArgs& a, hipStream_t st) {
   if (bf16) launch_oproj_t<bf16_t>(true, a, st);
   else launch_oproj_t<float>(false, a, st);
