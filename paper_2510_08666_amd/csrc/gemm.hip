@@ -776,10 +776,11 @@ __global__ __launch_bounds__(DENSE_TASKS * DENSE_KH * WAVE) void gemm_dense_kern
 }
 
 // True when the dense form takes the call (many rows, K a whole number of staged chunks per team).
-// (min_T: the dense form takes over above this many tokens.  With two token tiles the split-K form of the QKV
-// projection hands 12.6 MB of partial sums between workgroups for 25 MB of weights and the dense form is faster,
-// 19.1 against 27.9 us; for the output projection, a third of the weights, split-K stays ahead, 11.5 against 17.1.)
-static bool dense_applies(int T, int ksteps, int min_T = 2 * TILE) { return T > min_T && ksteps % (WKC * DENSE_KH) == 0; }
+// (Above 64 tokens.  With two token tiles the split-K form of the QKV projection used to hand 12.6 MB of partial
+// sums between workgroups, 8 slices per task, and the dense form was faster, 19.1 against 27.9 us; with the two
+// slices that ksplit_slices() now gives a launch of 96 tasks it takes 14.9 us.  For the output projection, a third
+// of the weights, split-K was ahead all along, 11.5 against 17.1.)
+static bool dense_applies(int T, int ksteps) { return T > 2 * TILE && ksteps % (WKC * DENSE_KH) == 0; }
 
 template <typename E, int WT, int TASKS, class Epi>
 static void launch_dense_as(const E* W, int ksteps, const E* B, int T, int n_tasks, const Epi& epi, hipStream_t st) {
@@ -806,7 +807,7 @@ template <typename E> static void launch_qkv_t(bool bf16, const QkvArgs& a, hipS
   const int D = a.geom.n_heads * a.geom.head_dim;
   QkvEpi<E> epi{(E*)a.q, a.q_plane, (E*)a.kv_layer, a.geom, a.meta.tok_seq, a.meta.tok_pos, a.page_table,
                 a.pt_stride, a.cos_tab, a.sin_tab, a.norm, a.T, a.H, D};
-  if (dense_applies(a.T, a.H / ET<E>::KS, TILE))
+  if (dense_applies(a.T, a.H / ET<E>::KS))
     launch_dense<E>((const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, 3 * D / 64, epi, st);
   else
     launch_ksplit<E>(bf16, (const E*)a.w, a.H / ET<E>::KS, (const E*)a.xn, a.T, a.H, 3 * D / 64, a.part,
